@@ -1,0 +1,5 @@
+"""fp64 CPU oracle for GFormer attention forward.  TEST INFRASTRUCTURE ONLY.
+
+Nothing on the product path may import this package: only tests, the smoke
+check and the benchmark's cpu_baseline leg do.
+"""

@@ -1,0 +1,196 @@
+/*
+ * fp64 CPU oracle for GFormer attention forward.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain definition of what the GPU library computes.  It
+ * shares no source, header, table or helper with the HIP path and must never be
+ * linked or called by it; only the tests, the smoke check and the cpu_baseline
+ * leg of the benchmark use it.
+ *
+ * What is computed (GFormer, arXiv 2412.19829):
+ *   - Section III-A: heads are split in two groups.  Heads [0, H0) run windowed
+ *     causal softmax attention, heads [H0, H) run causal linear attention.  The
+ *     output of head h lands in head h's slot; nothing is summed across groups.
+ *   - Section III-B: windowed head.  Token i attends to the w tokens ending at
+ *     itself, j in [max(0, i-w+1), i]; softmax (Eq. 1, with the causal mask of
+ *     section II-A) over exactly those scores; weighted sum of V rows.
+ *   - Section III-C, Algorithm 1: linear head.  A (E x E) and Z (E) are running
+ *     sums of phi(K_j) (x) V_j and phi(K_j) over j <= i (token i is added before
+ *     row i is read out); H_i = phi(Q_i)^T A / (phi(Q_i) . Z).  The printed last
+ *     line of the algorithm names an undefined S and K'; it is read as Q'^T A,
+ *     which is what the prose around it and section II-B describe.
+ *   - Section II-B: phi(x) = elu(x) + 1.
+ *
+ * Two routines cover the linear head: the explicit O(N^2) masked sum (the plain
+ * definition: weights a_ij = phi(q_i).phi(k_j), j <= i) and Algorithm 1's
+ * recurrence.  They are written separately and are tested against each other.
+ *
+ * Layout: dense row-major [B, H, N, d] doubles.  All arithmetic in double.
+ * Pins: see tests/test_oracle_pins.py (worked 4-token examples in exact
+ * rationals, a library softmax-attention routine, closed forms, invariants).
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_PHI_ELU1 = 0, ORACLE_PHI_IDENTITY = 1 };
+enum { ORACLE_LINEAR_QUADRATIC = 0, ORACLE_LINEAR_RECURRENT = 1 };
+
+/* Section II-B: phi(x) = elu(x) + 1, i.e. x + 1 for x > 0 and exp(x) otherwise. */
+static double feature_map(double x, int phi)
+{
+    if (phi == ORACLE_PHI_IDENTITY) return x;
+    return x > 0.0 ? x + 1.0 : exp(x);
+}
+
+/* Section III-B + Eq. 1: one windowed causal softmax head, [N, d] row-major. */
+int gformer_oracle_windowed_head_f64(const double *q, const double *k, const double *v,
+                                     double *out, int N, int d, int window, double scale)
+{
+    if (!q || !k || !v || !out || N < 0 || d < 1 || window < 1) return 1;
+    double *s = (double *)malloc(sizeof(double) * (size_t)(window > N ? (N > 0 ? N : 1) : window));
+    if (!s) return 2;
+    for (int i = 0; i < N; ++i) {
+        int lo = i - window + 1;
+        if (lo < 0) lo = 0;
+        int cnt = i - lo + 1;
+        double m = -INFINITY;
+        for (int j = lo; j <= i; ++j) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += q[(size_t)i * d + c] * k[(size_t)j * d + c];
+            acc *= scale;
+            s[j - lo] = acc;
+            if (acc > m) m = acc;
+        }
+        double l = 0.0;
+        for (int t = 0; t < cnt; ++t) {
+            s[t] = exp(s[t] - m);
+            l += s[t];
+        }
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int j = lo; j <= i; ++j) acc += s[j - lo] * v[(size_t)j * d + c];
+            out[(size_t)i * d + c] = acc / l;
+        }
+    }
+    free(s);
+    return 0;
+}
+
+/* Linear head, plain definition: out_i = sum_{j<=i} a_ij v_j / (sum_{j<=i} a_ij + eps),
+ * a_ij = phi(q_i) . phi(k_j).  O(N^2 d). */
+int gformer_oracle_linear_head_quadratic_f64(const double *q, const double *k, const double *v,
+                                             double *out, int N, int d, int phi, double eps)
+{
+    if (!q || !k || !v || !out || N < 0 || d < 1) return 1;
+    size_t nd = (size_t)N * d;
+    double *fq = (double *)malloc(sizeof(double) * (nd ? nd : 1));
+    double *fk = (double *)malloc(sizeof(double) * (nd ? nd : 1));
+    double *a = (double *)malloc(sizeof(double) * (size_t)(N ? N : 1));
+    if (!fq || !fk || !a) { free(fq); free(fk); free(a); return 2; }
+    for (size_t t = 0; t < nd; ++t) {
+        fq[t] = feature_map(q[t], phi);
+        fk[t] = feature_map(k[t], phi);
+    }
+    for (int i = 0; i < N; ++i) {
+        double den = 0.0;
+        for (int j = 0; j <= i; ++j) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += fq[(size_t)i * d + c] * fk[(size_t)j * d + c];
+            a[j] = acc;
+            den += acc;
+        }
+        den += eps;
+        for (int e = 0; e < d; ++e) {
+            double num = 0.0;
+            for (int j = 0; j <= i; ++j) num += a[j] * v[(size_t)j * d + e];
+            out[(size_t)i * d + e] = num / den;
+        }
+    }
+    free(fq); free(fk); free(a);
+    return 0;
+}
+
+/* Linear head, Algorithm 1: running A (d x d) and Z (d), token i added before read-out. */
+int gformer_oracle_linear_head_recurrent_f64(const double *q, const double *k, const double *v,
+                                             double *out, int N, int d, int phi, double eps)
+{
+    if (!q || !k || !v || !out || N < 0 || d < 1) return 1;
+    double *A = (double *)calloc((size_t)d * d, sizeof(double));
+    double *Z = (double *)calloc((size_t)d, sizeof(double));
+    double *qp = (double *)malloc(sizeof(double) * (size_t)d);
+    double *kp = (double *)malloc(sizeof(double) * (size_t)d);
+    if (!A || !Z || !qp || !kp) { free(A); free(Z); free(qp); free(kp); return 2; }
+    for (int i = 0; i < N; ++i) {
+        for (int c = 0; c < d; ++c) {
+            qp[c] = feature_map(q[(size_t)i * d + c], phi);
+            kp[c] = feature_map(k[(size_t)i * d + c], phi);
+        }
+        for (int c = 0; c < d; ++c) {
+            for (int e = 0; e < d; ++e) A[(size_t)c * d + e] += kp[c] * v[(size_t)i * d + e];
+            Z[c] += kp[c];
+        }
+        double den = 0.0;
+        for (int c = 0; c < d; ++c) den += qp[c] * Z[c];
+        den += eps;
+        for (int e = 0; e < d; ++e) {
+            double num = 0.0;
+            for (int c = 0; c < d; ++c) num += qp[c] * A[(size_t)c * d + e];
+            out[(size_t)i * d + e] = num / den;
+        }
+    }
+    free(A); free(Z); free(qp); free(kp);
+    return 0;
+}
+
+/* Whole layer (section III-A head split) over dense [B, H, N, d].
+ * linear_form selects which of the two linear routines runs on heads >= n_sparse_heads.
+ * threads <= 0 lets OpenMP decide.  Returns 0, or the first non-zero head status. */
+int gformer_oracle_fwd_f64(const double *q, const double *k, const double *v, double *out,
+                           int B, int H, int N, int d, int window, int n_sparse_heads,
+                           int phi, double softmax_scale, double eps, int linear_form,
+                           int threads)
+{
+    if (!q || !k || !v || !out) return 1;
+    if (B < 0 || H < 0 || N < 0 || d < 1 || window < 1) return 1;
+    if (n_sparse_heads < 0 || n_sparse_heads > H) return 1;
+    int status = 0;
+    long total = (long)B * H;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < total; ++bh) {
+        int h = (int)(bh % H);
+        size_t off = (size_t)bh * N * d;
+        int rc;
+        if (h < n_sparse_heads)
+            rc = gformer_oracle_windowed_head_f64(q + off, k + off, v + off, out + off, N, d,
+                                                  window, softmax_scale);
+        else if (linear_form == ORACLE_LINEAR_RECURRENT)
+            rc = gformer_oracle_linear_head_recurrent_f64(q + off, k + off, v + off, out + off,
+                                                          N, d, phi, eps);
+        else
+            rc = gformer_oracle_linear_head_quadratic_f64(q + off, k + off, v + off, out + off,
+                                                          N, d, phi, eps);
+        if (rc != 0) {
+#pragma omp critical
+            if (status == 0) status = rc;
+        }
+    }
+    return status;
+}
+
+int gformer_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

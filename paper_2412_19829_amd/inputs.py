@@ -1,0 +1,148 @@
+"""Seeded synthetic Q/K/V generators for GFormer attention workloads.
+
+This module holds no arithmetic of the attention method itself: it only draws
+random tensors, applies the per-workload input scaling, and rounds to bf16.
+Both the test oracle and the HIP path are fed from here so that they see the
+exact same values; neither of them is imported here.
+
+Recipe (one independent stream per head, so that any single head of a large
+workload can be regenerated without materialising the whole tensor):
+
+    rng  = numpy.random.default_rng([seed, b, h])
+    qkv  = rng.standard_normal((3, N, d), float32) * sigma
+    q    = qkv[0] * q_scale          (q_scale = 1/sqrt(d) when Q is pre-scaled)
+    k    = qkv[1] ; k[j] *= outlier_gain for j % outlier_every == 0
+    v    = qkv[2]
+
+For bf16 workloads the values are rounded once to bf16 (round to nearest even)
+and both sides consume the rounded values, so input quantisation is never
+counted as error.
+
+The shapes stand in for the activations of the GPT-Neo/ViT-shaped models the
+paper times (section IV-A: batch 4, 16 heads, head size 64, N from 1k to 6k);
+the paper's datasets and weights are not needed for the attention forward.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Iterable, Tuple
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    B: int
+    H: int
+    N: int
+    d: int
+    window: int
+    dtype: str              # "f32" or "bf16"
+    seed: int
+    sigma: float = 1.0      # std of the raw normal draws
+    q_prescaled: bool = True  # multiply Q by 1/sqrt(d) in the generator
+    outlier_every: int = 0  # keys with j % outlier_every == 0 are multiplied ...
+    outlier_gain: float = 1.0  # ... by this gain (0 = no outliers)
+    n_sparse_heads: int = 0  # default head split H0 (heads [0,H0) windowed)
+
+    def with_(self, **kw) -> "Workload":
+        return replace(self, **kw)
+
+
+# The workloads named by the benchmark contract.  `n_sparse_heads` defaults to
+# the 3/16 ratio the paper found best for causal attention (section IV-D).
+WORKLOADS = {
+    "tiny_f32": Workload("tiny_f32", 1, 1, 256, 64, 32, "f32", 1001, n_sparse_heads=1),
+    "gpt2_small": Workload("gpt2_small", 1, 12, 2048, 64, 128, "bf16", 1002, n_sparse_heads=2),
+    "llm7b": Workload("llm7b", 4, 32, 8192, 128, 256, "bf16", 1003, n_sparse_heads=6),
+    "long32k": Workload("long32k", 1, 32, 32768, 128, 512, "bf16", 1004, sigma=0.5,
+                        q_prescaled=False, outlier_every=64, outlier_gain=8.0,
+                        n_sparse_heads=6),
+    # the paper's own timing shape (section IV-A, IV-D): B=4, H=16, E=64, 3 sparse heads
+    "paper_gpt_4k": Workload("paper_gpt_4k", 4, 16, 4096, 64, 128, "bf16", 1006,
+                             n_sparse_heads=3),
+}
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (nearest, ties to even); returns uint16 bit patterns."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32)
+    # NaN stays NaN; the generators never produce one, but keep the helper total.
+    nan = np.isnan(x)
+    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    r = ((u + bias) >> np.uint32(16)).astype(np.uint16)
+    if nan.any():
+        r = np.where(nan, np.uint16(0x7FC0), r)
+    return r
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns (uint16) to float32, exactly."""
+    b = np.ascontiguousarray(b, dtype=np.uint16)
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """float32 -> nearest bfloat16 -> float32."""
+    return bf16_bits_to_f32(f32_to_bf16_bits(x))
+
+
+def make_head(wl: Workload, b: int, h: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Q, K, V of one (batch, head) as float32 arrays [N, d].
+
+    For bf16 workloads the returned float32 values are exactly representable in
+    bf16 (already rounded)."""
+    rng = np.random.default_rng([wl.seed, b, h])
+    qkv = rng.standard_normal((3, wl.N, wl.d), dtype=np.float32)
+    if wl.sigma != 1.0:
+        qkv *= np.float32(wl.sigma)
+    q, k, v = qkv[0], qkv[1], qkv[2]
+    if wl.q_prescaled:
+        q = q * np.float32(1.0 / np.sqrt(wl.d))
+    if wl.outlier_every > 0:
+        k = k.copy()
+        k[:: wl.outlier_every] *= np.float32(wl.outlier_gain)
+    if wl.dtype == "bf16":
+        q, k, v = round_to_bf16(q), round_to_bf16(k), round_to_bf16(v)
+    return (np.ascontiguousarray(q, dtype=np.float32),
+            np.ascontiguousarray(k, dtype=np.float32),
+            np.ascontiguousarray(v, dtype=np.float32))
+
+
+def make_qkv(wl: Workload, heads: Iterable[Tuple[int, int]] | None = None):
+    """Q, K, V as float32 arrays [B, H, N, d] (dense, head-major).
+
+    With `heads`, returns arrays [len(heads), N, d] holding only those (b, h)."""
+    if heads is None:
+        q = np.empty((wl.B, wl.H, wl.N, wl.d), np.float32)
+        k = np.empty_like(q)
+        v = np.empty_like(q)
+        for b in range(wl.B):
+            for h in range(wl.H):
+                q[b, h], k[b, h], v[b, h] = make_head(wl, b, h)
+        return q, k, v
+    heads = list(heads)
+    q = np.empty((len(heads), wl.N, wl.d), np.float32)
+    k = np.empty_like(q)
+    v = np.empty_like(q)
+    for i, (b, h) in enumerate(heads):
+        q[i], k[i], v[i] = make_head(wl, b, h)
+    return q, k, v
+
+
+def sample_heads(wl: Workload, n_sparse_heads: int, seed: int = 7) -> list:
+    """A small fixed sample of (b, h) pairs: first and last head of each mode
+    group plus two seeded-random ones per group."""
+    rng = np.random.default_rng([wl.seed, seed])
+    picks = []
+    groups = [range(0, n_sparse_heads), range(n_sparse_heads, wl.H)]
+    for g in groups:
+        if len(g) == 0:
+            continue
+        cand = {(0, g[0]), (wl.B - 1, g[-1])}
+        for _ in range(2):
+            cand.add((int(rng.integers(0, wl.B)), int(g[0] + rng.integers(0, len(g)))))
+        picks.extend(sorted(cand))
+    return picks

@@ -1,0 +1,460 @@
+"""Pins for the fp64 oracle (CPU only).
+
+The oracle is checked against things it did not produce: hand-derived exact
+examples (tests/golden), a library softmax-attention routine, exact rational
+brute force, closed forms and invariants of the definitions.  A set of planted
+wrong readings (written here, on the CPU) must each be rejected by the goldens.
+"""
+from __future__ import annotations
+
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cpu_oracle as co
+from oracle import numpy_twin as tw
+from tests.helpers import load_golden, max_abs, parse_matrix, parse_scalar
+
+TIGHT = 1e-12
+
+
+def _rand(shape, seed, scale=1.0):
+    return np.random.default_rng(seed).standard_normal(shape) * scale
+
+
+# ---------------------------------------------------------------------------
+# hand examples (exact rationals)
+# ---------------------------------------------------------------------------
+
+WINDOW_IMPLS = {
+    "c": lambda q, k, v, w: co.windowed_head(q, k, v, w, 1.0),
+    "numpy": lambda q, k, v, w: tw.windowed_head(q, k, v, w, 1.0),
+}
+LINEAR_IMPLS = {
+    "c_quadratic": lambda q, k, v: co.linear_head(q, k, v, form=co.LINEAR_QUADRATIC),
+    "c_recurrent": lambda q, k, v: co.linear_head(q, k, v, form=co.LINEAR_RECURRENT),
+    "numpy_recurrent": lambda q, k, v: tw.linear_head_recurrent(q, k, v),
+    "numpy_quadratic": lambda q, k, v: tw.linear_head_quadratic(q, k, v),
+}
+
+
+@pytest.mark.parametrize("impl", sorted(WINDOW_IMPLS))
+def test_window_example_exact(impl):
+    g = load_golden("window_4token.json")
+    q, k, v = parse_matrix(g["q"]), parse_matrix(g["k"]), parse_matrix(g["v"])
+    for w, rows in g["expected"].items():
+        got = WINDOW_IMPLS[impl](q, k, v, int(w))
+        assert max_abs(got, parse_matrix(rows)) < 1e-14, (impl, w)
+
+
+@pytest.mark.parametrize("impl", sorted(LINEAR_IMPLS))
+def test_linear_example_exact(impl):
+    g = load_golden("linear_4token.json")
+    q, k, v = parse_matrix(g["q"]), parse_matrix(g["k"]), parse_matrix(g["v"])
+    got = LINEAR_IMPLS[impl](q, k, v)
+    assert max_abs(got, parse_matrix(g["expected"])) < 1e-14
+    # the order of operations printed in the paper's PyTorch listing is not Algorithm 1
+    assert max_abs(got, parse_matrix(g["must_reject"])) > 0.05
+
+
+def test_linear_example_intermediates():
+    """The fixture's own phi, num and den columns are consistent with its inputs."""
+    g = load_golden("linear_4token.json")
+    q, k, v = parse_matrix(g["q"]), parse_matrix(g["k"]), parse_matrix(g["v"])
+    assert max_abs(tw.phi_elu1(q), parse_matrix(g["phi_q"])) < 1e-15
+    assert max_abs(tw.phi_elu1(k), parse_matrix(g["phi_k"])) < 1e-15
+    fq = [[Fraction(t) for t in r] for r in g["phi_q"]]
+    fk = [[Fraction(t) for t in r] for r in g["phi_k"]]
+    fv = [[Fraction(t) for t in r] for r in g["v"]]
+    for i in range(4):
+        a = [sum(fq[i][c] * fk[j][c] for c in range(2)) for j in range(i + 1)]
+        assert sum(a) == Fraction(g["den"][i])
+        for e in range(2):
+            assert sum(a[j] * fv[j][e] for j in range(i + 1)) == Fraction(g["num"][i][e])
+            assert sum(a[j] * fv[j][e] for j in range(i + 1)) / sum(a) == Fraction(g["expected"][i][e])
+
+
+@pytest.mark.parametrize("impl", sorted(LINEAR_IMPLS))
+def test_linear_head_size_one(impl):
+    g = load_golden("linear_d1.json")
+    q, k, v = parse_matrix(g["q"]), parse_matrix(g["k"]), parse_matrix(g["v"])
+    assert max_abs(LINEAR_IMPLS[impl](q, k, v), parse_matrix(g["expected"])) < 1e-14
+
+
+# ---------------------------------------------------------------------------
+# planted wrong readings must fail the goldens (mistakes are planted here, on the CPU)
+# ---------------------------------------------------------------------------
+
+def _wrong_window(q, k, v, w, kind):
+    N, d = q.shape
+    out = np.zeros((N, d))
+    for i in range(N):
+        if kind == "w_plus_one":
+            lo, hi = max(0, i - w), i
+        elif kind == "exclude_self":
+            lo, hi = max(0, i - w), max(0, i - 1)
+        elif kind == "not_causal":
+            lo, hi = max(0, i - w + 1), min(N - 1, i + w - 1)
+        else:
+            lo, hi = max(0, i - w + 1), i
+        s = k[lo:hi + 1] @ q[i]
+        if kind == "transposed_qk":
+            s = q[lo:hi + 1] @ k[i]
+        if kind == "half_scale":
+            s = 0.5 * s
+        e = np.exp(s - s.max())
+        if kind == "no_normalise":
+            out[i] = e @ v[lo:hi + 1]
+        else:
+            out[i] = (e / e.sum()) @ v[lo:hi + 1]
+    return out
+
+
+@pytest.mark.parametrize("kind", ["w_plus_one", "exclude_self", "not_causal", "transposed_qk",
+                                  "half_scale", "no_normalise"])
+def test_window_golden_rejects_wrong_readings(kind):
+    g = load_golden("window_4token.json")
+    q, k, v = parse_matrix(g["q"]), parse_matrix(g["k"]), parse_matrix(g["v"])
+    worst = max(max_abs(_wrong_window(q, k, v, int(w), kind), parse_matrix(rows))
+                for w, rows in g["expected"].items())
+    assert worst > 1e-3, kind
+
+
+def _wrong_linear(q, k, v, kind):
+    N, d = q.shape
+    fq, fk = tw.phi_elu1(q), tw.phi_elu1(k)
+    if kind == "elu_without_plus_one":
+        fq, fk = fq - 1.0, fk - 1.0
+    if kind == "phi_on_q_only":
+        fk = k
+    A = np.zeros((d, d)); Z = np.zeros(d); out = np.zeros((N, d))
+    for i in range(N):
+        if kind == "exclusive_prefix":
+            num, den = fq[i] @ A, fq[i] @ Z
+            A += np.outer(fk[i], v[i]); Z += fk[i]
+            out[i] = num / den if den != 0 else 0.0
+            continue
+        if kind == "transposed_state":
+            A += np.outer(v[i], fk[i])
+        else:
+            A += np.outer(fk[i], v[i])
+        Z += fk[i]
+        if kind == "k_reads_state":      # the garbled last line of Algorithm 1 taken literally
+            out[i] = (fk[i] @ A) / (fq[i] @ Z)
+        elif kind == "no_normaliser":
+            out[i] = fq[i] @ A
+        else:
+            out[i] = (fq[i] @ A) / (fq[i] @ Z)
+    return out
+
+
+@pytest.mark.parametrize("kind", ["exclusive_prefix", "transposed_state", "k_reads_state",
+                                  "no_normaliser", "elu_without_plus_one", "phi_on_q_only"])
+def test_linear_golden_rejects_wrong_readings(kind):
+    g = load_golden("linear_4token.json")
+    q, k, v = parse_matrix(g["q"]), parse_matrix(g["k"]), parse_matrix(g["v"])
+    with np.errstate(all="ignore"):
+        got = _wrong_linear(q, k, v, kind)
+    assert not np.allclose(got, parse_matrix(g["expected"]), atol=1e-3, equal_nan=False), kind
+
+
+# ---------------------------------------------------------------------------
+# feature map (section II-B)
+# ---------------------------------------------------------------------------
+
+def test_feature_map_values_through_the_oracle():
+    """With d = 1, N = 1 .. the first output is v_0; use a 2-token probe to read phi(k) back:
+    out_1 = (phi(k0) v0 + phi(k1) v1) / (phi(k0) + phi(k1)) with v = (0, 1), k0 = 0 (phi = 1)."""
+    for x, want in [(0.0, 1.0), (-math.log(2.0), 0.5), (2.5, 3.5), (-30.0, math.exp(-30.0)),
+                    (1e-9, 1.0 + 1e-9), (-1e-9, math.exp(-1e-9))]:
+        q = np.array([[0.3], [0.7]]); k = np.array([[0.0], [x]]); v = np.array([[0.0], [1.0]])
+        for form in (co.LINEAR_QUADRATIC, co.LINEAR_RECURRENT):
+            got = co.linear_head(q, k, v, form=form)[1, 0]
+            assert abs(got - want / (1.0 + want)) < 1e-15 * max(1.0, want), (x, form)
+
+
+def test_feature_map_positive_and_continuous():
+    x = np.linspace(-40, 40, 4001)
+    y = tw.phi_elu1(x)
+    assert (y > 0).all()
+    assert np.all(np.diff(y) > 0)
+    assert abs(tw.phi_elu1(np.array([0.0]))[0] - 1.0) == 0.0
+
+
+# ---------------------------------------------------------------------------
+# library second opinion: Eq. 1 with the causal mask == torch SDPA (fp64, CPU)
+# ---------------------------------------------------------------------------
+
+def _sdpa(q, k, v, mask=None, causal=False):
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64))[None, None]
+    o = torch.nn.functional.scaled_dot_product_attention(
+        t(q), t(k), t(v), attn_mask=mask, is_causal=causal, scale=1.0)
+    return o[0, 0].numpy()
+
+
+@pytest.mark.parametrize("N,d,w", [(37, 8, 37), (64, 16, 100), (5, 3, 5)])
+def test_window_covering_sequence_is_full_causal_attention(N, d, w):
+    q, k, v = _rand((N, d), 1), _rand((N, d), 2), _rand((N, d), 3)
+    want = _sdpa(q, k, v, causal=True)
+    assert max_abs(co.windowed_head(q, k, v, w), want) < TIGHT
+    assert max_abs(tw.windowed_head(q, k, v, w), want) < TIGHT
+
+
+@pytest.mark.parametrize("N,d,w", [(50, 8, 1), (50, 8, 2), (67, 16, 13), (130, 4, 64), (96, 32, 33)])
+def test_window_matches_library_attention_with_band_mask(N, d, w):
+    q, k, v = _rand((N, d), 4), _rand((N, d), 5), _rand((N, d), 6)
+    i = torch.arange(N)[:, None]; j = torch.arange(N)[None, :]
+    mask = (j <= i) & (j > i - w)
+    want = _sdpa(q, k, v, mask=mask)
+    assert max_abs(co.windowed_head(q, k, v, w), want) < TIGHT
+    assert max_abs(tw.windowed_head(q, k, v, w), want) < TIGHT
+
+
+def test_softmax_scale_is_applied_to_scores():
+    N, d, w = 40, 8, 9
+    q, k, v = _rand((N, d), 7), _rand((N, d), 8), _rand((N, d), 9)
+    s = 1.0 / math.sqrt(d)
+    assert max_abs(co.windowed_head(q, k, v, w, s), co.windowed_head(q * s, k, v, w, 1.0)) < TIGHT
+    i = torch.arange(N)[:, None]; j = torch.arange(N)[None, :]
+    mask = (j <= i) & (j > i - w)
+    assert max_abs(co.windowed_head(q, k, v, w, s), _sdpa(q * s, k, v, mask=mask)) < TIGHT
+
+
+# ---------------------------------------------------------------------------
+# exact rational brute force (independent arithmetic)
+# ---------------------------------------------------------------------------
+
+def _frac_matrix(rng, n, d, lo=1, hi=9, signed=False):
+    m = [[Fraction(int(rng.integers(lo, hi)), int(rng.integers(1, 7))) for _ in range(d)]
+         for _ in range(n)]
+    if signed:
+        m = [[x * (1 if rng.integers(0, 2) else -1) for x in r] for r in m]
+    return m
+
+
+def _to_np(m):
+    return np.array([[float(x) for x in r] for r in m])
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_linear_identity_phi_against_exact_rationals(seed):
+    rng = np.random.default_rng(100 + seed)
+    N, d = 8, 2 + seed % 2
+    fq, fk = _frac_matrix(rng, N, d), _frac_matrix(rng, N, d)   # positive features
+    fv = _frac_matrix(rng, N, d, signed=True)
+    want = []
+    for i in range(N):
+        a = [sum(fq[i][c] * fk[j][c] for c in range(d)) for j in range(i + 1)]
+        want.append([sum(a[j] * fv[j][e] for j in range(i + 1)) / sum(a) for e in range(d)])
+    want = _to_np(want)
+    for form in (co.LINEAR_QUADRATIC, co.LINEAR_RECURRENT):
+        got = co.linear_head(_to_np(fq), _to_np(fk), _to_np(fv), phi=co.PHI_IDENTITY, form=form)
+        assert max_abs(got, want) < 1e-13
+    got = tw.linear_head_recurrent(_to_np(fq), _to_np(fk), _to_np(fv), phi=lambda x: x)
+    assert max_abs(got, want) < 1e-13
+
+
+@pytest.mark.parametrize("seed,w", [(0, 1), (1, 3), (2, 5), (3, 8)])
+def test_window_against_exact_rationals(seed, w):
+    """Keys are logs of rationals along q's only non-zero axis, so softmax weights are rational."""
+    rng = np.random.default_rng(200 + seed)
+    N, d = 8, 2
+    r = [Fraction(int(rng.integers(1, 12)), int(rng.integers(1, 5))) for _ in range(N)]
+    fv = _frac_matrix(rng, N, d, signed=True)
+    q = np.tile(np.array([[0.0, 1.0]]), (N, 1))
+    k = np.array([[float(rng.standard_normal()), math.log(float(x))] for x in r])
+    want = []
+    for i in range(N):
+        lo = max(0, i - w + 1)
+        tot = sum(r[lo:i + 1])
+        want.append([sum(r[j] * fv[j][e] for j in range(lo, i + 1)) / tot for e in range(d)])
+    assert max_abs(co.windowed_head(q, k, _to_np(fv), w), _to_np(want)) < 1e-13
+    assert max_abs(tw.windowed_head(q, k, _to_np(fv), w), _to_np(want)) < 1e-13
+
+
+# ---------------------------------------------------------------------------
+# equivalence of forms and of the two implementations
+# ---------------------------------------------------------------------------
+
+def chunked_linear(q, k, v, C, phi=tw.phi_elu1, eps=0.0):
+    """Chunk-parallel rearrangement of Algorithm 1 (host-side statement of what the GPU kernel
+    does): inside a chunk the masked quadratic form, across chunks the carried state."""
+    N, d = q.shape
+    S = np.zeros((d, d)); z = np.zeros(d); out = np.zeros((N, d))
+    for s0 in range(0, N, C):
+        fq, fk, vc = phi(q[s0:s0 + C]), phi(k[s0:s0 + C]), v[s0:s0 + C]
+        a = np.tril(fq @ fk.T)
+        num = a @ vc + fq @ S
+        den = a.sum(1) + fq @ z + eps
+        out[s0:s0 + C] = num / den[:, None]
+        S += fk.T @ vc
+        z += fk.sum(0)
+    return out
+
+
+@pytest.mark.parametrize("N,d", [(1, 4), (2, 1), (33, 8), (100, 16), (257, 64)])
+def test_linear_forms_agree(N, d):
+    q, k, v = _rand((N, d), 11), _rand((N, d), 12), _rand((N, d), 13)
+    a = co.linear_head(q, k, v, form=co.LINEAR_QUADRATIC)
+    b = co.linear_head(q, k, v, form=co.LINEAR_RECURRENT)
+    c = tw.linear_head_recurrent(q, k, v)
+    e = tw.linear_head_quadratic(q, k, v)
+    assert max_abs(a, b) < 1e-11 and max_abs(a, c) < 1e-11 and max_abs(a, e) < 1e-11
+    for C in (1, 3, 7, 64, N, N + 5):
+        assert max_abs(a, chunked_linear(q, k, v, C)) < 1e-11, C
+
+
+def test_c_oracle_matches_numpy_twin_on_a_layer():
+    B, H, N, d, w, H0 = 2, 5, 70, 8, 17, 2
+    q, k, v = _rand((B, H, N, d), 21, 0.7), _rand((B, H, N, d), 22), _rand((B, H, N, d), 23)
+    a = co.attn_fwd(q, k, v, w, H0, softmax_scale=0.8, eps=0.0)
+    b = tw.attn_fwd(q, k, v, w, H0, softmax_scale=0.8)
+    assert max_abs(a, b) < 1e-11
+    r = co.attn_fwd(q, k, v, w, H0, softmax_scale=0.8, linear_form=co.LINEAR_RECURRENT, threads=3)
+    assert max_abs(a, r) < 1e-11
+    # head split (section III-A): slot h holds head h; the scale touches windowed heads only
+    for b_ in range(B):
+        for h in range(H):
+            if h < H0:
+                one = co.windowed_head(q[b_, h], k[b_, h], v[b_, h], w, 0.8)
+            else:
+                one = co.linear_head(q[b_, h], k[b_, h], v[b_, h])
+            assert max_abs(a[b_, h], one) == 0.0
+
+
+def test_head_result_depends_only_on_its_side_of_the_split():
+    B, H, N, d, w = 1, 4, 40, 8, 6
+    q, k, v = _rand((B, H, N, d), 31), _rand((B, H, N, d), 32), _rand((B, H, N, d), 33)
+    o1, o2, o3 = (co.attn_fwd(q, k, v, w, h0) for h0 in (1, 2, 3))
+    assert max_abs(o1[:, 0], o2[:, 0]) == 0.0 and max_abs(o2[:, 0], o3[:, 0]) == 0.0  # windowed
+    assert max_abs(o1[:, 3], o2[:, 3]) == 0.0 and max_abs(o2[:, 3], o3[:, 3]) == 0.0  # linear
+    assert max_abs(o2[:, 1], o3[:, 1]) == 0.0 and max_abs(o1[:, 1], o2[:, 1]) > 1e-3
+    perm = [2, 3, 0, 1]   # permuting heads inside one mode group permutes outputs
+    op = co.attn_fwd(q[:, perm], k[:, perm], v[:, perm], w, 0)
+    assert max_abs(op, co.attn_fwd(q, k, v, w, 0)[:, perm]) == 0.0
+
+
+# ---------------------------------------------------------------------------
+# invariants and closed forms
+# ---------------------------------------------------------------------------
+
+def _both_paths(q, k, v, w):
+    return [("window", co.windowed_head(q, k, v, w)),
+            ("linear_q", co.linear_head(q, k, v, form=co.LINEAR_QUADRATIC)),
+            ("linear_r", co.linear_head(q, k, v, form=co.LINEAR_RECURRENT))]
+
+
+def test_weights_sum_to_one():
+    N, d, w = 60, 8, 11
+    q, k = _rand((N, d), 41), _rand((N, d), 42)
+    for name, o in _both_paths(q, k, np.ones((N, d)), w):
+        assert max_abs(o, np.ones((N, d))) < 1e-13, name
+    const = np.tile(np.arange(d, dtype=np.float64)[None] - 3.0, (N, 1))
+    for name, o in _both_paths(q, k, const, w):
+        assert max_abs(o, const) < 1e-12, name
+
+
+def test_outputs_lie_in_convex_hull_of_visible_values():
+    N, d, w = 80, 6, 9
+    q, k, v = _rand((N, d), 43), _rand((N, d), 44), _rand((N, d), 45)
+    ow = co.windowed_head(q, k, v, w)
+    ol = co.linear_head(q, k, v)
+    for i in range(N):
+        lo = max(0, i - w + 1)
+        assert (ow[i] <= v[lo:i + 1].max(0) + 1e-12).all() and (ow[i] >= v[lo:i + 1].min(0) - 1e-12).all()
+        assert (ol[i] <= v[:i + 1].max(0) + 1e-12).all() and (ol[i] >= v[:i + 1].min(0) - 1e-12).all()
+
+
+def test_zero_queries_or_keys_give_plain_means():
+    N, d, w = 50, 5, 7
+    k, v = _rand((N, d), 46), _rand((N, d), 47)
+    zero = np.zeros((N, d))
+    win_mean = np.stack([v[max(0, i - w + 1):i + 1].mean(0) for i in range(N)])
+    pre_mean = np.cumsum(v, 0) / np.arange(1, N + 1)[:, None]
+    assert max_abs(co.windowed_head(zero, k, v, w), win_mean) < 1e-13
+    assert max_abs(co.windowed_head(k, zero, v, w), win_mean) < 1e-13
+    # phi(0) = 1 on every feature: all keys weigh the same whatever q is
+    assert max_abs(co.linear_head(k, zero, v), pre_mean) < 1e-12
+    assert max_abs(co.linear_head(k, zero, v, form=co.LINEAR_RECURRENT), pre_mean) < 1e-12
+
+
+def test_first_token_returns_its_own_value():
+    N, d = 9, 4
+    q, k, v = _rand((N, d), 48), _rand((N, d), 49), _rand((N, d), 50)
+    for name, o in _both_paths(q, k, v, 3):
+        assert max_abs(o[0], v[0]) < 1e-14, name
+
+
+def test_causality_and_window_locality():
+    N, d, w, t = 70, 6, 8, 31
+    q, k, v = _rand((N, d), 51), _rand((N, d), 52), _rand((N, d), 53)
+    k2, v2 = k.copy(), v.copy()
+    k2[t] += 1.0; v2[t] -= 2.0
+    base, pert = _both_paths(q, k, v, w), _both_paths(q, k2, v2, w)
+    for (name, a), (_, b) in zip(base, pert):
+        assert max_abs(a[:t], b[:t]) == 0.0, name          # nothing before t moves
+        assert max_abs(a[t], b[t]) > 1e-6, name
+        if name == "window":
+            assert max_abs(a[t + w:], b[t + w:]) == 0.0      # and nothing past the window
+            assert max_abs(a[t + w - 1], b[t + w - 1]) > 1e-9
+        else:
+            assert max_abs(a[-1], b[-1]) > 1e-9              # the linear state remembers
+    q2 = q.copy(); q2[t] *= -0.5
+    for (name, a), (_, b) in zip(base, _both_paths(q2, k, v, w)):
+        rows = np.abs(a - b).max(1)
+        assert rows[t] > 1e-9 and rows[:t].max() == 0.0 and rows[t + 1:].max() == 0.0, name
+
+
+def test_softmax_shift_invariance_with_large_shift():
+    N, d, w = 40, 8, 10
+    q, k, v = _rand((N, d), 54), _rand((N, d), 55), _rand((N, d), 56)
+    shift = 300.0 * _rand((1, d), 57)     # adds q_i.shift (hundreds) to every score of row i
+    assert max_abs(co.windowed_head(q, k, v, w), co.windowed_head(q, k + shift, v, w)) < 1e-9
+    big = co.windowed_head(50.0 * q, 50.0 * k, v, w)   # scores in the thousands: no overflow
+    assert np.isfinite(big).all()
+
+
+def test_linearity_in_values():
+    N, d, w = 45, 7, 6
+    q, k = _rand((N, d), 58), _rand((N, d), 59)
+    v1, v2 = _rand((N, d), 60), _rand((N, d), 61)
+    for (name, a), (_, b), (_, c) in zip(_both_paths(q, k, 2.0 * v1 - 3.0 * v2, w),
+                                         _both_paths(q, k, v1, w), _both_paths(q, k, v2, w)):
+        assert max_abs(a, 2.0 * b - 3.0 * c) < 1e-12, name
+
+
+def test_linear_scale_invariance_identity_phi():
+    N, d = 30, 5
+    rng = np.random.default_rng(62)
+    fq, fk = rng.uniform(0.1, 2.0, (N, d)), rng.uniform(0.1, 2.0, (N, d))
+    v = _rand((N, d), 63)
+    base = co.linear_head(fq, fk, v, phi=co.PHI_IDENTITY)
+    rowscale = rng.uniform(0.5, 4.0, (N, 1))
+    assert max_abs(base, co.linear_head(fq * rowscale, fk, v, phi=co.PHI_IDENTITY)) < 1e-13
+    assert max_abs(base, co.linear_head(fq, 7.5 * fk, v, phi=co.PHI_IDENTITY)) < 1e-13
+
+
+def test_eps_enters_the_linear_denominator_only():
+    N, d = 12, 3
+    q, k, v = _rand((N, d), 64), _rand((N, d), 65), _rand((N, d), 66)
+    a = tw.phi_elu1(q) @ tw.phi_elu1(k).T
+    a = np.tril(a)
+    want = (a @ v) / (a.sum(1, keepdims=True) + 0.25)
+    for form in (co.LINEAR_QUADRATIC, co.LINEAR_RECURRENT):
+        assert max_abs(co.linear_head(q, k, v, eps=0.25, form=form), want) < 1e-13
+
+
+def test_degenerate_shapes_and_errors():
+    z = np.zeros((0, 4))
+    assert co.windowed_head(z, z, z, 3).shape == (0, 4)
+    assert co.linear_head(z, z, z).shape == (0, 4)
+    one = np.ones((1, 1))
+    assert co.windowed_head(one, one, 2 * one, 1)[0, 0] == 2.0
+    assert co.linear_head(one, one, 2 * one)[0, 0] == 2.0
+    with pytest.raises(RuntimeError):
+        co.windowed_head(one, one, one, 0)
+    with pytest.raises(RuntimeError):
+        co.attn_fwd(np.ones((1, 2, 3, 4)), np.ones((1, 2, 3, 4)), np.ones((1, 2, 3, 4)), 2, 3)
