@@ -1,0 +1,136 @@
+/*
+ * gformer.h - C ABI of the GFormer attention forward library for AMD MI355X (gfx950).
+ *
+ * One call computes one attention layer forward over all heads, as defined in
+ * "GFormer: Accelerating Large Language Models with Optimized Transformers on
+ * Gaudi Processors" (arXiv 2412.19829):
+ *
+ *   - Section III-A (overview, Fig. 4): Q, K, V are split along the head dimension.
+ *     Heads [0, n_sparse_heads) run windowed causal softmax attention, heads
+ *     [n_sparse_heads, H) run causal linear attention.  Head h's result is written to
+ *     head h's slot of `out`; the two groups are never summed.
+ *   - Section III-B + Eq. 1: windowed head.  Token i attends to the `window` tokens
+ *     ending at itself, j in [max(0, i-window+1), i]:
+ *         out_i = sum_j softmax_j(softmax_scale * q_i.k_j) v_j
+ *   - Section III-C, Algorithm 1: linear head.  With A_i = sum_{j<=i} phi(k_j) (x) v_j and
+ *     Z_i = sum_{j<=i} phi(k_j) (token i included before row i is read out):
+ *         out_i = phi(q_i)^T A_i / (phi(q_i).Z_i + eps)
+ *   - Section II-B: phi(x) = elu(x) + 1 (GF_PHI_ELU1).  GF_PHI_IDENTITY lets the caller
+ *     pass already-mapped, strictly positive features (e.g. random features).
+ *
+ * Conventions
+ *   - q, k, v, out are DEVICE pointers, 16-byte aligned, owned by the caller.  The library
+ *     never allocates, frees or keeps a pointer.  `out` must not alias an input.
+ *   - Element (b, h, n, c) of a tensor lives at base + b*stride[0] + h*stride[1] +
+ *     n*stride[2] + c (strides in elements, last dimension contiguous).  All-zero strides
+ *     mean dense [B, H, N, d].  The paper's [B, N, H, E] layout is stride = {N*H*d, d, H*d}.
+ *     Strides must be multiples of 8 elements (16-byte rows for bf16).
+ *   - `workspace` is a DEVICE pointer of at least gformer_attn_workspace_bytes(...) bytes,
+ *     256-byte aligned; may be NULL when that size is 0.  It holds the per-segment linear
+ *     attention states and is fully rewritten by every call that uses it.
+ *   - `hip_stream` is a hipStream_t (NULL = default stream).  The call enqueues kernels and
+ *     returns; it never synchronises.
+ *   - No exception crosses this boundary.  Argument errors are detected on the host before
+ *     anything is launched and reported through gf_status.
+ *   - Supported: d in {64, 128}; any N >= 0 (N == 0 or B*H == 0 is a no-op); any window >= 1
+ *     (window >= N is full causal attention); 0 <= n_sparse_heads <= H;
+ *     chunk in {0, 64, 128}.  Everything else returns GF_ERR_UNSUPPORTED; nothing falls
+ *     back silently.
+ */
+#ifndef GFORMER_H
+#define GFORMER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GF_OK = 0,
+  GF_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad enum, misaligned pointer/stride */
+  GF_ERR_UNSUPPORTED = 2, /* valid request outside what the kernels cover (d, chunk, ...)   */
+  GF_ERR_WORKSPACE = 3,   /* workspace missing or smaller than gformer_attn_workspace_bytes */
+  GF_ERR_DEVICE = 4       /* a HIP launch or runtime call failed                             */
+} gf_status;
+
+typedef enum { GF_F32 = 0, GF_BF16 = 1 } gf_dtype; /* q, k, v, out share one dtype */
+typedef enum { GF_PHI_ELU1 = 0, GF_PHI_IDENTITY = 1 } gf_phi;
+
+/* Which implementation runs.  GF_IMPL_AUTO picks the MFMA kernels for bf16 and the scalar
+ * fp32 kernels for fp32.  GF_IMPL_SCALAR forces the plain-FMA kernels (fp32 arithmetic on
+ * either storage type); GF_IMPL_MFMA with GF_F32 is GF_ERR_UNSUPPORTED. */
+typedef enum { GF_IMPL_AUTO = 0, GF_IMPL_SCALAR = 1, GF_IMPL_MFMA = 2 } gf_impl;
+
+typedef struct gformer_params {
+  uint32_t struct_size;   /* = sizeof(gformer_params); anything else is GF_ERR_INVALID_ARG   */
+  int32_t dtype;          /* gf_dtype                                                        */
+  int32_t phi;            /* gf_phi, linear heads only                                       */
+  int32_t n_sparse_heads; /* H0: heads [0,H0) windowed softmax, heads [H0,H) causal linear   */
+  int32_t chunk;          /* linear-attention chunk C in {64,128}; 0 = library picks         */
+  int32_t segment_len;    /* tokens per linear-attention segment (multiple of chunk);        */
+                          /* 0 = library picks.  Segments of one head run in parallel and    */
+                          /* are stitched with a prefix over their (A, Z) states.            */
+  int32_t impl;           /* gf_impl                                                         */
+  int32_t launch_mask;    /* 0 = everything.  Otherwise a bit set of GF_LAUNCH_*: only those */
+                          /* kernels are enqueued (profiling aid; the skipped stages' data   */
+                          /* is taken as already present in the workspace).                  */
+  float softmax_scale;    /* multiplies q.k on windowed heads; 1.0 when Q is pre-scaled      */
+  float eps;              /* added to the linear denominator; 0 follows Algorithm 1          */
+  int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3]; /* (b, h, n) element strides   */
+} gformer_params;
+
+enum {
+  GF_LAUNCH_WINDOWED = 1,     /* windowed softmax heads                                */
+  GF_LAUNCH_LINEAR_STATE = 2, /* per-segment (A, Z) sums + their exclusive prefix      */
+  GF_LAUNCH_LINEAR_MAIN = 4   /* linear heads read-out                                 */
+};
+
+/* What a call with these arguments would launch (host-only; touches no device). */
+typedef struct gformer_plan {
+  int32_t impl;             /* resolved gf_impl (SCALAR or MFMA)                        */
+  int32_t chunk;            /* resolved linear chunk C                                  */
+  int32_t segment_len;      /* resolved tokens per segment                              */
+  int32_t n_segments;       /* segments per linear head                                 */
+  int32_t windowed_blocks;  /* workgroups of the windowed kernel (0 if H0 == 0)         */
+  int32_t windowed_threads;
+  int32_t linear_blocks;    /* workgroups of the linear read-out kernel (0 if H0 == H)  */
+  int32_t linear_threads;
+  int32_t state_blocks;     /* workgroups of the segment-state kernel (0 if 1 segment)  */
+  int32_t reserved;
+  uint64_t workspace_bytes;
+} gformer_plan;
+
+/* Fills `p` with defaults: struct_size, dtype = GF_BF16, phi = GF_PHI_ELU1, H0 = 0, chunk,
+ * segment_len, impl, launch_mask = 0, softmax_scale = 1, eps = 0, dense strides. */
+void gformer_params_init(gformer_params* p);
+
+/* Bytes of device workspace gformer_attn_fwd needs for these arguments (0 if none).
+ * Returns 0 as well when the arguments are invalid; gformer_attn_fwd reports why. */
+size_t gformer_attn_workspace_bytes(int B, int H, int N, int d, int window,
+                                    const gformer_params* p);
+
+/* Validates like gformer_attn_fwd (pointers excepted) and describes the launch. */
+gf_status gformer_attn_plan(int B, int H, int N, int d, int window, const gformer_params* p,
+                            gformer_plan* plan);
+
+/* GFormer attention forward (section III; see the top of this file).
+ *   q, k, v : device, read-only, [B,H,N,d] through the strides in `p`
+ *   out     : device, written,   [B,H,N,d] through o_stride
+ * Enqueues on `hip_stream` and returns without synchronising.
+ * Errors: GF_ERR_INVALID_ARG / GF_ERR_UNSUPPORTED / GF_ERR_WORKSPACE before any launch;
+ * GF_ERR_DEVICE if HIP reports a launch failure. */
+gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int H,
+                           int N, int d, int window, const gformer_params* p, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
+const char* gformer_status_string(gf_status s);
+
+/* major*10000 + minor*100 + patch */
+int gformer_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GFORMER_H */

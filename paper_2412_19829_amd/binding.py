@@ -1,0 +1,184 @@
+"""Thin ctypes binding of libgformer_attn.so (see include/gformer.h).
+
+Argument marshalling only: every step of the attention forward runs in the HIP
+kernels behind the C ABI.  torch is used by callers for device memory and
+streams; this module only reads `data_ptr()` / shapes / strides from tensors.
+There is no CPU fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libgformer_attn.so")
+
+GF_OK, GF_ERR_INVALID_ARG, GF_ERR_UNSUPPORTED, GF_ERR_WORKSPACE, GF_ERR_DEVICE = range(5)
+GF_F32, GF_BF16 = 0, 1
+GF_PHI_ELU1, GF_PHI_IDENTITY = 0, 1
+GF_IMPL_AUTO, GF_IMPL_SCALAR, GF_IMPL_MFMA = 0, 1, 2
+GF_LAUNCH_WINDOWED, GF_LAUNCH_LINEAR_STATE, GF_LAUNCH_LINEAR_MAIN = 1, 2, 4
+
+EXPORTS = ("gformer_params_init", "gformer_attn_workspace_bytes", "gformer_attn_plan",
+           "gformer_attn_fwd", "gformer_status_string", "gformer_version")
+
+
+class GformerParams(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+                ("phi", ctypes.c_int32), ("n_sparse_heads", ctypes.c_int32),
+                ("chunk", ctypes.c_int32), ("segment_len", ctypes.c_int32),
+                ("impl", ctypes.c_int32), ("launch_mask", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float), ("eps", ctypes.c_float),
+                ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
+                ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3)]
+
+
+class GformerPlan(ctypes.Structure):
+    _fields_ = [("impl", ctypes.c_int32), ("chunk", ctypes.c_int32),
+                ("segment_len", ctypes.c_int32), ("n_segments", ctypes.c_int32),
+                ("windowed_blocks", ctypes.c_int32), ("windowed_threads", ctypes.c_int32),
+                ("linear_blocks", ctypes.c_int32), ("linear_threads", ctypes.c_int32),
+                ("state_blocks", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("workspace_bytes", ctypes.c_uint64)]
+
+    def as_dict(self) -> dict:
+        return {n: int(getattr(self, n)) for n, _ in self._fields_ if n != "reserved"}
+
+
+class GformerError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"gformer status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Load the shared library (built by paper_2412_19829_amd/build.py).  Fails loudly."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: run `python -m paper_2412_19829_amd.build` "
+                "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        P = ctypes.POINTER(GformerParams)
+        L.gformer_params_init.restype = None
+        L.gformer_params_init.argtypes = [P]
+        L.gformer_attn_workspace_bytes.restype = ctypes.c_size_t
+        L.gformer_attn_workspace_bytes.argtypes = [ctypes.c_int] * 5 + [P]
+        L.gformer_attn_plan.restype = ctypes.c_int
+        L.gformer_attn_plan.argtypes = [ctypes.c_int] * 5 + [P, ctypes.POINTER(GformerPlan)]
+        L.gformer_attn_fwd.restype = ctypes.c_int
+        L.gformer_attn_fwd.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 5 + \
+            [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.gformer_status_string.restype = ctypes.c_char_p
+        L.gformer_status_string.argtypes = [ctypes.c_int]
+        L.gformer_version.restype = ctypes.c_int
+        L.gformer_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def gformer_params_init() -> GformerParams:
+    p = GformerParams()
+    lib().gformer_params_init(ctypes.byref(p))
+    return p
+
+
+def make_params(dtype=GF_BF16, n_sparse_heads=0, phi=GF_PHI_ELU1, chunk=0, segment_len=0,
+                impl=GF_IMPL_AUTO, launch_mask=0, softmax_scale=1.0, eps=0.0,
+                q_stride=None, k_stride=None, v_stride=None, o_stride=None) -> GformerParams:
+    p = gformer_params_init()
+    p.dtype, p.n_sparse_heads, p.phi = int(dtype), int(n_sparse_heads), int(phi)
+    p.chunk, p.segment_len, p.impl, p.launch_mask = int(chunk), int(segment_len), int(impl), int(launch_mask)
+    p.softmax_scale, p.eps = float(softmax_scale), float(eps)
+    for name, val in (("q_stride", q_stride), ("k_stride", k_stride),
+                      ("v_stride", v_stride), ("o_stride", o_stride)):
+        if val is not None:
+            setattr(p, name, (ctypes.c_int64 * 3)(*[int(x) for x in val]))
+    return p
+
+
+def gformer_status_string(status: int) -> str:
+    return lib().gformer_status_string(int(status)).decode()
+
+
+def gformer_version() -> int:
+    return int(lib().gformer_version())
+
+
+def gformer_attn_workspace_bytes(B, H, N, d, window, params: GformerParams) -> int:
+    return int(lib().gformer_attn_workspace_bytes(B, H, N, d, window, ctypes.byref(params)))
+
+
+def gformer_attn_plan(B, H, N, d, window, params: GformerParams):
+    """Returns (status, GformerPlan)."""
+    plan = GformerPlan()
+    st = lib().gformer_attn_plan(B, H, N, d, window, ctypes.byref(params), ctypes.byref(plan))
+    return int(st), plan
+
+
+def gformer_attn_fwd_raw(q_ptr, k_ptr, v_ptr, out_ptr, B, H, N, d, window, params: GformerParams,
+                         workspace_ptr=0, workspace_bytes=0, stream=0) -> int:
+    """Direct call with integer device addresses; returns the gf_status."""
+    return int(lib().gformer_attn_fwd(
+        ctypes.c_void_p(q_ptr or None), ctypes.c_void_p(k_ptr or None),
+        ctypes.c_void_p(v_ptr or None), ctypes.c_void_p(out_ptr or None),
+        int(B), int(H), int(N), int(d), int(window), ctypes.byref(params),
+        ctypes.c_void_p(workspace_ptr or None), ctypes.c_size_t(int(workspace_bytes)),
+        ctypes.c_void_p(stream or None)))
+
+
+def _strides3(t):
+    s = t.stride()
+    if s[3] != 1 and t.shape[3] > 1:
+        raise ValueError("last dimension must be contiguous")
+    return (s[0], s[1], s[2])
+
+
+def gformer_attn_fwd(q, k, v, out, window: int, n_sparse_heads: int, *, phi=GF_PHI_ELU1,
+                     chunk=0, segment_len=0, impl=GF_IMPL_AUTO, launch_mask=0,
+                     softmax_scale=1.0, eps=0.0, workspace=None, stream: Optional[int] = None):
+    """GFormer attention forward on torch device tensors shaped [B, H, N, d] (any strides with
+    a contiguous last dimension, e.g. a permuted [B, N, H, d] buffer).
+
+    `out` is written in place and returned.  `workspace` is an optional uint8 device tensor
+    of at least gformer_attn_workspace_bytes(...) bytes; when omitted and one is needed it is
+    allocated with torch.empty (plumbing: the library itself never allocates).  The call is
+    asynchronous on `stream` (a raw hipStream_t; default: torch's current stream)."""
+    import torch
+
+    if not (q.is_cuda and k.is_cuda and v.is_cuda and out.is_cuda):
+        raise ValueError("q, k, v, out must be device tensors: there is no CPU path")
+    if not (q.dtype == k.dtype == v.dtype == out.dtype):
+        raise ValueError("q, k, v, out must share one dtype")
+    if q.dtype == torch.bfloat16:
+        dtype = GF_BF16
+    elif q.dtype == torch.float32:
+        dtype = GF_F32
+    else:
+        raise ValueError(f"unsupported dtype {q.dtype}")
+    if not (q.shape == k.shape == v.shape == out.shape) or q.dim() != 4:
+        raise ValueError("q, k, v, out must all be [B, H, N, d]")
+    B, H, N, d = (int(x) for x in q.shape)
+    params = make_params(dtype=dtype, n_sparse_heads=n_sparse_heads, phi=phi, chunk=chunk,
+                         segment_len=segment_len, impl=impl, launch_mask=launch_mask,
+                         softmax_scale=softmax_scale, eps=eps,
+                         q_stride=_strides3(q), k_stride=_strides3(k),
+                         v_stride=_strides3(v), o_stride=_strides3(out))
+    need = gformer_attn_workspace_bytes(B, H, N, d, window, params)
+    ws_ptr, ws_bytes = 0, 0
+    if need > 0:
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    st = gformer_attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                              B, H, N, d, window, params, ws_ptr, ws_bytes, stream)
+    if st != GF_OK:
+        raise GformerError(st, gformer_status_string(st))
+    return out

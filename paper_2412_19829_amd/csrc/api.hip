@@ -1,0 +1,211 @@
+// C ABI of the GFormer attention library: argument validation, launch planning, dispatch.
+// Everything up to the first launch is plain host code and can be exercised without a GPU.
+#include "../../include/gformer.h"
+
+#include <string.h>
+
+#include "common.hpp"
+
+namespace gformer {
+
+int mfma_linear_threads(int d) { return d == 128 ? 512 : 256; }
+
+namespace {
+
+struct Resolved {
+  gformer_plan plan;
+  int64_t qs[3], ks[3], vs[3], os[3];
+};
+
+bool strides_all_zero(const int64_t* s) { return s[0] == 0 && s[1] == 0 && s[2] == 0; }
+
+void dense_strides(int64_t* s, int H, int N, int d) {
+  s[0] = (int64_t)H * N * d;
+  s[1] = (int64_t)N * d;
+  s[2] = d;
+}
+
+gf_status check_strides(const int64_t* in, int64_t* out, int H, int N, int d) {
+  if (strides_all_zero(in)) {
+    dense_strides(out, H, N, d);
+    return GF_OK;
+  }
+  for (int i = 0; i < 3; ++i) {
+    if (in[i] < 0 || (in[i] % 8) != 0) return GF_ERR_INVALID_ARG;
+    out[i] = in[i];
+  }
+  if (N > 1 && in[2] < d) return GF_ERR_INVALID_ARG;  // rows would overlap
+  return GF_OK;
+}
+
+int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// Shared by gformer_attn_plan, gformer_attn_workspace_bytes and gformer_attn_fwd.
+gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* p, Resolved* r) {
+  memset(r, 0, sizeof(*r));
+  if (!p) return GF_ERR_INVALID_ARG;
+  if (p->struct_size != sizeof(gformer_params)) return GF_ERR_INVALID_ARG;
+  if (B < 0 || H < 0 || N < 0 || d < 1 || window < 1) return GF_ERR_INVALID_ARG;
+  if (p->dtype != GF_F32 && p->dtype != GF_BF16) return GF_ERR_INVALID_ARG;
+  if (p->phi != GF_PHI_ELU1 && p->phi != GF_PHI_IDENTITY) return GF_ERR_INVALID_ARG;
+  if (p->impl != GF_IMPL_AUTO && p->impl != GF_IMPL_SCALAR && p->impl != GF_IMPL_MFMA)
+    return GF_ERR_INVALID_ARG;
+  if (p->n_sparse_heads < 0 || p->n_sparse_heads > H) return GF_ERR_INVALID_ARG;
+  if (p->chunk < 0 || p->segment_len < 0) return GF_ERR_INVALID_ARG;
+  if (p->launch_mask < 0 || p->launch_mask > 7) return GF_ERR_INVALID_ARG;
+  if (!(p->softmax_scale == p->softmax_scale) || !(p->eps >= 0.f)) return GF_ERR_INVALID_ARG;
+  if (B > 65535 || H > 65535) return GF_ERR_UNSUPPORTED;  // grid y/z limits
+  gf_status st;
+  if ((st = check_strides(p->q_stride, r->qs, H, N, d)) != GF_OK) return st;
+  if ((st = check_strides(p->k_stride, r->ks, H, N, d)) != GF_OK) return st;
+  if ((st = check_strides(p->v_stride, r->vs, H, N, d)) != GF_OK) return st;
+  if ((st = check_strides(p->o_stride, r->os, H, N, d)) != GF_OK) return st;
+  if (d != 64 && d != 128) return GF_ERR_UNSUPPORTED;
+
+  int impl = p->impl;
+  if (impl == GF_IMPL_AUTO) impl = (p->dtype == GF_BF16) ? GF_IMPL_MFMA : GF_IMPL_SCALAR;
+  if (impl == GF_IMPL_MFMA && p->dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
+  if (p->chunk != 0 && p->chunk != 64 && p->chunk != 128) return GF_ERR_UNSUPPORTED;
+
+  gformer_plan& pl = r->plan;
+  pl.impl = impl;
+  const int H0 = p->n_sparse_heads, H1 = H - H0;
+  const long heads_lin = (long)B * H1;
+  if (impl == GF_IMPL_SCALAR) {
+    pl.chunk = 32;  // fixed by the fp32 kernel
+    pl.segment_len = N;
+    pl.n_segments = 1;
+    if (p->segment_len != 0 && p->segment_len < N) return GF_ERR_UNSUPPORTED;
+    pl.windowed_threads = kScalarThreads;
+    pl.windowed_blocks = (H0 > 0 && N > 0) ? B * H0 * ((N + kScalarWindowRows - 1) / kScalarWindowRows) : 0;
+    pl.linear_threads = kScalarThreads;
+    pl.linear_blocks = (H1 > 0 && N > 0) ? (int)heads_lin : 0;
+    pl.state_blocks = 0;
+    pl.workspace_bytes = 0;
+    return GF_OK;
+  }
+  pl.chunk = p->chunk ? p->chunk : 64;
+  int seg = p->segment_len;
+  if (seg != 0) {
+    if (seg % pl.chunk != 0) return GF_ERR_INVALID_ARG;
+  } else {
+    // Enough workgroups to cover the 256 compute units about twice, but segments no shorter
+    // than 8 chunks so the per-segment state traffic (d*d fp32) stays a small share.
+    const long target_blocks = 512;
+    const int min_seg = 8 * pl.chunk;
+    long nseg = heads_lin > 0 ? (target_blocks + heads_lin - 1) / heads_lin : 1;
+    long max_seg = N / min_seg;
+    if (nseg > max_seg) nseg = max_seg;
+    if (nseg < 1) nseg = 1;
+    seg = round_up((int)((N + nseg - 1) / nseg), pl.chunk);
+    if (seg < pl.chunk) seg = pl.chunk;
+  }
+  pl.segment_len = seg;
+  pl.n_segments = N > 0 ? (N + seg - 1) / seg : 1;
+  pl.windowed_threads = kMfmaWindowThreads;
+  pl.windowed_blocks = (H0 > 0 && N > 0) ? B * H0 * ((N + kMfmaWindowRows - 1) / kMfmaWindowRows) : 0;
+  pl.linear_threads = mfma_linear_threads(d);
+  pl.linear_blocks = (H1 > 0 && N > 0) ? (int)(heads_lin * pl.n_segments) : 0;
+  pl.state_blocks = (pl.n_segments > 1 && H1 > 0) ? (int)(heads_lin * (pl.n_segments - 1)) : 0;
+  pl.workspace_bytes = pl.state_blocks > 0
+      ? (uint64_t)heads_lin * pl.n_segments * ((uint64_t)d * d + d) * sizeof(float) : 0;
+  return GF_OK;
+}
+
+}  // namespace
+}  // namespace gformer
+
+using namespace gformer;
+
+extern "C" {
+
+void gformer_params_init(gformer_params* p) {
+  if (!p) return;
+  memset(p, 0, sizeof(*p));
+  p->struct_size = sizeof(gformer_params);
+  p->dtype = GF_BF16;
+  p->phi = GF_PHI_ELU1;
+  p->impl = GF_IMPL_AUTO;
+  p->softmax_scale = 1.0f;
+  p->eps = 0.0f;
+}
+
+size_t gformer_attn_workspace_bytes(int B, int H, int N, int d, int window,
+                                    const gformer_params* p) {
+  Resolved r;
+  if (resolve(B, H, N, d, window, p, &r) != GF_OK) return 0;
+  return (size_t)r.plan.workspace_bytes;
+}
+
+gf_status gformer_attn_plan(int B, int H, int N, int d, int window, const gformer_params* p,
+                            gformer_plan* plan) {
+  if (!plan) return GF_ERR_INVALID_ARG;
+  Resolved r;
+  gf_status st = resolve(B, H, N, d, window, p, &r);
+  *plan = r.plan;
+  return st;
+}
+
+gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int H,
+                           int N, int d, int window, const gformer_params* p, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  Resolved r;
+  gf_status st = resolve(B, H, N, d, window, p, &r);
+  if (st != GF_OK) return st;
+  if (B == 0 || H == 0 || N == 0) return GF_OK;
+  if (!q || !k || !v || !out) return GF_ERR_INVALID_ARG;
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15u) return GF_ERR_INVALID_ARG;
+  if (out == q || out == k || out == v) return GF_ERR_INVALID_ARG;
+  if (r.plan.workspace_bytes > 0) {
+    if (!workspace || workspace_bytes < r.plan.workspace_bytes) return GF_ERR_WORKSPACE;
+    if ((uintptr_t)workspace & 255u) return GF_ERR_INVALID_ARG;
+  }
+
+  AttnArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = TensorView{q, r.qs[0], r.qs[1], r.qs[2]};
+  a.k = TensorView{k, r.ks[0], r.ks[1], r.ks[2]};
+  a.v = TensorView{v, r.vs[0], r.vs[1], r.vs[2]};
+  a.out = out;
+  a.osb = r.os[0]; a.osh = r.os[1]; a.osn = r.os[2];
+  a.B = B; a.H = H; a.N = N; a.d = d;
+  a.window = window;
+  a.H0 = p->n_sparse_heads;
+  a.phi = p->phi;
+  a.scale = p->softmax_scale;
+  a.eps = p->eps;
+  a.chunk = r.plan.chunk;
+  a.segment_len = r.plan.segment_len;
+  a.n_segments = r.plan.n_segments;
+  a.ws_states = r.plan.workspace_bytes > 0 ? reinterpret_cast<float*>(workspace) : nullptr;
+
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  const int mask = p->launch_mask ? p->launch_mask : 7;
+  const bool bf16 = p->dtype == GF_BF16;
+  hipError_t e = hipSuccess;
+  if (r.plan.impl == GF_IMPL_SCALAR) {
+    if ((mask & GF_LAUNCH_WINDOWED) && e == hipSuccess) e = launch_windowed_scalar(a, bf16, s);
+    if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_scalar(a, bf16, s);
+  } else {
+    // Linear heads first: their workgroups run longest, the windowed ones fill in behind.
+    if ((mask & GF_LAUNCH_LINEAR_STATE) && e == hipSuccess) e = launch_linear_state_mfma(a, s);
+    if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_main_mfma(a, s);
+    if ((mask & GF_LAUNCH_WINDOWED) && e == hipSuccess) e = launch_windowed_mfma(a, s);
+  }
+  return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
+}
+
+const char* gformer_status_string(gf_status s) {
+  switch (s) {
+    case GF_OK: return "ok";
+    case GF_ERR_INVALID_ARG: return "invalid argument";
+    case GF_ERR_UNSUPPORTED: return "unsupported configuration";
+    case GF_ERR_WORKSPACE: return "workspace missing or too small";
+    case GF_ERR_DEVICE: return "HIP launch or runtime failure";
+  }
+  return "unknown status";
+}
+
+int gformer_version(void) { return 100; }
+
+}  // extern "C"

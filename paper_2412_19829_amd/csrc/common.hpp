@@ -1,0 +1,76 @@
+// Shared host/device declarations of the GFormer attention library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gformer {
+
+// One [B,H,N,d] tensor: element (b,h,n,c) at base + b*sb + h*sh + n*sn + c (elements).
+struct TensorView {
+  const void* base;
+  int64_t sb, sh, sn;
+};
+
+// Everything a kernel needs to know about one attention call.
+struct AttnArgs {
+  TensorView q, k, v;
+  void* out;
+  int64_t osb, osh, osn;
+  int B, H, N, d;
+  int window;
+  int H0;            // heads [0,H0) windowed, [H0,H) linear
+  int phi;           // gf_phi
+  float scale;       // softmax scale (windowed heads)
+  float eps;         // linear denominator epsilon
+  // linear-attention segmentation
+  int chunk;         // tokens per chunk
+  int segment_len;   // tokens per segment (multiple of chunk)
+  int n_segments;    // segments per head
+  float* ws_states;  // [B*H1, n_segments, d*d + d] fp32: per-segment sums, then exclusive prefixes
+};
+
+// bf16 storage helpers (round to nearest even on store).
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Storage;
+template <> struct Storage<float> {
+  static __device__ __forceinline__ float load(const void* p, int64_t i) {
+    return reinterpret_cast<const float*>(p)[i];
+  }
+  static __device__ __forceinline__ void store(void* p, int64_t i, float v) {
+    reinterpret_cast<float*>(p)[i] = v;
+  }
+};
+template <> struct Storage<uint16_t> {  // bf16 bit patterns
+  static __device__ __forceinline__ float load(const void* p, int64_t i) {
+    return bf16_bits_to_float(reinterpret_cast<const uint16_t*>(p)[i]);
+  }
+  static __device__ __forceinline__ void store(void* p, int64_t i, float v) {
+    reinterpret_cast<uint16_t*>(p)[i] = float_to_bf16_bits(v);
+  }
+};
+
+// Host-side launchers, one per kernel family.  Each returns the hipError_t of its launch.
+hipError_t launch_windowed_scalar(const AttnArgs& a, bool bf16, hipStream_t s);
+hipError_t launch_linear_scalar(const AttnArgs& a, bool bf16, hipStream_t s);
+hipError_t launch_windowed_mfma(const AttnArgs& a, hipStream_t s);
+hipError_t launch_linear_state_mfma(const AttnArgs& a, hipStream_t s);
+hipError_t launch_linear_main_mfma(const AttnArgs& a, hipStream_t s);
+
+// Launch geometry shared by the planner and the launchers.
+constexpr int kScalarWindowRows = 16;   // query rows per workgroup, scalar windowed kernel
+constexpr int kScalarThreads = 256;
+constexpr int kMfmaWindowRows = 128;    // query rows per workgroup, MFMA windowed kernel
+constexpr int kMfmaWindowThreads = 256;
+int mfma_linear_threads(int d);
+
+}  // namespace gformer

@@ -1,0 +1,242 @@
+// Plain-FMA kernels: fp32 arithmetic on fp32 or bf16 storage.  They are the fp32 path of the
+// library (reduced-precision operands never reach a matrix core here) and are written for
+// clarity; the MFMA kernels carry the bf16 performance path.
+#include "common.hpp"
+
+namespace gformer {
+
+namespace {
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+__device__ __forceinline__ float lane_bcast(float x, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
+}
+
+// Feature map of section II-B: phi(x) = elu(x) + 1.
+__device__ __forceinline__ float feature_map(float x, int phi) {
+  if (phi != 0) return x;
+  return x > 0.f ? x + 1.f : expf(x);
+}
+
+// ---------------------------------------------------------------------------------------
+// Windowed causal softmax head (section III-B, Eq. 1).  One wave owns one query at a time;
+// lanes own keys for the scores and value columns for the weighted sum.
+// grid = (ceil(N / kScalarWindowRows), H0, B), block = 256.
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kScalarThreads) void windowed_scalar_kernel(AttnArgs a) {
+  constexpr int CPL = D / 64;  // value columns per lane
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int64_t qoff = b * a.q.sb + h * a.q.sh;
+  const int64_t koff = b * a.k.sb + h * a.k.sh;
+  const int64_t voff = b * a.v.sb + h * a.v.sh;
+  const int64_t ooff = b * a.osb + h * a.osh;
+  constexpr int rows_per_wave = kScalarWindowRows / (kScalarThreads / 64);
+
+  for (int r = 0; r < rows_per_wave; ++r) {
+    const int i = blockIdx.x * kScalarWindowRows + wave * rows_per_wave + r;
+    if (i >= a.N) break;  // uniform per wave
+    float qreg[CPL];
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) qreg[cc] = Storage<T>::load(a.q.base, qoff + i * a.q.sn + cc * 64 + lane);
+    const int lo = max(0, i - a.window + 1);
+    float m = -INFINITY, l = 0.f;
+    float acc[CPL];
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) acc[cc] = 0.f;
+
+    for (int j0 = lo; j0 <= i; j0 += 64) {
+      const int j = j0 + lane;
+      const bool valid = j <= i;
+      float s = 0.f;
+      {
+        // lanes past the diagonal read row i again (in bounds) and are masked below
+        const int64_t kr = koff + (int64_t)min(j, i) * a.k.sn;
+#pragma unroll
+        for (int cc = 0; cc < CPL; ++cc) {
+#pragma unroll
+          for (int c = 0; c < 64; ++c)
+            s = fmaf(lane_bcast(qreg[cc], c), Storage<T>::load(a.k.base, kr + cc * 64 + c), s);
+        }
+      }
+      s = valid ? s * a.scale : -INFINITY;
+      const float m_new = fmaxf(m, wave_max(s));  // finite: key j0 is always valid
+      const float alpha = expf(m - m_new);        // exp(-inf) = 0 on the first tile
+      const float p = valid ? expf(s - m_new) : 0.f;
+      l = l * alpha + wave_sum(p);
+#pragma unroll
+      for (int cc = 0; cc < CPL; ++cc) acc[cc] *= alpha;
+      const int cnt = min(64, i - j0 + 1);
+      for (int jj = 0; jj < cnt; ++jj) {
+        const float pj = __shfl(p, jj, 64);
+        const int64_t vr = voff + (int64_t)(j0 + jj) * a.v.sn;
+#pragma unroll
+        for (int cc = 0; cc < CPL; ++cc)
+          acc[cc] = fmaf(pj, Storage<T>::load(a.v.base, vr + cc * 64 + lane), acc[cc]);
+      }
+      m = m_new;
+    }
+    const float inv = 1.f / l;
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc)
+      Storage<T>::store(a.out, ooff + i * a.osn + cc * 64 + lane, acc[cc] * inv);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Causal linear attention head (Algorithm 1), chunked: inside a chunk of CH tokens the masked
+// quadratic form, across chunks the carried state A (D x D) and Z (D), all fp32 in LDS.
+// One workgroup walks one head from token 0 to N-1.  grid = (H1, B), block = 256.
+// ---------------------------------------------------------------------------------------
+constexpr int kScalarChunk = 32;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kScalarThreads) void linear_scalar_kernel(AttnArgs a) {
+  constexpr int CH = kScalarChunk;
+  constexpr int G = kScalarThreads / D;        // thread groups along the non-e axis
+  constexpr int NUM_T = CH / G;                // tokens per thread in the read-out
+  constexpr int UPD_C = D / G;                 // state rows per thread in the update
+  extern __shared__ float smem[];
+  float* fq = smem;                 // [CH][D]
+  float* fk = fq + CH * D;          // [CH][D]
+  float* vv = fk + CH * D;          // [CH][D]
+  float* S = vv + CH * D;           // [D][D]   A of Algorithm 1, rows = feature c, cols = e
+  float* z = S + D * D;             // [D]
+  float* am = z + D;                // [CH][CH+1] masked feature products
+  float* den = am + CH * (CH + 1);  // [CH]
+
+  const int tid = threadIdx.x;
+  const int h = a.H0 + blockIdx.x, b = blockIdx.y;
+  const int64_t qoff = b * a.q.sb + h * a.q.sh;
+  const int64_t koff = b * a.k.sb + h * a.k.sh;
+  const int64_t voff = b * a.v.sb + h * a.v.sh;
+  const int64_t ooff = b * a.osb + h * a.osh;
+
+  for (int x = tid; x < D * D; x += kScalarThreads) S[x] = 0.f;
+  if (tid < D) z[tid] = 0.f;
+
+  const int e = tid % D;
+  const int g = tid / D;
+
+  for (int t0 = 0; t0 < a.N; t0 += CH) {
+    __syncthreads();  // previous chunk fully consumed (and the zero fill above is visible)
+    for (int x = tid; x < CH * D; x += kScalarThreads) {
+      const int t = x / D, c = x % D;
+      const int n = t0 + t;
+      float qv = 0.f, kv = 0.f, v_ = 0.f;
+      if (n < a.N) {
+        qv = feature_map(Storage<T>::load(a.q.base, qoff + (int64_t)n * a.q.sn + c), a.phi);
+        kv = feature_map(Storage<T>::load(a.k.base, koff + (int64_t)n * a.k.sn + c), a.phi);
+        v_ = Storage<T>::load(a.v.base, voff + (int64_t)n * a.v.sn + c);
+      }
+      fq[x] = qv; fk[x] = kv; vv[x] = v_;   // rows past N hold zeros and contribute nothing
+    }
+    __syncthreads();
+    // masked products a[t][u] = phi(q_t).phi(k_u) for u <= t
+    for (int x = tid; x < CH * CH; x += kScalarThreads) {
+      const int t = x / CH, u = x % CH;
+      float s = 0.f;
+      if (u <= t) {
+        for (int c = 0; c < D; ++c) s = fmaf(fq[t * D + c], fk[u * D + c], s);
+      }
+      am[t * (CH + 1) + u] = s;
+    }
+    __syncthreads();
+    if (tid < CH) {
+      float s = 0.f;
+      for (int u = 0; u <= tid; ++u) s += am[tid * (CH + 1) + u];
+      float zz = 0.f;
+      for (int c = 0; c < D; ++c) zz = fmaf(fq[tid * D + c], z[c], zz);
+      den[tid] = s + zz + a.eps;
+    }
+    // read-out: num[t][e] = sum_u a[t][u] v[u][e] + sum_c phi(q_t)[c] A[c][e]
+    float num[NUM_T];
+#pragma unroll
+    for (int i = 0; i < NUM_T; ++i) num[i] = 0.f;
+    for (int c = 0; c < D; ++c) {
+      const float sce = S[c * D + e];
+#pragma unroll
+      for (int i = 0; i < NUM_T; ++i) num[i] = fmaf(fq[(g + G * i) * D + c], sce, num[i]);
+    }
+    for (int u = 0; u < CH; ++u) {
+      const float vue = vv[u * D + e];
+#pragma unroll
+      for (int i = 0; i < NUM_T; ++i) num[i] = fmaf(am[(g + G * i) * (CH + 1) + u], vue, num[i]);
+    }
+    __syncthreads();  // den ready; all reads of S for this chunk done
+#pragma unroll
+    for (int i = 0; i < NUM_T; ++i) {
+      const int n = t0 + g + G * i;
+      if (n < a.N) Storage<T>::store(a.out, ooff + (int64_t)n * a.osn + e, num[i] / den[g + G * i]);
+    }
+    // state update: A[c][e] += sum_t phi(k_t)[c] v_t[e];  Z[c] += sum_t phi(k_t)[c]
+    float vcol[CH];
+#pragma unroll
+    for (int t = 0; t < CH; ++t) vcol[t] = vv[t * D + e];
+    for (int i = 0; i < UPD_C; ++i) {
+      const int c = g + G * i;
+      float s = S[c * D + e];
+#pragma unroll
+      for (int t = 0; t < CH; ++t) s = fmaf(fk[t * D + c], vcol[t], s);
+      S[c * D + e] = s;
+    }
+    if (tid < D) {
+      float s = z[tid];
+      for (int t = 0; t < CH; ++t) s += fk[t * D + tid];
+      z[tid] = s;
+    }
+  }
+}
+
+template <int D> size_t linear_scalar_smem() {
+  constexpr int CH = kScalarChunk;
+  return sizeof(float) * (size_t)(3 * CH * D + D * D + D + CH * (CH + 1) + CH);
+}
+
+}  // namespace
+
+hipError_t launch_windowed_scalar(const AttnArgs& a, bool bf16, hipStream_t s) {
+  if (a.H0 <= 0 || a.N <= 0 || a.B <= 0) return hipSuccess;
+  dim3 grid((a.N + kScalarWindowRows - 1) / kScalarWindowRows, a.H0, a.B);
+  dim3 block(kScalarThreads);
+  if (a.d == 64) {
+    if (bf16) windowed_scalar_kernel<uint16_t, 64><<<grid, block, 0, s>>>(a);
+    else windowed_scalar_kernel<float, 64><<<grid, block, 0, s>>>(a);
+  } else {
+    if (bf16) windowed_scalar_kernel<uint16_t, 128><<<grid, block, 0, s>>>(a);
+    else windowed_scalar_kernel<float, 128><<<grid, block, 0, s>>>(a);
+  }
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t launch_linear_scalar_t(const AttnArgs& a, hipStream_t s) {
+  const size_t smem = linear_scalar_smem<D>();
+  auto kern = linear_scalar_kernel<T, D>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e != hipSuccess) return e;
+  dim3 grid(a.H - a.H0, a.B);
+  kern<<<grid, dim3(kScalarThreads), smem, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_linear_scalar(const AttnArgs& a, bool bf16, hipStream_t s) {
+  if (a.H - a.H0 <= 0 || a.N <= 0 || a.B <= 0) return hipSuccess;
+  if (a.d == 64)
+    return bf16 ? launch_linear_scalar_t<uint16_t, 64>(a, s) : launch_linear_scalar_t<float, 64>(a, s);
+  return bf16 ? launch_linear_scalar_t<uint16_t, 128>(a, s) : launch_linear_scalar_t<float, 128>(a, s);
+}
+
+}  // namespace gformer

@@ -1,0 +1,138 @@
+"""Host-side behaviour of the C ABI (no GPU needed): the library loads, exports every symbol
+the header declares, validates arguments before any launch, and plans launches sensibly."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2412_19829_amd import binding as gb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _header_functions():
+    text = open(os.path.join(ROOT, "include", "gformer.h"), encoding="utf-8").read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gformer_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = gb.lib()
+    names = _header_functions()
+    assert set(names) == set(gb.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_status_strings():
+    assert gb.gformer_version() >= 100
+    seen = {gb.gformer_status_string(s) for s in range(5)}
+    assert len(seen) == 5 and "ok" in seen
+    assert "unknown" in gb.gformer_status_string(99)
+
+
+def test_params_init_defaults_and_struct_size():
+    p = gb.gformer_params_init()
+    assert p.struct_size == ctypes.sizeof(gb.GformerParams)
+    assert p.dtype == gb.GF_BF16 and p.phi == gb.GF_PHI_ELU1 and p.n_sparse_heads == 0
+    assert p.softmax_scale == 1.0 and p.eps == 0.0 and p.launch_mask == 0
+    assert list(p.q_stride) == [0, 0, 0] and list(p.o_stride) == [0, 0, 0]
+
+
+def _plan(B, H, N, d, w, **kw):
+    st, plan = gb.gformer_attn_plan(B, H, N, d, w, gb.make_params(**kw))
+    return st, plan.as_dict()
+
+
+def test_plan_headline_config():
+    st, pl = _plan(4, 32, 8192, 128, 256, n_sparse_heads=6)
+    assert st == gb.GF_OK and pl["impl"] == gb.GF_IMPL_MFMA
+    assert pl["chunk"] in (64, 128) and pl["segment_len"] % pl["chunk"] == 0
+    assert pl["n_segments"] * pl["segment_len"] >= 8192 > (pl["n_segments"] - 1) * pl["segment_len"]
+    assert pl["windowed_blocks"] == 4 * 6 * (8192 // 128)
+    assert pl["linear_blocks"] == 4 * 26 * pl["n_segments"]
+    want_ws = 4 * 26 * pl["n_segments"] * (128 * 128 + 128) * 4 if pl["n_segments"] > 1 else 0
+    assert pl["workspace_bytes"] == want_ws
+    assert gb.gformer_attn_workspace_bytes(4, 32, 8192, 128, 256, gb.make_params(n_sparse_heads=6)) == want_ws
+
+
+def test_plan_modes_and_overrides():
+    st, pl = _plan(1, 1, 256, 64, 32, dtype=gb.GF_F32, n_sparse_heads=1)
+    assert st == gb.GF_OK and pl["impl"] == gb.GF_IMPL_SCALAR and pl["workspace_bytes"] == 0
+    assert pl["linear_blocks"] == 0 and pl["windowed_blocks"] == 16
+    st, pl = _plan(1, 32, 32768, 128, 512, n_sparse_heads=0, chunk=128, segment_len=1024)
+    assert st == gb.GF_OK and pl["chunk"] == 128 and pl["segment_len"] == 1024 and pl["n_segments"] == 32
+    assert pl["state_blocks"] == 32 * 31 and pl["windowed_blocks"] == 0
+    st, pl = _plan(1, 2, 100, 64, 8, n_sparse_heads=0, segment_len=64)
+    assert st == gb.GF_OK and pl["n_segments"] == 2
+    st, pl = _plan(1, 2, 100, 64, 8, n_sparse_heads=2)
+    assert st == gb.GF_OK and pl["linear_blocks"] == 0 and pl["workspace_bytes"] == 0
+    st, pl = _plan(2, 4, 0, 64, 8)
+    assert st == gb.GF_OK and pl["linear_blocks"] == 0 and pl["windowed_blocks"] == 0
+
+
+@pytest.mark.parametrize("args,kw,want", [
+    ((1, 1, 16, 64, 0), {}, gb.GF_ERR_INVALID_ARG),               # window < 1
+    ((-1, 1, 16, 64, 4), {}, gb.GF_ERR_INVALID_ARG),
+    ((1, 1, -5, 64, 4), {}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"n_sparse_heads": 3}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"n_sparse_heads": -1}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"dtype": 7}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"phi": 2}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"impl": 9}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"eps": -1.0}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"eps": float("nan")}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"launch_mask": 8}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"q_stride": (1024, 512, 60)}, gb.GF_ERR_INVALID_ARG),   # not 16-byte rows
+    ((1, 2, 16, 64, 4), {"o_stride": (2048, 1024, 32)}, gb.GF_ERR_INVALID_ARG),  # rows overlap
+    ((1, 2, 256, 64, 4), {"chunk": 64, "segment_len": 96}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 96, 4), {}, gb.GF_ERR_UNSUPPORTED),               # head size
+    ((1, 2, 16, 64, 4), {"chunk": 48}, gb.GF_ERR_UNSUPPORTED),
+    ((1, 2, 16, 64, 4), {"chunk": 256}, gb.GF_ERR_UNSUPPORTED),
+    ((1, 2, 16, 64, 4), {"dtype": gb.GF_F32, "impl": gb.GF_IMPL_MFMA}, gb.GF_ERR_UNSUPPORTED),
+    ((1, 2, 256, 64, 4), {"dtype": gb.GF_F32, "segment_len": 64}, gb.GF_ERR_UNSUPPORTED),
+    ((70000, 2, 16, 64, 4), {}, gb.GF_ERR_UNSUPPORTED),
+])
+def test_argument_errors_are_reported_by_plan_and_fwd(args, kw, want):
+    p = gb.make_params(**kw)
+    st, _ = gb.gformer_attn_plan(*args, p)
+    assert st == want
+    assert gb.gformer_attn_workspace_bytes(*args, p) == 0
+    # the forward call rejects the same arguments on the host, before touching any device
+    assert gb.gformer_attn_fwd_raw(0x1000, 0x2000, 0x3000, 0x4000, *args, p) == want
+
+
+def test_fwd_pointer_checks_happen_on_the_host():
+    p = gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1)
+    a = (1, 1, 16, 64, 4)
+    assert gb.gformer_attn_fwd_raw(0, 0x2000, 0x3000, 0x4000, *a, p) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_attn_fwd_raw(0x1000, 0x2000, 0x3000, 0, *a, p) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_attn_fwd_raw(0x1008, 0x2000, 0x3000, 0x4000, *a, p) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_attn_fwd_raw(0x1000, 0x2000, 0x3000, 0x2000, *a, p) == gb.GF_ERR_INVALID_ARG  # alias
+    # empty problems are a no-op even with null pointers
+    assert gb.gformer_attn_fwd_raw(0, 0, 0, 0, 1, 1, 0, 64, 4, p) == gb.GF_OK
+    assert gb.gformer_attn_fwd_raw(0, 0, 0, 0, 0, 1, 16, 64, 4, p) == gb.GF_OK
+    bad = gb.make_params()
+    bad.struct_size = 12
+    assert gb.gformer_attn_fwd_raw(0x1000, 0x2000, 0x3000, 0x4000, *a, bad) == gb.GF_ERR_INVALID_ARG
+    assert gb.lib().gformer_attn_plan(1, 1, 16, 64, 4, None, ctypes.byref(gb.GformerPlan())) == gb.GF_ERR_INVALID_ARG
+
+
+def test_workspace_is_required_when_segments_are_used():
+    p = gb.make_params(n_sparse_heads=0, chunk=64, segment_len=64)
+    a = (1, 2, 256, 64, 8)
+    need = gb.gformer_attn_workspace_bytes(*a, p)
+    assert need == 1 * 2 * 4 * (64 * 64 + 64) * 4
+    assert gb.gformer_attn_fwd_raw(0x1000, 0x2000, 0x3000, 0x4000, *a, p, 0, 0) == gb.GF_ERR_WORKSPACE
+    assert gb.gformer_attn_fwd_raw(0x1000, 0x2000, 0x3000, 0x4000, *a, p, 0x10000, need - 1) == gb.GF_ERR_WORKSPACE
+    assert gb.gformer_attn_fwd_raw(0x1000, 0x2000, 0x3000, 0x4000, *a, p, 0x10010, need) == gb.GF_ERR_INVALID_ARG
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 1, 8, 64)
+    with pytest.raises(ValueError):
+        gb.gformer_attn_fwd(x, x, x, torch.empty_like(x), 4, 1)

@@ -1,0 +1,225 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element, on
+seeded inputs.  Tolerances: fp32 mode max-abs <= 1e-5; bf16 mode per-row relative L2 <= 2e-2."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+from oracle import cpu_oracle as co
+from paper_2412_19829_amd import binding as gb
+from paper_2412_19829_amd import inputs as gi
+from tests.gpu_util import BF16_ROW_REL_L2, F32_MAX_ABS, run_gpu
+from tests.helpers import max_abs, row_rel_l2
+
+pytestmark = pytest.mark.gpu
+
+SCALAR, MFMA = gb.GF_IMPL_SCALAR, gb.GF_IMPL_MFMA
+
+
+def check(gpu, ref, dtype, what=""):
+    assert np.isfinite(gpu).all(), f"non-finite output {what}"
+    if dtype == "f32":
+        err = max_abs(gpu, ref)
+        assert err <= F32_MAX_ABS, f"{what}: max-abs {err:.3e}"
+    else:
+        rel = row_rel_l2(gpu, ref)
+        worst = float(rel.max())
+        assert worst <= BF16_ROW_REL_L2, f"{what}: worst row rel-L2 {worst:.3e} at {np.unravel_index(rel.argmax(), rel.shape)}"
+
+
+def synth(B, H, N, d, dtype, seed, q_prescaled=True, sigma=1.0, **kw):
+    wl = gi.Workload("case", B, H, N, d, 1, dtype, seed, sigma=sigma, q_prescaled=q_prescaled, **kw)
+    return gi.make_qkv(wl)
+
+
+def oracle(q, k, v, window, H0, **kw):
+    big = q.shape[2] > 2048
+    return co.attn_fwd(q, k, v, window, H0,
+                       linear_form=co.LINEAR_RECURRENT if big else co.LINEAR_QUADRATIC, **kw)
+
+
+# ---------------------------------------------------------------------------------------
+# the benchmark contract's small configurations, in full
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("H0", [1, 0])
+def test_tiny_f32(H0):
+    wl = gi.WORKLOADS["tiny_f32"]
+    q, k, v = gi.make_qkv(wl)
+    got = run_gpu(q, k, v, "f32", wl.window, H0)
+    check(got, oracle(q, k, v, wl.window, H0), "f32", f"tiny_f32 H0={H0}")
+
+
+@pytest.mark.parametrize("impl", [SCALAR, MFMA], ids=["scalar", "mfma"])
+@pytest.mark.parametrize("H0", [12, 0, 2])
+def test_gpt2_small_bf16(H0, impl):
+    wl = gi.WORKLOADS["gpt2_small"]
+    q, k, v = gi.make_qkv(wl)
+    got = run_gpu(q, k, v, "bf16", wl.window, H0, impl=impl)
+    check(got, oracle(q, k, v, wl.window, H0), "bf16", f"gpt2_small H0={H0}")
+
+
+# ---------------------------------------------------------------------------------------
+# shapes that span several tiles with ragged tails, windows of every kind
+# ---------------------------------------------------------------------------------------
+
+SHAPES = [
+    # B, H, N, d, window, H0
+    (1, 2, 1, 64, 4, 1),
+    (2, 3, 77, 64, 1, 2),
+    (1, 4, 333, 64, 32, 2),
+    (1, 2, 300, 128, 100, 1),
+    (2, 2, 513, 128, 513, 1),
+    (1, 2, 200, 64, 1000, 1),     # window >= N: full causal attention
+    (1, 3, 1025, 128, 256, 1),
+    (1, 2, 640, 64, 129, 0),
+    (1, 2, 640, 128, 64, 2),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_f32_shapes(shape):
+    B, H, N, d, w, H0 = shape
+    q, k, v = synth(B, H, N, d, "f32", 11)
+    got = run_gpu(q, k, v, "f32", w, H0)
+    check(got, oracle(q, k, v, w, H0), "f32", str(shape))
+
+
+@pytest.mark.parametrize("impl", [SCALAR, MFMA], ids=["scalar", "mfma"])
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_bf16_shapes(shape, impl):
+    B, H, N, d, w, H0 = shape
+    q, k, v = synth(B, H, N, d, "bf16", 12)
+    got = run_gpu(q, k, v, "bf16", w, H0, impl=impl)
+    check(got, oracle(q, k, v, w, H0), "bf16", str(shape))
+
+
+@pytest.mark.parametrize("dtype,impl", [("f32", SCALAR), ("bf16", SCALAR), ("bf16", MFMA)],
+                         ids=["f32", "bf16-scalar", "bf16-mfma"])
+def test_paper_layout_strides(dtype, impl):
+    """Q, K, V and out stored [B, N, H, E] as in section III-A, passed through strides."""
+    B, H, N, d, w, H0 = 2, 4, 150, 64, 40, 1
+    q, k, v = synth(B, H, N, d, dtype, 13)
+    got = run_gpu(q, k, v, dtype, w, H0, layout="bnhd", impl=impl)
+    check(got, oracle(q, k, v, w, H0), dtype, "bnhd")
+
+
+@pytest.mark.parametrize("dtype,impl", [("f32", SCALAR), ("bf16", MFMA)], ids=["f32", "bf16-mfma"])
+def test_softmax_scale_eps_and_identity_phi(dtype, impl):
+    B, H, N, d, w, H0 = 1, 4, 260, 64, 48, 2
+    q, k, v = synth(B, H, N, d, dtype, 14, q_prescaled=False)
+    q[:, H0:] = np.abs(q[:, H0:]) + np.float32(0.125)   # positive features for the identity map
+    k[:, H0:] = np.abs(k[:, H0:]) + np.float32(0.125)
+    if dtype == "bf16":
+        q, k = gi.round_to_bf16(q), gi.round_to_bf16(k)
+    kw = dict(softmax_scale=0.125, eps=0.5)
+    got = run_gpu(q, k, v, dtype, w, H0, phi=gb.GF_PHI_IDENTITY, impl=impl, **kw)
+    ref = co.attn_fwd(q, k, v, w, H0, phi=co.PHI_IDENTITY, **kw)
+    check(got, ref, dtype, "scale/eps/identity")
+
+
+# ---------------------------------------------------------------------------------------
+# the MFMA path's launch geometry must not change results
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_linear_chunk_and_segment_invariance(d):
+    B, H, N, w = 1, 3, 1100, 16
+    q, k, v = synth(B, H, N, d, "bf16", 15)
+    ref = oracle(q, k, v, w, 0)
+    outs = {}
+    for chunk in (64, 128):
+        for seg in (0, chunk, 2 * chunk, 1280):
+            got = run_gpu(q, k, v, "bf16", w, 0, impl=MFMA, chunk=chunk, segment_len=seg)
+            check(got, ref, "bf16", f"chunk={chunk} seg={seg}")
+            outs[(chunk, seg)] = got
+    # one segment vs many: the same chunks are formed, only the carried state's rounding moves
+    assert float(row_rel_l2(outs[(64, 64)], outs[(64, 1280)]).max()) < 1e-2
+
+
+@pytest.mark.parametrize("dtype,impl", [("f32", SCALAR), ("bf16", MFMA)], ids=["f32", "bf16-mfma"])
+def test_causality_is_bit_exact(dtype, impl):
+    """Changing token t's key, value and query leaves every earlier output row bit-identical,
+    and on windowed heads also every row from t + window on."""
+    B, H, N, d, w, H0, t = 1, 2, 700, 64, 96, 1, 389
+    q, k, v = synth(B, H, N, d, dtype, 16)
+    base = run_gpu(q, k, v, dtype, w, H0, impl=impl)
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    k2[:, :, t] += 1.0; v2[:, :, t] -= 2.0; q2[:, :, t] *= -0.5
+    pert = run_gpu(q2, k2, v2, dtype, w, H0, impl=impl)
+    assert np.array_equal(base[:, :, :t], pert[:, :, :t])
+    assert np.array_equal(base[:, 0, t + w:], pert[:, 0, t + w:])
+    assert not np.array_equal(base[:, :, t], pert[:, :, t])
+    assert not np.array_equal(base[:, 1, -1], pert[:, 1, -1])   # the linear state remembers
+
+
+@pytest.mark.parametrize("dtype,impl", [("f32", SCALAR), ("bf16", MFMA)], ids=["f32", "bf16-mfma"])
+def test_repeat_runs_are_bit_identical(dtype, impl):
+    B, H, N, d, w, H0 = 2, 4, 900, 128, 200, 2
+    q, k, v = synth(B, H, N, d, dtype, 17)
+    a = run_gpu(q, k, v, dtype, w, H0, impl=impl)
+    b = run_gpu(q, k, v, dtype, w, H0, impl=impl)
+    assert np.array_equal(a, b)
+
+
+def test_head_split_extremes_and_slots():
+    B, H, N, d, w = 1, 4, 256, 64, 64
+    q, k, v = synth(B, H, N, d, "bf16", 18)
+    for H0 in (0, 1, 3, 4):
+        got = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA)
+        check(got, oracle(q, k, v, w, H0), "bf16", f"H0={H0}")
+
+
+def test_values_of_one_give_one():
+    """Weights sum to one on both paths (bf16 MFMA arithmetic keeps this to rounding)."""
+    B, H, N, d, w = 1, 2, 500, 128, 70
+    q, k, _ = synth(B, H, N, d, "bf16", 19)
+    v = np.ones_like(q)
+    got = run_gpu(q, k, v, "bf16", w, 1, impl=MFMA)
+    assert max_abs(got, np.ones_like(got)) < 1e-2
+
+
+def test_outlier_keys_and_unscaled_queries():
+    """Keys x8 every 64th token with unscaled queries: large logits stress the running-max
+    rescale, large phi(k) stresses the fp32 state."""
+    wl = gi.WORKLOADS["long32k"].with_(B=1, H=4, N=1536, window=512)
+    q, k, v = gi.make_qkv(wl)
+    got = run_gpu(q, k, v, "bf16", wl.window, 2, impl=MFMA)
+    check(got, oracle(q, k, v, wl.window, 2), "bf16", "outliers")
+
+
+# ---------------------------------------------------------------------------------------
+# full-size configurations: sampled heads against the oracle, every head for sanity
+# ---------------------------------------------------------------------------------------
+
+def _full_size(name, H0, **kw):
+    import torch
+    from tests.gpu_util import to_device, to_host
+    wl = gi.WORKLOADS[name]
+    q, k, v = gi.make_qkv(wl)
+    tq, tk, tv = (to_device(x, "bf16") for x in (q, k, v))
+    out = torch.full_like(tq, float("nan"))
+    gb.gformer_attn_fwd(tq, tk, tv, out, wl.window, H0, **kw)   # the bench's launch configuration
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out.float()).all())
+    for (b, h) in gi.sample_heads(wl, H0):
+        got = to_host(out[b, h])
+        if h < H0:
+            ref = co.windowed_head(q[b, h], k[b, h], v[b, h], wl.window)
+        else:
+            ref = co.linear_head(q[b, h], k[b, h], v[b, h], form=co.LINEAR_RECURRENT)
+        check(got, ref, "bf16", f"{name} head ({b},{h}) H0={H0}")
+
+
+@pytest.mark.parametrize("H0", [6, 32, 0])
+def test_llm7b_full_size_sampled_heads(H0):
+    _full_size("llm7b", H0)
+
+
+@pytest.mark.parametrize("chunk", [64, 128])
+def test_llm7b_chunk_sweep_sampled_heads(chunk):
+    _full_size("llm7b", 6, chunk=chunk)
+
+
+def test_long32k_full_size_sampled_heads():
+    _full_size("long32k", 6)
