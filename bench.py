@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the GFormer attention forward hot path on one MI355X.
+
+A step is one gformer_attn_fwd call over the whole layer (all heads: windowed softmax heads,
+linear heads, normalise + write) on seeded synthetic Q/K/V already resident in HBM.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llm7b] [--h0 6]
+
+Prints ONE JSON line (see the keys below).  `roofline` describes the dominant kernel, timed
+live with events on the launch stream; `cpu_baseline` is the fp64 oracle timed on the host
+cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def algorithmic_work(wl, H0):
+    """Algorithmic FLOPs and bytes of one layer call (definitions, not executed tile work)."""
+    N, d, w = wl.N, wl.d, min(wl.window, wl.N)
+    pairs = N * w - w * (w - 1) // 2                    # in-window (query, key) pairs per head
+    f_win = 4 * d * pairs                               # QK^T + PV
+    f_lin = N * (4 * d * d + 3 * d)                     # Algorithm 1 per token: update + read-out
+    bytes_head = 4 * N * d * 2                          # read Q, K, V once, write out once (bf16)
+    n_win, n_lin = wl.B * H0, wl.B * (wl.H - H0)
+    return {"flops_windowed": n_win * f_win, "flops_linear": n_lin * f_lin,
+            "bytes_windowed": n_win * bytes_head, "bytes_linear": n_lin * bytes_head,
+            "exp_count": n_win * pairs}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llm7b")
+    ap.add_argument("--h0", type=int, default=-1, help="sparse heads (default: workload's)")
+    ap.add_argument("--segment-len", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-modes", action="store_true", help="skip the pure-windowed / pure-linear runs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards by head/batch with no "
+              "communication; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2412_19829_amd import binding as gb
+    from paper_2412_19829_amd import inputs as gi
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    gb.lib()   # fail loudly if the HIP library is missing
+
+    wl = gi.WORKLOADS[args.workload]
+    H0 = wl.n_sparse_heads if args.h0 < 0 else args.h0
+    q, k, v = gi.make_qkv(wl)
+    def dev(x):
+        return torch.from_numpy(gi.f32_to_bf16_bits(x).view(np.int16)).cuda().view(torch.bfloat16)
+    tq, tk, tv = dev(q), dev(k), dev(v)
+    out = torch.empty_like(tq)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def make_call(h0, mask=0):
+        params = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=h0, segment_len=args.segment_len,
+                                launch_mask=mask)
+        need = gb.gformer_attn_workspace_bytes(wl.B, wl.H, wl.N, wl.d, wl.window, params)
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        ptrs = (tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), out.data_ptr())
+        def call():
+            st = gb.gformer_attn_fwd_raw(*ptrs, wl.B, wl.H, wl.N, wl.d, wl.window, params,
+                                         ws.data_ptr(), ws.numel(), stream)
+            if st != gb.GF_OK:
+                raise gb.GformerError(st, gb.gformer_status_string(st))
+        return call, params, ws
+
+    def time_steps(call, steps, warmup):
+        for _ in range(warmup):
+            call()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            call()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def event_time(call, steps):
+        """Average duration of what `call` enqueues, from events on the launch stream."""
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(steps)]
+        for a, b in evs:
+            a.record()
+            call()
+            b.record()
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in evs) / steps * 1e-3
+
+    # ---- the timed region: K whole-layer calls -----------------------------------------
+    call, params, ws = make_call(H0)
+    sec = time_steps(call, args.steps, args.warmup)
+    work = algorithmic_work(wl, H0)
+    flops = work["flops_windowed"] + work["flops_linear"]
+    nbytes = work["bytes_windowed"] + work["bytes_linear"]
+    st, plan = gb.gformer_attn_plan(wl.B, wl.H, wl.N, wl.d, wl.window, params)
+
+    # ---- per-kernel durations (same inputs, same stream), dominant kernel's roofline ----
+    kern = {}
+    for name, mask, present in (("windowed", gb.GF_LAUNCH_WINDOWED, H0 > 0),
+                                ("linear_state", gb.GF_LAUNCH_LINEAR_STATE, plan.state_blocks > 0),
+                                ("linear_main", gb.GF_LAUNCH_LINEAR_MAIN, H0 < wl.H)):
+        if present:
+            c, _, _w = make_call(H0, mask)
+            for _ in range(3):
+                c()
+            kern[name] = event_time(c, max(10, args.steps))
+    dominant = max(kern, key=kern.get)
+    if dominant == "windowed":
+        dom_bytes, dom_flops = work["bytes_windowed"], work["flops_windowed"]
+    elif dominant == "linear_main":
+        dom_bytes, dom_flops = work["bytes_linear"], work["flops_linear"]
+    else:  # state pass: reads K and V of all but the last segment
+        dom_bytes = work["bytes_linear"] // 2 * (plan.n_segments - 1) // plan.n_segments
+        dom_flops = work["flops_linear"] // 2
+    achieved_gbs = dom_bytes / kern[dominant] / 1e9
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved_gbs, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
+                "traffic": None,
+                "avg_launch_us": round(kern[dominant] * 1e6, 2),
+                "algorithmic_bytes_per_launch": dom_bytes,
+                "mfma_tflops": round(dom_flops / kern[dominant] / 1e12, 1),
+                "mfma_frac": round(dom_flops / kern[dominant] / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+
+    result = {
+        "metric": "GFormer attention fwd tokens/s",
+        "value": round(wl.B * wl.N / sec, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={wl.B} H={wl.H} N={wl.N} d={wl.d} window={wl.window} "
+                               f"n_sparse_heads={H0} bf16 in/out, fp32 accumulate and state",
+                   "chunk": plan.chunk, "segment_len": plan.segment_len,
+                   "n_segments": plan.n_segments, "seed": wl.seed},
+        "tflops": round(flops / sec / 1e12, 2),
+        "pct_mfma_peak": round(100 * flops / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
+        "gbs": round(nbytes / sec / 1e9, 1),
+        "pct_hbm_peak": round(100 * nbytes / sec / 1e9 / HBM_PEAK_GBS, 2),
+        "kernel_us": {k_: round(v_ * 1e6, 2) for k_, v_ in kern.items()},
+        "roofline": roofline,
+    }
+
+    # ---- the other two head splits of the same workload (context) ------------------------
+    if not args.no_modes:
+        modes = {}
+        for name, h0 in (("all_windowed", wl.H), ("all_linear", 0)):
+            c, _, _w = make_call(h0)
+            s = time_steps(c, max(5, args.steps // 2), 3)
+            wk = algorithmic_work(wl, h0)
+            fl = wk["flops_windowed"] + wk["flops_linear"]
+            by = wk["bytes_windowed"] + wk["bytes_linear"]
+            modes[name] = {"ms": round(s * 1e3, 4), "tokens_per_s": round(wl.B * wl.N / s, 1),
+                           "tflops": round(fl / s / 1e12, 2),
+                           "pct_mfma_peak": round(100 * fl / s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
+                           "pct_hbm_peak": round(100 * by / s / 1e9 / HBM_PEAK_GBS, 2)}
+        result["modes"] = modes
+
+    # ---- CPU baseline: the fp64 oracle on batch element 0 (all heads), host cores ---------
+    if not args.no_cpu_baseline:
+        from oracle import cpu_oracle as co
+        nb = min(wl.B, 4)   # bounded sample: at most 4 batch elements, every head of each
+        q0, k0, v0 = (x[:nb].astype(np.float64) for x in (q, k, v))
+        threads = co.max_threads()
+        t0 = time.perf_counter()
+        co.attn_fwd(q0, k0, v0, wl.window, H0, linear_form=co.LINEAR_RECURRENT)
+        t_cpu = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(nb * wl.N / t_cpu, 1), "unit": "tokens/s", "cores": threads,
+            "kind": "oracle",
+            "sample": f"{nb} of {wl.B} batch elements (all {wl.H} heads each, same head split), "
+                      f"fp64 C oracle: windowed heads by definition, linear heads by the "
+                      f"Algorithm-1 recurrence; {t_cpu:.2f} s wall on {threads} threads"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -34,8 +34,8 @@
  *     anything is launched and reported through gf_status.
  *   - Supported: d in {64, 128}; any N >= 0 (N == 0 or B*H == 0 is a no-op); any window >= 1
  *     (window >= N is full causal attention); 0 <= n_sparse_heads <= H;
- *     chunk in {0, 64, 128}.  Everything else returns GF_ERR_UNSUPPORTED; nothing falls
- *     back silently.
+ *     chunk in {0, 64}.  Everything else returns GF_ERR_UNSUPPORTED; nothing falls back
+ *     silently.
  */
 #ifndef GFORMER_H
 #define GFORMER_H
@@ -68,7 +68,7 @@ typedef struct gformer_params {
   int32_t dtype;          /* gf_dtype                                                        */
   int32_t phi;            /* gf_phi, linear heads only                                       */
   int32_t n_sparse_heads; /* H0: heads [0,H0) windowed softmax, heads [H0,H) causal linear   */
-  int32_t chunk;          /* linear-attention chunk C in {64,128}; 0 = library picks         */
+  int32_t chunk;          /* linear-attention chunk C: 64, or 0 = library picks               */
   int32_t segment_len;    /* tokens per linear-attention segment (multiple of chunk);        */
                           /* 0 = library picks.  Segments of one head run in parallel and    */
                           /* are stitched with a prefix over their (A, Z) states.            */

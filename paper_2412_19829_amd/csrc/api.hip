@@ -65,7 +65,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   int impl = p->impl;
   if (impl == GF_IMPL_AUTO) impl = (p->dtype == GF_BF16) ? GF_IMPL_MFMA : GF_IMPL_SCALAR;
   if (impl == GF_IMPL_MFMA && p->dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
-  if (p->chunk != 0 && p->chunk != 64 && p->chunk != 128) return GF_ERR_UNSUPPORTED;
+  if (p->chunk != 0 && p->chunk != 64) return GF_ERR_UNSUPPORTED;
 
   gformer_plan& pl = r->plan;
   pl.impl = impl;

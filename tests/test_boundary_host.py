@@ -50,7 +50,7 @@ def _plan(B, H, N, d, w, **kw):
 def test_plan_headline_config():
     st, pl = _plan(4, 32, 8192, 128, 256, n_sparse_heads=6)
     assert st == gb.GF_OK and pl["impl"] == gb.GF_IMPL_MFMA
-    assert pl["chunk"] in (64, 128) and pl["segment_len"] % pl["chunk"] == 0
+    assert pl["chunk"] == 64 and pl["segment_len"] % pl["chunk"] == 0
     assert pl["n_segments"] * pl["segment_len"] >= 8192 > (pl["n_segments"] - 1) * pl["segment_len"]
     assert pl["windowed_blocks"] == 4 * 6 * (8192 // 128)
     assert pl["linear_blocks"] == 4 * 26 * pl["n_segments"]
@@ -63,8 +63,8 @@ def test_plan_modes_and_overrides():
     st, pl = _plan(1, 1, 256, 64, 32, dtype=gb.GF_F32, n_sparse_heads=1)
     assert st == gb.GF_OK and pl["impl"] == gb.GF_IMPL_SCALAR and pl["workspace_bytes"] == 0
     assert pl["linear_blocks"] == 0 and pl["windowed_blocks"] == 16
-    st, pl = _plan(1, 32, 32768, 128, 512, n_sparse_heads=0, chunk=128, segment_len=1024)
-    assert st == gb.GF_OK and pl["chunk"] == 128 and pl["segment_len"] == 1024 and pl["n_segments"] == 32
+    st, pl = _plan(1, 32, 32768, 128, 512, n_sparse_heads=0, chunk=64, segment_len=1024)
+    assert st == gb.GF_OK and pl["chunk"] == 64 and pl["segment_len"] == 1024 and pl["n_segments"] == 32
     assert pl["state_blocks"] == 32 * 31 and pl["windowed_blocks"] == 0
     st, pl = _plan(1, 2, 100, 64, 8, n_sparse_heads=0, segment_len=64)
     assert st == gb.GF_OK and pl["n_segments"] == 2
@@ -92,6 +92,7 @@ def test_plan_modes_and_overrides():
     ((1, 2, 16, 96, 4), {}, gb.GF_ERR_UNSUPPORTED),               # head size
     ((1, 2, 16, 64, 4), {"chunk": 48}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 16, 64, 4), {"chunk": 256}, gb.GF_ERR_UNSUPPORTED),
+    ((1, 2, 16, 64, 4), {"chunk": 128}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 16, 64, 4), {"dtype": gb.GF_F32, "impl": gb.GF_IMPL_MFMA}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 256, 64, 4), {"dtype": gb.GF_F32, "segment_len": 64}, gb.GF_ERR_UNSUPPORTED),
     ((70000, 2, 16, 64, 4), {}, gb.GF_ERR_UNSUPPORTED),

@@ -128,8 +128,8 @@ def test_linear_chunk_and_segment_invariance(d):
     q, k, v = synth(B, H, N, d, "bf16", 15)
     ref = oracle(q, k, v, w, 0)
     outs = {}
-    for chunk in (64, 128):
-        for seg in (0, chunk, 2 * chunk, 1280):
+    for chunk in (64,):
+        for seg in (0, chunk, 2 * chunk, 320, 1280):
             got = run_gpu(q, k, v, "bf16", w, 0, impl=MFMA, chunk=chunk, segment_len=seg)
             check(got, ref, "bf16", f"chunk={chunk} seg={seg}")
             outs[(chunk, seg)] = got
@@ -146,6 +146,8 @@ def test_causality_is_bit_exact(dtype, impl):
     base = run_gpu(q, k, v, dtype, w, H0, impl=impl)
     q2, k2, v2 = q.copy(), k.copy(), v.copy()
     k2[:, :, t] += 1.0; v2[:, :, t] -= 2.0; q2[:, :, t] *= -0.5
+    if dtype == "bf16":
+        q2, k2, v2 = (gi.round_to_bf16(x) for x in (q2, k2, v2))
     pert = run_gpu(q2, k2, v2, dtype, w, H0, impl=impl)
     assert np.array_equal(base[:, :, :t], pert[:, :, :t])
     assert np.array_equal(base[:, 0, t + w:], pert[:, 0, t + w:])
@@ -192,22 +194,35 @@ def test_outlier_keys_and_unscaled_queries():
 # full-size configurations: sampled heads against the oracle, every head for sanity
 # ---------------------------------------------------------------------------------------
 
+_DEVICE_CACHE = {}
+
+
+def _device_inputs(name):
+    """Full-size inputs are generated once per workload and kept on the device."""
+    from tests.gpu_util import to_device
+    if name not in _DEVICE_CACHE:
+        _DEVICE_CACHE.clear()   # one workload resident at a time
+        wl = gi.WORKLOADS[name]
+        _DEVICE_CACHE[name] = tuple(to_device(x, "bf16") for x in gi.make_qkv(wl))
+    return _DEVICE_CACHE[name]
+
+
 def _full_size(name, H0, **kw):
     import torch
-    from tests.gpu_util import to_device, to_host
+    from tests.gpu_util import to_host
     wl = gi.WORKLOADS[name]
-    q, k, v = gi.make_qkv(wl)
-    tq, tk, tv = (to_device(x, "bf16") for x in (q, k, v))
+    tq, tk, tv = _device_inputs(name)
     out = torch.full_like(tq, float("nan"))
     gb.gformer_attn_fwd(tq, tk, tv, out, wl.window, H0, **kw)   # the bench's launch configuration
     torch.cuda.synchronize()
     assert bool(torch.isfinite(out.float()).all())
     for (b, h) in gi.sample_heads(wl, H0):
         got = to_host(out[b, h])
+        q, k, v = gi.make_head(wl, b, h)
         if h < H0:
-            ref = co.windowed_head(q[b, h], k[b, h], v[b, h], wl.window)
+            ref = co.windowed_head(q, k, v, wl.window)
         else:
-            ref = co.linear_head(q[b, h], k[b, h], v[b, h], form=co.LINEAR_RECURRENT)
+            ref = co.linear_head(q, k, v, form=co.LINEAR_RECURRENT)
         check(got, ref, "bf16", f"{name} head ({b},{h}) H0={H0}")
 
 
@@ -216,9 +231,9 @@ def test_llm7b_full_size_sampled_heads(H0):
     _full_size("llm7b", H0)
 
 
-@pytest.mark.parametrize("chunk", [64, 128])
-def test_llm7b_chunk_sweep_sampled_heads(chunk):
-    _full_size("llm7b", 6, chunk=chunk)
+@pytest.mark.parametrize("seg", [512, 8192])
+def test_llm7b_segment_sweep_sampled_heads(seg):
+    _full_size("llm7b", 6, chunk=64, segment_len=seg)
 
 
 def test_long32k_full_size_sampled_heads():
