@@ -6,14 +6,19 @@
 //     num = tril(phiQ phiK^T) V + phiQ A_prev ,   den = rowsum(tril(phiQ phiK^T)) + phiQ.Z_prev
 // and the carried state moves once per chunk: A += phiK^T V, Z += colsum(phiK).  Instead of
 // materialising one E x E outer product per token, a chunk's 64 outer products are one MFMA
-// contraction.  A and Z stay fp32 (accumulator registers / LDS); operands are bf16.
+// contraction.  A and Z stay fp32 (accumulator registers / LDS); MFMA operands are bf16.
+//
+// Work split inside a workgroup: wave w owns value columns 32w..32w+31, i.e. the state tiles
+// A[:, 32w..] (fp32 accumulators, lane = value column, registers = feature rows) and the
+// output tile num^T[32w.., all 64 queries].  Because a lane's accumulator registers are exactly
+// the k-slots an MFMA A operand wants (see mfma.hpp), phiQ A_prev is fed straight from the
+// state registers; phi(Q) is stored in LDS with its feature index permuted to match.  phi(K)
+// and V sit row-major in LDS and are read through the LDS transpose read wherever the
+// contraction runs over tokens.
 //
 // Segments of one head are stitched in three launches: (1) every segment but the last sums its
 // own (A, Z); (2) a tiny kernel turns those into exclusive prefixes; (3) the read-out kernel
 // starts each segment from its prefix.
-//
-// Everything is computed transposed (num^T = V^T P^T + A^T phiQ^T, value column x query) so one
-// lane owns one query column and normalisation is lane-local.
 #include "common.hpp"
 #include "mfma.hpp"
 
@@ -24,34 +29,32 @@ constexpr int CH = 64;  // tokens per chunk
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <int D> struct LinCfg {
-  static constexpr int NW = D / 16;           // waves per workgroup
-  static constexpr int NT = NW * 64;          // threads per workgroup
-  static constexpr int ROW = D + 8;           // bf16 elements per row of a row-major tile
-  static constexpr int TROW = CH + 8;         // bf16 elements per row of a transposed tile
   static constexpr int ET = D / 32;           // 32-wide tiles along a feature / value axis
-  static constexpr int STILES = ET * ET / NW; // state tiles per wave
-  static constexpr int KS = D / 16;           // k-steps over the feature axis
+  static constexpr int NW = ET;               // waves per workgroup: one per value-column tile
+  static constexpr int NT = NW * 64;          // threads per workgroup
+  static constexpr int QROW = D + 8;          // phi(Q): 128-bit row reads   (stride = 4 dw mod 64)
+  static constexpr int KROW = D + 16;         // phi(K): 64-bit row reads + transpose reads
+  static constexpr int VROW = D + 32;         // V: transpose reads only     (stride = 16 dw mod 64)
+  static constexpr int PROW = CH + 8;         // masked products, [query][key]
   static constexpr int C8 = D / 8;            // 16-byte pieces per row
+  static constexpr int PIECES = CH * C8 / NT; // pieces per thread per tensor per chunk (= 4)
   static constexpr int STATE = D * D + D;     // floats per (A, Z) state
 };
 
 template <int D> struct LinSmem {
   using C = LinCfg<D>;
-  uint16_t fq[CH * C::ROW];     // phi(Q) chunk, row-major [token][feature]
-  uint16_t fk[CH * C::ROW];     // phi(K) chunk, row-major
-  uint16_t fkt[D * C::TROW];    // phi(K)^T, [feature][token, permuted]
-  uint16_t vt[D * C::TROW];     // V^T, [value column][token, permuted]
-  uint16_t at[CH * C::TROW];    // masked products, [query][key, permuted]
-  uint16_t sb[D * C::ROW];      // bf16 copy of the state A, [value column][feature]
-  float z[2][D];                // Z, double-buffered across chunks
+  uint16_t fq[CH * C::QROW];   // phi(Q), feature index permuted by kperm32 inside 32-groups
+  uint16_t fk[CH * C::KROW];   // phi(K), natural order
+  uint16_t v[CH * C::VROW];    // V
+  uint16_t pt[CH * C::PROW];   // masked products P^T viewed as [query][key]
+  float z[2][D];               // Z in the same permuted feature order as fq; double-buffered
   float den[CH];
 };
 
 template <int D> struct StateSmem {
   using C = LinCfg<D>;
-  uint16_t fkt[D * C::TROW];
-  uint16_t vt[D * C::TROW];
-  float z[D];
+  uint16_t fk[CH * C::KROW];
+  uint16_t v[CH * C::VROW];
 };
 
 // phi(x) = elu(x) + 1 = max(x + 1, min(exp(x), 1))   (section II-B)
@@ -72,30 +75,12 @@ __device__ __forceinline__ u32x4 map_features(u32x4 v, int phi, bool valid) {
   return o;
 }
 
-// A 4-token x 8-column block: global rows -> registers.  Rows past N are clamped (in bounds).
-__device__ __forceinline__ void load_block(const uint16_t* base, int64_t sn, int row0, int col0,
-                                           int N, u32x4 (&r)[4]) {
+__device__ __forceinline__ float sum8_bf16(bf16x8 x) {
+  const u32x4 u = as_u32x4(x);
+  float s = 0.f;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = min(row0 + j, N - 1);
-    r[j] = *reinterpret_cast<const u32x4*>(base + (int64_t)row * sn + col0);
-  }
-}
-
-// Store a 4-token x 8-column block transposed: 8 rows (columns col0..col0+7) of 4 tokens each,
-// at the permuted position of token group `tok4` (multiple of 4, < 64).
-template <int TROW>
-__device__ __forceinline__ void store_block_transposed(uint16_t* dst, const u32x4 (&r)[4],
-                                                       int col0, int tok4) {
-  u32x2 col[8];
-  transpose_4x8_bf16(r, col);
-  const int pos = 32 * (tok4 / 32) + kperm32(tok4 % 32);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x2*>(&dst[(col0 + i) * TROW + pos]) = col[i];
-}
-
-__device__ __forceinline__ bf16x8 lds_operand(const uint16_t* p) {
-  return as_bf16x8(*reinterpret_cast<const u32x4*>(p));
+  for (int w = 0; w < 4; ++w) s += bf16_lo(u[w]) + bf16_hi(u[w]);
+  return s;
 }
 
 template <int D> struct HeadPtrs {
@@ -117,21 +102,36 @@ __device__ __forceinline__ HeadPtrs<D> head_ptrs(const AttnArgs& a, int head_lin
   return p;
 }
 
-// Z += column sums of the bf16 phi(K) chunk held transposed in LDS: 4 threads per feature.
+// State tile (ct, wave) in accumulator layout: lane = value column 32*wave + l%32,
+// register r = feature row 32*ct + 8*(r/4) + 4*(l/32) + r%4.  Workspace layout is [c][e] fp32.
 template <int D>
-__device__ __forceinline__ float chunk_feature_sum(const uint16_t* fkt, int tid) {
+__device__ __forceinline__ int state_index(int ct, int wave, int r, int ln, int lh) {
+  return (32 * ct + 8 * (r / 4) + 4 * lh + (r % 4)) * D + 32 * wave + ln;
+}
+
+// A += phiK^T V for this wave's value columns, from the row-major chunk tiles in LDS; returns
+// this lane's share of colsum(phiK) for features 32*wave + l%32 (tokens of its k-slot half).
+template <int D>
+__device__ __forceinline__ float update_state(f32x16 (&sacc)[LinCfg<D>::ET], const uint16_t* fk,
+                                              const uint16_t* v, int wave, int lane) {
   using C = LinCfg<D>;
-  const int c = tid >> 2, part = tid & 3;
-  const u32x4 x0 = *reinterpret_cast<const u32x4*>(&fkt[c * C::TROW + 16 * part]);
-  const u32x4 x1 = *reinterpret_cast<const u32x4*>(&fkt[c * C::TROW + 16 * part + 8]);
-  float s = 0.f;
+  const int lh = lane >> 5;
+  float zs = 0.f;
+  bf16x8 vb[CH / 16];
 #pragma unroll
-  for (int w = 0; w < 4; ++w) s += bf16_lo(x0[w]) + bf16_hi(x0[w]);
+  for (int kk = 0; kk < CH / 16; ++kk)
+    vb[kk] = lds_operand_tr(v, C::VROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
 #pragma unroll
-  for (int w = 0; w < 4; ++w) s += bf16_lo(x1[w]) + bf16_hi(x1[w]);
-  s += __shfl_xor(s, 1, 64);
-  s += __shfl_xor(s, 2, 64);
-  return s;
+  for (int ct = 0; ct < C::ET; ++ct) {
+#pragma unroll
+    for (int kk = 0; kk < CH / 16; ++kk) {
+      const bf16x8 fa =
+          lds_operand_tr(fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * ct, lane);
+      if (ct == wave) zs += sum8_bf16(fa);
+      sacc[ct] = mfma32(fa, vb[kk], sacc[ct]);
+    }
+  }
+  return zs;
 }
 
 // -----------------------------------------------------------------------------------------
@@ -139,7 +139,7 @@ __device__ __forceinline__ float chunk_feature_sum(const uint16_t* fkt, int tid)
 //     sum_{t in segment s} phi(k_t) (x) v_t  and  sum phi(k_t)  into workspace slot s+1.
 // -----------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(LinCfg<D>::NT) void linear_state_kernel(AttnArgs a) {
+__global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs a) {
   using C = LinCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   StateSmem<D>& sm = *reinterpret_cast<StateSmem<D>*>(smem_raw);
@@ -152,58 +152,45 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_state_kernel(AttnArgs a)
   const int seg_start = seg * a.segment_len;
   const int seg_end = min(N, seg_start + a.segment_len);
 
-  f32x16 sacc[C::STILES];
+  f32x16 sacc[C::ET];
 #pragma unroll
-  for (int i = 0; i < C::STILES; ++i)
+  for (int i = 0; i < C::ET; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[i][r] = 0.f;
-  if (tid < D) sm.z[tid] = 0.f;
+  float zacc = 0.f;
 
-  const bool k_thread = tid < C::NT / 2;
-  const int bt = k_thread ? tid : tid - C::NT / 2;
-  const int va = bt / C::C8, vc8 = bt % C::C8;
-  u32x4 blk[4];
+  u32x4 kst[C::PIECES], vst[C::PIECES];
   auto load_chunk = [&](int t0) {
-    load_block(k_thread ? hp.k : hp.v, k_thread ? a.k.sn : a.v.sn, t0 + 4 * va, 8 * vc8, N, blk);
+#pragma unroll
+    for (int i = 0; i < C::PIECES; ++i) {
+      const int c = tid + i * C::NT;
+      const int row = min(t0 + c / C::C8, N - 1);
+      kst[i] = *reinterpret_cast<const u32x4*>(hp.k + (int64_t)row * a.k.sn + 8 * (c % C::C8));
+      vst[i] = *reinterpret_cast<const u32x4*>(hp.v + (int64_t)row * a.v.sn + 8 * (c % C::C8));
+    }
   };
   load_chunk(seg_start);
   for (int t0 = seg_start; t0 < seg_end; t0 += CH) {
     __syncthreads();
-    if (k_thread) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) blk[j] = map_features(blk[j], a.phi, t0 + 4 * va + j < N);
-      store_block_transposed<C::TROW>(sm.fkt, blk, 8 * vc8, 4 * va);
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (t0 + 4 * va + j >= N) blk[j] = u32x4{0u, 0u, 0u, 0u};
-      store_block_transposed<C::TROW>(sm.vt, blk, 8 * vc8, 4 * va);
+    for (int i = 0; i < C::PIECES; ++i) {
+      const int c = tid + i * C::NT;
+      const int row = c / C::C8, col = 8 * (c % C::C8);
+      const bool valid = t0 + row < N;
+      *reinterpret_cast<u32x4*>(&sm.fk[row * C::KROW + col]) = map_features(kst[i], a.phi, valid);
+      *reinterpret_cast<u32x4*>(&sm.v[row * C::VROW + col]) = valid ? vst[i] : u32x4{0u, 0u, 0u, 0u};
     }
     __syncthreads();
     if (t0 + CH < seg_end) load_chunk(t0 + CH);
-#pragma unroll
-    for (int i = 0; i < C::STILES; ++i) {
-      const int ti = wave * C::STILES + i, ct = ti / C::ET, et = ti % C::ET;
-#pragma unroll
-      for (int kk = 0; kk < CH / 16; ++kk) {
-        const bf16x8 fa = lds_operand(&sm.fkt[(32 * ct + ln) * C::TROW + 16 * kk + 8 * lh]);
-        const bf16x8 vb = lds_operand(&sm.vt[(32 * et + ln) * C::TROW + 16 * kk + 8 * lh]);
-        sacc[i] = mfma32(fa, vb, sacc[i]);
-      }
-    }
-    const float zs = chunk_feature_sum<D>(sm.fkt, tid);
-    if ((tid & 3) == 0) sm.z[tid >> 2] += zs;  // each feature has exactly one writer
+    zacc += update_state<D>(sacc, sm.fk, sm.v, wave, lane);
   }
-  __syncthreads();
   float* dst = hp.state + (int64_t)(seg + 1) * C::STATE;
 #pragma unroll
-  for (int i = 0; i < C::STILES; ++i) {
-    const int ti = wave * C::STILES + i, ct = ti / C::ET, et = ti % C::ET;
+  for (int ct = 0; ct < C::ET; ++ct)
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-      dst[(32 * ct + 8 * (r / 4) + 4 * lh + (r % 4)) * D + 32 * et + ln] = sacc[i][r];
-  }
-  if (tid < D) dst[D * D + tid] = sm.z[tid];
+    for (int r = 0; r < 16; ++r) dst[state_index<D>(ct, wave, r, ln, lh)] = sacc[ct][r];
+  zacc += __shfl_xor(zacc, 32, 64);
+  if (lh == 0) dst[D * D + 32 * wave + ln] = zacc;
 }
 
 // (2) slots 1..n_segments-1 hold per-segment sums of segments 0..n_segments-2; make slot s the
@@ -225,7 +212,7 @@ __global__ __launch_bounds__(256) void linear_prefix_kernel(float* ws, int n_hea
 // (3) read-out.  Workgroup (head, segment) walks its chunks carrying (A, Z).
 // -----------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) {
+__global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_main_kernel(AttnArgs a) {
   using C = LinCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   LinSmem<D>& sm = *reinterpret_cast<LinSmem<D>*>(smem_raw);
@@ -238,89 +225,69 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
   const int seg_end = min(N, seg_start + a.segment_len);
   if (seg_start >= seg_end) return;  // uniform: nothing in this segment
 
-  // carried state: this wave's tiles of A in accumulator layout (lane = value column,
-  // registers = feature rows), Z in LDS
-  f32x16 sacc[C::STILES];
+  // carried state
+  f32x16 sacc[C::ET];
   const float* src = (seg > 0 && hp.state) ? hp.state + (int64_t)seg * C::STATE : nullptr;
 #pragma unroll
-  for (int i = 0; i < C::STILES; ++i) {
-    const int ti = wave * C::STILES + i, ct = ti / C::ET, et = ti % C::ET;
+  for (int ct = 0; ct < C::ET; ++ct)
 #pragma unroll
     for (int r = 0; r < 16; ++r)
-      sacc[i][r] = src ? src[(32 * ct + 8 * (r / 4) + 4 * lh + (r % 4)) * D + 32 * et + ln] : 0.f;
-  }
-  if (tid < D) sm.z[0][tid] = src ? src[D * D + tid] : 0.f;
-  auto publish_state = [&]() {  // bf16 copy of A for the phiQ A_prev product
-#pragma unroll
-    for (int i = 0; i < C::STILES; ++i) {
-      const int ti = wave * C::STILES + i, ct = ti / C::ET, et = ti % C::ET;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 pk;
-        pk[0] = pack_bf16(sacc[i][4 * g + 0], sacc[i][4 * g + 1]);
-        pk[1] = pack_bf16(sacc[i][4 * g + 2], sacc[i][4 * g + 3]);
-        *reinterpret_cast<u32x2*>(&sm.sb[(32 * et + ln) * C::ROW + 32 * ct + 8 * g + 4 * lh]) = pk;
-      }
-    }
-  };
-  publish_state();
+      sacc[ct][r] = src ? src[state_index<D>(ct, wave, r, ln, lh)] : 0.f;
+  if (lh == 0) sm.z[0][32 * wave + kperm32(ln)] = src ? src[D * D + 32 * wave + ln] : 0.f;
 
-  // global -> register staging: 2 row-major Q pieces per thread, one 4x8 block of K or V
-  const bool k_thread = tid < C::NT / 2;
-  const int bt = k_thread ? tid : tid - C::NT / 2;
-  const int va = bt / C::C8, vc8 = bt % C::C8;
-  u32x4 qst[2];
-  u32x4 blk[4];
+  // global -> register staging, row-major 16-byte pieces
+  u32x4 qst[C::PIECES], kst[C::PIECES], vst[C::PIECES];
   auto load_chunk = [&](int t0) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < C::PIECES; ++i) {
       const int c = tid + i * C::NT;
       const int row = min(t0 + c / C::C8, N - 1);
-      qst[i] = *reinterpret_cast<const u32x4*>(hp.q + (int64_t)row * a.q.sn + 8 * (c % C::C8));
+      const int col = 8 * (c % C::C8);
+      qst[i] = *reinterpret_cast<const u32x4*>(hp.q + (int64_t)row * a.q.sn + col);
+      kst[i] = *reinterpret_cast<const u32x4*>(hp.k + (int64_t)row * a.k.sn + col);
+      vst[i] = *reinterpret_cast<const u32x4*>(hp.v + (int64_t)row * a.v.sn + col);
     }
-    load_block(k_thread ? hp.k : hp.v, k_thread ? a.k.sn : a.v.sn, t0 + 4 * va, 8 * vc8, N, blk);
   };
 
-  const int et_n = wave % C::ET;  // this wave's tile of num^T: value columns 32*et_n ..
-  const int tq = wave / C::ET;    // .. by queries 32*tq ..
-  constexpr int PPT = C::NT / CH; // threads per query in the denominator
+  constexpr int PPT = C::NT / CH;  // threads per query in the denominator
   load_chunk(seg_start);
   int zc = 0;
   for (int t0 = seg_start; t0 < seg_end; t0 += CH, zc ^= 1) {
     __syncthreads();  // (1) previous chunk fully consumed
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < C::PIECES; ++i) {
       const int c = tid + i * C::NT;
-      *reinterpret_cast<u32x4*>(&sm.fq[(c / C::C8) * C::ROW + 8 * (c % C::C8)]) =
-          map_features(qst[i], a.phi, true);
+      const int row = c / C::C8, c8 = c % C::C8, col = 8 * c8;
+      const bool valid = t0 + row < N;
+      // phi(Q): features 8*c8 .. +7 go to permuted positions (two groups of 4, 8 apart)
+      const u32x4 fqv = map_features(qst[i], a.phi, true);
+      const int x = c8 % 4;
+      uint16_t* qd = &sm.fq[row * C::QROW + 32 * (c8 / 4) + 16 * (x / 2) + 4 * (x % 2)];
+      *reinterpret_cast<u32x2*>(qd) = u32x2{fqv[0], fqv[1]};
+      *reinterpret_cast<u32x2*>(qd + 8) = u32x2{fqv[2], fqv[3]};
+      *reinterpret_cast<u32x4*>(&sm.fk[row * C::KROW + col]) = map_features(kst[i], a.phi, valid);
+      *reinterpret_cast<u32x4*>(&sm.v[row * C::VROW + col]) = valid ? vst[i] : u32x4{0u, 0u, 0u, 0u};
     }
-    if (k_thread) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        blk[j] = map_features(blk[j], a.phi, t0 + 4 * va + j < N);
-        *reinterpret_cast<u32x4*>(&sm.fk[(4 * va + j) * C::ROW + 8 * vc8]) = blk[j];
-      }
-      store_block_transposed<C::TROW>(sm.fkt, blk, 8 * vc8, 4 * va);
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (t0 + 4 * va + j >= N) blk[j] = u32x4{0u, 0u, 0u, 0u};
-      store_block_transposed<C::TROW>(sm.vt, blk, 8 * vc8, 4 * va);
-    }
-    __syncthreads();  // (2) chunk tiles (and on the first pass the state copy) visible
+    __syncthreads();  // (2) chunk tiles (and on the first pass Z) visible
     if (t0 + CH < seg_end) load_chunk(t0 + CH);
 
     // masked products P^T[key][query] = phi(k_key).phi(q_query), key <= query: three 32x32
-    // tiles (the fourth lies above the diagonal), one each on waves 0..2
-    if (wave < 3) {
-      const int tk = wave == 2 ? 1 : 0, tqa = wave == 0 ? 0 : 1;
+    // tiles (the fourth lies above the diagonal), dealt round-robin to the waves
+#pragma unroll
+    for (int tile = 0; tile < 3; ++tile) {
+      if (tile % C::NW != wave) continue;
+      const int tk = tile == 2 ? 1 : 0, tqa = tile == 0 ? 0 : 1;
       f32x16 p;
 #pragma unroll
       for (int r = 0; r < 16; ++r) p[r] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < C::KS; ++ks) {
-        const bf16x8 ka = lds_operand(&sm.fk[(32 * tk + ln) * C::ROW + 16 * ks + 8 * lh]);
-        const bf16x8 qb = lds_operand(&sm.fq[(32 * tqa + ln) * C::ROW + 16 * ks + 8 * lh]);
+      for (int ks = 0; ks < D / 16; ++ks) {
+        // k-slot 8*lh + 4*g + j of this step is feature 16*ks + 8*g + 4*lh + j
+        const uint16_t* kr = &sm.fk[(32 * tk + ln) * C::KROW + 16 * ks + 4 * lh];
+        const u32x2 k0 = *reinterpret_cast<const u32x2*>(kr);
+        const u32x2 k1 = *reinterpret_cast<const u32x2*>(kr + 8);
+        const bf16x8 ka = as_bf16x8(u32x4{k0[0], k0[1], k1[0], k1[1]});
+        const bf16x8 qb = lds_read16(&sm.fq[(32 * tqa + ln) * C::QROW + 16 * ks + 8 * lh]);
         p = mfma32(ka, qb, p);
       }
       if (tk == tqa) {
@@ -333,21 +300,31 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
         u32x2 pk;
         pk[0] = pack_bf16(p[4 * g + 0], p[4 * g + 1]);
         pk[1] = pack_bf16(p[4 * g + 2], p[4 * g + 3]);
-        *reinterpret_cast<u32x2*>(
-            &sm.at[(32 * tqa + ln) * C::TROW + 32 * tk + 16 * (g / 2) + 8 * lh + 4 * (g % 2)]) = pk;
+        *reinterpret_cast<u32x2*>(&sm.pt[(32 * tqa + ln) * C::PROW + 32 * tk + 8 * g + 4 * lh]) = pk;
       }
     }
-    // num^T = A^T phiQ^T  (carried state part)
-    f32x16 num;
+    // num^T = A^T phiQ^T with A straight from the state registers
+    f32x16 num[2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) num[r] = 0.f;
+    for (int tq = 0; tq < 2; ++tq)
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) {
-      const bf16x8 sa = lds_operand(&sm.sb[(32 * et_n + ln) * C::ROW + 16 * ks + 8 * lh]);
-      const bf16x8 qb = lds_operand(&sm.fq[(32 * tq + ln) * C::ROW + 16 * ks + 8 * lh]);
-      num = mfma32(sa, qb, num);
+      for (int r = 0; r < 16; ++r) num[tq][r] = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < C::ET; ++ct) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        u32x4 sw;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sw[i] = pack_bf16(sacc[ct][8 * kb + 2 * i], sacc[ct][8 * kb + 2 * i + 1]);
+        const bf16x8 sa = as_bf16x8(sw);
+#pragma unroll
+        for (int tq = 0; tq < 2; ++tq) {
+          const bf16x8 qb = lds_read16(&sm.fq[(32 * tq + ln) * C::QROW + 32 * ct + 16 * kb + 8 * lh]);
+          num[tq] = mfma32(sa, qb, num[tq]);
+        }
+      }
     }
-    __syncthreads();  // (3) products visible; nobody reads the old state copy any more
+    __syncthreads();  // (3) products visible
 
     // denominator: rowsum of the (rounded) products + phi(q).Z_prev, PPT threads per query
     {
@@ -355,18 +332,18 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       constexpr int KW = CH / PPT;  // product slots per thread
       constexpr int CW = D / PPT;   // features per thread
       float s = 0.f;
-      const int kvis = qrow < 32 ? 32 : 64;  // slots >= 32 of the first 32 queries are unused
+      const int kvis = qrow < 32 ? 32 : 64;  // keys >= 32 are never visible to the first 32 queries
 #pragma unroll
       for (int x = 0; x < KW; x += 8) {
         if (KW * part + x < kvis) {
-          const u32x4 pv = *reinterpret_cast<const u32x4*>(&sm.at[qrow * C::TROW + KW * part + x]);
+          const u32x4 pv = *reinterpret_cast<const u32x4*>(&sm.pt[qrow * C::PROW + KW * part + x]);
 #pragma unroll
           for (int w = 0; w < 4; ++w) s += bf16_lo(pv[w]) + bf16_hi(pv[w]);
         }
       }
 #pragma unroll
       for (int x = 0; x < CW; x += 8) {
-        const u32x4 qv = *reinterpret_cast<const u32x4*>(&sm.fq[qrow * C::ROW + CW * part + x]);
+        const u32x4 qv = *reinterpret_cast<const u32x4*>(&sm.fq[qrow * C::QROW + CW * part + x]);
         const float* zz = &sm.z[zc][CW * part + x];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
@@ -378,45 +355,40 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       for (int o = 1; o < PPT; o <<= 1) s += __shfl_xor(s, o, 64);
       if (part == 0) sm.den[qrow] = s + a.eps;
     }
-    // num^T += V^T P^T  (inside the chunk); the first 32 queries see only the first 32 keys
+    // num^T += V^T P^T (inside the chunk); the first 32 queries see only the first 32 keys
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      if (kt <= tq) {
+    for (int kk = 0; kk < CH / 16; ++kk) {
+      const bf16x8 va_ =
+          lds_operand_tr(sm.v, C::VROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          const bf16x8 va_ = lds_operand(&sm.vt[(32 * et_n + ln) * C::TROW + 32 * kt + 16 * kb + 8 * lh]);
-          const bf16x8 pb = lds_operand(&sm.at[(32 * tq + ln) * C::TROW + 32 * kt + 16 * kb + 8 * lh]);
-          num = mfma32(va_, pb, num);
+      for (int tq = 0; tq < 2; ++tq) {
+        if (16 * kk < 32 * (tq + 1)) {
+          const bf16x8 pb = lds_read16(&sm.pt[(32 * tq + ln) * C::PROW + 16 * kk + 8 * lh]);
+          num[tq] = mfma32(va_, pb, num[tq]);
         }
       }
     }
-    // state update: A += phiK^T V, Z += colsum(phiK); then refresh the bf16 copy
-#pragma unroll
-    for (int i = 0; i < C::STILES; ++i) {
-      const int ti = wave * C::STILES + i, ct = ti / C::ET, et = ti % C::ET;
-#pragma unroll
-      for (int kk = 0; kk < CH / 16; ++kk) {
-        const bf16x8 fa = lds_operand(&sm.fkt[(32 * ct + ln) * C::TROW + 16 * kk + 8 * lh]);
-        const bf16x8 vb = lds_operand(&sm.vt[(32 * et + ln) * C::TROW + 16 * kk + 8 * lh]);
-        sacc[i] = mfma32(fa, vb, sacc[i]);
-      }
-    }
-    publish_state();
+    // state update: A += phiK^T V, Z += colsum(phiK)
     {
-      const float zs = chunk_feature_sum<D>(sm.fkt, tid);
-      if ((tid & 3) == 0) sm.z[zc ^ 1][tid >> 2] = sm.z[zc][tid >> 2] + zs;
+      float zs = update_state<D>(sacc, sm.fk, sm.v, wave, lane);
+      zs += __shfl_xor(zs, 32, 64);
+      const int zi = 32 * wave + kperm32(ln);
+      if (lh == 0) sm.z[zc ^ 1][zi] = sm.z[zc][zi] + zs;
     }
     __syncthreads();  // (4) denominators visible
-    const int qi = t0 + 32 * tq + ln;
-    if (qi < N) {
-      const float inv = 1.f / sm.den[32 * tq + ln];
-      uint16_t* orow = hp.o + (int64_t)qi * a.osn + 32 * et_n + 4 * lh;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 pk;
-        pk[0] = pack_bf16(num[4 * g + 0] * inv, num[4 * g + 1] * inv);
-        pk[1] = pack_bf16(num[4 * g + 2] * inv, num[4 * g + 3] * inv);
-        *reinterpret_cast<u32x2*>(orow + 8 * g) = pk;
+    for (int tq = 0; tq < 2; ++tq) {
+      const int qi = t0 + 32 * tq + ln;
+      if (qi < N) {
+        const float inv = 1.f / sm.den[32 * tq + ln];
+        uint16_t* orow = hp.o + (int64_t)qi * a.osn + 32 * wave + 4 * lh;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 pk;
+          pk[0] = pack_bf16(num[tq][4 * g + 0] * inv, num[tq][4 * g + 1] * inv);
+          pk[1] = pack_bf16(num[tq][4 * g + 2] * inv, num[tq][4 * g + 3] * inv);
+          *reinterpret_cast<u32x2*>(orow + 8 * g) = pk;
+        }
       }
     }
   }

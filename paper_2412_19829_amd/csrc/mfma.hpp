@@ -1,15 +1,20 @@
-// gfx950 matrix-core helpers shared by the bf16 kernels.
+// gfx950 matrix-core and LDS helpers shared by the bf16 kernels.
 //
 // Lane layout of v_mfma_f32_32x32x16_bf16 (D = A*B + C, A is 32x16, B is 16x32), lane l:
-//   A operand: row m = l % 32, k = 8*(l/32) .. 8*(l/32)+7          (8 bf16, 4 VGPRs)
-//   B operand: col n = l % 32, k = 8*(l/32) .. 8*(l/32)+7
+//   A operand: row m = l % 32, k-slots 8*(l/32) .. 8*(l/32)+7      (8 bf16, 4 VGPRs)
+//   B operand: col n = l % 32, k-slots 8*(l/32) .. 8*(l/32)+7
 //   C/D:       col n = l % 32, register r holds row m = 8*(r/4) + 4*(l/32) + r%4
-// A fp32 accumulator tile therefore keeps, per lane, one column and 16 of its rows; the rows a
-// lane owns in registers [8*kb, 8*kb+8) are exactly the 8 k-indices it must supply as a B
-// operand when the contraction index is permuted as
-//   pos(k) = 16*(k/16) + 8*((k/4)%2) + 4*((k/8)%2) + k%4          (within a 32-row tile)
-// so a score tile can feed the next MFMA straight from registers if the other operand is
-// stored in LDS in the same permuted order.
+// A fp32 accumulator tile therefore keeps, per lane, one column and 16 of its rows.  Registers
+// [8*kb, 8*kb+8) of a lane are rows 16*kb + 8*g + 4*(l/32) + j (g = 0..1, j = 0..3): fed back
+// as an MFMA operand they occupy k-slots 8*(l/32) + 4*g + j, i.e. the contraction index is
+// permuted inside each group of 32 by
+//   kperm32(k) = 16*(k/16) + 8*((k/4)%2) + 4*((k/8)%2) + k%4        (an involution)
+// An accumulator tile can thus feed the next MFMA straight from registers as long as the other
+// operand supplies its k-index in the same permuted order.
+//
+// LDS on this chip (measured): ds_read_b128 reaches ~220 B/clk/CU when 16 consecutive lanes
+// touch 64 distinct banks (row stride = 4 dwords mod 64); 64-bit reads, ds_read_b64_tr_b16
+// included, top out near 128 B/clk/CU; stores near 64-74 B/clk/CU.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -21,6 +26,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+typedef short v4i16_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -40,21 +46,37 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// Position of contraction index k (0..31) inside a permuted 32-group (see the top comment).
 __host__ __device__ constexpr int kperm32(int k) {
   return 16 * (k / 16) + 8 * ((k / 4) % 2) + 4 * ((k / 8) % 2) + k % 4;
 }
 
-// In-register transpose of a 4 (rows) x 8 (cols) bf16 block held as 4 x u32x4 (one row each)
-// into 8 x u32x2 (one column each: 4 consecutive rows).
-__device__ __forceinline__ void transpose_4x8_bf16(const u32x4 (&r)[4], u32x2 (&c)[8]) {
-#pragma unroll
-  for (int w = 0; w < 4; ++w) {  // dword w holds columns 2w (low half) and 2w+1 (high half)
-    c[2 * w][0] = __builtin_amdgcn_perm(r[1][w], r[0][w], 0x05040100u);
-    c[2 * w][1] = __builtin_amdgcn_perm(r[3][w], r[2][w], 0x05040100u);
-    c[2 * w + 1][0] = __builtin_amdgcn_perm(r[1][w], r[0][w], 0x07060302u);
-    c[2 * w + 1][1] = __builtin_amdgcn_perm(r[3][w], r[2][w], 0x07060302u);
-  }
+__device__ __forceinline__ bf16x8 lds_read16(const uint16_t* p) {
+  return as_bf16x8(*reinterpret_cast<const u32x4*>(p));
+}
+
+// LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane p passes the
+// address of 4 consecutive bf16; lane i of the group receives element (i % 4) of the values
+// addressed by lanes 4*j + i/4, j = 0..3.  With lane p pointing at row (row0 + p/4), columns
+// col0 + 4*(p%4) .. +3 of a row-major tile, lane i gets column col0 + i of rows row0 .. row0+3.
+__device__ __forceinline__ u32x2 lds_tr4(const uint16_t* p) {
+  const v4i16_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) v4i16_t*)(p));
+  return __builtin_bit_cast(u32x2, v);
+}
+
+// MFMA operand (lane l: row/col index l%32 of the operand = tile column col0 + l%32; 8 k-slots)
+// gathered from a ROW-MAJOR tile whose rows are the contraction index: slots 0..3 come from
+// tile rows rowA .. rowA+3 and slots 4..7 from rows rowB .. rowB+3 (callers add their own
+// dependence on l/32).  `stride` is the tile's row stride in elements.
+__device__ __forceinline__ bf16x8 lds_operand_tr(const uint16_t* tile, int stride, int rowA,
+                                                 int rowB, int col0, int lane) {
+  const int p = lane & 15;
+  const int col = col0 + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
+  const u32x2 a = lds_tr4(tile + (rowA + (p >> 2)) * stride + col);
+  const u32x2 b = lds_tr4(tile + (rowB + (p >> 2)) * stride + col);
+  u32x4 r;
+  r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+  return as_bf16x8(r);
 }
 
 }  // namespace gformer

@@ -2,8 +2,9 @@
 //
 // One workgroup (4 waves) owns 128 consecutive queries of one (batch, head); each wave owns 32
 // of them.  The band of keys those queries can see is walked in tiles of 64 keys; tiles outside
-// the band are never touched.  K tiles sit in LDS row-major, V tiles transposed (value column
-// major, keys in the permuted order of mfma.hpp), both shared by the 4 waves.
+// the band are never touched.  K and V tiles sit in LDS row-major, shared by the 4 waves; K is
+// read with 128-bit loads (contraction over the head dimension), V with the LDS transpose
+// read (contraction over keys).
 //
 // Per tile and wave:  S^T = K Q^T  (keys x queries, so one lane owns one query column and the
 // running max / sum / rescale are lane-local apart from one exchange between lane l and l^32),
@@ -21,10 +22,10 @@ constexpr int WQ = 32;               // queries per wave
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <int D> struct WinSmem {
-  static constexpr int KROW = D + 8;    // bf16 elements per K row (16 B pad: conflict-free b128)
-  static constexpr int VROW = BC + 8;   // bf16 elements per V^T row
+  static constexpr int KROW = D + 8;    // row stride = 4 dwords mod 64: conflict-free b128 reads
+  static constexpr int VROW = D + 32;   // row stride = 16 dwords mod 64: conflict-free tr reads
   uint16_t k[BC * KROW];
-  uint16_t vt[D * VROW];
+  uint16_t v[BC * VROW];
 };
 
 template <int D>
@@ -32,7 +33,6 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   constexpr int KS = D / 16;           // k-steps over the head dimension
   constexpr int MT = D / 32;           // 32-row tiles of O^T
   constexpr int KCH = BC * D / 8 / kMfmaWindowThreads;  // 16-byte K chunks per thread per tile
-  constexpr int VBLK = (BC / 4) * (D / 8);              // 4-key x 8-column V blocks per tile
   using Smem = WinSmem<D>;
   __shared__ __attribute__((aligned(16))) Smem sm;
 
@@ -76,10 +76,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
 
   // register staging of the next tile
   u32x4 kst[KCH];
-  u32x4 vst[4];
-  const bool v_loader = tid < VBLK;
-  const int va = tid / (D / 8);   // which group of 4 keys
-  const int vc8 = tid % (D / 8);  // which group of 8 value columns
+  u32x4 vst[KCH];
   auto load_tile = [&](int t) {
     const int t0 = t * BC;
 #pragma unroll
@@ -87,13 +84,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
       const int c = tid + i * kMfmaWindowThreads;
       const int row = min(t0 + c / (D / 8), N - 1);
       kst[i] = *reinterpret_cast<const u32x4*>(kp + (int64_t)row * a.k.sn + 8 * (c % (D / 8)));
-    }
-    if (v_loader) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int row = min(t0 + 4 * va + j, N - 1);
-        vst[j] = *reinterpret_cast<const u32x4*>(vp + (int64_t)row * a.v.sn + 8 * vc8);
-      }
+      vst[i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)row * a.v.sn + 8 * (c % (D / 8)));
     }
   };
   auto store_tile = [&]() {
@@ -101,14 +92,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
     for (int i = 0; i < KCH; ++i) {
       const int c = tid + i * kMfmaWindowThreads;
       *reinterpret_cast<u32x4*>(&sm.k[(c / (D / 8)) * Smem::KROW + 8 * (c % (D / 8))]) = kst[i];
-    }
-    if (v_loader) {
-      u32x2 col[8];
-      transpose_4x8_bf16(vst, col);
-      const int pos = kperm32((4 * va) % 32) + 32 * ((4 * va) / 32);
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-        *reinterpret_cast<u32x2*>(&sm.vt[(8 * vc8 + i) * Smem::VROW + pos]) = col[i];
+      *reinterpret_cast<u32x4*>(&sm.v[(c / (D / 8)) * Smem::VROW + 8 * (c % (D / 8))]) = vst[i];
     }
   };
 
@@ -189,8 +173,9 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
         const bf16x8 pbv = as_bf16x8(pw);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          const bf16x8 va_ = as_bf16x8(*reinterpret_cast<const u32x4*>(
-              &sm.vt[(32 * mt + ln) * Smem::VROW + 32 * kt + 16 * kb + 8 * lh]));
+          // keys in the order the score registers hold them: 16*kb + 4*lh + j, then + 8
+          const int r0 = 32 * kt + 16 * kb + 4 * lh;
+          const bf16x8 va_ = lds_operand_tr(sm.v, Smem::VROW, r0, r0 + 8, 32 * mt, lane);
           oacc[mt] = mfma32(va_, pbv, oacc[mt]);
         }
       }
