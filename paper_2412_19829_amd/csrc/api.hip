@@ -8,7 +8,7 @@
 
 namespace gformer {
 
-int mfma_linear_threads(int d) { return d == 128 ? 256 : 128; }
+int mfma_linear_threads(int d) { return d == 128 ? 512 : 256; }
 
 namespace {
 

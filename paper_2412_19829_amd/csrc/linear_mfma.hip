@@ -30,57 +30,73 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 template <int D> struct LinCfg {
   static constexpr int ET = D / 32;           // 32-wide tiles along a feature / value axis
-  static constexpr int NW = ET;               // waves per workgroup: one per value-column tile
-  static constexpr int NT = NW * 64;          // threads per workgroup
+  static constexpr int NWC = ET;              // compute waves: one per value-column tile
+  static constexpr int NTC = NWC * 64;        // compute threads
+  static constexpr int NT = 2 * NTC;          // + as many producer threads
   static constexpr int QROW = D + 8;          // phi(Q): 128-bit row reads   (stride = 4 dw mod 64)
   static constexpr int KROW = D + 16;         // phi(K): 64-bit row reads + transpose reads
   static constexpr int VROW = D + 32;         // V: transpose reads only     (stride = 16 dw mod 64)
   static constexpr int PROW = CH + 8;         // masked products, [query][key]
   static constexpr int C8 = D / 8;            // 16-byte pieces per row
-  static constexpr int PIECES = CH * C8 / NT; // pieces per thread per tensor per chunk (= 4)
+  static constexpr int RP = NTC / C8;         // rows covered by one pass of the producer threads
+  static constexpr int PIECES = CH / RP;      // pieces per producer thread per tensor per chunk
   static constexpr int STATE = D * D + D;     // floats per (A, Z) state
 };
 
-template <int D> struct LinSmem {
+template <int D> struct ChunkTiles {
   using C = LinCfg<D>;
   uint16_t fq[CH * C::QROW];   // phi(Q), feature index permuted by kperm32 inside 32-groups
   uint16_t fk[CH * C::KROW];   // phi(K), natural order
   uint16_t v[CH * C::VROW];    // V
+};
+
+template <int D> struct LinSmem {
+  using C = LinCfg<D>;
+  ChunkTiles<D> buf[2];        // chunk n in buf[n % 2]: producers fill one while the other is read
   uint16_t pt[CH * C::PROW];   // masked products P^T viewed as [query][key]
-  float z[2][D];               // Z in the same permuted feature order as fq; double-buffered
+  float z[2][D];               // Z in fq's permuted feature order; double-buffered across chunks
+  uint16_t zh[2][D];           // bf16(Z) and bf16(Z - bf16(Z)): Z to 16 mantissa bits for the
+  uint16_t zl[2][D];           // packed dot products of the denominator
   float den[CH];
 };
 
-template <int D> struct StateSmem {
+template <int D> struct StateTiles {
   using C = LinCfg<D>;
   uint16_t fk[CH * C::KROW];
   uint16_t v[CH * C::VROW];
 };
+template <int D> struct StateSmem {
+  StateTiles<D> buf[2];
+};
 
-// phi(x) = elu(x) + 1 = max(x + 1, min(exp(x), 1))   (section II-B)
+// phi(x) = elu(x) + 1 = max(x + 1, min(exp(x), 1))   (section II-B); the clamp rides on v_exp
 __device__ __forceinline__ float elu1(float x) {
-  const float e = fminf(__builtin_amdgcn_exp2f(x * kLog2e), 1.0f);
+  const float e = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(x * kLog2e), 0.0f, 1.0f);
   return fmaxf(x + 1.0f, e);
 }
 
-// Feature map on 8 packed bf16 values; invalid rows (past the sequence end) become zeros.
-__device__ __forceinline__ u32x4 map_features(u32x4 v, int phi, bool valid) {
+// Feature map on 8 packed bf16 values (ELU1 = true: phi(x) = elu(x)+1; false: identity).
+template <bool ELU1> __device__ __forceinline__ u32x4 map_features(u32x4 v) {
+  if (!ELU1) return v;
   u32x4 o;
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    float lo = bf16_lo(v[w]), hi = bf16_hi(v[w]);
-    if (phi == 0) { lo = elu1(lo); hi = elu1(hi); }
-    o[w] = valid ? pack_bf16(lo, hi) : 0u;
-  }
+  for (int w = 0; w < 4; ++w) o[w] = pack_bf16(elu1(bf16_lo(v[w])), elu1(bf16_hi(v[w])));
   return o;
 }
 
-__device__ __forceinline__ float sum8_bf16(bf16x8 x) {
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+// acc + a.lo*b.lo + a.hi*b.hi on packed bf16 pairs (v_dot2c_f32_bf16)
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
+                                         __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+constexpr uint32_t kOnesBf16x2 = 0x3f803f80u;
+
+__device__ __forceinline__ float sum8_bf16(bf16x8 x, float acc) {
   const u32x4 u = as_u32x4(x);
-  float s = 0.f;
 #pragma unroll
-  for (int w = 0; w < 4; ++w) s += bf16_lo(u[w]) + bf16_hi(u[w]);
-  return s;
+  for (int w = 0; w < 4; ++w) acc = dot2_bf16(u[w], kOnesBf16x2, acc);
+  return acc;
 }
 
 template <int D> struct HeadPtrs {
@@ -127,19 +143,51 @@ __device__ __forceinline__ float update_state(f32x16 (&sacc)[LinCfg<D>::ET], con
     for (int kk = 0; kk < CH / 16; ++kk) {
       const bf16x8 fa =
           lds_operand_tr(fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * ct, lane);
-      if (ct == wave) zs += sum8_bf16(fa);
+      if (ct == wave) zs = sum8_bf16(fa, zs);
       sacc[ct] = mfma32(fa, vb[kk], sacc[ct]);
     }
   }
   return zs;
 }
 
+// Producer-side view of one chunk: producer thread t moves 16-byte pieces (row r0 + i*RP,
+// columns col .. col+7), i = 0..PIECES-1, of each tensor from global memory to LDS.
+template <int D> struct Staging {
+  using C = LinCfg<D>;
+  int r0, col, qcol;
+  __device__ __forceinline__ explicit Staging(int ptid) : r0(ptid / C::C8), col(8 * (ptid % C::C8)) {
+    // phi(Q) pieces land at permuted feature positions: two groups of 4, 8 apart
+    const int c8 = ptid % C::C8;
+    qcol = 32 * (c8 / 4) + 16 * ((c8 % 4) / 2) + 4 * (c8 % 2);
+  }
+};
+
+// One tensor of one head as the producers read it: a uniform base pointer that advances by
+// whole chunks and a per-thread element offset that never changes, so a full chunk costs no
+// vector integer arithmetic.  Rows past N-1 (last chunk only) re-read row N-1, in bounds.
+template <int D> struct RowStream {
+  using C = LinCfg<D>;
+  const uint16_t* base;
+  int64_t sn;
+  uint32_t toff;
+  __device__ __forceinline__ RowStream(const uint16_t* b, int64_t sn_, const Staging<D>& st)
+      : base(b), sn(sn_), toff((uint32_t)(st.r0 * (int)sn_ + st.col)) {}
+  __device__ __forceinline__ u32x4 load(int t0, int i, int N, const Staging<D>& st) const {
+    if (t0 + CH <= N)
+      return *reinterpret_cast<const u32x4*>(base + (int64_t)(t0 + i * C::RP) * sn + toff);
+    return *reinterpret_cast<const u32x4*>(base + (int64_t)min(t0 + st.r0 + i * C::RP, N - 1) * sn + st.col);
+  }
+};
+
+constexpr u32x4 kZero4 = {0u, 0u, 0u, 0u};
+
 // -----------------------------------------------------------------------------------------
 // (1) per-segment state sums.  Workgroup (head, s) with s < n_segments-1 writes
 //     sum_{t in segment s} phi(k_t) (x) v_t  and  sum phi(k_t)  into workspace slot s+1.
+//     Waves [0, NWC) contract; waves [NWC, 2 NWC) load, map and stage the next chunk.
 // -----------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs a) {
+template <int D, bool ELU1>
+__global__ __launch_bounds__(LinCfg<D>::NT) void linear_state_kernel(AttnArgs a) {
   using C = LinCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   StateSmem<D>& sm = *reinterpret_cast<StateSmem<D>*>(smem_raw);
@@ -151,38 +199,60 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs
   const int N = a.N;
   const int seg_start = seg * a.segment_len;
   const int seg_end = min(N, seg_start + a.segment_len);
+  const int nchunks = (seg_end - seg_start + CH - 1) / CH;
 
+  if (wave >= C::NWC) {
+    // ---- producers ----
+    const Staging<D> st(tid - C::NTC);
+    const RowStream<D> ks(hp.k, a.k.sn, st), vs(hp.v, a.v.sn, st);
+    u32x4 ka[C::PIECES], va[C::PIECES], kb[C::PIECES], vb[C::PIECES];
+    auto load = [&](u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES], int n) {
+      const int t0 = seg_start + n * CH;
+#pragma unroll
+      for (int i = 0; i < C::PIECES; ++i) {
+        kr[i] = ks.load(t0, i, N, st);
+        vr[i] = vs.load(t0, i, N, st);
+      }
+    };
+    auto stage = [&](const u32x4 (&kr)[C::PIECES], const u32x4 (&vr)[C::PIECES], int n) {
+      const int t0 = seg_start + n * CH;
+      StateTiles<D>& b = sm.buf[n & 1];
+      const bool full = t0 + CH <= N;  // uniform; only the sequence's last chunk can be ragged
+#pragma unroll
+      for (int i = 0; i < C::PIECES; ++i) {
+        const int row = st.r0 + i * C::RP;
+        const bool valid = full || t0 + row < N;  // rows past the end contribute nothing
+        const u32x4 fk = map_features<ELU1>(kr[i]);
+        *reinterpret_cast<u32x4*>(&b.fk[row * C::KROW + st.col]) = valid ? fk : kZero4;
+        *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = valid ? vr[i] : kZero4;
+      }
+    };
+    load(ka, va, 0);
+    if (nchunks > 1) load(kb, vb, 1);
+    stage(ka, va, 0);
+    lds_barrier();
+    for (int n = 0; n < nchunks; n += 2) {
+      if (n + 2 < nchunks) load(ka, va, n + 2);
+      if (n + 1 < nchunks) stage(kb, vb, n + 1);
+      lds_barrier();
+      if (n + 1 >= nchunks) break;
+      if (n + 3 < nchunks) load(kb, vb, n + 3);
+      if (n + 2 < nchunks) stage(ka, va, n + 2);
+      lds_barrier();
+    }
+    return;
+  }
+  // ---- consumers ----
   f32x16 sacc[C::ET];
 #pragma unroll
   for (int i = 0; i < C::ET; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[i][r] = 0.f;
   float zacc = 0.f;
-
-  u32x4 kst[C::PIECES], vst[C::PIECES];
-  auto load_chunk = [&](int t0) {
-#pragma unroll
-    for (int i = 0; i < C::PIECES; ++i) {
-      const int c = tid + i * C::NT;
-      const int row = min(t0 + c / C::C8, N - 1);
-      kst[i] = *reinterpret_cast<const u32x4*>(hp.k + (int64_t)row * a.k.sn + 8 * (c % C::C8));
-      vst[i] = *reinterpret_cast<const u32x4*>(hp.v + (int64_t)row * a.v.sn + 8 * (c % C::C8));
-    }
-  };
-  load_chunk(seg_start);
-  for (int t0 = seg_start; t0 < seg_end; t0 += CH) {
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < C::PIECES; ++i) {
-      const int c = tid + i * C::NT;
-      const int row = c / C::C8, col = 8 * (c % C::C8);
-      const bool valid = t0 + row < N;
-      *reinterpret_cast<u32x4*>(&sm.fk[row * C::KROW + col]) = map_features(kst[i], a.phi, valid);
-      *reinterpret_cast<u32x4*>(&sm.v[row * C::VROW + col]) = valid ? vst[i] : u32x4{0u, 0u, 0u, 0u};
-    }
-    __syncthreads();
-    if (t0 + CH < seg_end) load_chunk(t0 + CH);
-    zacc += update_state<D>(sacc, sm.fk, sm.v, wave, lane);
+  lds_barrier();
+  for (int n = 0; n < nchunks; ++n) {
+    zacc += update_state<D>(sacc, sm.buf[n & 1].fk, sm.buf[n & 1].v, wave, lane);
+    lds_barrier();
   }
   float* dst = hp.state + (int64_t)(seg + 1) * C::STATE;
 #pragma unroll
@@ -210,9 +280,13 @@ __global__ __launch_bounds__(256) void linear_prefix_kernel(float* ws, int n_hea
 
 // -----------------------------------------------------------------------------------------
 // (3) read-out.  Workgroup (head, segment) walks its chunks carrying (A, Z).
+//     Waves [0, NWC): MFMA work, denominators, normalise + write.  Waves [NWC, 2 NWC): load
+//     chunk n+2 from global memory, apply phi to chunk n+1 and stage it in the other LDS buffer,
+//     so the feature map's vector work overlaps the matrix work of chunk n on every SIMD.
+//     Two workgroup barriers per chunk: (a) masked products visible, (b) buffers change hands.
 // -----------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_main_kernel(AttnArgs a) {
+template <int D, bool ELU1>
+__global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) {
   using C = LinCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   LinSmem<D>& sm = *reinterpret_cast<LinSmem<D>*>(smem_raw);
@@ -224,8 +298,87 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_main_kernel(AttnArgs 
   const int seg_start = seg * a.segment_len;
   const int seg_end = min(N, seg_start + a.segment_len);
   if (seg_start >= seg_end) return;  // uniform: nothing in this segment
+  const int nchunks = (seg_end - seg_start + CH - 1) / CH;
 
-  // carried state
+  if (wave >= C::NWC) {
+    // ---- producers ----
+    const Staging<D> st(tid - C::NTC);
+    const RowStream<D> qs(hp.q, a.q.sn, st), ks(hp.k, a.k.sn, st), vs(hp.v, a.v.sn, st);
+    u32x4 qa[C::PIECES], ka[C::PIECES], va[C::PIECES], qb[C::PIECES], kb[C::PIECES], vb[C::PIECES];
+    auto load = [&](u32x4 (&qr)[C::PIECES], u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES], int n) {
+      const int t0 = seg_start + n * CH;
+#pragma unroll
+      for (int i = 0; i < C::PIECES; ++i) {
+        qr[i] = qs.load(t0, i, N, st);
+        kr[i] = ks.load(t0, i, N, st);
+        vr[i] = vs.load(t0, i, N, st);
+      }
+    };
+    // phi(Q) of chunk n -> buf[n % 2]
+    auto stage_q = [&](const u32x4 (&qr)[C::PIECES], int n) {
+      ChunkTiles<D>& b = sm.buf[n & 1];
+#pragma unroll
+      for (int i = 0; i < C::PIECES; ++i) {
+        const u32x4 fqv = map_features<ELU1>(qr[i]);
+        uint16_t* qd = &b.fq[(st.r0 + i * C::RP) * C::QROW + st.qcol];
+        *reinterpret_cast<u32x2*>(qd) = u32x2{fqv[0], fqv[1]};
+        *reinterpret_cast<u32x2*>(qd + 8) = u32x2{fqv[2], fqv[3]};
+      }
+    };
+    // phi(K) and V of chunk n -> buf[n % 2]; rows past the sequence end become zeros
+    auto stage_kv = [&](const u32x4 (&kr)[C::PIECES], const u32x4 (&vr)[C::PIECES], int n) {
+      const int t0 = seg_start + n * CH;
+      ChunkTiles<D>& b = sm.buf[n & 1];
+      if (t0 + CH <= N) {
+#pragma unroll
+        for (int i = 0; i < C::PIECES; ++i) {
+          const int row = st.r0 + i * C::RP;
+          *reinterpret_cast<u32x4*>(&b.fk[row * C::KROW + st.col]) = map_features<ELU1>(kr[i]);
+          *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = vr[i];
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < C::PIECES; ++i) {
+          const int row = st.r0 + i * C::RP;
+          const bool valid = t0 + row < N;
+          const u32x4 fk = map_features<ELU1>(kr[i]);
+          *reinterpret_cast<u32x4*>(&b.fk[row * C::KROW + st.col]) = valid ? fk : kZero4;
+          *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = valid ? vr[i] : kZero4;
+        }
+      }
+    };
+    load(qa, ka, va, 0);
+    if (nchunks > 1) load(qb, kb, vb, 1);
+    stage_q(qa, 0);
+    stage_kv(ka, va, 0);
+    lds_barrier();  // chunk 0 staged
+    // Per chunk n the consumers run [products, state read-out] (a) [denominators, in-chunk
+    // part, state update] (b) [normalise, write].  The staging of chunk n+1 is split the same
+    // way so that neither side idles at a barrier: phi(Q) before (a), phi(K) and V before (b).
+    for (int n = 0; n < nchunks; n += 2) {
+      if (n + 1 < nchunks) stage_q(qb, n + 1);
+      lds_barrier();  // (a)
+      if (n + 1 < nchunks) stage_kv(kb, vb, n + 1);
+      if (n + 2 < nchunks) load(qa, ka, va, n + 2);
+      lds_barrier();  // (b)
+      if (n + 1 >= nchunks) break;
+      if (n + 2 < nchunks) stage_q(qa, n + 2);
+      lds_barrier();  // (a)
+      if (n + 2 < nchunks) stage_kv(ka, va, n + 2);
+      if (n + 3 < nchunks) load(qb, kb, vb, n + 3);
+      lds_barrier();  // (b)
+    }
+    return;
+  }
+
+  // ---- consumers ----
+  // Z lives in LDS as fp32 plus a bf16 hi/lo split, in fq's permuted feature order
+  auto put_z = [&](int buf, int zi, float zval) {
+    sm.z[buf][zi] = zval;
+    const uint16_t hi = (uint16_t)(pack_bf16(zval, 0.f) & 0xffffu);
+    sm.zh[buf][zi] = hi;
+    sm.zl[buf][zi] = (uint16_t)(pack_bf16(zval - __uint_as_float((uint32_t)hi << 16), 0.f) & 0xffffu);
+  };
   f32x16 sacc[C::ET];
   const float* src = (seg > 0 && hp.state) ? hp.state + (int64_t)seg * C::STATE : nullptr;
 #pragma unroll
@@ -233,49 +386,20 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_main_kernel(AttnArgs 
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       sacc[ct][r] = src ? src[state_index<D>(ct, wave, r, ln, lh)] : 0.f;
-  if (lh == 0) sm.z[0][32 * wave + kperm32(ln)] = src ? src[D * D + 32 * wave + ln] : 0.f;
+  if (lh == 0) put_z(0, 32 * wave + kperm32(ln), src ? src[D * D + 32 * wave + ln] : 0.f);
+  lds_barrier();  // chunk 0 staged, Z visible
 
-  // global -> register staging, row-major 16-byte pieces
-  u32x4 qst[C::PIECES], kst[C::PIECES], vst[C::PIECES];
-  auto load_chunk = [&](int t0) {
-#pragma unroll
-    for (int i = 0; i < C::PIECES; ++i) {
-      const int c = tid + i * C::NT;
-      const int row = min(t0 + c / C::C8, N - 1);
-      const int col = 8 * (c % C::C8);
-      qst[i] = *reinterpret_cast<const u32x4*>(hp.q + (int64_t)row * a.q.sn + col);
-      kst[i] = *reinterpret_cast<const u32x4*>(hp.k + (int64_t)row * a.k.sn + col);
-      vst[i] = *reinterpret_cast<const u32x4*>(hp.v + (int64_t)row * a.v.sn + col);
-    }
-  };
-
-  constexpr int PPT = C::NT / CH;  // threads per query in the denominator
-  load_chunk(seg_start);
-  int zc = 0;
-  for (int t0 = seg_start; t0 < seg_end; t0 += CH, zc ^= 1) {
-    __syncthreads();  // (1) previous chunk fully consumed
-#pragma unroll
-    for (int i = 0; i < C::PIECES; ++i) {
-      const int c = tid + i * C::NT;
-      const int row = c / C::C8, c8 = c % C::C8, col = 8 * c8;
-      const bool valid = t0 + row < N;
-      // phi(Q): features 8*c8 .. +7 go to permuted positions (two groups of 4, 8 apart)
-      const u32x4 fqv = map_features(qst[i], a.phi, true);
-      const int x = c8 % 4;
-      uint16_t* qd = &sm.fq[row * C::QROW + 32 * (c8 / 4) + 16 * (x / 2) + 4 * (x % 2)];
-      *reinterpret_cast<u32x2*>(qd) = u32x2{fqv[0], fqv[1]};
-      *reinterpret_cast<u32x2*>(qd + 8) = u32x2{fqv[2], fqv[3]};
-      *reinterpret_cast<u32x4*>(&sm.fk[row * C::KROW + col]) = map_features(kst[i], a.phi, valid);
-      *reinterpret_cast<u32x4*>(&sm.v[row * C::VROW + col]) = valid ? vst[i] : u32x4{0u, 0u, 0u, 0u};
-    }
-    __syncthreads();  // (2) chunk tiles (and on the first pass Z) visible
-    if (t0 + CH < seg_end) load_chunk(t0 + CH);
+  constexpr int PPT = C::NTC / CH;  // threads per query in the denominator
+  for (int n = 0; n < nchunks; ++n) {
+    const int t0 = seg_start + n * CH;
+    const int zc = n & 1;
+    const ChunkTiles<D>& b = sm.buf[n & 1];
 
     // masked products P^T[key][query] = phi(k_key).phi(q_query), key <= query: three 32x32
-    // tiles (the fourth lies above the diagonal), dealt round-robin to the waves
+    // tiles (the fourth lies above the diagonal), dealt round-robin to the compute waves
 #pragma unroll
     for (int tile = 0; tile < 3; ++tile) {
-      if (tile % C::NW != wave) continue;
+      if (tile % C::NWC != wave) continue;
       const int tk = tile == 2 ? 1 : 0, tqa = tile == 0 ? 0 : 1;
       f32x16 p;
 #pragma unroll
@@ -283,12 +407,12 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_main_kernel(AttnArgs 
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
         // k-slot 8*lh + 4*g + j of this step is feature 16*ks + 8*g + 4*lh + j
-        const uint16_t* kr = &sm.fk[(32 * tk + ln) * C::KROW + 16 * ks + 4 * lh];
+        const uint16_t* kr = &b.fk[(32 * tk + ln) * C::KROW + 16 * ks + 4 * lh];
         const u32x2 k0 = *reinterpret_cast<const u32x2*>(kr);
         const u32x2 k1 = *reinterpret_cast<const u32x2*>(kr + 8);
-        const bf16x8 ka = as_bf16x8(u32x4{k0[0], k0[1], k1[0], k1[1]});
-        const bf16x8 qb = lds_read16(&sm.fq[(32 * tqa + ln) * C::QROW + 16 * ks + 8 * lh]);
-        p = mfma32(ka, qb, p);
+        const bf16x8 ka_ = as_bf16x8(u32x4{k0[0], k0[1], k1[0], k1[1]});
+        const bf16x8 qb_ = lds_read16(&b.fq[(32 * tqa + ln) * C::QROW + 16 * ks + 8 * lh]);
+        p = mfma32(ka_, qb_, p);
       }
       if (tk == tqa) {
 #pragma unroll
@@ -312,21 +436,22 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_main_kernel(AttnArgs 
 #pragma unroll
     for (int ct = 0; ct < C::ET; ++ct) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int kb_ = 0; kb_ < 2; ++kb_) {
         u32x4 sw;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sw[i] = pack_bf16(sacc[ct][8 * kb + 2 * i], sacc[ct][8 * kb + 2 * i + 1]);
+        for (int i = 0; i < 4; ++i) sw[i] = pack_bf16(sacc[ct][8 * kb_ + 2 * i], sacc[ct][8 * kb_ + 2 * i + 1]);
         const bf16x8 sa = as_bf16x8(sw);
 #pragma unroll
         for (int tq = 0; tq < 2; ++tq) {
-          const bf16x8 qb = lds_read16(&sm.fq[(32 * tq + ln) * C::QROW + 32 * ct + 16 * kb + 8 * lh]);
-          num[tq] = mfma32(sa, qb, num[tq]);
+          const bf16x8 qv = lds_read16(&b.fq[(32 * tq + ln) * C::QROW + 32 * ct + 16 * kb_ + 8 * lh]);
+          num[tq] = mfma32(sa, qv, num[tq]);
         }
       }
     }
-    __syncthreads();  // (3) products visible
+    lds_barrier();  // (a) products visible
 
-    // denominator: rowsum of the (rounded) products + phi(q).Z_prev, PPT threads per query
+    // denominator: rowsum of the (rounded) products + phi(q).Z_prev, PPT threads per query,
+    // all on packed bf16 pairs
     {
       const int qrow = tid / PPT, part = tid % PPT;
       constexpr int KW = CH / PPT;  // product slots per thread
@@ -338,17 +463,18 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_main_kernel(AttnArgs 
         if (KW * part + x < kvis) {
           const u32x4 pv = *reinterpret_cast<const u32x4*>(&sm.pt[qrow * C::PROW + KW * part + x]);
 #pragma unroll
-          for (int w = 0; w < 4; ++w) s += bf16_lo(pv[w]) + bf16_hi(pv[w]);
+          for (int w = 0; w < 4; ++w) s = dot2_bf16(pv[w], kOnesBf16x2, s);
         }
       }
 #pragma unroll
       for (int x = 0; x < CW; x += 8) {
-        const u32x4 qv = *reinterpret_cast<const u32x4*>(&sm.fq[qrow * C::QROW + CW * part + x]);
-        const float* zz = &sm.z[zc][CW * part + x];
+        const u32x4 qv = *reinterpret_cast<const u32x4*>(&b.fq[qrow * C::QROW + CW * part + x]);
+        const u32x4 zh = *reinterpret_cast<const u32x4*>(&sm.zh[zc][CW * part + x]);
+        const u32x4 zl = *reinterpret_cast<const u32x4*>(&sm.zl[zc][CW * part + x]);
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          s = fmaf(bf16_lo(qv[w]), zz[2 * w], s);
-          s = fmaf(bf16_hi(qv[w]), zz[2 * w + 1], s);
+          s = dot2_bf16(qv[w], zh[w], s);
+          s = dot2_bf16(qv[w], zl[w], s);
         }
       }
 #pragma unroll
@@ -359,7 +485,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_main_kernel(AttnArgs 
 #pragma unroll
     for (int kk = 0; kk < CH / 16; ++kk) {
       const bf16x8 va_ =
-          lds_operand_tr(sm.v, C::VROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
+          lds_operand_tr(b.v, C::VROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
 #pragma unroll
       for (int tq = 0; tq < 2; ++tq) {
         if (16 * kk < 32 * (tq + 1)) {
@@ -370,12 +496,12 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_main_kernel(AttnArgs 
     }
     // state update: A += phiK^T V, Z += colsum(phiK)
     {
-      float zs = update_state<D>(sacc, sm.fk, sm.v, wave, lane);
+      float zs = update_state<D>(sacc, b.fk, b.v, wave, lane);
       zs += __shfl_xor(zs, 32, 64);
       const int zi = 32 * wave + kperm32(ln);
-      if (lh == 0) sm.z[zc ^ 1][zi] = sm.z[zc][zi] + zs;
+      if (lh == 0) put_z(zc ^ 1, zi, sm.z[zc][zi] + zs);
     }
-    __syncthreads();  // (4) denominators visible
+    lds_barrier();  // (b) denominators visible; this chunk's tiles are free again
 #pragma unroll
     for (int tq = 0; tq < 2; ++tq) {
       const int qi = t0 + 32 * tq + ln;
@@ -394,15 +520,24 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_main_kernel(AttnArgs 
   }
 }
 
+template <typename K> hipError_t allow_lds(K kern, int smem) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+}
+
 template <int D> hipError_t launch_state_t(const AttnArgs& a, hipStream_t s) {
   using C = LinCfg<D>;
   const int heads = a.B * (a.H - a.H0);
-  auto kern = linear_state_kernel<D>;
   const int smem = (int)sizeof(StateSmem<D>);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-  if (e != hipSuccess) return e;
-  kern<<<dim3(heads * (a.n_segments - 1)), dim3(C::NT), smem, s>>>(a);
+  const dim3 grid(heads * (a.n_segments - 1)), block(C::NT);
+  hipError_t e;
+  if (a.phi == 0) {
+    if ((e = allow_lds(linear_state_kernel<D, true>, smem)) != hipSuccess) return e;
+    linear_state_kernel<D, true><<<grid, block, smem, s>>>(a);
+  } else {
+    if ((e = allow_lds(linear_state_kernel<D, false>, smem)) != hipSuccess) return e;
+    linear_state_kernel<D, false><<<grid, block, smem, s>>>(a);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (a.n_segments > 2) {
     linear_prefix_kernel<<<dim3((C::STATE + 255) / 256, heads), dim3(256), 0, s>>>(
@@ -415,12 +550,16 @@ template <int D> hipError_t launch_state_t(const AttnArgs& a, hipStream_t s) {
 template <int D> hipError_t launch_main_t(const AttnArgs& a, hipStream_t s) {
   using C = LinCfg<D>;
   const int heads = a.B * (a.H - a.H0);
-  auto kern = linear_main_kernel<D>;
   const int smem = (int)sizeof(LinSmem<D>);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-  if (e != hipSuccess) return e;
-  kern<<<dim3(heads * a.n_segments), dim3(C::NT), smem, s>>>(a);
+  const dim3 grid(heads * a.n_segments), block(C::NT);
+  hipError_t e;
+  if (a.phi == 0) {
+    if ((e = allow_lds(linear_main_kernel<D, true>, smem)) != hipSuccess) return e;
+    linear_main_kernel<D, true><<<grid, block, smem, s>>>(a);
+  } else {
+    if ((e = allow_lds(linear_main_kernel<D, false>, smem)) != hipSuccess) return e;
+    linear_main_kernel<D, false><<<grid, block, smem, s>>>(a);
+  }
   return hipGetLastError();
 }
 

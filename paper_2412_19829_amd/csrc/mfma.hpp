@@ -50,6 +50,15 @@ __host__ __device__ constexpr int kperm32(int k) {
   return 16 * (k / 16) + 8 * ((k / 4) % 2) + 4 * ((k / 8) % 2) + k % 4;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load and store (vmcnt(0)), which would expose the full memory latency of
+// prefetches that are deliberately left in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __device__ __forceinline__ bf16x8 lds_read16(const uint16_t* p) {
   return as_bf16x8(*reinterpret_cast<const u32x4*>(p));
 }

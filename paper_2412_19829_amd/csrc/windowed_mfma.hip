@@ -98,9 +98,9 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
 
   load_tile(kfirst);
   for (int t = kfirst; t <= klast; ++t) {
-    __syncthreads();  // every wave is done reading the previous tile
+    lds_barrier();  // every wave is done reading the previous tile
     store_tile();
-    __syncthreads();
+    lds_barrier();
     if (t < klast) load_tile(t + 1);  // in flight while this tile is computed
 
     const int t0 = t * BC;
