@@ -37,6 +37,7 @@ template <int D> struct LinCfg {
   static constexpr int KROW = D + 16;         // phi(K): 64-bit row reads + transpose reads
   static constexpr int VROW = D + 32;         // V: transpose reads only     (stride = 16 dw mod 64)
   static constexpr int PROW = CH + 8;         // masked products, [query][key]
+  static constexpr int OROW = D + 8;          // normalised output rows on their way to memory
   static constexpr int C8 = D / 8;            // 16-byte pieces per row
   static constexpr int RP = NTC / C8;         // rows covered by one pass of the producer threads
   static constexpr int PIECES = CH / RP;      // pieces per producer thread per tensor per chunk
@@ -58,6 +59,7 @@ template <int D> struct LinSmem {
   uint16_t zh[2][D];           // bf16(Z) and bf16(Z - bf16(Z)): Z to 16 mantissa bits for the
   uint16_t zl[2][D];           // packed dot products of the denominator
   float den[CH];
+  uint16_t ot[CH * C::OROW];   // finished output rows of the previous chunk, [query][value]
 };
 
 template <int D> struct StateTiles {
@@ -347,27 +349,43 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
         }
       }
     };
+    // finished rows of chunk n: LDS -> global, 16 bytes per lane, whole rows per 16 lanes
+    auto store_out = [&](int n) {
+      const int t0 = seg_start + n * CH;
+#pragma unroll
+      for (int i = 0; i < C::PIECES; ++i) {
+        const int row = st.r0 + i * C::RP;
+        const u32x4 o = *reinterpret_cast<const u32x4*>(&sm.ot[row * C::OROW + st.col]);
+        if (t0 + row < N)
+          *reinterpret_cast<u32x4*>(hp.o + (int64_t)(t0 + row) * a.osn + st.col) = o;
+      }
+    };
     load(qa, ka, va, 0);
     if (nchunks > 1) load(qb, kb, vb, 1);
     stage_q(qa, 0);
     stage_kv(ka, va, 0);
     lds_barrier();  // chunk 0 staged
     // Per chunk n the consumers run [products, state read-out] (a) [denominators, in-chunk
-    // part, state update] (b) [normalise, write].  The staging of chunk n+1 is split the same
-    // way so that neither side idles at a barrier: phi(Q) before (a), phi(K) and V before (b).
+    // part, state update] (b) [normalise into LDS].  The producers' work for chunk n+1 is split
+    // the same way so that neither side idles at a barrier: phi(Q) before (a); after (a) the
+    // write-out of chunk n-1, phi(K), V and the loads of chunk n+2.
     for (int n = 0; n < nchunks; n += 2) {
       if (n + 1 < nchunks) stage_q(qb, n + 1);
       lds_barrier();  // (a)
+      if (n > 0) store_out(n - 1);
       if (n + 1 < nchunks) stage_kv(kb, vb, n + 1);
       if (n + 2 < nchunks) load(qa, ka, va, n + 2);
       lds_barrier();  // (b)
       if (n + 1 >= nchunks) break;
       if (n + 2 < nchunks) stage_q(qa, n + 2);
       lds_barrier();  // (a)
+      store_out(n);
       if (n + 2 < nchunks) stage_kv(ka, va, n + 2);
       if (n + 3 < nchunks) load(qb, kb, vb, n + 3);
       lds_barrier();  // (b)
     }
+    lds_barrier();  // (c) last chunk's rows are in LDS
+    store_out(nchunks - 1);
     return;
   }
 
@@ -387,20 +405,28 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
     for (int r = 0; r < 16; ++r)
       sacc[ct][r] = src ? src[state_index<D>(ct, wave, r, ln, lh)] : 0.f;
   if (lh == 0) put_z(0, 32 * wave + kperm32(ln), src ? src[D * D + 32 * wave + ln] : 0.f);
+  // the product tile above the diagonal (keys 32.., queries ..31) is never computed: it stays 0
+  for (int x = tid; x < 32 * 32 / 8; x += C::NTC)
+    *reinterpret_cast<u32x4*>(&sm.pt[(x / 4) * C::PROW + 32 + 8 * (x % 4)]) = kZero4;
+  __builtin_amdgcn_s_setprio(2);  // matrix waves first; the staging waves fill the gaps
   lds_barrier();  // chunk 0 staged, Z visible
 
   constexpr int PPT = C::NTC / CH;  // threads per query in the denominator
   for (int n = 0; n < nchunks; ++n) {
-    const int t0 = seg_start + n * CH;
     const int zc = n & 1;
     const ChunkTiles<D>& b = sm.buf[n & 1];
 
     // masked products P^T[key][query] = phi(k_key).phi(q_query), key <= query: three 32x32
-    // tiles (the fourth lies above the diagonal), dealt round-robin to the compute waves
+    // tiles (the fourth lies above the diagonal).  Tile t goes to wave t % NWC; code is kept
+    // branch-free (waves without a tile recompute tile 0 and drop it) so that it can be
+    // scheduled together with the state read-out below.
+    constexpr int NTILE = (3 + C::NWC - 1) / C::NWC;  // product tiles per wave
 #pragma unroll
-    for (int tile = 0; tile < 3; ++tile) {
-      if (tile % C::NWC != wave) continue;
-      const int tk = tile == 2 ? 1 : 0, tqa = tile == 0 ? 0 : 1;
+    for (int rep = 0; rep < NTILE; ++rep) {
+      const int tile = wave + rep * C::NWC;
+      const bool mine = tile < 3;
+      const int tk = tile == 2 ? 1 : 0, tqa = (tile == 1 || tile == 2) ? 1 : 0;
+      const bool diag = tk == tqa;
       f32x16 p;
 #pragma unroll
       for (int r = 0; r < 16; ++r) p[r] = 0.f;
@@ -414,17 +440,17 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
         const bf16x8 qb_ = lds_read16(&b.fq[(32 * tqa + ln) * C::QROW + 16 * ks + 8 * lh]);
         p = mfma32(ka_, qb_, p);
       }
-      if (tk == tqa) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (8 * (r / 4) + 4 * lh + (r % 4) > ln) p[r] = 0.f;
-      }
+      for (int r = 0; r < 16; ++r)
+        if (diag && 8 * (r / 4) + 4 * lh + (r % 4) > ln) p[r] = 0.f;
+      if (mine) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 pk;
-        pk[0] = pack_bf16(p[4 * g + 0], p[4 * g + 1]);
-        pk[1] = pack_bf16(p[4 * g + 2], p[4 * g + 3]);
-        *reinterpret_cast<u32x2*>(&sm.pt[(32 * tqa + ln) * C::PROW + 32 * tk + 8 * g + 4 * lh]) = pk;
+        for (int g = 0; g < 4; ++g) {
+          u32x2 pk;
+          pk[0] = pack_bf16(p[4 * g + 0], p[4 * g + 1]);
+          pk[1] = pack_bf16(p[4 * g + 2], p[4 * g + 3]);
+          *reinterpret_cast<u32x2*>(&sm.pt[(32 * tqa + ln) * C::PROW + 32 * tk + 8 * g + 4 * lh]) = pk;
+        }
       }
     }
     // num^T = A^T phiQ^T with A straight from the state registers
@@ -457,14 +483,11 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       constexpr int KW = CH / PPT;  // product slots per thread
       constexpr int CW = D / PPT;   // features per thread
       float s = 0.f;
-      const int kvis = qrow < 32 ? 32 : 64;  // keys >= 32 are never visible to the first 32 queries
 #pragma unroll
-      for (int x = 0; x < KW; x += 8) {
-        if (KW * part + x < kvis) {
-          const u32x4 pv = *reinterpret_cast<const u32x4*>(&sm.pt[qrow * C::PROW + KW * part + x]);
+      for (int x = 0; x < KW; x += 8) {  // the never-visible tile holds zeros
+        const u32x4 pv = *reinterpret_cast<const u32x4*>(&sm.pt[qrow * C::PROW + KW * part + x]);
 #pragma unroll
-          for (int w = 0; w < 4; ++w) s = dot2_bf16(pv[w], kOnesBf16x2, s);
-        }
+        for (int w = 0; w < 4; ++w) s = dot2_bf16(pv[w], kOnesBf16x2, s);
       }
 #pragma unroll
       for (int x = 0; x < CW; x += 8) {
@@ -502,22 +525,21 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       if (lh == 0) put_z(zc ^ 1, zi, sm.z[zc][zi] + zs);
     }
     lds_barrier();  // (b) denominators visible; this chunk's tiles are free again
+    // normalise; the rows go to LDS and the producers write them out in whole rows
 #pragma unroll
     for (int tq = 0; tq < 2; ++tq) {
-      const int qi = t0 + 32 * tq + ln;
-      if (qi < N) {
-        const float inv = 1.f / sm.den[32 * tq + ln];
-        uint16_t* orow = hp.o + (int64_t)qi * a.osn + 32 * wave + 4 * lh;
+      const float inv = 1.f / sm.den[32 * tq + ln];
+      uint16_t* orow = &sm.ot[(32 * tq + ln) * C::OROW + 32 * wave + 4 * lh];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          u32x2 pk;
-          pk[0] = pack_bf16(num[tq][4 * g + 0] * inv, num[tq][4 * g + 1] * inv);
-          pk[1] = pack_bf16(num[tq][4 * g + 2] * inv, num[tq][4 * g + 3] * inv);
-          *reinterpret_cast<u32x2*>(orow + 8 * g) = pk;
-        }
+      for (int g = 0; g < 4; ++g) {
+        u32x2 pk;
+        pk[0] = pack_bf16(num[tq][4 * g + 0] * inv, num[tq][4 * g + 1] * inv);
+        pk[1] = pack_bf16(num[tq][4 * g + 2] * inv, num[tq][4 * g + 3] * inv);
+        *reinterpret_cast<u32x2*>(orow + 8 * g) = pk;
       }
     }
   }
+  lds_barrier();  // (c)
 }
 
 template <typename K> hipError_t allow_lds(K kern, int smem) {
