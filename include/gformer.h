@@ -26,10 +26,15 @@
  *     mean dense [B, H, N, d].  The paper's [B, N, H, E] layout is stride = {N*H*d, d, H*d}.
  *     Strides must be multiples of 8 elements (16-byte rows for bf16).
  *   - `workspace` is a DEVICE pointer of at least gformer_attn_workspace_bytes(...) bytes,
- *     256-byte aligned; may be NULL when that size is 0.  It holds the per-segment linear
- *     attention states and is fully rewritten by every call that uses it.
+ *     256-byte aligned; may be NULL when that size is 0.  It holds the linear-attention
+ *     states carried into each piece and is rewritten by every call that uses it.
  *   - `hip_stream` is a hipStream_t (NULL = default stream).  The call enqueues kernels and
- *     returns; it never synchronises.
+ *     returns; it never synchronises.  When both head groups are present the windowed heads
+ *     are enqueued on one library-owned, default-priority side stream per device that waits
+ *     for the work already in `hip_stream` and that `hip_stream` waits for before going on
+ *     (an event fork/join, also valid under stream capture); the stream and its two events are
+ *     created on first use and kept until the process ends.  Calls are serialised by a mutex
+ *     while they enqueue.
  *   - No exception crosses this boundary.  Argument errors are detected on the host before
  *     anything is launched and reported through gf_status.
  *   - Supported: d in {64, 128}; any N >= 0 (N == 0 or B*H == 0 is a no-op); any window >= 1
@@ -69,13 +74,19 @@ typedef struct gformer_params {
   int32_t phi;            /* gf_phi, linear heads only                                       */
   int32_t n_sparse_heads; /* H0: heads [0,H0) windowed softmax, heads [H0,H) causal linear   */
   int32_t chunk;          /* linear-attention chunk C: 64, or 0 = library picks               */
-  int32_t segment_len;    /* tokens per linear-attention segment (multiple of chunk);        */
-                          /* 0 = library picks.  Segments of one head run in parallel and    */
-                          /* are stitched with a prefix over their (A, Z) states.            */
+  int32_t segment_len;    /* 0 = library picks: the chunks of all linear heads are cut into  */
+                          /* equal pieces with no regard to head boundaries, one workgroup   */
+                          /* each.  > 0 (multiple of chunk): every head is cut into segments */
+                          /* of this many tokens.  Either way pieces run in parallel and are */
+                          /* stitched with a prefix over their (A, Z) states.                */
   int32_t impl;           /* gf_impl                                                         */
   int32_t launch_mask;    /* 0 = everything.  Otherwise a bit set of GF_LAUNCH_*: only those */
                           /* kernels are enqueued (profiling aid; the skipped stages' data   */
                           /* is taken as already present in the workspace).                  */
+  int32_t no_overlap;     /* 0: the windowed heads run on a library-owned side stream that   */
+                          /* forks from and joins `hip_stream`, next to the linear heads.    */
+                          /* 1: everything is enqueued on `hip_stream` one after another.    */
+  int32_t reserved0;
   float softmax_scale;    /* multiplies q.k on windowed heads; 1.0 when Q is pre-scaled      */
   float eps;              /* added to the linear denominator; 0 follows Algorithm 1          */
   int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3]; /* (b, h, n) element strides   */
@@ -83,7 +94,7 @@ typedef struct gformer_params {
 
 enum {
   GF_LAUNCH_WINDOWED = 1,     /* windowed softmax heads                                */
-  GF_LAUNCH_LINEAR_STATE = 2, /* per-segment (A, Z) sums + their exclusive prefix      */
+  GF_LAUNCH_LINEAR_STATE = 2, /* per-piece (A, Z) sums + their prefix inside each head */
   GF_LAUNCH_LINEAR_MAIN = 4   /* linear heads read-out                                 */
 };
 
@@ -91,19 +102,20 @@ enum {
 typedef struct gformer_plan {
   int32_t impl;             /* resolved gf_impl (SCALAR or MFMA)                        */
   int32_t chunk;            /* resolved linear chunk C                                  */
-  int32_t segment_len;      /* resolved tokens per segment                              */
-  int32_t n_segments;       /* segments per linear head                                 */
+  int32_t segment_len;      /* resolved tokens per piece of linear-attention work       */
+  int32_t n_segments;       /* pieces in total (= linear_blocks)                        */
   int32_t windowed_blocks;  /* workgroups of the windowed kernel (0 if H0 == 0)         */
   int32_t windowed_threads;
   int32_t linear_blocks;    /* workgroups of the linear read-out kernel (0 if H0 == H)  */
   int32_t linear_threads;
-  int32_t state_blocks;     /* workgroups of the segment-state kernel (0 if 1 segment)  */
+  int32_t state_blocks;     /* pieces that start inside a head and need a carried state */
   int32_t reserved;
   uint64_t workspace_bytes;
 } gformer_plan;
 
 /* Fills `p` with defaults: struct_size, dtype = GF_BF16, phi = GF_PHI_ELU1, H0 = 0, chunk,
- * segment_len, impl, launch_mask = 0, softmax_scale = 1, eps = 0, dense strides. */
+ * segment_len, impl, launch_mask = 0, no_overlap = 0, softmax_scale = 1, eps = 0, dense
+ * strides. */
 void gformer_params_init(gformer_params* p);
 
 /* Bytes of device workspace gformer_attn_fwd needs for these arguments (0 if none).

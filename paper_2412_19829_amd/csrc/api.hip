@@ -4,6 +4,8 @@
 
 #include <string.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 namespace gformer {
@@ -15,7 +17,37 @@ namespace {
 struct Resolved {
   gformer_plan plan;
   int64_t qs[3], ks[3], vs[3], os[3];
+  int cph, vcph, piece_chunks;
 };
+
+constexpr long kComputeUnits = 256;  // MI355X
+
+// One side stream and a fork/join event pair per device, created on first use and kept for the
+// life of the process.  Default priority on purpose.
+constexpr int kMaxDevices = 64;
+struct SideStream {
+  bool ready = false;
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+SideStream g_side[kMaxDevices];
+std::mutex g_enqueue_mutex;
+
+hipError_t side_stream_for_current_device(SideStream** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  SideStream& s = g_side[dev];
+  if (!s.ready) {
+    if ((e = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking)) != hipSuccess) return e;
+    if ((e = hipEventCreateWithFlags(&s.fork, hipEventDisableTiming)) != hipSuccess) return e;
+    if ((e = hipEventCreateWithFlags(&s.join, hipEventDisableTiming)) != hipSuccess) return e;
+    s.ready = true;
+  }
+  *out = &s;
+  return hipSuccess;
+}
 
 bool strides_all_zero(const int64_t* s) { return s[0] == 0 && s[1] == 0 && s[2] == 0; }
 
@@ -53,6 +85,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   if (p->n_sparse_heads < 0 || p->n_sparse_heads > H) return GF_ERR_INVALID_ARG;
   if (p->chunk < 0 || p->segment_len < 0) return GF_ERR_INVALID_ARG;
   if (p->launch_mask < 0 || p->launch_mask > 7) return GF_ERR_INVALID_ARG;
+  if (p->no_overlap != 0 && p->no_overlap != 1) return GF_ERR_INVALID_ARG;
   if (!(p->softmax_scale == p->softmax_scale) || !(p->eps >= 0.f)) return GF_ERR_INVALID_ARG;
   if (B > 65535 || H > 65535) return GF_ERR_UNSUPPORTED;  // grid y/z limits
   gf_status st;
@@ -74,7 +107,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   if (impl == GF_IMPL_SCALAR) {
     pl.chunk = 32;  // fixed by the fp32 kernel
     pl.segment_len = N;
-    pl.n_segments = 1;
+    pl.n_segments = (H1 > 0 && N > 0) ? (int)heads_lin : 0;  // one workgroup walks a whole head
     if (p->segment_len != 0 && p->segment_len < N) return GF_ERR_UNSUPPORTED;
     pl.windowed_threads = kScalarThreads;
     pl.windowed_blocks = (H0 > 0 && N > 0) ? B * H0 * ((N + kScalarWindowRows - 1) / kScalarWindowRows) : 0;
@@ -85,30 +118,38 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
     return GF_OK;
   }
   pl.chunk = p->chunk ? p->chunk : 64;
-  int seg = p->segment_len;
-  if (seg != 0) {
-    if (seg % pl.chunk != 0) return GF_ERR_INVALID_ARG;
-  } else {
-    // Enough workgroups to cover the 256 compute units about twice, but segments no shorter
-    // than 8 chunks so the per-segment state traffic (d*d fp32) stays a small share.
-    const long target_blocks = 512;
-    const int min_seg = 8 * pl.chunk;
-    long nseg = heads_lin > 0 ? (target_blocks + heads_lin - 1) / heads_lin : 1;
-    long max_seg = N / min_seg;
-    if (nseg > max_seg) nseg = max_seg;
-    if (nseg < 1) nseg = 1;
-    seg = round_up((int)((N + nseg - 1) / nseg), pl.chunk);
-    if (seg < pl.chunk) seg = pl.chunk;
+  const long cph = N > 0 ? (N + pl.chunk - 1) / pl.chunk : 0;  // real chunks per head
+  long piece = 0, vcph = cph, pieces = 0, mid = 0;
+  if (p->segment_len != 0) {
+    if (p->segment_len % pl.chunk != 0) return GF_ERR_INVALID_ARG;
+    piece = p->segment_len / pl.chunk;
+    const long per_head = cph > 0 ? (cph + piece - 1) / piece : 0;
+    vcph = per_head * piece;
+    pieces = heads_lin * per_head;
+    mid = heads_lin * (per_head > 0 ? per_head - 1 : 0);
+  } else if (heads_lin > 0 && cph > 0) {
+    // One workgroup per compute unit (its LDS holds one), each with the same number of chunks;
+    // pieces no shorter than 8 chunks so the carried state (d*d fp32 in, d*d out) stays a small
+    // share of the traffic.
+    const long total = heads_lin * cph;
+    piece = (total + kComputeUnits - 1) / kComputeUnits;
+    if (piece < 8) piece = 8;
+    if (piece > total) piece = total;
+    pieces = (total + piece - 1) / piece;
+    for (long q = 1; q < pieces; ++q) mid += ((q * piece) % cph) != 0;
   }
-  pl.segment_len = seg;
-  pl.n_segments = N > 0 ? (N + seg - 1) / seg : 1;
+  if (pieces > 0x7fffffffL / 64) return GF_ERR_UNSUPPORTED;
+  r->cph = (int)cph;
+  r->vcph = (int)vcph;
+  r->piece_chunks = (int)piece;
+  pl.segment_len = (int)(piece * pl.chunk);
+  pl.n_segments = (int)pieces;
   pl.windowed_threads = kMfmaWindowThreads;
   pl.windowed_blocks = (H0 > 0 && N > 0) ? B * H0 * ((N + kMfmaWindowRows - 1) / kMfmaWindowRows) : 0;
   pl.linear_threads = mfma_linear_threads(d);
-  pl.linear_blocks = (H1 > 0 && N > 0) ? (int)(heads_lin * pl.n_segments) : 0;
-  pl.state_blocks = (pl.n_segments > 1 && H1 > 0) ? (int)(heads_lin * (pl.n_segments - 1)) : 0;
-  pl.workspace_bytes = pl.state_blocks > 0
-      ? (uint64_t)heads_lin * pl.n_segments * ((uint64_t)d * d + d) * sizeof(float) : 0;
+  pl.linear_blocks = (int)pieces;
+  pl.state_blocks = (int)mid;
+  pl.workspace_bytes = mid > 0 ? (uint64_t)pieces * ((uint64_t)d * d + d) * sizeof(float) : 0;
   return GF_OK;
 }
 
@@ -175,8 +216,10 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
   a.scale = p->softmax_scale;
   a.eps = p->eps;
   a.chunk = r.plan.chunk;
-  a.segment_len = r.plan.segment_len;
-  a.n_segments = r.plan.n_segments;
+  a.cph = r.cph;
+  a.vcph = r.vcph;
+  a.piece_chunks = r.piece_chunks;
+  a.n_pieces = r.plan.n_segments;
   a.ws_states = r.plan.workspace_bytes > 0 ? reinterpret_cast<float*>(workspace) : nullptr;
 
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
@@ -187,10 +230,25 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
     if ((mask & GF_LAUNCH_WINDOWED) && e == hipSuccess) e = launch_windowed_scalar(a, bf16, s);
     if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_scalar(a, bf16, s);
   } else {
-    // Linear heads first: their workgroups run longest, the windowed ones fill in behind.
+    const bool win = (mask & GF_LAUNCH_WINDOWED) && a.H0 > 0;
+    const bool lin = (mask & (GF_LAUNCH_LINEAR_STATE | GF_LAUNCH_LINEAR_MAIN)) && a.H0 < a.H;
+    std::lock_guard<std::mutex> lock(g_enqueue_mutex);
+    SideStream* side = nullptr;
+    if (win && lin && !p->no_overlap) e = side_stream_for_current_device(&side);
+    if (side && e == hipSuccess) {
+      // fork: the windowed heads wait for what is already in `s`, then run beside the linear ones
+      e = hipEventRecord(side->fork, s);
+      if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
+      if (e == hipSuccess) e = launch_windowed_mfma(a, side->stream);
+      if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
+    }
     if ((mask & GF_LAUNCH_LINEAR_STATE) && e == hipSuccess) e = launch_linear_state_mfma(a, s);
     if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_main_mfma(a, s);
-    if ((mask & GF_LAUNCH_WINDOWED) && e == hipSuccess) e = launch_windowed_mfma(a, s);
+    if (side) {
+      if (e == hipSuccess) e = hipStreamWaitEvent(s, side->join, 0);  // join
+    } else if (win && e == hipSuccess) {
+      e = launch_windowed_mfma(a, s);
+    }
   }
   return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
 }

@@ -23,11 +23,17 @@ struct AttnArgs {
   int phi;           // gf_phi
   float scale;       // softmax scale (windowed heads)
   float eps;         // linear denominator epsilon
-  // linear-attention segmentation
+  // Linear-attention work split.  The chunks (64 tokens) of all linear heads form one list in
+  // which head i owns virtual chunks [i*vcph, (i+1)*vcph), the first `cph` of them real.  The
+  // list is cut into `n_pieces` pieces of `piece_chunks` chunks; one workgroup walks one piece.
+  // vcph == cph: pieces are cut with no regard to head boundaries (balanced);
+  // vcph  > cph: every head is padded to a whole number of pieces (uniform segments per head).
   int chunk;         // tokens per chunk
-  int segment_len;   // tokens per segment (multiple of chunk)
-  int n_segments;    // segments per head
-  float* ws_states;  // [B*H1, n_segments, d*d + d] fp32: per-segment sums, then exclusive prefixes
+  int cph;           // real chunks per head = ceil(N / chunk)
+  int vcph;          // virtual chunks per head
+  int piece_chunks;  // chunks per piece
+  int n_pieces;      // pieces = workgroups of the read-out kernel
+  float* ws_states;  // [n_pieces, d*d + d] fp32: slot p = (A, Z) of p's head just before piece p
 };
 
 // bf16 storage helpers (round to nearest even on store).

@@ -16,9 +16,12 @@
 // and V sit row-major in LDS and are read through the LDS transpose read wherever the
 // contraction runs over tokens.
 //
-// Segments of one head are stitched in three launches: (1) every segment but the last sums its
-// own (A, Z); (2) a tiny kernel turns those into exclusive prefixes; (3) the read-out kernel
-// starts each segment from its prefix.
+// The chunks of all linear heads form one list that is cut into equal pieces, one workgroup
+// each, with no regard to head boundaries (or, on request, into uniform segments per head).
+// Pieces are stitched in three launches: (1) for every piece boundary that falls inside a
+// head, sum (A, Z) over the part of that head lying in the piece before it; (2) a tiny kernel
+// turns those sums into running sums inside each head; (3) the read-out kernel starts each
+// piece from the state carried to its first chunk and restarts from zero at head boundaries.
 #include "common.hpp"
 #include "mfma.hpp"
 
@@ -104,7 +107,6 @@ __device__ __forceinline__ float sum8_bf16(bf16x8 x, float acc) {
 template <int D> struct HeadPtrs {
   const uint16_t *q, *k, *v;
   uint16_t* o;
-  float* state;  // this head's [n_segments][STATE] block of the workspace (may be null)
 };
 
 template <int D>
@@ -116,8 +118,33 @@ __device__ __forceinline__ HeadPtrs<D> head_ptrs(const AttnArgs& a, int head_lin
   p.k = reinterpret_cast<const uint16_t*>(a.k.base) + b * a.k.sb + h * a.k.sh;
   p.v = reinterpret_cast<const uint16_t*>(a.v.base) + b * a.v.sb + h * a.v.sh;
   p.o = reinterpret_cast<uint16_t*>(a.out) + b * a.osb + h * a.osh;
-  p.state = a.ws_states ? a.ws_states + (int64_t)head_linear * a.n_segments * LinCfg<D>::STATE : nullptr;
   return p;
+}
+
+// Walks the chunk list of a piece: (linear head, chunk inside the head), one step at a time.
+// All state is wave-uniform; the head's pointers are recomputed only when a head boundary is
+// crossed.
+template <int D> struct ChunkCursor {
+  int head, lc;
+  HeadPtrs<D> hp;
+  __device__ __forceinline__ ChunkCursor(const AttnArgs& a, int g)
+      : head(g / a.vcph), lc(g % a.vcph), hp(head_ptrs<D>(a, g / a.vcph)) {}
+  __device__ __forceinline__ void next(const AttnArgs& a, bool more) {
+    if (++lc == a.vcph && more) {
+      lc = 0;
+      ++head;
+      hp = head_ptrs<D>(a, head);
+    }
+  }
+  __device__ __forceinline__ int t0() const { return lc * CH; }
+};
+
+// Real chunks of piece p: global chunks [g0, g0 + n).  A piece that would run into a head's
+// virtual padding (uniform-segment mode) stops at the head's last real chunk.
+__device__ __forceinline__ int piece_chunk_count(const AttnArgs& a, int g0, int n_heads) {
+  int n = min(a.piece_chunks, n_heads * a.vcph - g0);
+  if (a.vcph != a.cph) n = min(n, a.cph - g0 % a.vcph);
+  return n;
 }
 
 // State tile (ct, wave) in accumulator layout: lane = value column 32*wave + l%32,
@@ -164,28 +191,24 @@ template <int D> struct Staging {
   }
 };
 
-// One tensor of one head as the producers read it: a uniform base pointer that advances by
-// whole chunks and a per-thread element offset that never changes, so a full chunk costs no
-// vector integer arithmetic.  Rows past N-1 (last chunk only) re-read row N-1, in bounds.
-template <int D> struct RowStream {
+// A full chunk is read with a uniform row base plus a per-thread element offset that never
+// changes, so it costs no vector integer arithmetic.  Rows past N-1 (a head's last chunk only)
+// re-read row N-1, in bounds.
+template <int D>
+__device__ __forceinline__ u32x4 load_piece(const uint16_t* base, int64_t sn, uint32_t toff,
+                                            int t0, int i, int N, const Staging<D>& st) {
   using C = LinCfg<D>;
-  const uint16_t* base;
-  int64_t sn;
-  uint32_t toff;
-  __device__ __forceinline__ RowStream(const uint16_t* b, int64_t sn_, const Staging<D>& st)
-      : base(b), sn(sn_), toff((uint32_t)(st.r0 * (int)sn_ + st.col)) {}
-  __device__ __forceinline__ u32x4 load(int t0, int i, int N, const Staging<D>& st) const {
-    if (t0 + CH <= N)
-      return *reinterpret_cast<const u32x4*>(base + (int64_t)(t0 + i * C::RP) * sn + toff);
-    return *reinterpret_cast<const u32x4*>(base + (int64_t)min(t0 + st.r0 + i * C::RP, N - 1) * sn + st.col);
-  }
-};
+  if (t0 + CH <= N)
+    return *reinterpret_cast<const u32x4*>(base + (int64_t)(t0 + i * C::RP) * sn + toff);
+  return *reinterpret_cast<const u32x4*>(base + (int64_t)min(t0 + st.r0 + i * C::RP, N - 1) * sn + st.col);
+}
 
 constexpr u32x4 kZero4 = {0u, 0u, 0u, 0u};
 
 // -----------------------------------------------------------------------------------------
-// (1) per-segment state sums.  Workgroup (head, s) with s < n_segments-1 writes
-//     sum_{t in segment s} phi(k_t) (x) v_t  and  sum phi(k_t)  into workspace slot s+1.
+// (1) state sums.  Workgroup q-1 serves the piece boundary at global chunk q*piece_chunks: if
+//     it falls inside a head it sums phi(k_t) (x) v_t and phi(k_t) over the chunks of that head
+//     that lie in piece q-1 and writes them to workspace slot q.
 //     Waves [0, NWC) contract; waves [NWC, 2 NWC) load, map and stage the next chunk.
 // -----------------------------------------------------------------------------------------
 template <int D, bool ELU1>
@@ -195,31 +218,34 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_state_kernel(AttnArgs a)
   StateSmem<D>& sm = *reinterpret_cast<StateSmem<D>*>(smem_raw);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
-  const int nsm1 = a.n_segments - 1;
-  const int head = blockIdx.x / nsm1, seg = blockIdx.x % nsm1;
+  const int q = blockIdx.x + 1;
+  const int e = q * a.piece_chunks;          // the boundary, as a global chunk index
+  if (e % a.vcph == 0) return;               // on a head boundary: nothing is carried
+  const int head = e / a.vcph;
+  const int lc1 = e % a.vcph;                // chunks [lc0, lc1) of `head`
+  const int lc0 = max(lc1 - a.piece_chunks, 0);
   const HeadPtrs<D> hp = head_ptrs<D>(a, head);
   const int N = a.N;
-  const int seg_start = seg * a.segment_len;
-  const int seg_end = min(N, seg_start + a.segment_len);
-  const int nchunks = (seg_end - seg_start + CH - 1) / CH;
+  const int nchunks = lc1 - lc0;
 
   if (wave >= C::NWC) {
     // ---- producers ----
     const Staging<D> st(tid - C::NTC);
-    const RowStream<D> ks(hp.k, a.k.sn, st), vs(hp.v, a.v.sn, st);
+    const uint32_t koff = (uint32_t)(st.r0 * (int)a.k.sn + st.col);
+    const uint32_t voff = (uint32_t)(st.r0 * (int)a.v.sn + st.col);
     u32x4 ka[C::PIECES], va[C::PIECES], kb[C::PIECES], vb[C::PIECES];
     auto load = [&](u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES], int n) {
-      const int t0 = seg_start + n * CH;
+      const int t0 = (lc0 + n) * CH;
 #pragma unroll
       for (int i = 0; i < C::PIECES; ++i) {
-        kr[i] = ks.load(t0, i, N, st);
-        vr[i] = vs.load(t0, i, N, st);
+        kr[i] = load_piece<D>(hp.k, a.k.sn, koff, t0, i, N, st);
+        vr[i] = load_piece<D>(hp.v, a.v.sn, voff, t0, i, N, st);
       }
     };
     auto stage = [&](const u32x4 (&kr)[C::PIECES], const u32x4 (&vr)[C::PIECES], int n) {
-      const int t0 = seg_start + n * CH;
+      const int t0 = (lc0 + n) * CH;
       StateTiles<D>& b = sm.buf[n & 1];
-      const bool full = t0 + CH <= N;  // uniform; only the sequence's last chunk can be ragged
+      const bool full = t0 + CH <= N;  // uniform; only a head's last chunk can be ragged
 #pragma unroll
       for (int i = 0; i < C::PIECES; ++i) {
         const int row = st.r0 + i * C::RP;
@@ -256,7 +282,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_state_kernel(AttnArgs a)
     zacc += update_state<D>(sacc, sm.buf[n & 1].fk, sm.buf[n & 1].v, wave, lane);
     lds_barrier();
   }
-  float* dst = hp.state + (int64_t)(seg + 1) * C::STATE;
+  float* dst = a.ws_states + (int64_t)q * C::STATE;
 #pragma unroll
   for (int ct = 0; ct < C::ET; ++ct)
 #pragma unroll
@@ -265,27 +291,31 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_state_kernel(AttnArgs a)
   if (lh == 0) dst[D * D + 32 * wave + ln] = zacc;
 }
 
-// (2) slots 1..n_segments-1 hold per-segment sums of segments 0..n_segments-2; make slot s the
-//     sum of all segments before s.
-__global__ __launch_bounds__(256) void linear_prefix_kernel(float* ws, int n_heads, int n_segments,
+// (2) Slot q holds the sums over the part of its head that lies in piece q-1.  Inside every
+//     head, turn them into running sums: slot q = state of the head just before piece q.
+__global__ __launch_bounds__(256) void linear_prefix_kernel(float* ws, int n_heads, int vcph,
+                                                             int piece_chunks, int n_pieces,
                                                              int state_floats) {
   const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int head = blockIdx.y;
   if (x >= state_floats || head >= n_heads) return;
-  float* p = ws + (int64_t)head * n_segments * state_floats + x;
-  float run = p[state_floats];
-  for (int s = 2; s < n_segments; ++s) {
-    run += p[(int64_t)s * state_floats];
-    p[(int64_t)s * state_floats] = run;
+  const int64_t g_lo = (int64_t)head * vcph, g_hi = g_lo + vcph;
+  float run = 0.f;
+  for (int64_t q = g_lo / piece_chunks + 1; q < n_pieces && q * piece_chunks < g_hi; ++q) {
+    float* p = ws + q * state_floats + x;
+    run += *p;
+    *p = run;
   }
 }
 
 // -----------------------------------------------------------------------------------------
-// (3) read-out.  Workgroup (head, segment) walks its chunks carrying (A, Z).
-//     Waves [0, NWC): MFMA work, denominators, normalise + write.  Waves [NWC, 2 NWC): load
-//     chunk n+2 from global memory, apply phi to chunk n+1 and stage it in the other LDS buffer,
-//     so the feature map's vector work overlaps the matrix work of chunk n on every SIMD.
-//     Two workgroup barriers per chunk: (a) masked products visible, (b) buffers change hands.
+// (3) read-out.  Workgroup p walks the chunks of piece p carrying (A, Z); at a head's first
+//     chunk the state restarts from zero, at a piece start inside a head from workspace slot p.
+//     Waves [0, NWC): MFMA work, denominators, normalise.  Waves [NWC, 2 NWC): load chunk n+2
+//     from global memory, apply phi to chunk n+1 and stage it in the other LDS buffer, write
+//     chunk n-1's finished rows; the feature map's vector work thus overlaps the matrix work
+//     of chunk n on every SIMD.  Two workgroup barriers per chunk: (a) masked products
+//     visible, (b) buffers change hands.
 // -----------------------------------------------------------------------------------------
 template <int D, bool ELU1>
 __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) {
@@ -294,29 +324,33 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
   LinSmem<D>& sm = *reinterpret_cast<LinSmem<D>*>(smem_raw);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
-  const int head = blockIdx.x / a.n_segments, seg = blockIdx.x % a.n_segments;
-  const HeadPtrs<D> hp = head_ptrs<D>(a, head);
+  const int n_heads = a.B * (a.H - a.H0);
+  const int g0 = blockIdx.x * a.piece_chunks;
+  const int nchunks = piece_chunk_count(a, g0, n_heads);
+  if (nchunks <= 0) return;  // uniform
   const int N = a.N;
-  const int seg_start = seg * a.segment_len;
-  const int seg_end = min(N, seg_start + a.segment_len);
-  if (seg_start >= seg_end) return;  // uniform: nothing in this segment
-  const int nchunks = (seg_end - seg_start + CH - 1) / CH;
 
   if (wave >= C::NWC) {
     // ---- producers ----
     const Staging<D> st(tid - C::NTC);
-    const RowStream<D> qs(hp.q, a.q.sn, st), ks(hp.k, a.k.sn, st), vs(hp.v, a.v.sn, st);
+    const uint32_t qoff = (uint32_t)(st.r0 * (int)a.q.sn + st.col);
+    const uint32_t koff = (uint32_t)(st.r0 * (int)a.k.sn + st.col);
+    const uint32_t voff = (uint32_t)(st.r0 * (int)a.v.sn + st.col);
+    ChunkCursor<D> cl(a, g0), cs(a, g0), co(a, g0);  // next chunk to load / stage / write out
     u32x4 qa[C::PIECES], ka[C::PIECES], va[C::PIECES], qb[C::PIECES], kb[C::PIECES], vb[C::PIECES];
-    auto load = [&](u32x4 (&qr)[C::PIECES], u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES], int n) {
-      const int t0 = seg_start + n * CH;
+    int nl = 0, no = 0;  // chunks loaded / written so far
+    auto load = [&](u32x4 (&qr)[C::PIECES], u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES]) {
+      const int t0 = cl.t0();
 #pragma unroll
       for (int i = 0; i < C::PIECES; ++i) {
-        qr[i] = qs.load(t0, i, N, st);
-        kr[i] = ks.load(t0, i, N, st);
-        vr[i] = vs.load(t0, i, N, st);
+        qr[i] = load_piece<D>(cl.hp.q, a.q.sn, qoff, t0, i, N, st);
+        kr[i] = load_piece<D>(cl.hp.k, a.k.sn, koff, t0, i, N, st);
+        vr[i] = load_piece<D>(cl.hp.v, a.v.sn, voff, t0, i, N, st);
       }
+      ++nl;
+      cl.next(a, nl < nchunks);
     };
-    // phi(Q) of chunk n -> buf[n % 2]
+    // phi(Q) of the chunk at `cs` -> buf[n % 2]
     auto stage_q = [&](const u32x4 (&qr)[C::PIECES], int n) {
       ChunkTiles<D>& b = sm.buf[n & 1];
 #pragma unroll
@@ -327,9 +361,9 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
         *reinterpret_cast<u32x2*>(qd + 8) = u32x2{fqv[2], fqv[3]};
       }
     };
-    // phi(K) and V of chunk n -> buf[n % 2]; rows past the sequence end become zeros
+    // phi(K) and V of the chunk at `cs` -> buf[n % 2]; rows past the head's end become zeros
     auto stage_kv = [&](const u32x4 (&kr)[C::PIECES], const u32x4 (&vr)[C::PIECES], int n) {
-      const int t0 = seg_start + n * CH;
+      const int t0 = cs.t0();
       ChunkTiles<D>& b = sm.buf[n & 1];
       if (t0 + CH <= N) {
 #pragma unroll
@@ -348,20 +382,23 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
           *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = valid ? vr[i] : kZero4;
         }
       }
+      cs.next(a, n + 1 < nchunks);
     };
-    // finished rows of chunk n: LDS -> global, 16 bytes per lane, whole rows per 16 lanes
-    auto store_out = [&](int n) {
-      const int t0 = seg_start + n * CH;
+    // finished rows of the chunk at `co`: LDS -> global, 16 bytes per lane, whole rows per 16 lanes
+    auto store_out = [&]() {
+      const int t0 = co.t0();
 #pragma unroll
       for (int i = 0; i < C::PIECES; ++i) {
         const int row = st.r0 + i * C::RP;
         const u32x4 o = *reinterpret_cast<const u32x4*>(&sm.ot[row * C::OROW + st.col]);
         if (t0 + row < N)
-          *reinterpret_cast<u32x4*>(hp.o + (int64_t)(t0 + row) * a.osn + st.col) = o;
+          *reinterpret_cast<u32x4*>(co.hp.o + (int64_t)(t0 + row) * a.osn + st.col) = o;
       }
+      ++no;
+      co.next(a, no < nchunks);
     };
-    load(qa, ka, va, 0);
-    if (nchunks > 1) load(qb, kb, vb, 1);
+    load(qa, ka, va);
+    if (nchunks > 1) load(qb, kb, vb);
     stage_q(qa, 0);
     stage_kv(ka, va, 0);
     lds_barrier();  // chunk 0 staged
@@ -372,20 +409,20 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
     for (int n = 0; n < nchunks; n += 2) {
       if (n + 1 < nchunks) stage_q(qb, n + 1);
       lds_barrier();  // (a)
-      if (n > 0) store_out(n - 1);
+      if (n > 0) store_out();
       if (n + 1 < nchunks) stage_kv(kb, vb, n + 1);
-      if (n + 2 < nchunks) load(qa, ka, va, n + 2);
+      if (n + 2 < nchunks) load(qa, ka, va);
       lds_barrier();  // (b)
       if (n + 1 >= nchunks) break;
       if (n + 2 < nchunks) stage_q(qa, n + 2);
       lds_barrier();  // (a)
-      store_out(n);
+      store_out();
       if (n + 2 < nchunks) stage_kv(ka, va, n + 2);
-      if (n + 3 < nchunks) load(qb, kb, vb, n + 3);
+      if (n + 3 < nchunks) load(qb, kb, vb);
       lds_barrier();  // (b)
     }
     lds_barrier();  // (c) last chunk's rows are in LDS
-    store_out(nchunks - 1);
+    store_out();
     return;
   }
 
@@ -398,7 +435,8 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
     sm.zl[buf][zi] = (uint16_t)(pack_bf16(zval - __uint_as_float((uint32_t)hi << 16), 0.f) & 0xffffu);
   };
   f32x16 sacc[C::ET];
-  const float* src = (seg > 0 && hp.state) ? hp.state + (int64_t)seg * C::STATE : nullptr;
+  int lc = g0 % a.vcph;  // chunk index inside the current head
+  const float* src = (lc > 0 && a.ws_states) ? a.ws_states + (int64_t)blockIdx.x * C::STATE : nullptr;
 #pragma unroll
   for (int ct = 0; ct < C::ET; ++ct)
 #pragma unroll
@@ -415,6 +453,8 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
   for (int n = 0; n < nchunks; ++n) {
     const int zc = n & 1;
     const ChunkTiles<D>& b = sm.buf[n & 1];
+    const bool head_ends = (lc + 1 == a.vcph);  // the next chunk starts a new head from zero
+    lc = head_ends ? 0 : lc + 1;
 
     // masked products P^T[key][query] = phi(k_key).phi(q_query), key <= query: three 32x32
     // tiles (the fourth lies above the diagonal).  Tile t goes to wave t % NWC; code is kept
@@ -517,12 +557,18 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
         }
       }
     }
-    // state update: A += phiK^T V, Z += colsum(phiK)
+    // state update: A += phiK^T V, Z += colsum(phiK); a new head starts from zero instead
     {
       float zs = update_state<D>(sacc, b.fk, b.v, wave, lane);
       zs += __shfl_xor(zs, 32, 64);
       const int zi = 32 * wave + kperm32(ln);
-      if (lh == 0) put_z(zc ^ 1, zi, sm.z[zc][zi] + zs);
+      if (lh == 0) put_z(zc ^ 1, zi, head_ends ? 0.f : sm.z[zc][zi] + zs);
+      if (head_ends) {
+#pragma unroll
+        for (int ct = 0; ct < C::ET; ++ct)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[ct][r] = 0.f;
+      }
     }
     lds_barrier();  // (b) denominators visible; this chunk's tiles are free again
     // normalise; the rows go to LDS and the producers write them out in whole rows
@@ -551,7 +597,7 @@ template <int D> hipError_t launch_state_t(const AttnArgs& a, hipStream_t s) {
   using C = LinCfg<D>;
   const int heads = a.B * (a.H - a.H0);
   const int smem = (int)sizeof(StateSmem<D>);
-  const dim3 grid(heads * (a.n_segments - 1)), block(C::NT);
+  const dim3 grid(a.n_pieces - 1), block(C::NT);
   hipError_t e;
   if (a.phi == 0) {
     if ((e = allow_lds(linear_state_kernel<D, true>, smem)) != hipSuccess) return e;
@@ -561,9 +607,9 @@ template <int D> hipError_t launch_state_t(const AttnArgs& a, hipStream_t s) {
     linear_state_kernel<D, false><<<grid, block, smem, s>>>(a);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (a.n_segments > 2) {
+  if (a.vcph > a.piece_chunks) {  // a head can hold more than one carried boundary
     linear_prefix_kernel<<<dim3((C::STATE + 255) / 256, heads), dim3(256), 0, s>>>(
-        a.ws_states, heads, a.n_segments, C::STATE);
+        a.ws_states, heads, a.vcph, a.piece_chunks, a.n_pieces, C::STATE);
     e = hipGetLastError();
   }
   return e;
@@ -571,9 +617,8 @@ template <int D> hipError_t launch_state_t(const AttnArgs& a, hipStream_t s) {
 
 template <int D> hipError_t launch_main_t(const AttnArgs& a, hipStream_t s) {
   using C = LinCfg<D>;
-  const int heads = a.B * (a.H - a.H0);
   const int smem = (int)sizeof(LinSmem<D>);
-  const dim3 grid(heads * a.n_segments), block(C::NT);
+  const dim3 grid(a.n_pieces), block(C::NT);
   hipError_t e;
   if (a.phi == 0) {
     if ((e = allow_lds(linear_main_kernel<D, true>, smem)) != hipSuccess) return e;
@@ -588,12 +633,12 @@ template <int D> hipError_t launch_main_t(const AttnArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_linear_state_mfma(const AttnArgs& a, hipStream_t s) {
-  if (a.H - a.H0 <= 0 || a.N <= 0 || a.B <= 0 || a.n_segments <= 1) return hipSuccess;
+  if (a.H - a.H0 <= 0 || a.N <= 0 || a.B <= 0 || a.n_pieces <= 1 || !a.ws_states) return hipSuccess;
   return a.d == 64 ? launch_state_t<64>(a, s) : launch_state_t<128>(a, s);
 }
 
 hipError_t launch_linear_main_mfma(const AttnArgs& a, hipStream_t s) {
-  if (a.H - a.H0 <= 0 || a.N <= 0 || a.B <= 0) return hipSuccess;
+  if (a.H - a.H0 <= 0 || a.N <= 0 || a.B <= 0 || a.n_pieces <= 0) return hipSuccess;
   return a.d == 64 ? launch_main_t<64>(a, s) : launch_main_t<128>(a, s);
 }
 

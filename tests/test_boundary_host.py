@@ -50,11 +50,14 @@ def _plan(B, H, N, d, w, **kw):
 def test_plan_headline_config():
     st, pl = _plan(4, 32, 8192, 128, 256, n_sparse_heads=6)
     assert st == gb.GF_OK and pl["impl"] == gb.GF_IMPL_MFMA
-    assert pl["chunk"] == 64 and pl["segment_len"] % pl["chunk"] == 0
-    assert pl["n_segments"] * pl["segment_len"] >= 8192 > (pl["n_segments"] - 1) * pl["segment_len"]
+    # 104 linear heads x 128 chunks cut into equal pieces, one per compute unit
+    assert pl["chunk"] == 64 and pl["segment_len"] == 52 * 64
+    assert pl["n_segments"] == 256 and pl["linear_blocks"] == 256
     assert pl["windowed_blocks"] == 4 * 6 * (8192 // 128)
-    assert pl["linear_blocks"] == 4 * 26 * pl["n_segments"]
-    want_ws = 4 * 26 * pl["n_segments"] * (128 * 128 + 128) * 4 if pl["n_segments"] > 1 else 0
+    # boundaries q*52 that are not multiples of 128 need a carried state
+    mid = sum(1 for q in range(1, 256) if (q * 52) % 128 != 0)
+    assert pl["state_blocks"] == mid
+    want_ws = 256 * (128 * 128 + 128) * 4
     assert pl["workspace_bytes"] == want_ws
     assert gb.gformer_attn_workspace_bytes(4, 32, 8192, 128, 256, gb.make_params(n_sparse_heads=6)) == want_ws
 
@@ -63,15 +66,24 @@ def test_plan_modes_and_overrides():
     st, pl = _plan(1, 1, 256, 64, 32, dtype=gb.GF_F32, n_sparse_heads=1)
     assert st == gb.GF_OK and pl["impl"] == gb.GF_IMPL_SCALAR and pl["workspace_bytes"] == 0
     assert pl["linear_blocks"] == 0 and pl["windowed_blocks"] == 16
+    # uniform segments per head on request
     st, pl = _plan(1, 32, 32768, 128, 512, n_sparse_heads=0, chunk=64, segment_len=1024)
-    assert st == gb.GF_OK and pl["chunk"] == 64 and pl["segment_len"] == 1024 and pl["n_segments"] == 32
+    assert st == gb.GF_OK and pl["chunk"] == 64 and pl["segment_len"] == 1024 and pl["n_segments"] == 32 * 32
     assert pl["state_blocks"] == 32 * 31 and pl["windowed_blocks"] == 0
+    assert pl["workspace_bytes"] == 32 * 32 * (128 * 128 + 128) * 4
     st, pl = _plan(1, 2, 100, 64, 8, n_sparse_heads=0, segment_len=64)
-    assert st == gb.GF_OK and pl["n_segments"] == 2
+    assert st == gb.GF_OK and pl["n_segments"] == 4 and pl["state_blocks"] == 2
+    # short problems: one piece, nothing carried, no workspace
+    st, pl = _plan(1, 2, 100, 64, 8, n_sparse_heads=0)
+    assert st == gb.GF_OK and pl["n_segments"] == 1 and pl["segment_len"] == 4 * 64 and pl["workspace_bytes"] == 0
     st, pl = _plan(1, 2, 100, 64, 8, n_sparse_heads=2)
     assert st == gb.GF_OK and pl["linear_blocks"] == 0 and pl["workspace_bytes"] == 0
     st, pl = _plan(2, 4, 0, 64, 8)
     assert st == gb.GF_OK and pl["linear_blocks"] == 0 and pl["windowed_blocks"] == 0
+    # pieces that divide the head length carry nothing across their aligned boundaries
+    st, pl = _plan(1, 64, 8192, 128, 256, n_sparse_heads=0)   # 64 heads x 128 chunks / 256 = 32
+    assert st == gb.GF_OK and pl["segment_len"] == 32 * 64 and pl["n_segments"] == 256
+    assert pl["state_blocks"] == 64 * 3
 
 
 @pytest.mark.parametrize("args,kw,want", [
@@ -86,6 +98,7 @@ def test_plan_modes_and_overrides():
     ((1, 2, 16, 64, 4), {"eps": -1.0}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"eps": float("nan")}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"launch_mask": 8}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"no_overlap": 2}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"q_stride": (1024, 512, 60)}, gb.GF_ERR_INVALID_ARG),   # not 16-byte rows
     ((1, 2, 16, 64, 4), {"o_stride": (2048, 1024, 32)}, gb.GF_ERR_INVALID_ARG),  # rows overlap
     ((1, 2, 256, 64, 4), {"chunk": 64, "segment_len": 96}, gb.GF_ERR_INVALID_ARG),
@@ -126,7 +139,7 @@ def test_workspace_is_required_when_segments_are_used():
     p = gb.make_params(n_sparse_heads=0, chunk=64, segment_len=64)
     a = (1, 2, 256, 64, 8)
     need = gb.gformer_attn_workspace_bytes(*a, p)
-    assert need == 1 * 2 * 4 * (64 * 64 + 64) * 4
+    assert need == 1 * 2 * 4 * (64 * 64 + 64) * 4   # one slot per piece
     assert gb.gformer_attn_fwd_raw(0x1000, 0x2000, 0x3000, 0x4000, *a, p, 0, 0) == gb.GF_ERR_WORKSPACE
     assert gb.gformer_attn_fwd_raw(0x1000, 0x2000, 0x3000, 0x4000, *a, p, 0x10000, need - 1) == gb.GF_ERR_WORKSPACE
     assert gb.gformer_attn_fwd_raw(0x1000, 0x2000, 0x3000, 0x4000, *a, p, 0x10010, need) == gb.GF_ERR_INVALID_ARG

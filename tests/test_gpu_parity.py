@@ -74,6 +74,9 @@ SHAPES = [
     (1, 3, 1025, 128, 256, 1),
     (1, 2, 640, 64, 129, 0),
     (1, 2, 640, 128, 64, 2),
+    (2, 8, 200, 64, 16, 0),       # many short linear heads: one piece of work spans several heads
+    (1, 5, 700, 128, 64, 1),      # pieces of linear work cut across head boundaries
+    (3, 3, 1000, 64, 50, 1),
 ]
 
 
@@ -162,6 +165,16 @@ def test_repeat_runs_are_bit_identical(dtype, impl):
     a = run_gpu(q, k, v, dtype, w, H0, impl=impl)
     b = run_gpu(q, k, v, dtype, w, H0, impl=impl)
     assert np.array_equal(a, b)
+
+
+def test_side_stream_and_serial_enqueue_agree():
+    """Windowed heads on the library's side stream (default) vs everything on one stream."""
+    B, H, N, d, w, H0 = 2, 6, 1500, 128, 200, 2
+    q, k, v = synth(B, H, N, d, "bf16", 20)
+    a = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA)
+    b = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA, no_overlap=1)
+    assert np.array_equal(a, b)
+    check(a, oracle(q, k, v, w, H0), "bf16", "side stream")
 
 
 def test_head_split_extremes_and_slots():
