@@ -17,7 +17,7 @@ namespace {
 struct Resolved {
   gformer_plan plan;
   int64_t qs[3], ks[3], vs[3], os[3];
-  int cph, vcph, piece_chunks;
+  int cph, vcph, piece_chunks, state_sub;
 };
 
 constexpr long kComputeUnits = 256;  // MI355X
@@ -119,7 +119,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   }
   pl.chunk = p->chunk ? p->chunk : 64;
   const long cph = N > 0 ? (N + pl.chunk - 1) / pl.chunk : 0;  // real chunks per head
-  long piece = 0, vcph = cph, pieces = 0, mid = 0;
+  long piece = 0, vcph = cph, pieces = 0, mid = 0, sub = 1;
   if (p->segment_len != 0) {
     if (p->segment_len % pl.chunk != 0) return GF_ERR_INVALID_ARG;
     piece = p->segment_len / pl.chunk;
@@ -135,13 +135,22 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
     piece = (total + kComputeUnits - 1) / kComputeUnits;
     if (piece < 8) piece = 8;
     if (piece > total) piece = total;
+    if (piece % 2 != 0 && piece < total) ++piece;  // even, so the state pass can halve it
     pieces = (total + piece - 1) / piece;
-    for (long q = 1; q < pieces; ++q) mid += ((q * piece) % cph) != 0;
+    // The state pass works on half pieces (two workgroups per compute unit fit there), which
+    // evens out its load: a sub-piece is summed iff a piece boundary follows it inside its head.
+    sub = piece % 2 == 0 ? 2 : 1;
+    const long ls = piece / sub;
+    for (long j = 1; j < pieces * sub; ++j) {
+      const long e = j * ls, next_main = (j + sub - 1) / sub * piece;
+      mid += (e % cph) != 0 && next_main < (e / cph + 1) * cph && next_main < total;
+    }
   }
   if (pieces > 0x7fffffffL / 64) return GF_ERR_UNSUPPORTED;
   r->cph = (int)cph;
   r->vcph = (int)vcph;
   r->piece_chunks = (int)piece;
+  r->state_sub = (int)sub;
   pl.segment_len = (int)(piece * pl.chunk);
   pl.n_segments = (int)pieces;
   pl.windowed_threads = kMfmaWindowThreads;
@@ -149,7 +158,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   pl.linear_threads = mfma_linear_threads(d);
   pl.linear_blocks = (int)pieces;
   pl.state_blocks = (int)mid;
-  pl.workspace_bytes = mid > 0 ? (uint64_t)pieces * ((uint64_t)d * d + d) * sizeof(float) : 0;
+  pl.workspace_bytes = mid > 0 ? (uint64_t)pieces * sub * ((uint64_t)d * d + d) * sizeof(float) : 0;
   return GF_OK;
 }
 
@@ -220,6 +229,7 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
   a.vcph = r.vcph;
   a.piece_chunks = r.piece_chunks;
   a.n_pieces = r.plan.n_segments;
+  a.state_sub = r.state_sub;
   a.ws_states = r.plan.workspace_bytes > 0 ? reinterpret_cast<float*>(workspace) : nullptr;
 
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
@@ -242,13 +252,15 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
       if (e == hipSuccess) e = launch_windowed_mfma(a, side->stream);
       if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
     }
+    // The read-out kernel wants every compute unit at once (one piece each), so only the state
+    // pass, whose small workgroups pack two to a unit, shares the chip with the windowed heads.
     if ((mask & GF_LAUNCH_LINEAR_STATE) && e == hipSuccess) e = launch_linear_state_mfma(a, s);
-    if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_main_mfma(a, s);
     if (side) {
       if (e == hipSuccess) e = hipStreamWaitEvent(s, side->join, 0);  // join
     } else if (win && e == hipSuccess) {
       e = launch_windowed_mfma(a, s);
     }
+    if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_main_mfma(a, s);
   }
   return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
 }

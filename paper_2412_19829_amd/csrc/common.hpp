@@ -33,8 +33,17 @@ struct AttnArgs {
   int vcph;          // virtual chunks per head
   int piece_chunks;  // chunks per piece
   int n_pieces;      // pieces = workgroups of the read-out kernel
-  float* ws_states;  // [n_pieces, d*d + d] fp32: slot p = (A, Z) of p's head just before piece p
+  int state_sub;     // the state pass cuts every piece into this many equal sub-pieces (1 or 2)
+  float* ws_states;  // [n_pieces*state_sub, d*d + d] fp32: slot j = (A, Z) of its head just
+                     // before global chunk j*piece_chunks/state_sub (piece p reads slot p*state_sub)
 };
+
+// With few carried boundaries per head the read-out kernel adds up the per-sub-piece sums
+// itself (independent loads, no extra launch); with many, a prefix kernel runs first and the
+// read-out kernel reads a single slot.
+__host__ __device__ inline bool uses_prefix_kernel(const AttnArgs& a) {
+  return a.vcph / (a.piece_chunks / a.state_sub) > 6;
+}
 
 // bf16 storage helpers (round to nearest even on store).
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {

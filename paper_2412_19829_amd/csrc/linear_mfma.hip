@@ -89,14 +89,6 @@ template <bool ELU1> __device__ __forceinline__ u32x4 map_features(u32x4 v) {
   return o;
 }
 
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
-// acc + a.lo*b.lo + a.hi*b.hi on packed bf16 pairs (v_dot2c_f32_bf16)
-__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
-                                         __builtin_bit_cast(bf16x2_t, b), acc, false);
-}
-constexpr uint32_t kOnesBf16x2 = 0x3f803f80u;
-
 __device__ __forceinline__ float sum8_bf16(bf16x8 x, float acc) {
   const u32x4 u = as_u32x4(x);
 #pragma unroll
@@ -198,32 +190,40 @@ template <int D>
 __device__ __forceinline__ u32x4 load_piece(const uint16_t* base, int64_t sn, uint32_t toff,
                                             int t0, int i, int N, const Staging<D>& st) {
   using C = LinCfg<D>;
+  // streamed once: non-temporal loads (measured: ~7.1 TB/s vs ~6.1 TB/s for plain loads)
   if (t0 + CH <= N)
-    return *reinterpret_cast<const u32x4*>(base + (int64_t)(t0 + i * C::RP) * sn + toff);
-  return *reinterpret_cast<const u32x4*>(base + (int64_t)min(t0 + st.r0 + i * C::RP, N - 1) * sn + st.col);
+    return __builtin_nontemporal_load(
+        reinterpret_cast<const u32x4*>(base + (int64_t)(t0 + i * C::RP) * sn + toff));
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(
+      base + (int64_t)min(t0 + st.r0 + i * C::RP, N - 1) * sn + st.col));
 }
 
 constexpr u32x4 kZero4 = {0u, 0u, 0u, 0u};
 
 // -----------------------------------------------------------------------------------------
-// (1) state sums.  Workgroup q-1 serves the piece boundary at global chunk q*piece_chunks: if
-//     it falls inside a head it sums phi(k_t) (x) v_t and phi(k_t) over the chunks of that head
-//     that lie in piece q-1 and writes them to workspace slot q.
+// (1) state sums.  Every piece is cut into state_sub equal sub-pieces.  Workgroup j-1 serves the
+//     sub-piece boundary at global chunk e = j*piece_chunks/state_sub: if e falls inside a head
+//     and a piece boundary follows inside the same head, it sums phi(k_t) (x) v_t and phi(k_t)
+//     over the chunks of that head lying in sub-piece j-1 and writes them to workspace slot j.
 //     Waves [0, NWC) contract; waves [NWC, 2 NWC) load, map and stage the next chunk.
 // -----------------------------------------------------------------------------------------
 template <int D, bool ELU1>
-__global__ __launch_bounds__(LinCfg<D>::NT) void linear_state_kernel(AttnArgs a) {
+__global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs a) {
   using C = LinCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   StateSmem<D>& sm = *reinterpret_cast<StateSmem<D>*>(smem_raw);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
   const int q = blockIdx.x + 1;
-  const int e = q * a.piece_chunks;          // the boundary, as a global chunk index
+  const int ls = a.piece_chunks / a.state_sub;
+  const int e = q * ls;                      // the boundary, as a global chunk index
   if (e % a.vcph == 0) return;               // on a head boundary: nothing is carried
   const int head = e / a.vcph;
+  const int next_main = (q + a.state_sub - 1) / a.state_sub * a.piece_chunks;
+  if (next_main >= (head + 1) * a.vcph || next_main >= a.n_pieces * a.piece_chunks)
+    return;                                  // no piece starts later in this head: nobody reads it
   const int lc1 = e % a.vcph;                // chunks [lc0, lc1) of `head`
-  const int lc0 = max(lc1 - a.piece_chunks, 0);
+  const int lc0 = max(lc1 - ls, 0);
   const HeadPtrs<D> hp = head_ptrs<D>(a, head);
   const int N = a.N;
   const int nchunks = lc1 - lc0;
@@ -291,18 +291,22 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_state_kernel(AttnArgs a)
   if (lh == 0) dst[D * D + 32 * wave + ln] = zacc;
 }
 
-// (2) Slot q holds the sums over the part of its head that lies in piece q-1.  Inside every
-//     head, turn them into running sums: slot q = state of the head just before piece q.
+// (2) Slot j holds the sums over the part of its head that lies in sub-piece j-1.  Inside every
+//     head, turn them into running sums: slot j = state of the head just before sub-piece j.
+//     Stops after the head's last piece boundary (later slots were not written and are not read).
 __global__ __launch_bounds__(256) void linear_prefix_kernel(float* ws, int n_heads, int vcph,
-                                                             int piece_chunks, int n_pieces,
+                                                             int sub_chunks, int n_sub, int state_sub,
                                                              int state_floats) {
   const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int head = blockIdx.y;
   if (x >= state_floats || head >= n_heads) return;
   const int64_t g_lo = (int64_t)head * vcph, g_hi = g_lo + vcph;
+  const int64_t total = (int64_t)n_sub * sub_chunks;
   float run = 0.f;
-  for (int64_t q = g_lo / piece_chunks + 1; q < n_pieces && q * piece_chunks < g_hi; ++q) {
-    float* p = ws + q * state_floats + x;
+  for (int64_t j = g_lo / sub_chunks + 1; j < n_sub && j * sub_chunks < g_hi; ++j) {
+    const int64_t next_main = (j + state_sub - 1) / state_sub * state_sub * sub_chunks;
+    if (next_main >= g_hi || next_main >= total) break;
+    float* p = ws + j * state_floats + x;
     run += *p;
     *p = run;
   }
@@ -337,7 +341,9 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
     const uint32_t koff = (uint32_t)(st.r0 * (int)a.k.sn + st.col);
     const uint32_t voff = (uint32_t)(st.r0 * (int)a.v.sn + st.col);
     ChunkCursor<D> cl(a, g0), cs(a, g0), co(a, g0);  // next chunk to load / stage / write out
-    u32x4 qa[C::PIECES], ka[C::PIECES], va[C::PIECES], qb[C::PIECES], kb[C::PIECES], vb[C::PIECES];
+    // three register sets: chunk m travels in set m % 3, loaded three chunks ahead of its use
+    u32x4 qa[C::PIECES], ka[C::PIECES], va[C::PIECES], qb[C::PIECES], kb[C::PIECES], vb[C::PIECES],
+        qc[C::PIECES], kc[C::PIECES], vc[C::PIECES];
     int nl = 0, no = 0;  // chunks loaded / written so far
     auto load = [&](u32x4 (&qr)[C::PIECES], u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES]) {
       const int t0 = cl.t0();
@@ -392,33 +398,42 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
         const int row = st.r0 + i * C::RP;
         const u32x4 o = *reinterpret_cast<const u32x4*>(&sm.ot[row * C::OROW + st.col]);
         if (t0 + row < N)
-          *reinterpret_cast<u32x4*>(co.hp.o + (int64_t)(t0 + row) * a.osn + st.col) = o;
+          __builtin_nontemporal_store(
+              o, reinterpret_cast<u32x4*>(co.hp.o + (int64_t)(t0 + row) * a.osn + st.col));
       }
       ++no;
       co.next(a, no < nchunks);
     };
     load(qa, ka, va);
     if (nchunks > 1) load(qb, kb, vb);
+    if (nchunks > 2) load(qc, kc, vc);
     stage_q(qa, 0);
     stage_kv(ka, va, 0);
     lds_barrier();  // chunk 0 staged
     // Per chunk n the consumers run [products, state read-out] (a) [denominators, in-chunk
     // part, state update] (b) [normalise into LDS].  The producers' work for chunk n+1 is split
-    // the same way so that neither side idles at a barrier: phi(Q) before (a); after (a) the
-    // write-out of chunk n-1, phi(K), V and the loads of chunk n+2.
-    for (int n = 0; n < nchunks; n += 2) {
+    // the same way so that neither side idles at a barrier: the loads of chunk n+3 and phi(Q)
+    // before (a); after (a) the write-out of chunk n-1, phi(K) and V.
+    for (int n = 0; n < nchunks; n += 3) {
+      if (n + 3 < nchunks) load(qa, ka, va);   // set A (chunk n) was staged during chunk n-1
       if (n + 1 < nchunks) stage_q(qb, n + 1);
       lds_barrier();  // (a)
       if (n > 0) store_out();
       if (n + 1 < nchunks) stage_kv(kb, vb, n + 1);
-      if (n + 2 < nchunks) load(qa, ka, va);
       lds_barrier();  // (b)
       if (n + 1 >= nchunks) break;
-      if (n + 2 < nchunks) stage_q(qa, n + 2);
+      if (n + 4 < nchunks) load(qb, kb, vb);
+      if (n + 2 < nchunks) stage_q(qc, n + 2);
       lds_barrier();  // (a)
       store_out();
-      if (n + 2 < nchunks) stage_kv(ka, va, n + 2);
-      if (n + 3 < nchunks) load(qb, kb, vb);
+      if (n + 2 < nchunks) stage_kv(kc, vc, n + 2);
+      lds_barrier();  // (b)
+      if (n + 2 >= nchunks) break;
+      if (n + 5 < nchunks) load(qc, kc, vc);
+      if (n + 3 < nchunks) stage_q(qa, n + 3);
+      lds_barrier();  // (a)
+      store_out();
+      if (n + 3 < nchunks) stage_kv(ka, va, n + 3);
       lds_barrier();  // (b)
     }
     lds_barrier();  // (c) last chunk's rows are in LDS
@@ -436,13 +451,26 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
   };
   f32x16 sacc[C::ET];
   int lc = g0 % a.vcph;  // chunk index inside the current head
-  const float* src = (lc > 0 && a.ws_states) ? a.ws_states + (int64_t)blockIdx.x * C::STATE : nullptr;
 #pragma unroll
   for (int ct = 0; ct < C::ET; ++ct)
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-      sacc[ct][r] = src ? src[state_index<D>(ct, wave, r, ln, lh)] : 0.f;
-  if (lh == 0) put_z(0, 32 * wave + kperm32(ln), src ? src[D * D + 32 * wave + ln] : 0.f);
+    for (int r = 0; r < 16; ++r) sacc[ct][r] = 0.f;
+  float z0 = 0.f;
+  if (lc > 0 && a.ws_states) {
+    // state carried into this piece: the running sum of its head's sub-piece sums up to here
+    const int ls = a.piece_chunks / a.state_sub;
+    const int j_last = g0 / ls;
+    const int j_first = uses_prefix_kernel(a) ? j_last : (g0 - lc) / ls + 1;
+    for (int j = j_first; j <= j_last; ++j) {
+      const float* src = a.ws_states + (int64_t)j * C::STATE;
+#pragma unroll
+      for (int ct = 0; ct < C::ET; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[ct][r] += src[state_index<D>(ct, wave, r, ln, lh)];
+      z0 += src[D * D + 32 * wave + ln];
+    }
+  }
+  if (lh == 0) put_z(0, 32 * wave + kperm32(ln), z0);
   // the product tile above the diagonal (keys 32.., queries ..31) is never computed: it stays 0
   for (int x = tid; x < 32 * 32 / 8; x += C::NTC)
     *reinterpret_cast<u32x4*>(&sm.pt[(x / 4) * C::PROW + 32 + 8 * (x % 4)]) = kZero4;
@@ -597,7 +625,7 @@ template <int D> hipError_t launch_state_t(const AttnArgs& a, hipStream_t s) {
   using C = LinCfg<D>;
   const int heads = a.B * (a.H - a.H0);
   const int smem = (int)sizeof(StateSmem<D>);
-  const dim3 grid(a.n_pieces - 1), block(C::NT);
+  const dim3 grid(a.n_pieces * a.state_sub - 1), block(C::NT);
   hipError_t e;
   if (a.phi == 0) {
     if ((e = allow_lds(linear_state_kernel<D, true>, smem)) != hipSuccess) return e;
@@ -607,9 +635,10 @@ template <int D> hipError_t launch_state_t(const AttnArgs& a, hipStream_t s) {
     linear_state_kernel<D, false><<<grid, block, smem, s>>>(a);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (a.vcph > a.piece_chunks) {  // a head can hold more than one carried boundary
+  if (uses_prefix_kernel(a)) {
     linear_prefix_kernel<<<dim3((C::STATE + 255) / 256, heads), dim3(256), 0, s>>>(
-        a.ws_states, heads, a.vcph, a.piece_chunks, a.n_pieces, C::STATE);
+        a.ws_states, heads, a.vcph, a.piece_chunks / a.state_sub, a.n_pieces * a.state_sub,
+        a.state_sub, C::STATE);
     e = hipGetLastError();
   }
   return e;

@@ -46,6 +46,18 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
+// acc + a.lo*b.lo + a.hi*b.hi on packed bf16 pairs (v_dot2c_f32_bf16)
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
+                                         __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+constexpr uint32_t kOnesBf16x2 = 0x3f803f80u;
+// acc + lo + hi of a packed bf16 pair
+__device__ __forceinline__ float dot2_ones_bf16(uint32_t a, float acc) {
+  return dot2_bf16(a, kOnesBf16x2, acc);
+}
+
 __host__ __device__ constexpr int kperm32(int k) {
   return 16 * (k / 16) + 8 * ((k / 4) % 2) + 4 * ((k / 8) % 2) + k % 4;
 }

@@ -41,8 +41,21 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   const int wave = tid >> 6;
   const int ln = lane & 31;   // query column / operand row
   const int lh = lane >> 5;   // which half of the k-slots
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int i0 = blockIdx.x * BR;
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Neighbouring query
+  // blocks of a head share most of their key band, so the logical block order (query block
+  // fastest, then head, then batch) is laid out such that each XCD gets one contiguous run of it.
+  const int nqb = (a.N + BR - 1) / BR;
+  const int total = nqb * a.H0 * a.B;
+  constexpr int kXcds = 8;
+  int lb = blockIdx.x;
+  {
+    const int per = total / kXcds, rem = total % kXcds;   // first `rem` XCDs get one more
+    const int xcd = lb % kXcds, slot = lb / kXcds;
+    lb = xcd * per + min(xcd, rem) + slot;
+  }
+  const int qb = lb % nqb;
+  const int h = (lb / nqb) % a.H0, b = lb / (nqb * a.H0);
+  const int i0 = qb * BR;
   const int q0 = i0 + wave * WQ;
   const int N = a.N, w = a.window;
 
@@ -59,7 +72,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
     const uint16_t* qr = qp + (int64_t)qi * a.q.sn + 8 * lh;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-      qreg[ks] = as_bf16x8(*reinterpret_cast<const u32x4*>(qr + 16 * ks));
+      qreg[ks] = as_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qr + 16 * ks)));
   }
 
   f32x16 oacc[MT];
@@ -72,7 +85,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
 
   const int kfirst = max(0, i0 - w + 1) / BC;
   const int klast = min(N - 1, i0 + BR - 1) / BC;
-  const float sc = a.scale * kLog2e;
+  const float sc = a.scale * kLog2e;  // base-2 logits = raw score * sc
 
   // register staging of the next tile
   u32x4 kst[KCH];
@@ -121,46 +134,61 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
         s[kt] = mfma32(ka, qreg[ks], s[kt]);
       }
     }
-    // scale to base-2 logits, mask, tile max
-    float mloc = -INFINITY;
+    // Online softmax in base 2 on the raw scores: p = 2^(s*sc - m), m a per-query reference.
+    // The reference follows the running maximum lazily: accumulators are rescaled only when
+    // some query's maximum grows by more than 8 (weights stay <= 2^8, harmless in bf16/fp32),
+    // which after the first tile or two is rare.
     const int qi = q0 + ln;
+    const bool neg = sc < 0.f;                    // uniform; a negative scale turns max into min
+    const float worst = neg ? INFINITY : -INFINITY;
+    if (need_mask) {
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+      for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float x = s[kt][r] * sc;
-        if (need_mask) {
+        for (int r = 0; r < 16; ++r) {
           const int j = t0 + 32 * kt + 8 * (r / 4) + 4 * lh + (r % 4);
-          x = (j <= qi && j > qi - w) ? x : -INFINITY;
+          if (!(j <= qi && j > qi - w)) s[kt][r] = worst;
         }
-        s[kt][r] = x;
-        mloc = fmaxf(mloc, x);
-      }
     }
+    float ext = worst;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; r += 2)
+        ext = neg ? fminf(ext, fminf(s[kt][r], s[kt][r + 1])) : fmaxf(ext, fmaxf(s[kt][r], s[kt][r + 1]));
+    float mloc = (ext == worst) ? -INFINITY : ext * sc;   // no visible key in this lane's half
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-    const float m_new = fmaxf(m_run, mloc);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;  // a query with no visible key yet
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-    m_run = m_new;
-    float lsum = 0.f;
+    if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.f) != 0) {   // wave-uniform
+      const float m_new = fmaxf(m_run, mloc);
+      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);  // 0 on the first visible tile
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
+    }
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;  // a query with no visible key yet
     uint32_t pb[2][8];  // P^T as packed bf16: pb[kt][4*kb + i] covers registers 8*kb+2i, +1
+    float lsum = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
       for (int r = 0; r < 16; r += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(s[kt][r] - m_use);
-        const float p1 = __builtin_amdgcn_exp2f(s[kt][r + 1] - m_use);
+        float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][r], sc, -m_use));
+        float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], sc, -m_use));
+        if (need_mask) {   // also covers sc == 0, where the masked product would be NaN
+          if (s[kt][r] == worst) p0 = 0.f;
+          if (s[kt][r + 1] == worst) p1 = 0.f;
+        }
         const uint32_t pk = pack_bf16(p0, p1);
         pb[kt][r / 2] = pk;
         // the row sum uses the rounded weights the PV product sees
-        lsum += bf16_lo(pk) + bf16_hi(pk);
+        lsum = dot2_ones_bf16(pk, lsum);
       }
     }
-    l_run = l_run * alpha + lsum;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
+    l_run += lsum;
 
     // O^T += V^T P^T
 #pragma unroll
@@ -182,12 +210,16 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
     }
   }
 
-  // normalise and write: lane owns query q0+ln, value columns 32*mt + 8*g + 4*lh + 0..3
+  // normalise; rows go through LDS (the K/V tiles are dead by now) so that they leave as whole
+  // rows, 16 bytes per lane.  Lane owns query q0+ln, value columns 32*mt + 8*g + 4*lh + 0..3.
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.f / l_tot;
-  const int qi = q0 + ln;
-  if (qi < N) {
-    uint16_t* orow = op + (int64_t)qi * a.osn;
+  constexpr int OROW = D + 8;
+  static_assert(BR * OROW * 2 <= (int)sizeof(Smem), "output staging must fit in the tile memory");
+  uint16_t* ot = reinterpret_cast<uint16_t*>(&sm);
+  lds_barrier();  // every wave has left the tile loop
+  {
+    uint16_t* orow = ot + (WQ * wave + ln) * OROW + 4 * lh;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
@@ -195,8 +227,19 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
         u32x2 pk;
         pk[0] = pack_bf16(oacc[mt][4 * g + 0] * inv, oacc[mt][4 * g + 1] * inv);
         pk[1] = pack_bf16(oacc[mt][4 * g + 2] * inv, oacc[mt][4 * g + 3] * inv);
-        *reinterpret_cast<u32x2*>(orow + 32 * mt + 8 * g + 4 * lh) = pk;
+        *reinterpret_cast<u32x2*>(orow + 32 * mt + 8 * g) = pk;
       }
+    }
+  }
+  lds_barrier();
+  constexpr int OPIECES = BR * (D / 8) / kMfmaWindowThreads;
+#pragma unroll
+  for (int i = 0; i < OPIECES; ++i) {
+    const int c = tid + i * kMfmaWindowThreads;
+    const int row = c / (D / 8), col = 8 * (c % (D / 8));
+    if (i0 + row < N) {
+      const u32x4 o = *reinterpret_cast<const u32x4*>(ot + row * OROW + col);
+      __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(op + (int64_t)(i0 + row) * a.osn + col));
     }
   }
 }
@@ -205,7 +248,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
 
 hipError_t launch_windowed_mfma(const AttnArgs& a, hipStream_t s) {
   if (a.H0 <= 0 || a.N <= 0 || a.B <= 0) return hipSuccess;
-  dim3 grid((a.N + BR - 1) / BR, a.H0, a.B);
+  dim3 grid(((a.N + BR - 1) / BR) * a.H0 * a.B);
   dim3 block(kMfmaWindowThreads);
   if (a.d == 64) windowed_mfma_kernel<64><<<grid, block, 0, s>>>(a);
   else windowed_mfma_kernel<128><<<grid, block, 0, s>>>(a);

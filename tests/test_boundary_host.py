@@ -54,10 +54,15 @@ def test_plan_headline_config():
     assert pl["chunk"] == 64 and pl["segment_len"] == 52 * 64
     assert pl["n_segments"] == 256 and pl["linear_blocks"] == 256
     assert pl["windowed_blocks"] == 4 * 6 * (8192 // 128)
-    # boundaries q*52 that are not multiples of 128 need a carried state
-    mid = sum(1 for q in range(1, 256) if (q * 52) % 128 != 0)
-    assert pl["state_blocks"] == mid
-    want_ws = 256 * (128 * 128 + 128) * 4
+    # The state pass works on half pieces (26 chunks).  A half-piece boundary e inside a head is
+    # summed iff a piece boundary (multiple of 52) at or after e lies inside the same head.
+    mid = 0
+    for j in range(1, 512):
+        e = 26 * j
+        nxt = -(-e // 52) * 52
+        mid += (e % 128 != 0) and nxt < (e // 128 + 1) * 128 and nxt < 104 * 128
+    assert pl["state_blocks"] == mid == 448
+    want_ws = 512 * (128 * 128 + 128) * 4
     assert pl["workspace_bytes"] == want_ws
     assert gb.gformer_attn_workspace_bytes(4, 32, 8192, 128, 256, gb.make_params(n_sparse_heads=6)) == want_ws
 
@@ -83,7 +88,7 @@ def test_plan_modes_and_overrides():
     # pieces that divide the head length carry nothing across their aligned boundaries
     st, pl = _plan(1, 64, 8192, 128, 256, n_sparse_heads=0)   # 64 heads x 128 chunks / 256 = 32
     assert st == gb.GF_OK and pl["segment_len"] == 32 * 64 and pl["n_segments"] == 256
-    assert pl["state_blocks"] == 64 * 3
+    assert pl["state_blocks"] == 64 * 6    # half pieces of 16 chunks: 6 summed boundaries per head
 
 
 @pytest.mark.parametrize("args,kw,want", [
