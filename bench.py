@@ -39,6 +39,24 @@ def algorithmic_work(wl, H0):
             "exp_count": n_win * pairs}
 
 
+def measured_traffic(kernel: str, workload: str, h0: int):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE scaled by a plain copy), or None when no summary covers this workload."""
+    if workload != "llm7b" or h0 != 6:
+        return None
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_llm7b.txt")
+    names = {"linear_main": "linear_main_kernel", "linear_state": "linear_state_kernel",
+             "windowed": "windowed_mfma_kernel"}
+    try:
+        for line in open(path, encoding="utf-8"):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "hbm_bytes_per_launch" and parts[1] == names.get(kernel):
+                return int(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -139,7 +157,7 @@ def main() -> int:
     achieved_gbs = dom_bytes / kern[dominant] / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved_gbs, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
-                "traffic": None,
+                "traffic": measured_traffic(dominant, wl.name, H0),
                 "avg_launch_us": round(kern[dominant] * 1e6, 2),
                 "algorithmic_bytes_per_launch": dom_bytes,
                 "mfma_tflops": round(dom_flops / kern[dominant] / 1e12, 1),
