@@ -65,7 +65,7 @@ def main() -> int:
     ap.add_argument("--workload", default="llm7b")
     ap.add_argument("--h0", type=int, default=-1, help="sparse heads (default: workload's)")
     ap.add_argument("--segment-len", type=int, default=0)
-    ap.add_argument("--no-overlap", action="store_true", help="enqueue everything on one stream")
+    ap.add_argument("--overlap", action="store_true", help="windowed heads on the library's side stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-modes", action="store_true", help="skip the pure-windowed / pure-linear runs")
     args = ap.parse_args()
@@ -96,7 +96,7 @@ def main() -> int:
 
     def make_call(h0, mask=0):
         params = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=h0, segment_len=args.segment_len,
-                                launch_mask=mask, no_overlap=int(args.no_overlap))
+                                launch_mask=mask, overlap=int(args.overlap))
         need = gb.gformer_attn_workspace_bytes(wl.B, wl.H, wl.N, wl.d, wl.window, params)
         ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
         ptrs = (tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), out.data_ptr())

@@ -29,8 +29,8 @@
  *     256-byte aligned; may be NULL when that size is 0.  It holds the linear-attention
  *     states carried into each piece and is rewritten by every call that uses it.
  *   - `hip_stream` is a hipStream_t (NULL = default stream).  The call enqueues kernels and
- *     returns; it never synchronises.  When both head groups are present the windowed heads
- *     are enqueued on one library-owned, default-priority side stream per device that waits
+ *     returns; it never synchronises.  With params.overlap = 1 and both head groups present the
+ *     windowed heads are enqueued on one library-owned, default-priority side stream per device that waits
  *     for the work already in `hip_stream` and that `hip_stream` waits for before going on
  *     (an event fork/join, also valid under stream capture); the stream and its two events are
  *     created on first use and kept until the process ends.  Calls are serialised by a mutex
@@ -83,9 +83,9 @@ typedef struct gformer_params {
   int32_t launch_mask;    /* 0 = everything.  Otherwise a bit set of GF_LAUNCH_*: only those */
                           /* kernels are enqueued (profiling aid; the skipped stages' data   */
                           /* is taken as already present in the workspace).                  */
-  int32_t no_overlap;     /* 0: the windowed heads run on a library-owned side stream that   */
-                          /* forks from and joins `hip_stream`, next to the linear heads.    */
-                          /* 1: everything is enqueued on `hip_stream` one after another.    */
+  int32_t overlap;        /* 0: everything is enqueued on `hip_stream` one after another.    */
+                          /* 1: the windowed heads run on a library-owned side stream that   */
+                          /* forks from and joins `hip_stream`, next to the state pass.      */
   int32_t reserved0;
   float softmax_scale;    /* multiplies q.k on windowed heads; 1.0 when Q is pre-scaled      */
   float eps;              /* added to the linear denominator; 0 follows Algorithm 1          */
@@ -114,7 +114,7 @@ typedef struct gformer_plan {
 } gformer_plan;
 
 /* Fills `p` with defaults: struct_size, dtype = GF_BF16, phi = GF_PHI_ELU1, H0 = 0, chunk,
- * segment_len, impl, launch_mask = 0, no_overlap = 0, softmax_scale = 1, eps = 0, dense
+ * segment_len, impl, launch_mask = 0, overlap = 0, softmax_scale = 1, eps = 0, dense
  * strides. */
 void gformer_params_init(gformer_params* p);
 

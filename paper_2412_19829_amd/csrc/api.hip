@@ -85,7 +85,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   if (p->n_sparse_heads < 0 || p->n_sparse_heads > H) return GF_ERR_INVALID_ARG;
   if (p->chunk < 0 || p->segment_len < 0) return GF_ERR_INVALID_ARG;
   if (p->launch_mask < 0 || p->launch_mask > 7) return GF_ERR_INVALID_ARG;
-  if (p->no_overlap != 0 && p->no_overlap != 1) return GF_ERR_INVALID_ARG;
+  if (p->overlap != 0 && p->overlap != 1) return GF_ERR_INVALID_ARG;
   if (!(p->softmax_scale == p->softmax_scale) || !(p->eps >= 0.f)) return GF_ERR_INVALID_ARG;
   if (B > 65535 || H > 65535) return GF_ERR_UNSUPPORTED;  // grid y/z limits
   gf_status st;
@@ -244,7 +244,7 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
     const bool lin = (mask & (GF_LAUNCH_LINEAR_STATE | GF_LAUNCH_LINEAR_MAIN)) && a.H0 < a.H;
     std::lock_guard<std::mutex> lock(g_enqueue_mutex);
     SideStream* side = nullptr;
-    if (win && lin && !p->no_overlap) e = side_stream_for_current_device(&side);
+    if (win && lin && p->overlap) e = side_stream_for_current_device(&side);
     if (side && e == hipSuccess) {
       // fork: the windowed heads wait for what is already in `s`, then run beside the linear ones
       e = hipEventRecord(side->fork, s);

@@ -140,10 +140,37 @@ __device__ __forceinline__ int piece_chunk_count(const AttnArgs& a, int g0, int 
 }
 
 // State tile (ct, wave) in accumulator layout: lane = value column 32*wave + l%32,
-// register r = feature row 32*ct + 8*(r/4) + 4*(l/32) + r%4.  Workspace layout is [c][e] fp32.
+// register r = feature row 32*ct + 8*(r/4) + 4*(l/32) + r%4.  The workspace keeps A in exactly
+// this order (tile, lane, register) so that a lane moves its 16 values of a tile as four 16-byte
+// accesses; Z follows at offset D*D in natural feature order.
 template <int D>
-__device__ __forceinline__ int state_index(int ct, int wave, int r, int ln, int lh) {
-  return (32 * ct + 8 * (r / 4) + 4 * lh + (r % 4)) * D + 32 * wave + ln;
+__device__ __forceinline__ int state_tile_offset(int ct, int wave, int lane) {
+  return ((ct * LinCfg<D>::NWC + wave) * 64 + lane) * 16;
+}
+template <int D>
+__device__ __forceinline__ void state_store(float* dst, const f32x16 (&sacc)[LinCfg<D>::ET],
+                                            int wave, int lane) {
+#pragma unroll
+  for (int ct = 0; ct < LinCfg<D>::ET; ++ct) {
+    float4* p = reinterpret_cast<float4*>(dst + state_tile_offset<D>(ct, wave, lane));
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      p[g] = make_float4(sacc[ct][4 * g], sacc[ct][4 * g + 1], sacc[ct][4 * g + 2], sacc[ct][4 * g + 3]);
+  }
+}
+template <int D>
+__device__ __forceinline__ void state_add(f32x16 (&sacc)[LinCfg<D>::ET], const float* src,
+                                          int wave, int lane) {
+#pragma unroll
+  for (int ct = 0; ct < LinCfg<D>::ET; ++ct) {
+    const float4* p = reinterpret_cast<const float4*>(src + state_tile_offset<D>(ct, wave, lane));
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 x = p[g];
+      sacc[ct][4 * g] += x.x; sacc[ct][4 * g + 1] += x.y;
+      sacc[ct][4 * g + 2] += x.z; sacc[ct][4 * g + 3] += x.w;
+    }
+  }
 }
 
 // A += phiK^T V for this wave's value columns, from the row-major chunk tiles in LDS; returns
@@ -283,10 +310,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs
     lds_barrier();
   }
   float* dst = a.ws_states + (int64_t)q * C::STATE;
-#pragma unroll
-  for (int ct = 0; ct < C::ET; ++ct)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) dst[state_index<D>(ct, wave, r, ln, lh)] = sacc[ct][r];
+  state_store<D>(dst, sacc, wave, lane);
   zacc += __shfl_xor(zacc, 32, 64);
   if (lh == 0) dst[D * D + 32 * wave + ln] = zacc;
 }
@@ -463,10 +487,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
     const int j_first = uses_prefix_kernel(a) ? j_last : (g0 - lc) / ls + 1;
     for (int j = j_first; j <= j_last; ++j) {
       const float* src = a.ws_states + (int64_t)j * C::STATE;
-#pragma unroll
-      for (int ct = 0; ct < C::ET; ++ct)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[ct][r] += src[state_index<D>(ct, wave, r, ln, lh)];
+      state_add<D>(sacc, src, wave, lane);
       z0 += src[D * D + 32 * wave + ln];
     }
   }

@@ -21,11 +21,14 @@ constexpr int BC = 64;               // keys per tile
 constexpr int WQ = 32;               // queries per wave
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <int D> struct WinSmem {
+template <int D> struct WinTiles {
   static constexpr int KROW = D + 8;    // row stride = 4 dwords mod 64: conflict-free b128 reads
   static constexpr int VROW = D + 32;   // row stride = 16 dwords mod 64: conflict-free tr reads
   uint16_t k[BC * KROW];
   uint16_t v[BC * VROW];
+};
+template <int D> struct WinSmem {
+  WinTiles<D> buf[2];  // tile t in buf[t % 2]: one is filled while the other is read
 };
 
 template <int D>
@@ -34,7 +37,9 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   constexpr int MT = D / 32;           // 32-row tiles of O^T
   constexpr int KCH = BC * D / 8 / kMfmaWindowThreads;  // 16-byte K chunks per thread per tile
   using Smem = WinSmem<D>;
-  __shared__ __attribute__((aligned(16))) Smem sm;
+  using Tiles = WinTiles<D>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -85,129 +90,145 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
 
   const int kfirst = max(0, i0 - w + 1) / BC;
   const int klast = min(N - 1, i0 + BR - 1) / BC;
-  const float sc = a.scale * kLog2e;  // base-2 logits = raw score * sc
+  // base-2 logits = raw score * sc; a zero scale is nudged so that masked (infinite) scores
+  // still map to weight 0 instead of NaN
+  const float sc = (a.scale == 0.f ? 1e-30f : a.scale) * kLog2e;
 
-  // register staging of the next tile
+  // register staging of a tile on its way from global memory to LDS: thread t moves 16-byte
+  // pieces (row t/C8 + i*RP, columns 8*(t%C8)..), a uniform row base plus a constant offset
+  constexpr int C8 = D / 8, RP = kMfmaWindowThreads / C8;
+  static_assert(KCH * RP == BC, "tile rows must be covered exactly");
+  const int prow = tid / C8, pcol = 8 * (tid % C8);
+  const uint32_t koff = (uint32_t)(prow * (int)a.k.sn + pcol), voff = (uint32_t)(prow * (int)a.v.sn + pcol);
   u32x4 kst[KCH];
   u32x4 vst[KCH];
   auto load_tile = [&](int t) {
     const int t0 = t * BC;
+    if (t0 + BC <= N) {
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int c = tid + i * kMfmaWindowThreads;
-      const int row = min(t0 + c / (D / 8), N - 1);
-      kst[i] = *reinterpret_cast<const u32x4*>(kp + (int64_t)row * a.k.sn + 8 * (c % (D / 8)));
-      vst[i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)row * a.v.sn + 8 * (c % (D / 8)));
-    }
-  };
-  auto store_tile = [&]() {
+      for (int i = 0; i < KCH; ++i) {
+        kst[i] = *reinterpret_cast<const u32x4*>(kp + (int64_t)(t0 + i * RP) * a.k.sn + koff);
+        vst[i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)(t0 + i * RP) * a.v.sn + voff);
+      }
+    } else {  // last tile of the sequence: rows past N-1 re-read row N-1 (in bounds, masked later)
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int c = tid + i * kMfmaWindowThreads;
-      *reinterpret_cast<u32x4*>(&sm.k[(c / (D / 8)) * Smem::KROW + 8 * (c % (D / 8))]) = kst[i];
-      *reinterpret_cast<u32x4*>(&sm.v[(c / (D / 8)) * Smem::VROW + 8 * (c % (D / 8))]) = vst[i];
-    }
-  };
-
-  load_tile(kfirst);
-  for (int t = kfirst; t <= klast; ++t) {
-    lds_barrier();  // every wave is done reading the previous tile
-    store_tile();
-    lds_barrier();
-    if (t < klast) load_tile(t + 1);  // in flight while this tile is computed
-
-    const int t0 = t * BC;
-    // keys visible to query i: i - w < j <= i
-    if (t0 > q0 + WQ - 1 || t0 + BC - 1 <= q0 - w) continue;  // nothing for this wave's queries
-    const bool need_mask = !(t0 + BC - 1 <= q0 && t0 > q0 + WQ - 1 - w);
-
-    // S^T = K Q^T for the two 32-key halves of the tile
-    f32x16 s[2];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
-      const uint16_t* krow = &sm.k[(32 * kt + ln) * Smem::KROW + 8 * lh];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4*>(krow + 16 * ks));
-        s[kt] = mfma32(ka, qreg[ks], s[kt]);
+      for (int i = 0; i < KCH; ++i) {
+        const int row = min(t0 + prow + i * RP, N - 1);
+        kst[i] = *reinterpret_cast<const u32x4*>(kp + (int64_t)row * a.k.sn + pcol);
+        vst[i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)row * a.v.sn + pcol);
       }
     }
-    // Online softmax in base 2 on the raw scores: p = 2^(s*sc - m), m a per-query reference.
-    // The reference follows the running maximum lazily: accumulators are rescaled only when
-    // some query's maximum grows by more than 8 (weights stay <= 2^8, harmless in bf16/fp32),
-    // which after the first tile or two is rare.
-    const int qi = q0 + ln;
-    const bool neg = sc < 0.f;                    // uniform; a negative scale turns max into min
-    const float worst = neg ? INFINITY : -INFINITY;
-    if (need_mask) {
+  };
+  auto store_tile = [&](Tiles& b) {
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      *reinterpret_cast<u32x4*>(&b.k[(prow + i * RP) * Tiles::KROW + pcol]) = kst[i];
+      *reinterpret_cast<u32x4*>(&b.v[(prow + i * RP) * Tiles::VROW + pcol]) = vst[i];
+    }
+  };
+
+  // Tile t is computed from buf[t % 2] while tile t+1 is stored into the other buffer and tile
+  // t+2 is on its way from memory: one barrier per tile.
+  load_tile(kfirst);
+  store_tile(sm.buf[0]);
+  if (kfirst < klast) load_tile(kfirst + 1);
+  lds_barrier();
+  for (int t = kfirst; t <= klast; ++t) {
+    const Tiles& cur = sm.buf[(t - kfirst) & 1];
+    if (t < klast) store_tile(sm.buf[(t - kfirst + 1) & 1]);
+    if (t + 1 < klast) load_tile(t + 2);
+    const int t0 = t * BC;
+    // keys visible to query i: i - w < j <= i; a tile with none for this wave's queries is skipped
+    if (!(t0 > q0 + WQ - 1 || t0 + BC - 1 <= q0 - w)) {
+      const bool need_mask = !(t0 + BC - 1 <= q0 && t0 > q0 + WQ - 1 - w);
+
+      // S^T = K Q^T for the two 32-key halves of the tile
+      f32x16 s[2];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+        const uint16_t* krow = &cur.k[(32 * kt + ln) * Tiles::KROW + 8 * lh];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4*>(krow + 16 * ks));
+          s[kt] = mfma32(ka, qreg[ks], s[kt]);
+        }
+      }
+      // Online softmax in base 2 on the raw scores: p = 2^(s*sc - m), m a per-query reference.
+      // The reference follows the running maximum lazily: accumulators are rescaled only when
+      // some query's maximum grows by more than 8 (weights stay <= 2^8, harmless in bf16/fp32),
+      // which after the first tile or two is rare.
+      const bool neg = sc < 0.f;                    // uniform; a negative scale turns max into min
+      const float worst = neg ? INFINITY : -INFINITY;
+      if (need_mask) {
+        // register (kt, r) of this lane is key t0 + c + 4*lh, c = 32*kt + 8*(r/4) + r%4;
+        // visible iff 0 <= (qi - key) < w
+        const int rel = q0 + ln - t0 - 4 * lh;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int c = 32 * kt + 8 * (r / 4) + (r % 4);
+            if ((unsigned)(rel - c) >= (unsigned)w) s[kt][r] = worst;
+          }
+      }
+      float ext = worst;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = t0 + 32 * kt + 8 * (r / 4) + 4 * lh + (r % 4);
-          if (!(j <= qi && j > qi - w)) s[kt][r] = worst;
-        }
-    }
-    float ext = worst;
+        for (int r = 0; r < 16; r += 2)
+          ext = neg ? fminf(ext, fminf(s[kt][r], s[kt][r + 1])) : fmaxf(ext, fmaxf(s[kt][r], s[kt][r + 1]));
+      float mloc = (ext == worst) ? -INFINITY : ext * sc;   // no visible key in this lane's half
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+      if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.f) != 0) {   // wave-uniform
+        const float m_new = fmaxf(m_run, mloc);
+        const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);  // 0 on the first visible tile
+        m_run = m_new;
+        l_run *= alpha;
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int r = 0; r < 16; r += 2)
-        ext = neg ? fminf(ext, fminf(s[kt][r], s[kt][r + 1])) : fmaxf(ext, fmaxf(s[kt][r], s[kt][r + 1]));
-    float mloc = (ext == worst) ? -INFINITY : ext * sc;   // no visible key in this lane's half
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-    if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.f) != 0) {   // wave-uniform
-      const float m_new = fmaxf(m_run, mloc);
-      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);  // 0 on the first visible tile
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
-    }
-    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;  // a query with no visible key yet
-    uint32_t pb[2][8];  // P^T as packed bf16: pb[kt][4*kb + i] covers registers 8*kb+2i, +1
-    float lsum = 0.f;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][r], sc, -m_use));
-        float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], sc, -m_use));
-        if (need_mask) {   // also covers sc == 0, where the masked product would be NaN
-          if (s[kt][r] == worst) p0 = 0.f;
-          if (s[kt][r + 1] == worst) p1 = 0.f;
-        }
-        const uint32_t pk = pack_bf16(p0, p1);
-        pb[kt][r / 2] = pk;
-        // the row sum uses the rounded weights the PV product sees
-        lsum = dot2_ones_bf16(pk, lsum);
+          for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
       }
-    }
-    l_run += lsum;
+      const float m_use = (m_run == -INFINITY) ? 0.f : m_run;  // a query with no visible key yet
+      uint32_t pb[2][8];  // P^T as packed bf16: pb[kt][4*kb + i] covers registers 8*kb+2i, +1
+      float lsum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][r], sc, -m_use));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], sc, -m_use));
+          const uint32_t pk = pack_bf16(p0, p1);
+          pb[kt][r / 2] = pk;
+          // the row sum uses the rounded weights the PV product sees
+          lsum = dot2_ones_bf16(pk, lsum);
+        }
+      }
+      l_run += lsum;
 
-    // O^T += V^T P^T
+      // O^T += V^T P^T
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+      for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        u32x4 pw;
-        pw[0] = pb[kt][4 * kb + 0]; pw[1] = pb[kt][4 * kb + 1];
-        pw[2] = pb[kt][4 * kb + 2]; pw[3] = pb[kt][4 * kb + 3];
-        const bf16x8 pbv = as_bf16x8(pw);
+        for (int kb = 0; kb < 2; ++kb) {
+          u32x4 pw;
+          pw[0] = pb[kt][4 * kb + 0]; pw[1] = pb[kt][4 * kb + 1];
+          pw[2] = pb[kt][4 * kb + 2]; pw[3] = pb[kt][4 * kb + 3];
+          const bf16x8 pbv = as_bf16x8(pw);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          // keys in the order the score registers hold them: 16*kb + 4*lh + j, then + 8
-          const int r0 = 32 * kt + 16 * kb + 4 * lh;
-          const bf16x8 va_ = lds_operand_tr(sm.v, Smem::VROW, r0, r0 + 8, 32 * mt, lane);
-          oacc[mt] = mfma32(va_, pbv, oacc[mt]);
+          for (int mt = 0; mt < MT; ++mt) {
+            // keys in the order the score registers hold them: 16*kb + 4*lh + j, then + 8
+            const int r0 = 32 * kt + 16 * kb + 4 * lh;
+            const bf16x8 va_ = lds_operand_tr(cur.v, Tiles::VROW, r0, r0 + 8, 32 * mt, lane);
+            oacc[mt] = mfma32(va_, pbv, oacc[mt]);
+          }
         }
       }
     }
+    lds_barrier();  // tile t is consumed, tile t+1 is in place
   }
 
   // normalise; rows go through LDS (the K/V tiles are dead by now) so that they leave as whole
@@ -216,8 +237,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   const float inv = 1.f / l_tot;
   constexpr int OROW = D + 8;
   static_assert(BR * OROW * 2 <= (int)sizeof(Smem), "output staging must fit in the tile memory");
-  uint16_t* ot = reinterpret_cast<uint16_t*>(&sm);
-  lds_barrier();  // every wave has left the tile loop
+  uint16_t* ot = reinterpret_cast<uint16_t*>(&sm);  // the loop's last barrier has freed the tiles
   {
     uint16_t* orow = ot + (WQ * wave + ln) * OROW + 4 * lh;
 #pragma unroll
@@ -250,8 +270,20 @@ hipError_t launch_windowed_mfma(const AttnArgs& a, hipStream_t s) {
   if (a.H0 <= 0 || a.N <= 0 || a.B <= 0) return hipSuccess;
   dim3 grid(((a.N + BR - 1) / BR) * a.H0 * a.B);
   dim3 block(kMfmaWindowThreads);
-  if (a.d == 64) windowed_mfma_kernel<64><<<grid, block, 0, s>>>(a);
-  else windowed_mfma_kernel<128><<<grid, block, 0, s>>>(a);
+  hipError_t e;
+  if (a.d == 64) {
+    const int smem = (int)sizeof(WinSmem<64>);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(windowed_mfma_kernel<64>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    windowed_mfma_kernel<64><<<grid, block, smem, s>>>(a);
+  } else {
+    const int smem = (int)sizeof(WinSmem<128>);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(windowed_mfma_kernel<128>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    windowed_mfma_kernel<128><<<grid, block, smem, s>>>(a);
+  }
   return hipGetLastError();
 }
 

@@ -103,7 +103,7 @@ def test_plan_modes_and_overrides():
     ((1, 2, 16, 64, 4), {"eps": -1.0}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"eps": float("nan")}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"launch_mask": 8}, gb.GF_ERR_INVALID_ARG),
-    ((1, 2, 16, 64, 4), {"no_overlap": 2}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"overlap": 2}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"q_stride": (1024, 512, 60)}, gb.GF_ERR_INVALID_ARG),   # not 16-byte rows
     ((1, 2, 16, 64, 4), {"o_stride": (2048, 1024, 32)}, gb.GF_ERR_INVALID_ARG),  # rows overlap
     ((1, 2, 256, 64, 4), {"chunk": 64, "segment_len": 96}, gb.GF_ERR_INVALID_ARG),

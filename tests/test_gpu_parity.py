@@ -168,11 +168,11 @@ def test_repeat_runs_are_bit_identical(dtype, impl):
 
 
 def test_side_stream_and_serial_enqueue_agree():
-    """Windowed heads on the library's side stream (default) vs everything on one stream."""
+    """Windowed heads on the library's side stream vs everything on one stream (default)."""
     B, H, N, d, w, H0 = 2, 6, 1500, 128, 200, 2
     q, k, v = synth(B, H, N, d, "bf16", 20)
-    a = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA)
-    b = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA, no_overlap=1)
+    a = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA, overlap=1)
+    b = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA, overlap=0)
     assert np.array_equal(a, b)
     check(a, oracle(q, k, v, w, H0), "bf16", "side stream")
 
