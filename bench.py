@@ -60,8 +60,11 @@ def measured_traffic(kernel: str, workload: str, h0: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--ramp-ms", type=float, default=300.0,
+                    help="untimed calls issued before the warmup steps until the device has been busy this long "
+                         "(the card needs tens of milliseconds of load to reach its steady clocks)")
     ap.add_argument("--workload", default="llm7b")
     ap.add_argument("--h0", type=int, default=-1, help="sparse heads (default: workload's)")
     ap.add_argument("--segment-len", type=int, default=0)
@@ -107,7 +110,15 @@ def main() -> int:
                 raise gb.GformerError(st, gb.gformer_status_string(st))
         return call, params, ws
 
+    def ramp(call):
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < args.ramp_ms:
+            for _ in range(20):
+                call()
+            torch.cuda.synchronize()
+
     def time_steps(call, steps, warmup):
+        ramp(call)
         for _ in range(warmup):
             call()
         torch.cuda.synchronize()
@@ -145,7 +156,7 @@ def main() -> int:
             c, _, _w = make_call(H0, mask)
             for _ in range(3):
                 c()
-            kern[name] = event_time(c, max(10, args.steps))
+            kern[name] = event_time(c, min(max(10, args.steps), 200))
     dominant = max(kern, key=kern.get)
     if dominant == "windowed":
         dom_bytes, dom_flops = work["bytes_windowed"], work["flops_windowed"]
@@ -168,6 +179,7 @@ def main() -> int:
         "value": round(wl.B * wl.N / sec, 1),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ramp_ms": args.ramp_ms,
         "ms_per_step": round(sec * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
