@@ -24,14 +24,16 @@
  *   - Element (b, h, n, c) of a tensor lives at base + b*stride[0] + h*stride[1] +
  *     n*stride[2] + c (strides in elements, last dimension contiguous).  All-zero strides
  *     mean dense [B, H, N, d].  The paper's [B, N, H, E] layout is stride = {N*H*d, d, H*d}.
- *     Strides must be multiples of 8 elements (16-byte rows for bf16).
+ *     Strides must be multiples of 8 elements (16-byte rows for bf16); the row stride
+ *     stride[2] may not exceed 2^20 elements (GF_ERR_UNSUPPORTED beyond).
  *   - `workspace` is a DEVICE pointer of at least gformer_attn_workspace_bytes(...) bytes,
  *     256-byte aligned; may be NULL when that size is 0.  It holds the linear-attention
  *     states carried into each piece and is rewritten by every call that uses it.
  *   - `hip_stream` is a hipStream_t (NULL = default stream).  The call enqueues kernels and
- *     returns; it never synchronises.  With params.overlap = 1 and both head groups present the
- *     windowed heads are enqueued on one library-owned, default-priority side stream per device that waits
- *     for the work already in `hip_stream` and that `hip_stream` waits for before going on
+ *     returns; it never synchronises.  With params.overlap = 1 and both head groups present
+ *     the windowed heads are enqueued on one library-owned, default-priority side stream per
+ *     device that waits for the work already in `hip_stream` and that `hip_stream` waits for
+ *     before going on
  *     (an event fork/join, also valid under stream capture); the stream and its two events are
  *     created on first use and kept until the process ends.  Calls are serialised by a mutex
  *     while they enqueue.

@@ -49,6 +49,8 @@ hipError_t side_stream_for_current_device(SideStream** out) {
   return hipSuccess;
 }
 
+constexpr int64_t kMaxRowStride = 1 << 20;  // elements
+
 bool strides_all_zero(const int64_t* s) { return s[0] == 0 && s[1] == 0 && s[2] == 0; }
 
 void dense_strides(int64_t* s, int H, int N, int d) {
@@ -67,6 +69,7 @@ gf_status check_strides(const int64_t* in, int64_t* out, int H, int N, int d) {
     out[i] = in[i];
   }
   if (N > 1 && in[2] < d) return GF_ERR_INVALID_ARG;  // rows would overlap
+  if (in[2] > kMaxRowStride) return GF_ERR_UNSUPPORTED;  // kernels keep in-chunk offsets in 32 bits
   return GF_OK;
 }
 

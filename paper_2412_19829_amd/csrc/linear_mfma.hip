@@ -25,6 +25,8 @@
 #include "common.hpp"
 #include "mfma.hpp"
 
+#include <type_traits>
+
 namespace gformer {
 namespace {
 
@@ -210,19 +212,33 @@ template <int D> struct Staging {
   }
 };
 
-// A full chunk is read with a uniform row base plus a per-thread element offset that never
-// changes, so it costs no vector integer arithmetic.  Rows past N-1 (a head's last chunk only)
-// re-read row N-1, in bounds.
+// One tensor's chunk as seen by a producer thread: piece i is read from a wave-uniform base
+// (row t0 + i*RP of the head, kept in scalar registers) plus one per-thread byte offset that
+// never changes, so a load costs no vector address arithmetic beyond its clamp.  Rows past N-1
+// (a head's last chunk only) re-read row N-1, in bounds.  Streamed once: non-temporal loads
+// (measured ~7.1 TB/s vs ~6.1 TB/s for plain loads).
+template <int D> struct PieceOffsets {
+  uint32_t off;   // byte offset of (row r0, columns col..col+7) from the piece's first row
+  uint32_t colb;  // byte offset of the thread's columns inside a row
+  int sn;         // row stride in elements
+  __device__ __forceinline__ PieceOffsets(const Staging<D>& st, int64_t row_stride)
+      : off(2u * (uint32_t)(st.r0 * (int)row_stride + st.col)), colb(2u * (uint32_t)st.col),
+        sn((int)row_stride) {}
+};
 template <int D>
-__device__ __forceinline__ u32x4 load_piece(const uint16_t* base, int64_t sn, uint32_t toff,
-                                            int t0, int i, int N, const Staging<D>& st) {
+__device__ __forceinline__ void load_chunk(u32x4 (&dst)[LinCfg<D>::PIECES], const uint16_t* head,
+                                           int t0, int N, const PieceOffsets<D>& po) {
   using C = LinCfg<D>;
-  // streamed once: non-temporal loads (measured: ~7.1 TB/s vs ~6.1 TB/s for plain loads)
-  if (t0 + CH <= N)
-    return __builtin_nontemporal_load(
-        reinterpret_cast<const u32x4*>(base + (int64_t)(t0 + i * C::RP) * sn + toff));
-  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(
-      base + (int64_t)min(t0 + st.r0 + i * C::RP, N - 1) * sn + st.col));
+  const int last = min(N - 1 - t0, CH - 1);  // last valid row of the chunk
+  const char* chunk = reinterpret_cast<const char*>(head + (int64_t)t0 * po.sn);
+#pragma unroll
+  for (int i = 0; i < C::PIECES; ++i) {
+    const int first = min(i * C::RP, last);  // uniform: the piece's first row, clamped
+    const char* base = chunk + 2u * (uint32_t)(first * po.sn);
+    const uint32_t lim = 2u * (uint32_t)((last - first) * po.sn) + po.colb;
+    dst[i] = __builtin_nontemporal_load(
+        reinterpret_cast<const u32x4*>(base + (size_t)min(po.off, lim)));
+  }
 }
 
 constexpr u32x4 kZero4 = {0u, 0u, 0u, 0u};
@@ -258,16 +274,12 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs
   if (wave >= C::NWC) {
     // ---- producers ----
     const Staging<D> st(tid - C::NTC);
-    const uint32_t koff = (uint32_t)(st.r0 * (int)a.k.sn + st.col);
-    const uint32_t voff = (uint32_t)(st.r0 * (int)a.v.sn + st.col);
+    const PieceOffsets<D> ko(st, a.k.sn), vo(st, a.v.sn);
     u32x4 ka[C::PIECES], va[C::PIECES], kb[C::PIECES], vb[C::PIECES];
     auto load = [&](u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES], int n) {
       const int t0 = (lc0 + n) * CH;
-#pragma unroll
-      for (int i = 0; i < C::PIECES; ++i) {
-        kr[i] = load_piece<D>(hp.k, a.k.sn, koff, t0, i, N, st);
-        vr[i] = load_piece<D>(hp.v, a.v.sn, voff, t0, i, N, st);
-      }
+      load_chunk<D>(kr, hp.k, t0, N, ko);
+      load_chunk<D>(vr, hp.v, t0, N, vo);
     };
     auto stage = [&](const u32x4 (&kr)[C::PIECES], const u32x4 (&vr)[C::PIECES], int n) {
       const int t0 = (lc0 + n) * CH;
@@ -282,18 +294,31 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs
         *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = valid ? vr[i] : kZero4;
       }
     };
+    // chunk m travels in set m % 2; a set is reloaded (two chunks ahead) as soon as it is staged.
+    // Steady rounds are compiled without conditions so that the compiler's wait counters know
+    // exactly which loads are in flight.
     load(ka, va, 0);
     if (nchunks > 1) load(kb, vb, 1);
     stage(ka, va, 0);
+    if (nchunks > 2) load(ka, va, 2);
     lds_barrier();
+    auto round2 = [&](int n, auto steady) {
+      constexpr bool S = decltype(steady)::value;
+      if (S || n + 1 < nchunks) stage(kb, vb, n + 1);
+      if (S || n + 3 < nchunks) load(kb, vb, n + 3);
+      lds_barrier();
+      if (!S && n + 1 >= nchunks) return false;
+      if (S || n + 2 < nchunks) stage(ka, va, n + 2);
+      if (S || n + 4 < nchunks) load(ka, va, n + 4);
+      lds_barrier();
+      return true;
+    };
     for (int n = 0; n < nchunks; n += 2) {
-      if (n + 2 < nchunks) load(ka, va, n + 2);
-      if (n + 1 < nchunks) stage(kb, vb, n + 1);
-      lds_barrier();
-      if (n + 1 >= nchunks) break;
-      if (n + 3 < nchunks) load(kb, vb, n + 3);
-      if (n + 2 < nchunks) stage(ka, va, n + 2);
-      lds_barrier();
+      if (n + 4 < nchunks) {
+        round2(n, std::true_type{});
+      } else if (!round2(n, std::false_type{})) {
+        break;
+      }
     }
     return;
   }
@@ -361,22 +386,17 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
   if (wave >= C::NWC) {
     // ---- producers ----
     const Staging<D> st(tid - C::NTC);
-    const uint32_t qoff = (uint32_t)(st.r0 * (int)a.q.sn + st.col);
-    const uint32_t koff = (uint32_t)(st.r0 * (int)a.k.sn + st.col);
-    const uint32_t voff = (uint32_t)(st.r0 * (int)a.v.sn + st.col);
+    const PieceOffsets<D> qo(st, a.q.sn), ko(st, a.k.sn), vo(st, a.v.sn);
     ChunkCursor<D> cl(a, g0), cs(a, g0), co(a, g0);  // next chunk to load / stage / write out
-    // three register sets: chunk m travels in set m % 3, loaded three chunks ahead of its use
-    u32x4 qa[C::PIECES], ka[C::PIECES], va[C::PIECES], qb[C::PIECES], kb[C::PIECES], vb[C::PIECES],
-        qc[C::PIECES], kc[C::PIECES], vc[C::PIECES];
+    // two register sets: chunk m travels in set m % 2; a set is reloaded with the chunk two
+    // further on as soon as it has been staged
+    u32x4 q0[C::PIECES], k0[C::PIECES], v0[C::PIECES], q1[C::PIECES], k1[C::PIECES], v1[C::PIECES];
     int nl = 0, no = 0;  // chunks loaded / written so far
-    auto load = [&](u32x4 (&qr)[C::PIECES], u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES]) {
+    auto load_q = [&](u32x4 (&qr)[C::PIECES]) { load_chunk<D>(qr, cl.hp.q, cl.t0(), N, qo); };
+    auto load_kv = [&](u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES]) {
       const int t0 = cl.t0();
-#pragma unroll
-      for (int i = 0; i < C::PIECES; ++i) {
-        qr[i] = load_piece<D>(cl.hp.q, a.q.sn, qoff, t0, i, N, st);
-        kr[i] = load_piece<D>(cl.hp.k, a.k.sn, koff, t0, i, N, st);
-        vr[i] = load_piece<D>(cl.hp.v, a.v.sn, voff, t0, i, N, st);
-      }
+      load_chunk<D>(kr, cl.hp.k, t0, N, ko);
+      load_chunk<D>(vr, cl.hp.v, t0, N, vo);
       ++nl;
       cl.next(a, nl < nchunks);
     };
@@ -428,37 +448,52 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       ++no;
       co.next(a, no < nchunks);
     };
-    load(qa, ka, va);
-    if (nchunks > 1) load(qb, kb, vb);
-    if (nchunks > 2) load(qc, kc, vc);
-    stage_q(qa, 0);
-    stage_kv(ka, va, 0);
+    load_q(q0);
+    load_kv(k0, v0);
+    if (nchunks > 1) {
+      load_q(q1);
+      load_kv(k1, v1);
+    }
+    stage_q(q0, 0);
+    stage_kv(k0, v0, 0);
+    if (nchunks > 2) {
+      load_q(q0);
+      load_kv(k0, v0);
+    }
     lds_barrier();  // chunk 0 staged
     // Per chunk n the consumers run [products, state read-out] (a) [denominators, in-chunk
     // part, state update] (b) [normalise into LDS].  The producers' work for chunk n+1 is split
-    // the same way so that neither side idles at a barrier: the loads of chunk n+3 and phi(Q)
-    // before (a); after (a) the write-out of chunk n-1, phi(K) and V.
-    for (int n = 0; n < nchunks; n += 3) {
-      if (n + 3 < nchunks) load(qa, ka, va);   // set A (chunk n) was staged during chunk n-1
-      if (n + 1 < nchunks) stage_q(qb, n + 1);
+    // the same way so that neither side idles at a barrier: phi(Q) before (a); after (a) the
+    // write-out of chunk n-1, phi(K) and V; each set's reload (chunk n+3) follows its staging.
+    // Two chunks per round (one per register set).  In a steady round every load, stage and
+    // write-out happens, so the round is compiled without conditions: the wait counters the
+    // compiler derives for a conditional load assume it may not have been issued, which makes
+    // the waits for older loads cover the newest ones as well.
+    auto round2 = [&](int n, auto steady) {
+      constexpr bool S = decltype(steady)::value;
+      if (S || n + 1 < nchunks) stage_q(q1, n + 1);
+      if (S || n + 3 < nchunks) load_q(q1);
       lds_barrier();  // (a)
-      if (n > 0) store_out();
-      if (n + 1 < nchunks) stage_kv(kb, vb, n + 1);
+      if (S || n > 0) store_out();
+      if (S || n + 1 < nchunks) stage_kv(k1, v1, n + 1);
+      if (S || n + 3 < nchunks) load_kv(k1, v1);
       lds_barrier();  // (b)
-      if (n + 1 >= nchunks) break;
-      if (n + 4 < nchunks) load(qb, kb, vb);
-      if (n + 2 < nchunks) stage_q(qc, n + 2);
+      if (!S && n + 1 >= nchunks) return false;
+      if (S || n + 2 < nchunks) stage_q(q0, n + 2);
+      if (S || n + 4 < nchunks) load_q(q0);
       lds_barrier();  // (a)
       store_out();
-      if (n + 2 < nchunks) stage_kv(kc, vc, n + 2);
+      if (S || n + 2 < nchunks) stage_kv(k0, v0, n + 2);
+      if (S || n + 4 < nchunks) load_kv(k0, v0);
       lds_barrier();  // (b)
-      if (n + 2 >= nchunks) break;
-      if (n + 5 < nchunks) load(qc, kc, vc);
-      if (n + 3 < nchunks) stage_q(qa, n + 3);
-      lds_barrier();  // (a)
-      store_out();
-      if (n + 3 < nchunks) stage_kv(ka, va, n + 3);
-      lds_barrier();  // (b)
+      return true;
+    };
+    for (int n = 0; n < nchunks; n += 2) {
+      if (n > 0 && n + 4 < nchunks) {
+        round2(n, std::true_type{});
+      } else if (!round2(n, std::false_type{})) {
+        break;
+      }
     }
     lds_barrier();  // (c) last chunk's rows are in LDS
     store_out();

@@ -106,6 +106,7 @@ def test_plan_modes_and_overrides():
     ((1, 2, 16, 64, 4), {"overlap": 2}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"q_stride": (1024, 512, 60)}, gb.GF_ERR_INVALID_ARG),   # not 16-byte rows
     ((1, 2, 16, 64, 4), {"o_stride": (2048, 1024, 32)}, gb.GF_ERR_INVALID_ARG),  # rows overlap
+    ((1, 2, 16, 64, 4), {"k_stride": (1 << 26, 1 << 25, (1 << 20) + 8)}, gb.GF_ERR_UNSUPPORTED),  # row stride limit
     ((1, 2, 256, 64, 4), {"chunk": 64, "segment_len": 96}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 96, 4), {}, gb.GF_ERR_UNSUPPORTED),               # head size
     ((1, 2, 16, 64, 4), {"chunk": 48}, gb.GF_ERR_UNSUPPORTED),
