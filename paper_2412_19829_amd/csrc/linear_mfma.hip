@@ -175,27 +175,39 @@ __device__ __forceinline__ void state_add(f32x16 (&sacc)[LinCfg<D>::ET], const f
   }
 }
 
-// A += phiK^T V for this wave's value columns, from the row-major chunk tiles in LDS; returns
-// this lane's share of colsum(phiK) for features 32*wave + l%32 (tokens of its k-slot half).
+// One 16-token step of A += phiK^T V for this wave's value columns: `vt` is the V^T operand of
+// tokens 16*kk.. (lane = value column 32*wave + l%32), phi(K) comes from its row-major LDS tile
+// through the transpose read.  Adds this lane's share of colsum(phiK) for feature
+// 32*wave + l%32 (the tokens of its k-slot half) to `zs`.  The ET accumulator tiles take turns,
+// so no matrix instruction waits for the one before it.
+template <int D>
+__device__ __forceinline__ float update_state_step(f32x16 (&sacc)[LinCfg<D>::ET], const uint16_t* fk,
+                                                   bf16x8 vt, int kk, int wave, int lane, float zs) {
+  using C = LinCfg<D>;
+  const int lh = lane >> 5;
+#pragma unroll
+  for (int ct = 0; ct < C::ET; ++ct) {
+    const bf16x8 fa =
+        lds_operand_tr(fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * ct, lane);
+    sacc[ct] = mfma32(fa, vt, sacc[ct]);
+  }
+  // the wave's own feature tile once more: cheaper than a wave-dependent branch or select
+  const bf16x8 fz =
+      lds_operand_tr(fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
+  return sum8_bf16(fz, zs);
+}
+// A += phiK^T V over a whole chunk; returns the lane's share of colsum(phiK).
 template <int D>
 __device__ __forceinline__ float update_state(f32x16 (&sacc)[LinCfg<D>::ET], const uint16_t* fk,
                                               const uint16_t* v, int wave, int lane) {
   using C = LinCfg<D>;
   const int lh = lane >> 5;
   float zs = 0.f;
-  bf16x8 vb[CH / 16];
 #pragma unroll
-  for (int kk = 0; kk < CH / 16; ++kk)
-    vb[kk] = lds_operand_tr(v, C::VROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
-#pragma unroll
-  for (int ct = 0; ct < C::ET; ++ct) {
-#pragma unroll
-    for (int kk = 0; kk < CH / 16; ++kk) {
-      const bf16x8 fa =
-          lds_operand_tr(fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * ct, lane);
-      if (ct == wave) zs = sum8_bf16(fa, zs);
-      sacc[ct] = mfma32(fa, vb[kk], sacc[ct]);
-    }
+  for (int kk = 0; kk < CH / 16; ++kk) {
+    const bf16x8 vt =
+        lds_operand_tr(v, C::VROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
+    zs = update_state_step<D>(sacc, fk, vt, kk, wave, lane, zs);
   }
   return zs;
 }
@@ -530,72 +542,115 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
   // the product tile above the diagonal (keys 32.., queries ..31) is never computed: it stays 0
   for (int x = tid; x < 32 * 32 / 8; x += C::NTC)
     *reinterpret_cast<u32x4*>(&sm.pt[(x / 4) * C::PROW + 32 + 8 * (x % 4)]) = kZero4;
+  if (tid < CH) sm.den[tid] = 1.f;  // read by the first pass of the loop before any row exists
   __builtin_amdgcn_s_setprio(2);  // matrix waves first; the staging waves fill the gaps
   lds_barrier();  // chunk 0 staged, Z visible
 
   constexpr int PPT = C::NTC / CH;  // threads per query in the denominator
+  // finished rows: divide by the denominators and hand them to the producers through LDS
+  auto normalise = [&](const f32x16 (&num)[2]) {
+#pragma unroll
+    for (int tq = 0; tq < 2; ++tq) {
+      const float inv = __builtin_amdgcn_rcpf(sm.den[32 * tq + ln]);
+      uint16_t* orow = &sm.ot[(32 * tq + ln) * C::OROW + 32 * wave + 4 * lh];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 pk;
+        pk[0] = pack_bf16(num[tq][4 * g + 0] * inv, num[tq][4 * g + 1] * inv);
+        pk[1] = pack_bf16(num[tq][4 * g + 2] * inv, num[tq][4 * g + 3] * inv);
+        *reinterpret_cast<u32x2*>(orow + 8 * g) = pk;
+      }
+    }
+  };
+  // Masked products P^T[key][query] = phi(k_key).phi(q_query), key <= query, are three 32x32
+  // tiles (the fourth lies above the diagonal); tile t goes to wave t % NWC.  A wave left
+  // without a tile repeats tile 0 and stores the same values to the same place, which keeps the
+  // code free of branches: the products and the state read-out then interleave in one block and
+  // neither chain of dependent matrix instructions has to wait for its own results.
+  constexpr int NTILE = (3 + C::NWC - 1) / C::NWC;  // product tiles per wave
+  constexpr int KS = D / 16;                        // contraction steps per product tile
+  constexpr int G1N = NTILE * KS;                   // product steps per chunk
+  constexpr int G2N = 2 * C::ET;                    // read-out steps (two MFMAs each)
+  static_assert(G1N % G2N == 0, "interleave ratio");
+  f32x16 num[2];
+#pragma unroll
+  for (int tq = 0; tq < 2; ++tq)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) num[tq][r] = 0.f;
   for (int n = 0; n < nchunks; ++n) {
     const int zc = n & 1;
     const ChunkTiles<D>& b = sm.buf[n & 1];
     const bool head_ends = (lc + 1 == a.vcph);  // the next chunk starts a new head from zero
     lc = head_ends ? 0 : lc + 1;
 
-    // masked products P^T[key][query] = phi(k_key).phi(q_query), key <= query: three 32x32
-    // tiles (the fourth lies above the diagonal).  Tile t goes to wave t % NWC; code is kept
-    // branch-free (waves without a tile recompute tile 0 and drop it) so that it can be
-    // scheduled together with the state read-out below.
-    constexpr int NTILE = (3 + C::NWC - 1) / C::NWC;  // product tiles per wave
-#pragma unroll
-    for (int rep = 0; rep < NTILE; ++rep) {
-      const int tile = wave + rep * C::NWC;
-      const bool mine = tile < 3;
-      const int tk = tile == 2 ? 1 : 0, tqa = (tile == 1 || tile == 2) ? 1 : 0;
-      const bool diag = tk == tqa;
-      f32x16 p;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) p[r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        // k-slot 8*lh + 4*g + j of this step is feature 16*ks + 8*g + 4*lh + j
-        const uint16_t* kr = &b.fk[(32 * tk + ln) * C::KROW + 16 * ks + 4 * lh];
-        const u32x2 k0 = *reinterpret_cast<const u32x2*>(kr);
-        const u32x2 k1 = *reinterpret_cast<const u32x2*>(kr + 8);
-        const bf16x8 ka_ = as_bf16x8(u32x4{k0[0], k0[1], k1[0], k1[1]});
-        const bf16x8 qb_ = lds_read16(&b.fq[(32 * tqa + ln) * C::QROW + 16 * ks + 8 * lh]);
-        p = mfma32(ka_, qb_, p);
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (diag && 8 * (r / 4) + 4 * lh + (r % 4) > ln) p[r] = 0.f;
-      if (mine) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          u32x2 pk;
-          pk[0] = pack_bf16(p[4 * g + 0], p[4 * g + 1]);
-          pk[1] = pack_bf16(p[4 * g + 2], p[4 * g + 3]);
-          *reinterpret_cast<u32x2*>(&sm.pt[(32 * tqa + ln) * C::PROW + 32 * tk + 8 * g + 4 * lh]) = pk;
-        }
-      }
-    }
-    // num^T = A^T phiQ^T with A straight from the state registers
-    f32x16 num[2];
+    // rows of the previous chunk (at n = 0: zeros over den = 1, never written out)
+    normalise(num);
 #pragma unroll
     for (int tq = 0; tq < 2; ++tq)
 #pragma unroll
       for (int r = 0; r < 16; ++r) num[tq][r] = 0.f;
+    f32x16 p[NTILE];
+    int tk[NTILE], tqa[NTILE];
 #pragma unroll
-    for (int ct = 0; ct < C::ET; ++ct) {
+    for (int rep = 0; rep < NTILE; ++rep) {
+      const int tile = (wave + rep * C::NWC) % 3;
+      tk[rep] = tile == 2 ? 1 : 0;
+      tqa[rep] = tile == 0 ? 0 : 1;
 #pragma unroll
-      for (int kb_ = 0; kb_ < 2; ++kb_) {
+      for (int r = 0; r < 16; ++r) p[rep][r] = 0.f;
+    }
+    // operands are fetched from LDS one step ahead of the matrix instructions that use them
+    struct StepOps {
+      bf16x8 kt, qt, q0, q1;
+    };
+    auto fetch = [&](int i) {
+      StepOps o;
+      const int rep = i / KS, ks = i % KS;
+      // k-slot 8*lh + 4*g + j of this step is feature 16*ks + 8*g + 4*lh + j
+      const uint16_t* kr = &b.fk[(32 * tk[rep] + ln) * C::KROW + 16 * ks + 4 * lh];
+      const u32x2 k0 = *reinterpret_cast<const u32x2*>(kr);
+      const u32x2 k1 = *reinterpret_cast<const u32x2*>(kr + 8);
+      o.kt = as_bf16x8(u32x4{k0[0], k0[1], k1[0], k1[1]});
+      o.qt = lds_read16(&b.fq[(32 * tqa[rep] + ln) * C::QROW + 16 * ks + 8 * lh]);
+      if (i % (G1N / G2N) == 0) {
+        const int j = i / (G1N / G2N), ct = j / 2, kb_ = j % 2;
+        o.q0 = lds_read16(&b.fq[ln * C::QROW + 32 * ct + 16 * kb_ + 8 * lh]);
+        o.q1 = lds_read16(&b.fq[(32 + ln) * C::QROW + 32 * ct + 16 * kb_ + 8 * lh]);
+      }
+      return o;
+    };
+    StepOps cur = fetch(0);
+#pragma unroll
+    for (int i = 0; i < G1N; ++i) {
+      StepOps nxt = cur;
+      if (i + 1 < G1N) nxt = fetch(i + 1);
+      p[i / KS] = mfma32(cur.kt, cur.qt, p[i / KS]);
+      if (i % (G1N / G2N) == 0) {
+        // num^T = A^T phiQ^T with A straight from the state registers
+        const int j = i / (G1N / G2N), ct = j / 2, kb_ = j % 2;
         u32x4 sw;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sw[i] = pack_bf16(sacc[ct][8 * kb_ + 2 * i], sacc[ct][8 * kb_ + 2 * i + 1]);
+        for (int x = 0; x < 4; ++x)
+          sw[x] = pack_bf16(sacc[ct][8 * kb_ + 2 * x], sacc[ct][8 * kb_ + 2 * x + 1]);
         const bf16x8 sa = as_bf16x8(sw);
+        num[0] = mfma32(sa, cur.q0, num[0]);
+        num[1] = mfma32(sa, cur.q1, num[1]);
+      }
+      cur = nxt;
+    }
 #pragma unroll
-        for (int tq = 0; tq < 2; ++tq) {
-          const bf16x8 qv = lds_read16(&b.fq[(32 * tq + ln) * C::QROW + 32 * ct + 16 * kb_ + 8 * lh]);
-          num[tq] = mfma32(sa, qv, num[tq]);
-        }
+    for (int rep = 0; rep < NTILE; ++rep) {
+      // on the diagonal tile key row 8*(r/4) + 4*lh + r%4 must not exceed query column ln
+      const int top = (tk[rep] == tqa[rep] ? ln : CH) - 4 * lh;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) p[rep][r] = (8 * (r / 4) + (r % 4) > top) ? 0.f : p[rep][r];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 pk;
+        pk[0] = pack_bf16(p[rep][4 * g + 0], p[rep][4 * g + 1]);
+        pk[1] = pack_bf16(p[rep][4 * g + 2], p[rep][4 * g + 3]);
+        *reinterpret_cast<u32x2*>(
+            &sm.pt[(32 * tqa[rep] + ln) * C::PROW + 32 * tk[rep] + 8 * g + 4 * lh]) = pk;
       }
     }
     lds_barrier();  // (a) products visible
@@ -628,22 +683,42 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       for (int o = 1; o < PPT; o <<= 1) s += __shfl_xor(s, o, 64);
       if (part == 0) sm.den[qrow] = s + a.eps;
     }
-    // num^T += V^T P^T (inside the chunk); the first 32 queries see only the first 32 keys
-#pragma unroll
-    for (int kk = 0; kk < CH / 16; ++kk) {
-      const bf16x8 va_ =
-          lds_operand_tr(b.v, C::VROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
-#pragma unroll
-      for (int tq = 0; tq < 2; ++tq) {
-        if (16 * kk < 32 * (tq + 1)) {
-          const bf16x8 pb = lds_read16(&sm.pt[(32 * tq + ln) * C::PROW + 16 * kk + 8 * lh]);
-          num[tq] = mfma32(va_, pb, num[tq]);
-        }
-      }
-    }
-    // state update: A += phiK^T V, Z += colsum(phiK); a new head starts from zero instead
+    // Over the chunk's tokens, 16 at a time, with one V^T operand serving both contractions:
+    // num^T += V^T P^T (the first 32 queries see only the first 32 keys) and the state update
+    // A += phiK^T V, Z += colsum(phiK); a new head starts from zero instead.
     {
-      float zs = update_state<D>(sacc, b.fk, b.v, wave, lane);
+      struct TokOps {
+        bf16x8 vt, pb[2], fa[C::ET], fz;
+      };
+      auto fetch_tok = [&](int kk) {
+        TokOps o;
+        o.vt = lds_operand_tr(b.v, C::VROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
+#pragma unroll
+        for (int tq = 0; tq < 2; ++tq)
+          if (16 * kk < 32 * (tq + 1))
+            o.pb[tq] = lds_read16(&sm.pt[(32 * tq + ln) * C::PROW + 16 * kk + 8 * lh]);
+#pragma unroll
+        for (int ct = 0; ct < C::ET; ++ct)
+          o.fa[ct] = lds_operand_tr(b.fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * ct, lane);
+        // the wave's own feature tile once more, for colsum(phiK): a second read costs less than
+        // picking it out of fa[] with a wave-dependent branch or select
+        o.fz = lds_operand_tr(b.fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
+        return o;
+      };
+      float zs = 0.f;
+      TokOps cur = fetch_tok(0);
+#pragma unroll
+      for (int kk = 0; kk < CH / 16; ++kk) {
+        TokOps nxt = cur;
+        if (kk + 1 < CH / 16) nxt = fetch_tok(kk + 1);
+#pragma unroll
+        for (int tq = 0; tq < 2; ++tq)
+          if (16 * kk < 32 * (tq + 1)) num[tq] = mfma32(cur.vt, cur.pb[tq], num[tq]);
+        zs = sum8_bf16(cur.fz, zs);
+#pragma unroll
+        for (int ct = 0; ct < C::ET; ++ct) sacc[ct] = mfma32(cur.fa[ct], cur.vt, sacc[ct]);
+        cur = nxt;
+      }
       zs += __shfl_xor(zs, 32, 64);
       const int zi = 32 * wave + kperm32(ln);
       if (lh == 0) put_z(zc ^ 1, zi, head_ends ? 0.f : sm.z[zc][zi] + zs);
@@ -655,20 +730,8 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       }
     }
     lds_barrier();  // (b) denominators visible; this chunk's tiles are free again
-    // normalise; the rows go to LDS and the producers write them out in whole rows
-#pragma unroll
-    for (int tq = 0; tq < 2; ++tq) {
-      const float inv = 1.f / sm.den[32 * tq + ln];
-      uint16_t* orow = &sm.ot[(32 * tq + ln) * C::OROW + 32 * wave + 4 * lh];
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 pk;
-        pk[0] = pack_bf16(num[tq][4 * g + 0] * inv, num[tq][4 * g + 1] * inv);
-        pk[1] = pack_bf16(num[tq][4 * g + 2] * inv, num[tq][4 * g + 3] * inv);
-        *reinterpret_cast<u32x2*>(orow + 8 * g) = pk;
-      }
-    }
   }
+  normalise(num);  // the last chunk's rows
   lds_barrier();  // (c)
 }
 
