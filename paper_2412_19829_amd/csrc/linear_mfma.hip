@@ -307,13 +307,17 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs
       }
     };
     // chunk m travels in set m % 2; a set is reloaded (two chunks ahead) as soon as it is staged.
-    // Steady rounds are compiled without conditions so that the compiler's wait counters know
-    // exactly which loads are in flight.
-    load(ka, va, 0);
-    if (nchunks > 1) load(kb, vb, 1);
-    stage(ka, va, 0);
-    if (nchunks > 2) load(ka, va, 2);
-    lds_barrier();
+    // A sub-piece of more than four chunks runs a condition-free lead-in and condition-free
+    // steady rounds, so that the compiler's wait counters know exactly which loads are in
+    // flight; only its last rounds (and short sub-pieces) test before every load and stage.
+    auto lead_in = [&](auto steady) {
+      constexpr bool S = decltype(steady)::value;
+      load(ka, va, 0);
+      if (S || nchunks > 1) load(kb, vb, 1);
+      stage(ka, va, 0);
+      if (S || nchunks > 2) load(ka, va, 2);
+      lds_barrier();
+    };
     auto round2 = [&](int n, auto steady) {
       constexpr bool S = decltype(steady)::value;
       if (S || n + 1 < nchunks) stage(kb, vb, n + 1);
@@ -325,13 +329,15 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs
       lds_barrier();
       return true;
     };
-    for (int n = 0; n < nchunks; n += 2) {
-      if (n + 4 < nchunks) {
-        round2(n, std::true_type{});
-      } else if (!round2(n, std::false_type{})) {
-        break;
-      }
+    int n = 0;
+    if (nchunks > 4) {
+      lead_in(std::true_type{});
+      for (; n + 4 < nchunks; n += 2) round2(n, std::true_type{});
+    } else {
+      lead_in(std::false_type{});
     }
+    for (; n < nchunks; n += 2)
+      if (!round2(n, std::false_type{})) break;
     return;
   }
   // ---- consumers ----
@@ -412,37 +418,43 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       ++nl;
       cl.next(a, nl < nchunks);
     };
+    // phi(Q) of the first QPRE pieces, in place in their registers, one phase before they are
+    // staged: spreads the feature map's vector work over both phases of a chunk
+    constexpr int QPRE = C::PIECES / 2;
+    auto map_q_pre = [&](u32x4 (&qr)[C::PIECES]) {
+#pragma unroll
+      for (int i = 0; i < QPRE; ++i) qr[i] = map_features<ELU1>(qr[i]);
+    };
     // phi(Q) of the chunk at `cs` -> buf[n % 2]
     auto stage_q = [&](const u32x4 (&qr)[C::PIECES], int n) {
       ChunkTiles<D>& b = sm.buf[n & 1];
 #pragma unroll
       for (int i = 0; i < C::PIECES; ++i) {
-        const u32x4 fqv = map_features<ELU1>(qr[i]);
+        const u32x4 fqv = i < QPRE ? qr[i] : map_features<ELU1>(qr[i]);
         uint16_t* qd = &b.fq[(st.r0 + i * C::RP) * C::QROW + st.qcol];
         *reinterpret_cast<u32x2*>(qd) = u32x2{fqv[0], fqv[1]};
         *reinterpret_cast<u32x2*>(qd + 8) = u32x2{fqv[2], fqv[3]};
       }
     };
+    // phi(K) of the first KEARLY pieces, in place in their registers: vector work moved in front
+    // of barrier (a), where the producers would otherwise wait for the matrix waves
+    constexpr int KEARLY = C::PIECES / 2;
+    auto map_k_early = [&](u32x4 (&kr)[C::PIECES]) {
+#pragma unroll
+      for (int i = 0; i < KEARLY; ++i) kr[i] = map_features<ELU1>(kr[i]);
+    };
     // phi(K) and V of the chunk at `cs` -> buf[n % 2]; rows past the head's end become zeros
     auto stage_kv = [&](const u32x4 (&kr)[C::PIECES], const u32x4 (&vr)[C::PIECES], int n) {
       const int t0 = cs.t0();
       ChunkTiles<D>& b = sm.buf[n & 1];
-      if (t0 + CH <= N) {
+      const bool full = t0 + CH <= N;  // uniform; only a head's last chunk can be ragged
 #pragma unroll
-        for (int i = 0; i < C::PIECES; ++i) {
-          const int row = st.r0 + i * C::RP;
-          *reinterpret_cast<u32x4*>(&b.fk[row * C::KROW + st.col]) = map_features<ELU1>(kr[i]);
-          *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = vr[i];
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < C::PIECES; ++i) {
-          const int row = st.r0 + i * C::RP;
-          const bool valid = t0 + row < N;
-          const u32x4 fk = map_features<ELU1>(kr[i]);
-          *reinterpret_cast<u32x4*>(&b.fk[row * C::KROW + st.col]) = valid ? fk : kZero4;
-          *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = valid ? vr[i] : kZero4;
-        }
+      for (int i = 0; i < C::PIECES; ++i) {
+        const int row = st.r0 + i * C::RP;
+        const bool valid = full || t0 + row < N;
+        const u32x4 fk = i < KEARLY ? kr[i] : map_features<ELU1>(kr[i]);
+        *reinterpret_cast<u32x4*>(&b.fk[row * C::KROW + st.col]) = valid ? fk : kZero4;
+        *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = valid ? vr[i] : kZero4;
       }
       cs.next(a, n + 1 < nchunks);
     };
@@ -460,53 +472,75 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       ++no;
       co.next(a, no < nchunks);
     };
-    load_q(q0);
-    load_kv(k0, v0);
-    if (nchunks > 1) {
-      load_q(q1);
-      load_kv(k1, v1);
-    }
-    stage_q(q0, 0);
-    stage_kv(k0, v0, 0);
-    if (nchunks > 2) {
+    // Per chunk n the consumers run [products, state read-out] (a) [denominators, in-chunk
+    // part, state update] (b).  The producers' work for chunk n+1 is split the same way so that
+    // neither side idles at a barrier: phi(Q) and half of phi(K) before (a); after (a) the
+    // write-out of chunk n-1, the rest of phi(K) and V; each set's reload (chunk n+3) follows
+    // its staging.  Two chunks per round (one per register set).
+    //
+    // The wait counters the compiler derives for a load that sits behind a condition assume it
+    // may not have been issued, which makes the waits for older loads cover the newest ones as
+    // well.  A piece of more than four chunks therefore runs a condition-free lead-in and
+    // condition-free steady rounds; only its last rounds (and short pieces) take the general
+    // code with a test in front of every load, stage and write-out.
+    constexpr int kGeneral = 0, kFirst = 1, kSteady = 2;
+    auto lead_in = [&](auto mode) {
+      constexpr bool S = decltype(mode)::value != kGeneral;
       load_q(q0);
       load_kv(k0, v0);
-    }
-    lds_barrier();  // chunk 0 staged
-    // Per chunk n the consumers run [products, state read-out] (a) [denominators, in-chunk
-    // part, state update] (b) [normalise into LDS].  The producers' work for chunk n+1 is split
-    // the same way so that neither side idles at a barrier: phi(Q) before (a); after (a) the
-    // write-out of chunk n-1, phi(K) and V; each set's reload (chunk n+3) follows its staging.
-    // Two chunks per round (one per register set).  In a steady round every load, stage and
-    // write-out happens, so the round is compiled without conditions: the wait counters the
-    // compiler derives for a conditional load assume it may not have been issued, which makes
-    // the waits for older loads cover the newest ones as well.
-    auto round2 = [&](int n, auto steady) {
-      constexpr bool S = decltype(steady)::value;
-      if (S || n + 1 < nchunks) stage_q(q1, n + 1);
+      if (S || nchunks > 1) {
+        load_q(q1);
+        load_kv(k1, v1);
+      }
+      map_q_pre(q0);
+      stage_q(q0, 0);
+      map_k_early(k0);
+      stage_kv(k0, v0, 0);
+      if (S || nchunks > 2) {
+        load_q(q0);
+        load_kv(k0, v0);
+      }
+      if (S || nchunks > 1) map_q_pre(q1);
+      lds_barrier();  // chunk 0 staged
+    };
+    auto round2 = [&](int n, auto mode) {
+      constexpr int M = decltype(mode)::value;
+      constexpr bool S = M != kGeneral;
+      if (S || n + 1 < nchunks) {
+        stage_q(q1, n + 1);
+        map_k_early(k1);
+      }
       if (S || n + 3 < nchunks) load_q(q1);
       lds_barrier();  // (a)
-      if (S || n > 0) store_out();
+      if (M == kSteady || (M == kGeneral && n > 0)) store_out();
       if (S || n + 1 < nchunks) stage_kv(k1, v1, n + 1);
       if (S || n + 3 < nchunks) load_kv(k1, v1);
+      if (S || n + 2 < nchunks) map_q_pre(q0);
       lds_barrier();  // (b)
       if (!S && n + 1 >= nchunks) return false;
-      if (S || n + 2 < nchunks) stage_q(q0, n + 2);
+      if (S || n + 2 < nchunks) {
+        stage_q(q0, n + 2);
+        map_k_early(k0);
+      }
       if (S || n + 4 < nchunks) load_q(q0);
       lds_barrier();  // (a)
       store_out();
       if (S || n + 2 < nchunks) stage_kv(k0, v0, n + 2);
       if (S || n + 4 < nchunks) load_kv(k0, v0);
+      if (S || n + 3 < nchunks) map_q_pre(q1);
       lds_barrier();  // (b)
       return true;
     };
-    for (int n = 0; n < nchunks; n += 2) {
-      if (n > 0 && n + 4 < nchunks) {
-        round2(n, std::true_type{});
-      } else if (!round2(n, std::false_type{})) {
-        break;
-      }
+    int n = 0;
+    if (nchunks > 4) {
+      lead_in(std::integral_constant<int, kFirst>{});
+      round2(0, std::integral_constant<int, kFirst>{});
+      for (n = 2; n + 4 < nchunks; n += 2) round2(n, std::integral_constant<int, kSteady>{});
+    } else {
+      lead_in(std::integral_constant<int, kGeneral>{});
     }
+    for (; n < nchunks; n += 2)
+      if (!round2(n, std::integral_constant<int, kGeneral>{})) break;
     lds_barrier();  // (c) last chunk's rows are in LDS
     store_out();
     return;
@@ -570,8 +604,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
   constexpr int NTILE = (3 + C::NWC - 1) / C::NWC;  // product tiles per wave
   constexpr int KS = D / 16;                        // contraction steps per product tile
   constexpr int G1N = NTILE * KS;                   // product steps per chunk
-  constexpr int G2N = 2 * C::ET;                    // read-out steps (two MFMAs each)
-  static_assert(G1N % G2N == 0, "interleave ratio");
+  static_assert(KS == 2 * C::ET, "a product tile and the read-out take the same contraction steps");
   f32x16 num[2];
 #pragma unroll
   for (int tq = 0; tq < 2; ++tq)
@@ -583,12 +616,6 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
     const bool head_ends = (lc + 1 == a.vcph);  // the next chunk starts a new head from zero
     lc = head_ends ? 0 : lc + 1;
 
-    // rows of the previous chunk (at n = 0: zeros over den = 1, never written out)
-    normalise(num);
-#pragma unroll
-    for (int tq = 0; tq < 2; ++tq)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) num[tq][r] = 0.f;
     f32x16 p[NTILE];
     int tk[NTILE], tqa[NTILE];
 #pragma unroll
@@ -596,12 +623,10 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       const int tile = (wave + rep * C::NWC) % 3;
       tk[rep] = tile == 2 ? 1 : 0;
       tqa[rep] = tile == 0 ? 0 : 1;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) p[rep][r] = 0.f;
     }
     // operands are fetched from LDS one step ahead of the matrix instructions that use them
     struct StepOps {
-      bf16x8 kt, qt, q0, q1;
+      bf16x8 kt, q0, q1;
     };
     auto fetch = [&](int i) {
       StepOps o;
@@ -611,23 +636,36 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
       const u32x2 k0 = *reinterpret_cast<const u32x2*>(kr);
       const u32x2 k1 = *reinterpret_cast<const u32x2*>(kr + 8);
       o.kt = as_bf16x8(u32x4{k0[0], k0[1], k1[0], k1[1]});
-      o.qt = lds_read16(&b.fq[(32 * tqa[rep] + ln) * C::QROW + 16 * ks + 8 * lh]);
-      if (i % (G1N / G2N) == 0) {
-        const int j = i / (G1N / G2N), ct = j / 2, kb_ = j % 2;
-        o.q0 = lds_read16(&b.fq[ln * C::QROW + 32 * ct + 16 * kb_ + 8 * lh]);
-        o.q1 = lds_read16(&b.fq[(32 + ln) * C::QROW + 32 * ct + 16 * kb_ + 8 * lh]);
-      }
+      // phi(Q) rows 0..31 and 32..63, features of contraction step ks: the read-out step
+      // 2*ct + kb = ks uses both, the product tile the one of its query half
+      o.q0 = lds_read16(&b.fq[ln * C::QROW + 16 * ks + 8 * lh]);
+      o.q1 = lds_read16(&b.fq[(32 + ln) * C::QROW + 16 * ks + 8 * lh]);
       return o;
     };
-    StepOps cur = fetch(0);
+    constexpr int PD = 3;  // steps between an operand fetch and its use
+    StepOps ops[G1N];
+#pragma unroll
+    for (int i = 0; i < PD && i < G1N; ++i) ops[i] = fetch(i);
+    __builtin_amdgcn_sched_barrier(0);
+    // rows of the previous chunk (at n = 0: zeros over den = 1, never written out), while the
+    // first operands are on their way
+    normalise(num);
+#pragma unroll
+    for (int tq = 0; tq < 2; ++tq)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) num[tq][r] = 0.f;
+#pragma unroll
+    for (int rep = 0; rep < NTILE; ++rep)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) p[rep][r] = 0.f;
 #pragma unroll
     for (int i = 0; i < G1N; ++i) {
-      StepOps nxt = cur;
-      if (i + 1 < G1N) nxt = fetch(i + 1);
-      p[i / KS] = mfma32(cur.kt, cur.qt, p[i / KS]);
-      if (i % (G1N / G2N) == 0) {
+      if (i + PD < G1N) ops[i + PD] = fetch(i + PD);
+      const StepOps& cur = ops[i];
+      p[i / KS] = mfma32(cur.kt, tqa[i / KS] ? cur.q1 : cur.q0, p[i / KS]);
+      if (i / KS == 0) {
         // num^T = A^T phiQ^T with A straight from the state registers
-        const int j = i / (G1N / G2N), ct = j / 2, kb_ = j % 2;
+        const int ct = i / 2, kb_ = i % 2;
         u32x4 sw;
 #pragma unroll
         for (int x = 0; x < 4; ++x)
@@ -636,7 +674,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
         num[0] = mfma32(sa, cur.q0, num[0]);
         num[1] = mfma32(sa, cur.q1, num[1]);
       }
-      cur = nxt;
+      __builtin_amdgcn_sched_barrier(0);  // keep the fetches PD steps ahead of their use
     }
 #pragma unroll
     for (int rep = 0; rep < NTILE; ++rep) {
@@ -655,37 +693,10 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
     }
     lds_barrier();  // (a) products visible
 
-    // denominator: rowsum of the (rounded) products + phi(q).Z_prev, PPT threads per query,
-    // all on packed bf16 pairs
-    {
-      const int qrow = tid / PPT, part = tid % PPT;
-      constexpr int KW = CH / PPT;  // product slots per thread
-      constexpr int CW = D / PPT;   // features per thread
-      float s = 0.f;
-#pragma unroll
-      for (int x = 0; x < KW; x += 8) {  // the never-visible tile holds zeros
-        const u32x4 pv = *reinterpret_cast<const u32x4*>(&sm.pt[qrow * C::PROW + KW * part + x]);
-#pragma unroll
-        for (int w = 0; w < 4; ++w) s = dot2_bf16(pv[w], kOnesBf16x2, s);
-      }
-#pragma unroll
-      for (int x = 0; x < CW; x += 8) {
-        const u32x4 qv = *reinterpret_cast<const u32x4*>(&b.fq[qrow * C::QROW + CW * part + x]);
-        const u32x4 zh = *reinterpret_cast<const u32x4*>(&sm.zh[zc][CW * part + x]);
-        const u32x4 zl = *reinterpret_cast<const u32x4*>(&sm.zl[zc][CW * part + x]);
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          s = dot2_bf16(qv[w], zh[w], s);
-          s = dot2_bf16(qv[w], zl[w], s);
-        }
-      }
-#pragma unroll
-      for (int o = 1; o < PPT; o <<= 1) s += __shfl_xor(s, o, 64);
-      if (part == 0) sm.den[qrow] = s + a.eps;
-    }
     // Over the chunk's tokens, 16 at a time, with one V^T operand serving both contractions:
     // num^T += V^T P^T (the first 32 queries see only the first 32 keys) and the state update
-    // A += phiK^T V, Z += colsum(phiK); a new head starts from zero instead.
+    // A += phiK^T V, Z += colsum(phiK); a new head starts from zero instead.  Operands are
+    // fetched PDB steps ahead; the denominators are computed while the first ones arrive.
     {
       struct TokOps {
         bf16x8 vt, pb[2], fa[C::ET], fz;
@@ -705,19 +716,51 @@ __global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) 
         o.fz = lds_operand_tr(b.fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
         return o;
       };
-      float zs = 0.f;
-      TokOps cur = fetch_tok(0);
+      constexpr int NK = CH / 16, PDB = 2;
+      TokOps tok[NK];
 #pragma unroll
-      for (int kk = 0; kk < CH / 16; ++kk) {
-        TokOps nxt = cur;
-        if (kk + 1 < CH / 16) nxt = fetch_tok(kk + 1);
+      for (int kk = 0; kk < PDB && kk < NK; ++kk) tok[kk] = fetch_tok(kk);
+      __builtin_amdgcn_sched_barrier(0);
+      // denominator: rowsum of the (rounded) products + phi(q).Z_prev, PPT threads per query,
+      // all on packed bf16 pairs
+      {
+        const int qrow = tid / PPT, part = tid % PPT;
+        constexpr int KW = CH / PPT;  // product slots per thread
+        constexpr int CW = D / PPT;   // features per thread
+        float s = 0.f;
+#pragma unroll
+        for (int x = 0; x < KW; x += 8) {  // the never-visible tile holds zeros
+          const u32x4 pv = *reinterpret_cast<const u32x4*>(&sm.pt[qrow * C::PROW + KW * part + x]);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) s = dot2_bf16(pv[w], kOnesBf16x2, s);
+        }
+#pragma unroll
+        for (int x = 0; x < CW; x += 8) {
+          const u32x4 qv = *reinterpret_cast<const u32x4*>(&b.fq[qrow * C::QROW + CW * part + x]);
+          const u32x4 zh = *reinterpret_cast<const u32x4*>(&sm.zh[zc][CW * part + x]);
+          const u32x4 zl = *reinterpret_cast<const u32x4*>(&sm.zl[zc][CW * part + x]);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            s = dot2_bf16(qv[w], zh[w], s);
+            s = dot2_bf16(qv[w], zl[w], s);
+          }
+        }
+#pragma unroll
+        for (int o = 1; o < PPT; o <<= 1) s += __shfl_xor(s, o, 64);
+        sm.den[qrow] = s + a.eps;  // every part holds the same sum
+      }
+      float zs = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) {
+        if (kk + PDB < NK) tok[kk + PDB] = fetch_tok(kk + PDB);
+        const TokOps& cur = tok[kk];
 #pragma unroll
         for (int tq = 0; tq < 2; ++tq)
           if (16 * kk < 32 * (tq + 1)) num[tq] = mfma32(cur.vt, cur.pb[tq], num[tq]);
         zs = sum8_bf16(cur.fz, zs);
 #pragma unroll
         for (int ct = 0; ct < C::ET; ++ct) sacc[ct] = mfma32(cur.fa[ct], cur.vt, sacc[ct]);
-        cur = nxt;
+        __builtin_amdgcn_sched_barrier(0);
       }
       zs += __shfl_xor(zs, 32, 64);
       const int zi = 32 * wave + kperm32(ln);
