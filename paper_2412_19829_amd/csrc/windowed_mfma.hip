@@ -31,7 +31,9 @@ template <int D> struct WinSmem {
   WinTiles<D> buf[2];  // tile t in buf[t % 2]: one is filled while the other is read
 };
 
-template <int D>
+// NEG: the softmax scale is negative, so the largest logit belongs to the smallest raw score
+// (a compile-time switch keeps the running-extremum code free of branches).
+template <int D, bool NEG>
 __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(AttnArgs a) {
   constexpr int KS = D / 16;           // k-steps over the head dimension
   constexpr int MT = D / 32;           // 32-row tiles of O^T
@@ -99,24 +101,26 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   constexpr int C8 = D / 8, RP = kMfmaWindowThreads / C8;
   static_assert(KCH * RP == BC, "tile rows must be covered exactly");
   const int prow = tid / C8, pcol = 8 * (tid % C8);
-  const uint32_t koff = (uint32_t)(prow * (int)a.k.sn + pcol), voff = (uint32_t)(prow * (int)a.v.sn + pcol);
+  // piece i is read from a wave-uniform base (row t0 + i*RP, in scalar registers) plus one
+  // per-thread byte offset that never changes, clamped so that rows past N-1 (last tile of the
+  // sequence only) re-read row N-1: in bounds, masked later
+  const int ksn = (int)a.k.sn, vsn = (int)a.v.sn;
+  const uint32_t colb = 2u * (uint32_t)pcol;
+  const uint32_t koff = 2u * (uint32_t)(prow * ksn) + colb, voff = 2u * (uint32_t)(prow * vsn) + colb;
   u32x4 kst[KCH];
   u32x4 vst[KCH];
   auto load_tile = [&](int t) {
     const int t0 = t * BC;
-    if (t0 + BC <= N) {
+    const int last = min(N - 1 - t0, BC - 1);
+    const char* kbase = reinterpret_cast<const char*>(kp + (int64_t)t0 * ksn);
+    const char* vbase = reinterpret_cast<const char*>(vp + (int64_t)t0 * vsn);
 #pragma unroll
-      for (int i = 0; i < KCH; ++i) {
-        kst[i] = *reinterpret_cast<const u32x4*>(kp + (int64_t)(t0 + i * RP) * a.k.sn + koff);
-        vst[i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)(t0 + i * RP) * a.v.sn + voff);
-      }
-    } else {  // last tile of the sequence: rows past N-1 re-read row N-1 (in bounds, masked later)
-#pragma unroll
-      for (int i = 0; i < KCH; ++i) {
-        const int row = min(t0 + prow + i * RP, N - 1);
-        kst[i] = *reinterpret_cast<const u32x4*>(kp + (int64_t)row * a.k.sn + pcol);
-        vst[i] = *reinterpret_cast<const u32x4*>(vp + (int64_t)row * a.v.sn + pcol);
-      }
+    for (int i = 0; i < KCH; ++i) {
+      const int first = min(i * RP, last);  // uniform
+      const uint32_t klim = 2u * (uint32_t)((last - first) * ksn) + colb;
+      const uint32_t vlim = 2u * (uint32_t)((last - first) * vsn) + colb;
+      kst[i] = *reinterpret_cast<const u32x4*>(kbase + 2u * (uint32_t)(first * ksn) + (size_t)min(koff, klim));
+      vst[i] = *reinterpret_cast<const u32x4*>(vbase + 2u * (uint32_t)(first * vsn) + (size_t)min(voff, vlim));
     }
   };
   auto store_tile = [&](Tiles& b) {
@@ -159,8 +163,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
       // The reference follows the running maximum lazily: accumulators are rescaled only when
       // some query's maximum grows by more than 8 (weights stay <= 2^8, harmless in bf16/fp32),
       // which after the first tile or two is rare.
-      const bool neg = sc < 0.f;                    // uniform; a negative scale turns max into min
-      const float worst = neg ? INFINITY : -INFINITY;
+      constexpr float worst = NEG ? INFINITY : -INFINITY;
       if (need_mask) {
         // register (kt, r) of this lane is key t0 + c + 4*lh, c = 32*kt + 8*(r/4) + r%4;
         // visible iff 0 <= (qi - key) < w
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int c = 32 * kt + 8 * (r / 4) + (r % 4);
-            if ((unsigned)(rel - c) >= (unsigned)w) s[kt][r] = worst;
+            s[kt][r] = ((unsigned)(rel - c) >= (unsigned)w) ? worst : s[kt][r];
           }
       }
       float ext = worst;
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; r += 2)
-          ext = neg ? fminf(ext, fminf(s[kt][r], s[kt][r + 1])) : fmaxf(ext, fmaxf(s[kt][r], s[kt][r + 1]));
+          ext = NEG ? fminf(ext, fminf(s[kt][r], s[kt][r + 1])) : fmaxf(ext, fmaxf(s[kt][r], s[kt][r + 1]));
       float mloc = (ext == worst) ? -INFINITY : ext * sc;   // no visible key in this lane's half
       mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
       if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.f) != 0) {   // wave-uniform
@@ -270,20 +273,21 @@ hipError_t launch_windowed_mfma(const AttnArgs& a, hipStream_t s) {
   if (a.H0 <= 0 || a.N <= 0 || a.B <= 0) return hipSuccess;
   dim3 grid(((a.N + BR - 1) / BR) * a.H0 * a.B);
   dim3 block(kMfmaWindowThreads);
-  hipError_t e;
+  const bool neg = a.scale < 0.f;
+  hipError_t e = hipSuccess;
+  auto launch = [&](auto kern, int smem) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e == hipSuccess) kern<<<grid, block, smem, s>>>(a);
+  };
   if (a.d == 64) {
-    const int smem = (int)sizeof(WinSmem<64>);
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(windowed_mfma_kernel<64>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    windowed_mfma_kernel<64><<<grid, block, smem, s>>>(a);
+    if (neg) launch(windowed_mfma_kernel<64, true>, (int)sizeof(WinSmem<64>));
+    else launch(windowed_mfma_kernel<64, false>, (int)sizeof(WinSmem<64>));
   } else {
-    const int smem = (int)sizeof(WinSmem<128>);
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(windowed_mfma_kernel<128>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    windowed_mfma_kernel<128><<<grid, block, smem, s>>>(a);
+    if (neg) launch(windowed_mfma_kernel<128, true>, (int)sizeof(WinSmem<128>));
+    else launch(windowed_mfma_kernel<128, false>, (int)sizeof(WinSmem<128>));
   }
+  if (e != hipSuccess) return e;
   return hipGetLastError();
 }
 
