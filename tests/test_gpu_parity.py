@@ -121,6 +121,18 @@ def test_softmax_scale_eps_and_identity_phi(dtype, impl):
     check(got, ref, dtype, "scale/eps/identity")
 
 
+@pytest.mark.parametrize("dtype,impl", [("f32", SCALAR), ("bf16", MFMA)], ids=["f32", "bf16-mfma"])
+@pytest.mark.parametrize("scale", [-0.25, 0.0], ids=["negative", "zero"])
+def test_negative_and_zero_softmax_scale(dtype, impl, scale):
+    """A negative scale makes the smallest raw score the largest logit; a zero scale makes every
+    visible key weigh the same (plain window mean).  Both are legal inputs of Eq. 1."""
+    B, H, N, d, w, H0 = 1, 2, 330, 64, 70, 2
+    q, k, v = synth(B, H, N, d, dtype, 21, q_prescaled=False)
+    got = run_gpu(q, k, v, dtype, w, H0, impl=impl, softmax_scale=scale)
+    ref = co.attn_fwd(q, k, v, w, H0, softmax_scale=scale)
+    check(got, ref, dtype, f"scale={scale}")
+
+
 # ---------------------------------------------------------------------------------------
 # the MFMA path's launch geometry must not change results
 # ---------------------------------------------------------------------------------------
