@@ -129,15 +129,16 @@ def main() -> int:
         return (time.perf_counter() - t0) / steps
 
     def event_time(call, steps):
-        """Average duration of what `call` enqueues, from events on the launch stream."""
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for _ in range(steps)]
-        for a, b in evs:
-            a.record()
+        """Average duration of what `call` enqueues: `steps` launches back to back between one
+        pair of events on the launch stream (an event pair per launch would add the gap the
+        event packets themselves open between launches)."""
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
             call()
-            b.record()
+        b.record()
         torch.cuda.synchronize()
-        return sum(a.elapsed_time(b) for a, b in evs) / steps * 1e-3
+        return a.elapsed_time(b) / steps * 1e-3
 
     # ---- the timed region: K whole-layer calls -----------------------------------------
     call, params, ws = make_call(H0)
@@ -154,9 +155,8 @@ def main() -> int:
                                 ("linear_main", gb.GF_LAUNCH_LINEAR_MAIN, H0 < wl.H)):
         if present:
             c, _, _w = make_call(H0, mask)
-            for _ in range(3):
-                c()
-            kern[name] = event_time(c, min(max(10, args.steps), 200))
+            ramp(c)
+            kern[name] = event_time(c, 200)
     dominant = max(kern, key=kern.get)
     if dominant == "windowed":
         dom_bytes, dom_flops = work["bytes_windowed"], work["flops_windowed"]
