@@ -40,6 +40,9 @@ def lib():
         L.gformer_oracle_fwd_f64.argtypes = [_dp, _dp, _dp, _dp] + [ctypes.c_int] * 7 + \
             [ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_int]
         L.gformer_oracle_max_threads.restype = ctypes.c_int
+        L.gformer_oracle_random_features_f64.restype = ctypes.c_int
+        L.gformer_oracle_random_features_f64.argtypes = [_dp, _dp, _dp, ctypes.c_long,
+                                                         ctypes.c_int, ctypes.c_int]
         _lib = L
     return _lib
 
@@ -84,6 +87,23 @@ def attn_fwd(q, k, v, window, n_sparse_heads, phi=PHI_ELU1, softmax_scale=1.0, e
                                       int(threads))
     if rc:
         raise RuntimeError(f"oracle layer call failed: {rc}")
+    return out
+
+
+def random_features(x, w):
+    """Positive random features of the rows of x ([..., d]) under projection w ([m, d]):
+    exp(w_i . x - |x|^2 / 2) / sqrt(m), shape [..., m] (section III-A's alternative phi)."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    w, wp = _c(w)
+    m, d = w.shape
+    if x.shape[-1] != d:
+        raise ValueError("x and w disagree on d")
+    rows = int(np.prod(x.shape[:-1], dtype=np.int64))
+    out = np.empty(x.shape[:-1] + (m,), np.float64)
+    rc = lib().gformer_oracle_random_features_f64(x.ctypes.data_as(_dp), wp, out.ctypes.data_as(_dp),
+                                                  rows, d, m)
+    if rc:
+        raise RuntimeError(f"oracle random features failed: {rc}")
     return out
 
 

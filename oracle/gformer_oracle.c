@@ -19,6 +19,9 @@
  *     line of the algorithm names an undefined S and K'; it is read as Q'^T A,
  *     which is what the prose around it and section II-B describe.
  *   - Section II-B: phi(x) = elu(x) + 1.
+ *   - Section III-A (design text): positive random features as an alternative phi, applied as a
+ *     pre-map of Q and K (gformer_oracle_random_features_f64 below) in front of Algorithm 1
+ *     run with the identity map.
  *
  * Two routines cover the linear head: the explicit O(N^2) masked sum (the plain
  * definition: weights a_ij = phi(q_i).phi(k_j), j <= i) and Algorithm 1's
@@ -184,6 +187,34 @@ int gformer_oracle_fwd_f64(const double *q, const double *k, const double *v, do
         }
     }
     return status;
+}
+
+/*
+ * Positive random features (section III-A names them for the linear heads, Algorithm 1 calls
+ * them "random feature maps"; neither prints a formula, so this is the construction of the work
+ * they cite): for a projection matrix W of m rows w_i,
+ *     phi(x)_i = exp(w_i . x - |x|^2 / 2) / sqrt(m),   i = 0..m-1,
+ * every entry positive, and over Gaussian rows E[phi(q) . phi(k)] = exp(q . k).
+ * x: [rows, d], w: [m, d], out: [rows, m], all row-major doubles.
+ */
+int gformer_oracle_random_features_f64(const double *x, const double *w, double *out, long rows,
+                                       int d, int m)
+{
+    if (!x || !w || !out || rows < 0 || d < 1 || m < 1) return 1;
+    const double inv_sqrt_m = 1.0 / sqrt((double)m);
+    for (long r = 0; r < rows; ++r) {
+        const double *xr = x + (size_t)r * d;
+        double half_sq = 0.0;
+        for (int c = 0; c < d; ++c) half_sq += xr[c] * xr[c];
+        half_sq *= 0.5;
+        for (int i = 0; i < m; ++i) {
+            const double *wi = w + (size_t)i * d;
+            double dot = 0.0;
+            for (int c = 0; c < d; ++c) dot += wi[c] * xr[c];
+            out[(size_t)r * m + i] = exp(dot - half_sq) * inv_sqrt_m;
+        }
+    }
+    return 0;
 }
 
 int gformer_oracle_max_threads(void)

@@ -458,3 +458,71 @@ def test_degenerate_shapes_and_errors():
         co.windowed_head(one, one, one, 0)
     with pytest.raises(RuntimeError):
         co.attn_fwd(np.ones((1, 2, 3, 4)), np.ones((1, 2, 3, 4)), np.ones((1, 2, 3, 4)), 2, 3)
+
+
+# ---------------------------------------------------------------------------------------
+# positive random features (section III-A's alternative feature map)
+# ---------------------------------------------------------------------------------------
+
+def _rf_expected(g):
+    const = {"sqrt_e": g["sqrt_e"], "inv_sqrt_e": g["inv_sqrt_e"], "e_m3_2": g["e_m3_2"], "one": 1.0}
+    return np.array([[const[t] * g["inv_sqrt_3"] for t in row] for row in g["expected_terms"]])
+
+
+def test_random_features_worked_example():
+    g = load_golden("random_features_3.json")
+    got = co.random_features(np.array(g["x"], float), np.array(g["w"], float))
+    assert got.shape == (2, 3)
+    assert max_abs(got, _rf_expected(g)) < 1e-15
+
+
+@pytest.mark.parametrize("kind", ["no_norm_term", "plus_norm_term", "no_sqrt_m"])
+def test_random_features_golden_rejects_wrong_readings(kind):
+    """Dropping the -|x|^2/2 term, flipping its sign or forgetting 1/sqrt(m) all miss the fixture."""
+    g = load_golden("random_features_3.json")
+    wrong = np.array(g["must_reject"][kind]) * (1.0 if kind == "no_sqrt_m" else g["inv_sqrt_3"])
+    assert max_abs(wrong, _rf_expected(g)[0]) > 0.1
+
+
+def test_random_features_estimate_the_exponential_kernel():
+    """E over Gaussian rows of phi(q).phi(k) is exp(q.k): the defining property of the
+    construction, checked by Monte Carlo with 400k rows (standard error well below the bound)."""
+    rng = np.random.default_rng(77)
+    d, m = 4, 400_000
+    w = rng.standard_normal((m, d))
+    for _ in range(3):
+        q = rng.standard_normal(d) * 0.4
+        k = rng.standard_normal(d) * 0.4
+        est = float(co.random_features(q[None], w)[0] @ co.random_features(k[None], w)[0])
+        assert abs(est / math.exp(float(q @ k)) - 1.0) < 0.02
+
+
+def test_random_features_log_is_linear_minus_half_square():
+    """log phi(x+y) = log phi(x) + log phi(y) - x.y + log(m)/2 for every feature, and
+    log phi(2x) = 4 log phi(x) - 2 w.x + 3 log(m)/2: both fix the -1/2 of the squared norm and
+    the 1/sqrt(m) without evaluating an exponential in the test."""
+    rng = np.random.default_rng(78)
+    d, m = 5, 7
+    w = rng.standard_normal((m, d))
+    x, y = rng.standard_normal(d), rng.standard_normal(d)
+    lx, ly, lxy, l2x = (np.log(co.random_features(v[None], w)[0]) for v in (x, y, x + y, 2 * x))
+    assert max_abs(lxy, lx + ly - float(x @ y) + 0.5 * math.log(m)) < 1e-12
+    assert max_abs(l2x, 4 * lx - 2 * (w @ x) + 1.5 * math.log(m)) < 1e-12
+    # rows of W enter one feature each, in order
+    w2 = w.copy(); w2[3] += 1.0
+    delta = np.log(co.random_features(x[None], w2)[0]) - lx
+    assert max_abs(delta, np.eye(m)[3] * float(x.sum())) < 1e-12
+
+
+def test_random_features_feed_algorithm_1_as_kernel_weights():
+    """Linear head with pre-mapped features and the identity map == causal kernel regression
+    with weights phi(q_i).phi(k_j), written out here with a dense matrix."""
+    rng = np.random.default_rng(79)
+    N, d = 9, 4
+    q, k, v = (rng.standard_normal((N, d)) * 0.5 for _ in range(3))
+    w = rng.standard_normal((d, d))
+    fq, fk = co.random_features(q, w), co.random_features(k, w)
+    got = co.linear_head(fq, fk, v, phi=co.PHI_IDENTITY)
+    a = np.tril(fq @ fk.T)
+    assert max_abs(got, (a @ v) / a.sum(1, keepdims=True)) < 1e-12
+    assert (fq > 0).all() and (fk > 0).all()
