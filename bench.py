@@ -208,6 +208,37 @@ def main() -> int:
                            "tflops": round(fl / s / 1e12, 2),
                            "pct_mfma_peak": round(100 * fl / s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
                            "pct_hbm_peak": round(100 * by / s / 1e9 / HBM_PEAK_GBS, 2)}
+        # Section III-A's alternative feature map: Q and K of the linear heads mapped by the
+        # random-feature kernel (two launches), then the same layer with the identity map.
+        if H0 < wl.H:
+            rng = np.random.default_rng(wl.seed + 7)
+            tw = dev(gi.round_to_bf16(rng.standard_normal((wl.d, wl.d)).astype(np.float32)))
+            tq2, tk2 = tq.clone(), (tk * 0.25).to(torch.bfloat16)   # |k| kept moderate (no stabiliser)
+            tk3 = tk2.clone()
+            def premap():
+                gb.gformer_random_features(tq, tw, tq2, H0, wl.H, stream=stream)
+                gb.gformer_random_features(tk2, tw, tk3, H0, wl.H, stream=stream)
+            ramp(premap)
+            t_pre = event_time(premap, 100) / 2.0          # per launch
+            params_id = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=H0, phi=gb.GF_PHI_IDENTITY,
+                                       segment_len=args.segment_len)
+            need = gb.gformer_attn_workspace_bytes(wl.B, wl.H, wl.N, wl.d, wl.window, params_id)
+            ws_id = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+            def layer_rf():
+                premap()
+                st_ = gb.gformer_attn_fwd_raw(tq2.data_ptr(), tk3.data_ptr(), tv.data_ptr(), out.data_ptr(),
+                                              wl.B, wl.H, wl.N, wl.d, wl.window, params_id,
+                                              ws_id.data_ptr(), ws_id.numel(), stream)
+                if st_ != gb.GF_OK:
+                    raise gb.GformerError(st_, gb.gformer_status_string(st_))
+            s_rf = time_steps(layer_rf, max(5, args.steps // 2), 3)
+            pre_bytes = 2 * wl.B * (wl.H - H0) * wl.N * wl.d * 2   # one tensor read, one written
+            modes["random_features"] = {
+                "ms": round(s_rf * 1e3, 4), "tokens_per_s": round(wl.B * wl.N / s_rf, 1),
+                "premap_us_per_launch": round(t_pre * 1e6, 2),
+                "premap_gbs": round(pre_bytes / t_pre / 1e9, 1),
+                "premap_frac_hbm_peak": round(pre_bytes / t_pre / 1e9 / HBM_PEAK_GBS, 4),
+                "note": "two pre-map launches (Q, K of the linear heads) + the layer with the identity map"}
         result["modes"] = modes
 
     # ---- CPU baseline: the fp64 oracle on batch element 0 (all heads), host cores ---------

@@ -139,6 +139,38 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
                            int N, int d, int window, const gformer_params* p, void* workspace,
                            size_t workspace_bytes, void* hip_stream);
 
+/* Positive random features as a pre-map of Q or K for the linear heads.  Section III-A names
+ * "positive orthogonal random features" for the linear part and Algorithm 1 "random feature
+ * maps"; neither prints them, so the formula is the construction of the work they cite:
+ *     out[b,h,n,i] = exp( sum_c w[i][c] * x[b,h,n,c]  -  |x[b,h,n,:]|^2 / 2 ) / sqrt(m)
+ * for heads head_begin <= h < head_end (the linear heads); other heads of `out` are not touched.
+ * The mapped tensors are then passed to gformer_attn_fwd with phi = GF_PHI_IDENTITY (the windowed
+ * heads of that call still read the unmapped heads, so map in place or into a copy).
+ *   x   : device, [B,H,N,d] through x_stride, read
+ *   w   : device, [m,d] dense row-major, same element type as x; drawing (and orthogonalising)
+ *         its rows is the caller's business
+ *   out : device, [B,H,N,m] through o_stride, written; may be the same buffer and strides as x
+ *         (in place), must not overlap it otherwise
+ * Supported: m == d in {64,128} (the carried state of the linear heads is d x d); anything else
+ * GF_ERR_UNSUPPORTED.  No workspace.  Asynchronous on `hip_stream`.  Values outside the range of
+ * the element type overflow like any other float expression: keep |x| moderate (the cited
+ * construction subtracts a stabiliser, which cancels in the attention ratio). */
+typedef struct gformer_feature_params {
+  uint32_t struct_size;   /* = sizeof(gformer_feature_params)                                */
+  int32_t dtype;          /* gf_dtype of x, w and out                                        */
+  int32_t head_begin;     /* first head to map                                               */
+  int32_t head_end;       /* one past the last head to map                                   */
+  int32_t impl;           /* gf_impl; AUTO = MFMA for bf16, scalar for fp32                  */
+  int32_t reserved0;
+  int64_t x_stride[3], o_stride[3]; /* (b, h, n) element strides; all-zero = dense [B,H,N,d] */
+} gformer_feature_params;
+
+/* struct_size set, dtype = GF_BF16, head_begin = head_end = 0, impl = AUTO, dense strides */
+void gformer_feature_params_init(gformer_feature_params* p);
+
+gf_status gformer_random_features(const void* x, const void* w, void* out, int B, int H, int N,
+                                  int d, int m, const gformer_feature_params* p, void* hip_stream);
+
 const char* gformer_status_string(gf_status s);
 
 /* major*10000 + minor*100 + patch */

@@ -21,7 +21,8 @@ GF_IMPL_AUTO, GF_IMPL_SCALAR, GF_IMPL_MFMA = 0, 1, 2
 GF_LAUNCH_WINDOWED, GF_LAUNCH_LINEAR_STATE, GF_LAUNCH_LINEAR_MAIN = 1, 2, 4
 
 EXPORTS = ("gformer_params_init", "gformer_attn_workspace_bytes", "gformer_attn_plan",
-           "gformer_attn_fwd", "gformer_status_string", "gformer_version")
+           "gformer_attn_fwd", "gformer_feature_params_init", "gformer_random_features",
+           "gformer_status_string", "gformer_version")
 
 
 class GformerParams(ctypes.Structure):
@@ -45,6 +46,13 @@ class GformerPlan(ctypes.Structure):
 
     def as_dict(self) -> dict:
         return {n: int(getattr(self, n)) for n, _ in self._fields_ if n != "reserved"}
+
+
+class GformerFeatureParams(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+                ("head_begin", ctypes.c_int32), ("head_end", ctypes.c_int32),
+                ("impl", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+                ("x_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3)]
 
 
 class GformerError(RuntimeError):
@@ -75,6 +83,12 @@ def lib():
         L.gformer_attn_fwd.restype = ctypes.c_int
         L.gformer_attn_fwd.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 5 + \
             [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        FP = ctypes.POINTER(GformerFeatureParams)
+        L.gformer_feature_params_init.restype = None
+        L.gformer_feature_params_init.argtypes = [FP]
+        L.gformer_random_features.restype = ctypes.c_int
+        L.gformer_random_features.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 5 + \
+            [FP, ctypes.c_void_p]
         L.gformer_status_string.restype = ctypes.c_char_p
         L.gformer_status_string.argtypes = [ctypes.c_int]
         L.gformer_version.restype = ctypes.c_int
@@ -181,6 +195,61 @@ def gformer_attn_fwd(q, k, v, out, window: int, n_sparse_heads: int, *, phi=GF_P
         stream = torch.cuda.current_stream(q.device).cuda_stream
     st = gformer_attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
                               B, H, N, d, window, params, ws_ptr, ws_bytes, stream)
+    if st != GF_OK:
+        raise GformerError(st, gformer_status_string(st))
+    return out
+
+
+def gformer_feature_params_init() -> GformerFeatureParams:
+    p = GformerFeatureParams()
+    lib().gformer_feature_params_init(ctypes.byref(p))
+    return p
+
+
+def make_feature_params(dtype=GF_BF16, head_begin=0, head_end=0, impl=GF_IMPL_AUTO,
+                        x_stride=None, o_stride=None) -> GformerFeatureParams:
+    p = gformer_feature_params_init()
+    p.dtype, p.head_begin, p.head_end, p.impl = int(dtype), int(head_begin), int(head_end), int(impl)
+    for name, val in (("x_stride", x_stride), ("o_stride", o_stride)):
+        if val is not None:
+            setattr(p, name, (ctypes.c_int64 * 3)(*[int(v) for v in val]))
+    return p
+
+
+def gformer_random_features_raw(x_ptr, w_ptr, out_ptr, B, H, N, d, m, params: GformerFeatureParams,
+                                stream=0) -> int:
+    """Direct call with integer device addresses; returns the gf_status."""
+    return int(lib().gformer_random_features(
+        ctypes.c_void_p(x_ptr or None), ctypes.c_void_p(w_ptr or None),
+        ctypes.c_void_p(out_ptr or None), int(B), int(H), int(N), int(d), int(m),
+        ctypes.byref(params), ctypes.c_void_p(stream or None)))
+
+
+def gformer_random_features(x, w, out, head_begin: int, head_end: int, *, impl=GF_IMPL_AUTO,
+                            stream: Optional[int] = None):
+    """Positive random features of heads [head_begin, head_end) of x ([B,H,N,d] device tensor)
+    under the projection w ([d,d], dense), written to the same heads of `out` (may be x itself)."""
+    import torch
+
+    if not (x.is_cuda and w.is_cuda and out.is_cuda):
+        raise ValueError("x, w, out must be device tensors: there is no CPU path")
+    if not (x.dtype == w.dtype == out.dtype):
+        raise ValueError("x, w, out must share one dtype")
+    if x.dtype == torch.bfloat16:
+        dtype = GF_BF16
+    elif x.dtype == torch.float32:
+        dtype = GF_F32
+    else:
+        raise ValueError(f"unsupported dtype {x.dtype}")
+    if x.dim() != 4 or out.shape != x.shape or w.dim() != 2 or not w.is_contiguous():
+        raise ValueError("x, out must be [B, H, N, d] and w a dense [m, d] matrix")
+    B, H, N, d = (int(v) for v in x.shape)
+    params = make_feature_params(dtype=dtype, head_begin=head_begin, head_end=head_end, impl=impl,
+                                 x_stride=_strides3(x), o_stride=_strides3(out))
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+    st = gformer_random_features_raw(x.data_ptr(), w.data_ptr(), out.data_ptr(), B, H, N, d,
+                                     int(w.shape[0]), params, stream)
     if st != GF_OK:
         raise GformerError(st, gformer_status_string(st))
     return out

@@ -268,6 +268,53 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
   return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
 }
 
+void gformer_feature_params_init(gformer_feature_params* p) {
+  if (!p) return;
+  memset(p, 0, sizeof(*p));
+  p->struct_size = sizeof(gformer_feature_params);
+  p->dtype = GF_BF16;
+  p->impl = GF_IMPL_AUTO;
+}
+
+gf_status gformer_random_features(const void* x, const void* w, void* out, int B, int H, int N,
+                                  int d, int m, const gformer_feature_params* p, void* hip_stream) {
+  if (!p || p->struct_size != sizeof(gformer_feature_params)) return GF_ERR_INVALID_ARG;
+  if (B < 0 || H < 0 || N < 0 || d < 1 || m < 1) return GF_ERR_INVALID_ARG;
+  if (p->dtype != GF_F32 && p->dtype != GF_BF16) return GF_ERR_INVALID_ARG;
+  if (p->impl != GF_IMPL_AUTO && p->impl != GF_IMPL_SCALAR && p->impl != GF_IMPL_MFMA)
+    return GF_ERR_INVALID_ARG;
+  if (p->head_begin < 0 || p->head_end < p->head_begin || p->head_end > H) return GF_ERR_INVALID_ARG;
+  if (B > 65535 || H > 65535) return GF_ERR_UNSUPPORTED;
+  int64_t xs[3], os[3];
+  gf_status st;
+  if ((st = check_strides(p->x_stride, xs, H, N, d)) != GF_OK) return st;
+  if ((st = check_strides(p->o_stride, os, H, N, m)) != GF_OK) return st;
+  if (m != d || (d != 64 && d != 128)) return GF_ERR_UNSUPPORTED;
+  int impl = p->impl;
+  if (impl == GF_IMPL_AUTO) impl = (p->dtype == GF_BF16) ? GF_IMPL_MFMA : GF_IMPL_SCALAR;
+  if (impl == GF_IMPL_MFMA && p->dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
+  if (B == 0 || N == 0 || p->head_end == p->head_begin) return GF_OK;
+  if (!x || !w || !out) return GF_ERR_INVALID_ARG;
+  if (((uintptr_t)x | (uintptr_t)w | (uintptr_t)out) & 15u) return GF_ERR_INVALID_ARG;
+  if (out == w) return GF_ERR_INVALID_ARG;
+  // in place is fine only when every element keeps its address
+  if (out == x && (xs[0] != os[0] || xs[1] != os[1] || xs[2] != os[2])) return GF_ERR_INVALID_ARG;
+  if ((int64_t)B * (p->head_end - p->head_begin) * N > 0x7fffffffLL) return GF_ERR_UNSUPPORTED;
+
+  FeatureArgs a;
+  memset(&a, 0, sizeof(a));
+  a.x = TensorView{x, xs[0], xs[1], xs[2]};
+  a.w = w;
+  a.out = out;
+  a.osb = os[0]; a.osh = os[1]; a.osn = os[2];
+  a.B = B; a.H = H; a.N = N; a.d = d;
+  a.head_begin = p->head_begin;
+  a.head_end = p->head_end;
+  const hipError_t e = launch_random_features(a, p->dtype == GF_BF16, impl == GF_IMPL_MFMA,
+                                              reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
+}
+
 const char* gformer_status_string(gf_status s) {
   switch (s) {
     case GF_OK: return "ok";

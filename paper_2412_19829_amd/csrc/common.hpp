@@ -74,12 +74,23 @@ template <> struct Storage<uint16_t> {  // bf16 bit patterns
   }
 };
 
+// One call of the random-feature pre-map: heads [head_begin, head_end) of x -> the same heads of out.
+struct FeatureArgs {
+  TensorView x;
+  const void* w;     // [d, d] row-major, same element type as x
+  void* out;
+  int64_t osb, osh, osn;
+  int B, H, N, d;
+  int head_begin, head_end;
+};
+
 // Host-side launchers, one per kernel family.  Each returns the hipError_t of its launch.
 hipError_t launch_windowed_scalar(const AttnArgs& a, bool bf16, hipStream_t s);
 hipError_t launch_linear_scalar(const AttnArgs& a, bool bf16, hipStream_t s);
 hipError_t launch_windowed_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_linear_state_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_linear_main_mfma(const AttnArgs& a, hipStream_t s);
+hipError_t launch_random_features(const FeatureArgs& a, bool bf16, bool mfma, hipStream_t s);
 
 // Launch geometry shared by the planner and the launchers.
 constexpr int kScalarWindowRows = 16;   // query rows per workgroup, scalar windowed kernel

@@ -156,3 +156,51 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(1, 1, 8, 64)
     with pytest.raises(ValueError):
         gb.gformer_attn_fwd(x, x, x, torch.empty_like(x), 4, 1)
+
+
+# ---------------------------------------------------------------------------------------
+# gformer_random_features: host-side checks
+# ---------------------------------------------------------------------------------------
+
+def test_feature_params_defaults():
+    p = gb.gformer_feature_params_init()
+    assert p.struct_size == ctypes.sizeof(gb.GformerFeatureParams)
+    assert p.dtype == gb.GF_BF16 and p.head_begin == 0 and p.head_end == 0 and p.impl == gb.GF_IMPL_AUTO
+    assert list(p.x_stride) == [0, 0, 0] and list(p.o_stride) == [0, 0, 0]
+
+
+@pytest.mark.parametrize("args,kw,want", [
+    ((1, 4, 16, 64, 64), {"head_begin": 1, "head_end": 5}, gb.GF_ERR_INVALID_ARG),
+    ((1, 4, 16, 64, 64), {"head_begin": 3, "head_end": 2}, gb.GF_ERR_INVALID_ARG),
+    ((1, 4, 16, 64, 64), {"head_begin": -1, "head_end": 2}, gb.GF_ERR_INVALID_ARG),
+    ((1, 4, 16, 64, 64), {"head_end": 4, "dtype": 5}, gb.GF_ERR_INVALID_ARG),
+    ((1, 4, 16, 64, 64), {"head_end": 4, "impl": 7}, gb.GF_ERR_INVALID_ARG),
+    ((1, 4, -1, 64, 64), {"head_end": 4}, gb.GF_ERR_INVALID_ARG),
+    ((1, 4, 16, 64, 64), {"head_end": 4, "x_stride": (4096, 1024, 60)}, gb.GF_ERR_INVALID_ARG),
+    ((1, 4, 16, 64, 128), {"head_end": 4}, gb.GF_ERR_UNSUPPORTED),    # m != d
+    ((1, 4, 16, 96, 96), {"head_end": 4}, gb.GF_ERR_UNSUPPORTED),     # head size
+    ((1, 4, 16, 64, 64), {"head_end": 4, "dtype": gb.GF_F32, "impl": gb.GF_IMPL_MFMA}, gb.GF_ERR_UNSUPPORTED),
+])
+def test_feature_argument_errors_are_reported_on_the_host(args, kw, want):
+    p = gb.make_feature_params(**kw)
+    assert gb.gformer_random_features_raw(0x1000, 0x2000, 0x3000, *args, p) == want
+
+
+def test_feature_pointer_checks_and_empty_problems():
+    p = gb.make_feature_params(dtype=gb.GF_F32, head_end=2)
+    a = (1, 2, 16, 64, 64)
+    assert gb.gformer_random_features_raw(0, 0x2000, 0x3000, *a, p) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_random_features_raw(0x1000, 0x2008, 0x3000, *a, p) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_random_features_raw(0x1000, 0x2000, 0x2000, *a, p) == gb.GF_ERR_INVALID_ARG  # out is w
+    # in place needs identical strides
+    q = gb.make_feature_params(dtype=gb.GF_F32, head_end=2, x_stride=(4096, 1024, 64), o_stride=(8192, 2048, 128))
+    assert gb.gformer_random_features_raw(0x1000, 0x2000, 0x1000, *a, q) == gb.GF_ERR_INVALID_ARG
+    # nothing to do: fine even with null pointers
+    assert gb.gformer_random_features_raw(0, 0, 0, 0, 2, 16, 64, 64, p) == gb.GF_OK
+    assert gb.gformer_random_features_raw(0, 0, 0, 1, 2, 0, 64, 64, p) == gb.GF_OK
+    e = gb.make_feature_params(dtype=gb.GF_F32, head_begin=1, head_end=1)
+    assert gb.gformer_random_features_raw(0, 0, 0, *a, e) == gb.GF_OK
+    with pytest.raises(ValueError):
+        import torch
+        t = torch.zeros(1, 2, 16, 64)
+        gb.gformer_random_features(t, torch.zeros(64, 64), t, 0, 2)   # host tensors: no CPU path

@@ -8,7 +8,7 @@ import pytest
 from oracle import cpu_oracle as co
 from paper_2412_19829_amd import binding as gb
 from paper_2412_19829_amd import inputs as gi
-from tests.gpu_util import BF16_ROW_REL_L2, F32_MAX_ABS, run_gpu
+from tests.gpu_util import BF16_ROW_REL_L2, F32_MAX_ABS, run_gpu, to_device, to_host
 from tests.helpers import max_abs, row_rel_l2
 
 pytestmark = pytest.mark.gpu
@@ -263,3 +263,83 @@ def test_llm7b_segment_sweep_sampled_heads(seg):
 
 def test_long32k_full_size_sampled_heads():
     _full_size("long32k", 6)
+
+
+# ---------------------------------------------------------------------------------------
+# positive random features (section III-A's alternative feature map) as a pre-map
+# ---------------------------------------------------------------------------------------
+
+def _rf_inputs(B, H, N, d, dtype, seed, sigma=0.35):
+    rng = np.random.default_rng(seed)
+    x = (rng.standard_normal((B, H, N, d)) * sigma).astype(np.float32)
+    w = rng.standard_normal((d, d)).astype(np.float32)
+    if dtype == "bf16":
+        x, w = gi.round_to_bf16(x), gi.round_to_bf16(w)
+    return x, w
+
+
+def _run_features(x, w, dtype, h0, h1, impl, in_place=False, layout="bhnd"):
+    import torch
+    tx, tw = to_device(x, dtype), to_device(w, dtype)
+    if layout == "bnhd":
+        tx = tx.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    out = tx if in_place else torch.full_like(tx, float("nan"))
+    gb.gformer_random_features(tx, tw, out, h0, h1, impl=impl)
+    torch.cuda.synchronize()
+    return to_host(out)
+
+
+RF_REL = {"f32": 2e-5, "bf16": 2.0 ** -7}   # fp32: exp of an fp32 dot product; bf16: one rounding
+
+
+@pytest.mark.parametrize("dtype,impl", [("f32", SCALAR), ("bf16", SCALAR), ("bf16", MFMA)],
+                         ids=["f32", "bf16-scalar", "bf16-mfma"])
+@pytest.mark.parametrize("shape", [(1, 2, 1, 64), (2, 3, 77, 64), (1, 4, 333, 128), (2, 2, 513, 128)],
+                         ids=str)
+def test_random_features_match_oracle(dtype, impl, shape):
+    B, H, N, d = shape
+    x, w = _rf_inputs(B, H, N, d, dtype, 31)
+    h0, h1 = (1, H) if H > 1 else (0, H)
+    got = _run_features(x, w, dtype, h0, h1, impl)
+    ref = co.random_features(x.astype(np.float64), w.astype(np.float64))
+    assert np.isnan(got[:, :h0]).all()                       # heads outside the range are not touched
+    rel = np.abs(got[:, h0:h1] - ref[:, h0:h1]) / ref[:, h0:h1]
+    assert float(rel.max()) <= RF_REL[dtype], float(rel.max())
+
+
+@pytest.mark.parametrize("dtype,impl", [("f32", SCALAR), ("bf16", MFMA)], ids=["f32", "bf16-mfma"])
+def test_random_features_in_place_and_paper_layout(dtype, impl):
+    B, H, N, d = 2, 3, 150, 64
+    x, w = _rf_inputs(B, H, N, d, dtype, 32)
+    ref = co.random_features(x.astype(np.float64), w.astype(np.float64))
+    a = _run_features(x, w, dtype, 1, 3, impl, in_place=True, layout="bnhd")
+    b = _run_features(x, w, dtype, 1, 3, impl)
+    assert np.array_equal(a[:, 0], x[:, 0].astype(np.float64))      # unmapped head keeps its values
+    assert np.array_equal(a[:, 1:], b[:, 1:])                        # same bits in place and out of place
+    assert float((np.abs(a[:, 1:] - ref[:, 1:]) / ref[:, 1:]).max()) <= RF_REL[dtype]
+
+
+@pytest.mark.parametrize("dtype,impl", [("f32", SCALAR), ("bf16", MFMA)], ids=["f32", "bf16-mfma"])
+def test_attention_with_random_features_end_to_end(dtype, impl):
+    """Q and K of the linear heads mapped on the device, then Algorithm 1 with the identity map;
+    the oracle does the same in fp64 from the unrounded features."""
+    import torch
+    B, H, N, d, w_, H0 = 1, 4, 400, 64, 48, 1
+    q, k, v = synth(B, H, N, d, dtype, 33)
+    rng = np.random.default_rng(34)
+    proj = rng.standard_normal((d, d)).astype(np.float32)
+    k = (k * np.float32(0.3)).astype(np.float32)          # keep exp(w.k - |k|^2/2) in a tame range
+    if dtype == "bf16":
+        proj, k = gi.round_to_bf16(proj), gi.round_to_bf16(k)
+    tq, tk, tv, tw = (to_device(t, dtype) for t in (q, k, v, proj))
+    gb.gformer_random_features(tq, tw, tq, H0, H, impl=impl)
+    gb.gformer_random_features(tk, tw, tk, H0, H, impl=impl)
+    out = torch.full_like(tq, float("nan"))
+    gb.gformer_attn_fwd(tq, tk, tv, out, w_, H0, phi=gb.GF_PHI_IDENTITY, impl=impl)
+    torch.cuda.synchronize()
+    got = to_host(out)
+    fq, fk = q.astype(np.float64).copy(), k.astype(np.float64).copy()
+    fq[:, H0:] = co.random_features(fq[:, H0:], proj.astype(np.float64))
+    fk[:, H0:] = co.random_features(fk[:, H0:], proj.astype(np.float64))
+    ref = co.attn_fwd(fq, fk, v, w_, H0, phi=co.PHI_IDENTITY)
+    check(got, ref, dtype, "random features end to end")
