@@ -343,3 +343,47 @@ def test_attention_with_random_features_end_to_end(dtype, impl):
     fk[:, H0:] = co.random_features(fk[:, H0:], proj.astype(np.float64))
     ref = co.attn_fwd(fq, fk, v, w_, H0, phi=co.PHI_IDENTITY)
     check(got, ref, dtype, "random features end to end")
+
+
+# ---------------------------------------------------------------------------------------
+# stream capture: the whole layer as one graph, replayed
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("overlap", [0, 1], ids=["serial", "side-stream"])
+def test_layer_under_stream_capture_replays_bit_identically(overlap):
+    """The call only enqueues kernels (and, with overlap, an event fork/join), so it can be
+    captured; every replay, with eager work and synchronisations in between, must reproduce the
+    eager result bit for bit."""
+    import torch
+    B, H, N, d, w, H0 = 1, 4, 900, 64, 80, 1
+    q, k, v = synth(B, H, N, d, "bf16", 41)
+    tq, tk, tv = (to_device(t, "bf16") for t in (q, k, v))
+    params = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=H0, overlap=overlap)
+    need = gb.gformer_attn_workspace_bytes(B, H, N, d, w, params)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    eager = torch.full_like(tq, float("nan"))
+    gb.gformer_attn_fwd(tq, tk, tv, eager, w, H0, overlap=overlap, workspace=ws)
+    torch.cuda.synchronize()
+    check(to_host(eager), oracle(q, k, v, w, H0), "bf16", "eager")
+
+    out = torch.full_like(tq, float("nan"))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            gb.gformer_attn_fwd(tq, tk, tv, out, w, H0, overlap=overlap, workspace=ws,
+                                stream=side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        ws.random_(0, 255)                       # the workspace is rewritten by every call
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"
+        # eager work between replays
+        tmp = torch.full_like(tq, float("nan"))
+        gb.gformer_attn_fwd(tq, tk, tv, tmp, w, H0, overlap=overlap)
+        torch.cuda.synchronize()
+        assert torch.equal(tmp.view(torch.int16), eager.view(torch.int16))
