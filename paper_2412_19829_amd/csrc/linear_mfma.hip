@@ -39,7 +39,8 @@ template <int D> struct LinCfg {
   static constexpr int NTC = NWC * 64;        // compute threads
   static constexpr int NT = 2 * NTC;          // + as many producer threads
   static constexpr int QROW = D + 8;          // phi(Q): 128-bit row reads   (stride = 4 dw mod 64)
-  static constexpr int KROW = D + 16;         // phi(K): 64-bit row reads + transpose reads
+  static constexpr int KROW = D == 64 ? D + 8 : D + 16;  // phi(K): 64-bit row reads + transpose
+                                              // reads (D = 64: 8 keeps two workgroups' LDS under 160 KB)
   static constexpr int VROW = D + 32;         // V: transpose reads only     (stride = 16 dw mod 64)
   static constexpr int PROW = CH + 8;         // masked products, [query][key]
   static constexpr int OROW = D + 8;          // normalised output rows on their way to memory
@@ -389,7 +390,7 @@ __global__ __launch_bounds__(256) void linear_prefix_kernel(float* ws, int n_hea
 //     visible, (b) buffers change hands.
 // -----------------------------------------------------------------------------------------
 template <int D, bool ELU1>
-__global__ __launch_bounds__(LinCfg<D>::NT) void linear_main_kernel(AttnArgs a) {
+__global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_kernel(AttnArgs a) {
   using C = LinCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   LinSmem<D>& sm = *reinterpret_cast<LinSmem<D>*>(smem_raw);
