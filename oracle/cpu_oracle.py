@@ -39,6 +39,14 @@ def lib():
         L.gformer_oracle_fwd_f64.restype = ctypes.c_int
         L.gformer_oracle_fwd_f64.argtypes = [_dp, _dp, _dp, _dp] + [ctypes.c_int] * 7 + \
             [ctypes.c_double, ctypes.c_double, ctypes.c_int, ctypes.c_int]
+        L.gformer_oracle_windowed_head_bidir_f64.restype = ctypes.c_int
+        L.gformer_oracle_windowed_head_bidir_f64.argtypes = L.gformer_oracle_windowed_head_f64.argtypes
+        for name in ("gformer_oracle_linear_head_bidir_f64", "gformer_oracle_linear_head_bidir_state_f64"):
+            f = getattr(L, name)
+            f.restype = ctypes.c_int
+            f.argtypes = L.gformer_oracle_linear_head_quadratic_f64.argtypes
+        L.gformer_oracle_fwd_bidir_f64.restype = ctypes.c_int
+        L.gformer_oracle_fwd_bidir_f64.argtypes = L.gformer_oracle_fwd_f64.argtypes
         L.gformer_oracle_max_threads.restype = ctypes.c_int
         L.gformer_oracle_random_features_f64.restype = ctypes.c_int
         L.gformer_oracle_random_features_f64.argtypes = [_dp, _dp, _dp, ctypes.c_long,
@@ -52,23 +60,30 @@ def _c(a):
     return a, a.ctypes.data_as(_dp)
 
 
-def windowed_head(q, k, v, window, scale=1.0):
+def windowed_head(q, k, v, window, scale=1.0, bidirectional=False):
+    """Causal: the w tokens ending at i.  Bidirectional: the w tokens centred on i."""
     q, qp = _c(q); k, kp = _c(k); v, vp = _c(v)
     N, d = q.shape
     out = np.empty((N, d), np.float64)
-    rc = lib().gformer_oracle_windowed_head_f64(qp, kp, vp, out.ctypes.data_as(_dp), N, d,
-                                                int(window), float(scale))
+    fn = (lib().gformer_oracle_windowed_head_bidir_f64 if bidirectional
+          else lib().gformer_oracle_windowed_head_f64)
+    rc = fn(qp, kp, vp, out.ctypes.data_as(_dp), N, d, int(window), float(scale))
     if rc:
         raise RuntimeError(f"oracle windowed head failed: {rc}")
     return out
 
 
-def linear_head(q, k, v, phi=PHI_ELU1, eps=0.0, form=LINEAR_QUADRATIC):
+def linear_head(q, k, v, phi=PHI_ELU1, eps=0.0, form=LINEAR_QUADRATIC, bidirectional=False):
+    """form: explicit sum over keys (LINEAR_QUADRATIC) or running / total state (LINEAR_RECURRENT)."""
     q, qp = _c(q); k, kp = _c(k); v, vp = _c(v)
     N, d = q.shape
     out = np.empty((N, d), np.float64)
-    fn = (lib().gformer_oracle_linear_head_recurrent_f64 if form == LINEAR_RECURRENT
-          else lib().gformer_oracle_linear_head_quadratic_f64)
+    if bidirectional:
+        fn = (lib().gformer_oracle_linear_head_bidir_state_f64 if form == LINEAR_RECURRENT
+              else lib().gformer_oracle_linear_head_bidir_f64)
+    else:
+        fn = (lib().gformer_oracle_linear_head_recurrent_f64 if form == LINEAR_RECURRENT
+              else lib().gformer_oracle_linear_head_quadratic_f64)
     rc = fn(qp, kp, vp, out.ctypes.data_as(_dp), N, d, int(phi), float(eps))
     if rc:
         raise RuntimeError(f"oracle linear head failed: {rc}")
@@ -76,12 +91,13 @@ def linear_head(q, k, v, phi=PHI_ELU1, eps=0.0, form=LINEAR_QUADRATIC):
 
 
 def attn_fwd(q, k, v, window, n_sparse_heads, phi=PHI_ELU1, softmax_scale=1.0, eps=0.0,
-             linear_form=LINEAR_QUADRATIC, threads=0):
+             linear_form=LINEAR_QUADRATIC, threads=0, bidirectional=False):
     """Whole layer over dense [B, H, N, d]; heads [0, n_sparse_heads) windowed, rest linear."""
     q, qp = _c(q); k, kp = _c(k); v, vp = _c(v)
     B, H, N, d = q.shape
     out = np.empty((B, H, N, d), np.float64)
-    rc = lib().gformer_oracle_fwd_f64(qp, kp, vp, out.ctypes.data_as(_dp), B, H, N, d,
+    fwd = lib().gformer_oracle_fwd_bidir_f64 if bidirectional else lib().gformer_oracle_fwd_f64
+    rc = fwd(qp, kp, vp, out.ctypes.data_as(_dp), B, H, N, d,
                                       int(window), int(n_sparse_heads), int(phi),
                                       float(softmax_scale), float(eps), int(linear_form),
                                       int(threads))

@@ -19,6 +19,8 @@
  *     line of the algorithm names an undefined S and K'; it is read as Q'^T A,
  *     which is what the prose around it and section II-B describe.
  *   - Section II-B: phi(x) = elu(x) + 1.
+ *   - Bidirectional variant (section IV's encoder / image workloads): window centred on the
+ *     token, linear head over all keys; routines *_bidir_* below.
  *   - Section III-A (design text): positive random features as an alternative phi, applied as a
  *     pre-map of Q and K (gformer_oracle_random_features_f64 below) in front of Algorithm 1
  *     run with the identity map.
@@ -181,6 +183,142 @@ int gformer_oracle_fwd_f64(const double *q, const double *k, const double *v, do
         else
             rc = gformer_oracle_linear_head_quadratic_f64(q + off, k + off, v + off, out + off,
                                                           N, d, phi, eps);
+        if (rc != 0) {
+#pragma omp critical
+            if (status == 0) status = rc;
+        }
+    }
+    return status;
+}
+
+/*
+ * Bidirectional variant (the encoder / image workloads of section IV, where a token sees both
+ * sides).  Section III-B speaks of a fixed-size window "surrounding each token" without saying
+ * how w splits; it is read as the w tokens centred on token i,
+ *     j in [i - floor(w/2), i + (w - 1 - floor(w/2))],  cut at the ends of the sequence
+ * (odd w: symmetric; even w: one more on the left; w = 1: the token itself).
+ */
+int gformer_oracle_windowed_head_bidir_f64(const double *q, const double *k, const double *v,
+                                           double *out, int N, int d, int window, double scale)
+{
+    if (!q || !k || !v || !out || N < 0 || d < 1 || window < 1) return 1;
+    double *s = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+    if (!s) return 2;
+    const long left = window / 2, right = (long)window - 1 - left;
+    for (int i = 0; i < N; ++i) {
+        long lo = (long)i - left, hi = (long)i + right;
+        if (lo < 0) lo = 0;
+        if (hi > N - 1) hi = N - 1;
+        double m = -INFINITY;
+        for (long j = lo; j <= hi; ++j) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += q[(size_t)i * d + c] * k[(size_t)j * d + c];
+            acc *= scale;
+            s[j - lo] = acc;
+            if (acc > m) m = acc;
+        }
+        double l = 0.0;
+        for (long j = lo; j <= hi; ++j) {
+            s[j - lo] = exp(s[j - lo] - m);
+            l += s[j - lo];
+        }
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (long j = lo; j <= hi; ++j) acc += s[j - lo] * v[(size_t)j * d + c];
+            out[(size_t)i * d + c] = acc / l;
+        }
+    }
+    free(s);
+    return 0;
+}
+
+/* Non-causal linear head, plain definition (section II-B without the causal restriction):
+ * out_i = sum_j a_ij v_j / (sum_j a_ij + eps) over ALL j, a_ij = phi(q_i) . phi(k_j). */
+int gformer_oracle_linear_head_bidir_f64(const double *q, const double *k, const double *v,
+                                         double *out, int N, int d, int phi, double eps)
+{
+    if (!q || !k || !v || !out || N < 0 || d < 1) return 1;
+    double *a = (double *)malloc(sizeof(double) * (size_t)(N ? N : 1));
+    if (!a) return 2;
+    for (int i = 0; i < N; ++i) {
+        double den = 0.0;
+        for (int j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c)
+                acc += feature_map(q[(size_t)i * d + c], phi) * feature_map(k[(size_t)j * d + c], phi);
+            a[j] = acc;
+            den += acc;
+        }
+        den += eps;
+        for (int e = 0; e < d; ++e) {
+            double num = 0.0;
+            for (int j = 0; j < N; ++j) num += a[j] * v[(size_t)j * d + e];
+            out[(size_t)i * d + e] = num / den;
+        }
+    }
+    free(a);
+    return 0;
+}
+
+/* The same head in the order section II-B recommends: S = phi(K)^T V and z = phi(K)^T 1 first,
+ * then out_i = phi(q_i)^T S / (phi(q_i) . z + eps).  Written separately; tested against the sum. */
+int gformer_oracle_linear_head_bidir_state_f64(const double *q, const double *k, const double *v,
+                                               double *out, int N, int d, int phi, double eps)
+{
+    if (!q || !k || !v || !out || N < 0 || d < 1) return 1;
+    double *S = (double *)calloc((size_t)d * d, sizeof(double));
+    double *z = (double *)calloc((size_t)d, sizeof(double));
+    if (!S || !z) { free(S); free(z); return 2; }
+    for (int j = 0; j < N; ++j)
+        for (int c = 0; c < d; ++c) {
+            const double f = feature_map(k[(size_t)j * d + c], phi);
+            z[c] += f;
+            for (int e = 0; e < d; ++e) S[(size_t)c * d + e] += f * v[(size_t)j * d + e];
+        }
+    for (int i = 0; i < N; ++i) {
+        double den = eps;
+        for (int c = 0; c < d; ++c) den += feature_map(q[(size_t)i * d + c], phi) * z[c];
+        for (int e = 0; e < d; ++e) {
+            double num = 0.0;
+            for (int c = 0; c < d; ++c) num += feature_map(q[(size_t)i * d + c], phi) * S[(size_t)c * d + e];
+            out[(size_t)i * d + e] = num / den;
+        }
+    }
+    free(S); free(z);
+    return 0;
+}
+
+/* Whole bidirectional layer: same head split as gformer_oracle_fwd_f64.
+ * linear_form: 0 = explicit sum over all keys, 1 = state first. */
+int gformer_oracle_fwd_bidir_f64(const double *q, const double *k, const double *v, double *out,
+                                 int B, int H, int N, int d, int window, int n_sparse_heads,
+                                 int phi, double softmax_scale, double eps, int linear_form,
+                                 int threads)
+{
+    if (!q || !k || !v || !out) return 1;
+    if (B < 0 || H < 0 || N < 0 || d < 1 || window < 1) return 1;
+    if (n_sparse_heads < 0 || n_sparse_heads > H) return 1;
+    int status = 0;
+    long total = (long)B * H;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < total; ++bh) {
+        int h = (int)(bh % H);
+        size_t off = (size_t)bh * N * d;
+        int rc;
+        if (h < n_sparse_heads)
+            rc = gformer_oracle_windowed_head_bidir_f64(q + off, k + off, v + off, out + off, N, d,
+                                                        window, softmax_scale);
+        else if (linear_form == 1)
+            rc = gformer_oracle_linear_head_bidir_state_f64(q + off, k + off, v + off, out + off,
+                                                            N, d, phi, eps);
+        else
+            rc = gformer_oracle_linear_head_bidir_f64(q + off, k + off, v + off, out + off, N, d,
+                                                      phi, eps);
         if (rc != 0) {
 #pragma omp critical
             if (status == 0) status = rc;

@@ -526,3 +526,101 @@ def test_random_features_feed_algorithm_1_as_kernel_weights():
     a = np.tril(fq @ fk.T)
     assert max_abs(got, (a @ v) / a.sum(1, keepdims=True)) < 1e-12
     assert (fq > 0).all() and (fk > 0).all()
+
+
+# ---------------------------------------------------------------------------------------
+# bidirectional variant: window centred on the token, linear head over all keys
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("w", [1, 2, 3, 4, 5, 9])
+def test_bidirectional_window_example_exact(w):
+    g, b = load_golden("window_4token.json"), load_golden("bidirectional_examples.json")
+    q, k, v = (parse_matrix(g[n]) for n in "qkv")
+    got = co.windowed_head(q, k, v, w, bidirectional=True)
+    assert max_abs(got, parse_matrix(b["window_expected"][str(w)])) < 1e-14
+    if w <= 2:   # nothing to the right of the token: the causal head gives the same rows
+        assert max_abs(got, co.windowed_head(q, k, v, w)) < 1e-15
+
+
+def test_bidirectional_window_golden_rejects_wrong_splits():
+    b = load_golden("bidirectional_examples.json")
+    exp4 = parse_matrix(b["window_expected"]["4"])[0]
+    exp3 = parse_matrix(b["window_expected"]["3"])[0]
+    assert max_abs(parse_matrix([b["window_must_reject"]["right_heavy_w4_row0"]])[0], exp4) > 0.1
+    assert max_abs(parse_matrix([b["window_must_reject"]["causal_w3_row0"]])[0], exp3) > 0.1
+
+
+@pytest.mark.parametrize("form", [co.LINEAR_QUADRATIC, co.LINEAR_RECURRENT])
+def test_bidirectional_linear_example_exact(form):
+    b = load_golden("bidirectional_examples.json")["linear"]
+    q, k, v = (parse_matrix(b[n]) for n in "qkv")
+    got = co.linear_head(q, k, v, phi=co.PHI_IDENTITY, form=form, bidirectional=True)
+    assert max_abs(got, parse_matrix(b["expected"])) < 1e-15
+    # the causal head differs already in row 0
+    assert max_abs(co.linear_head(q, k, v, phi=co.PHI_IDENTITY)[0], parse_matrix([b["causal_expected_row0"]])[0]) < 1e-15
+    d1 = load_golden("linear_d1.json")
+    q1, k1, v1 = (parse_matrix(d1[n]) for n in "qkv")
+    want = parse_matrix(load_golden("bidirectional_examples.json")["linear_d1_expected"])
+    assert max_abs(co.linear_head(q1, k1, v1, form=form, bidirectional=True), want) < 1e-14
+
+
+@pytest.mark.parametrize("N,d,w", [(37, 8, 5), (50, 16, 12), (23, 4, 1), (40, 8, 200)])
+def test_bidirectional_window_matches_library_attention_with_band_mask(N, d, w):
+    rng = np.random.default_rng(500 + N + w)
+    q, k, v = (rng.standard_normal((N, d)) for _ in range(3))
+    i, j = np.arange(N)[:, None], np.arange(N)[None, :]
+    left = w // 2
+    band = (j >= i - left) & (j <= i + (w - 1 - left))
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None], torch.from_numpy(k)[None], torch.from_numpy(v)[None],
+        attn_mask=torch.from_numpy(band)[None], scale=0.7)[0].numpy()
+    assert max_abs(co.windowed_head(q, k, v, w, scale=0.7, bidirectional=True), ref) < 1e-12
+    if w >= 2 * N:   # the window covers everything: plain softmax attention, no mask at all
+        full = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(q)[None], torch.from_numpy(k)[None], torch.from_numpy(v)[None], scale=0.7)[0].numpy()
+        assert max_abs(ref, full) < 1e-12
+
+
+def test_bidirectional_symmetries_and_links_to_the_causal_heads():
+    rng = np.random.default_rng(601)
+    N, d = 29, 6
+    q, k, v = (rng.standard_normal((N, d)) for _ in range(3))
+    lin = co.linear_head(q, k, v, bidirectional=True)
+    # the order of the (key, value) pairs does not matter to a head that sees them all
+    perm = rng.permutation(N)
+    assert max_abs(co.linear_head(q, k[perm], v[perm], bidirectional=True), lin) < 1e-12
+    # the last token of the causal head already sees every key
+    assert max_abs(lin[-1], co.linear_head(q, k, v)[-1]) < 1e-12
+    assert max_abs(co.linear_head(q, k, v, form=co.LINEAR_RECURRENT, bidirectional=True), lin) < 1e-12
+    # odd window: reversing the sequence reverses the output
+    for w in (1, 5, 11):
+        a = co.windowed_head(q, k, v, w, bidirectional=True)
+        b = co.windowed_head(q[::-1], k[::-1], v[::-1], w, bidirectional=True)[::-1]
+        assert max_abs(a, b) < 1e-12
+    # even window: one more key on the left than on the right
+    v_ones = np.zeros((N, d)); v_ones[:, 0] = np.arange(N)
+    k0 = np.zeros((N, d))       # uniform weights: output = mean index over the window
+    mid = co.windowed_head(q, k0, v_ones, 4, bidirectional=True)[10, 0]
+    assert abs(mid - (8 + 9 + 10 + 11) / 4) < 1e-12
+    # layer driver: head split and both linear forms
+    Q, K, V = (rng.standard_normal((2, 3, 17, 4)) for _ in range(3))
+    out = co.attn_fwd(Q, K, V, 6, 1, bidirectional=True)
+    assert max_abs(out[1, 0], co.windowed_head(Q[1, 0], K[1, 0], V[1, 0], 6, bidirectional=True)) < 1e-15
+    assert max_abs(out[0, 2], co.linear_head(Q[0, 2], K[0, 2], V[0, 2], bidirectional=True)) < 1e-15
+    out2 = co.attn_fwd(Q, K, V, 6, 1, bidirectional=True, linear_form=co.LINEAR_RECURRENT)
+    assert max_abs(out, out2) < 1e-12
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_bidirectional_linear_against_exact_rationals(seed):
+    rng = np.random.default_rng(700 + seed)
+    N, d = 6, 2
+    qi, ki, vi = (rng.integers(1, 6, (N, d)) for _ in range(3))
+    want = []
+    for i in range(N):
+        a = [sum(Fraction(int(qi[i, c])) * int(ki[j, c]) for c in range(d)) for j in range(N)]
+        den = sum(a)
+        want.append([float(sum(a[j] * int(vi[j, e]) for j in range(N)) / den) for e in range(d)])
+    got = co.linear_head(qi.astype(float), ki.astype(float), vi.astype(float), phi=co.PHI_IDENTITY,
+                         bidirectional=True)
+    assert max_abs(got, np.array(want)) < 1e-14
