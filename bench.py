@@ -239,6 +239,21 @@ def main() -> int:
                 "premap_gbs": round(pre_bytes / t_pre / 1e9, 1),
                 "premap_frac_hbm_peak": round(pre_bytes / t_pre / 1e9 / HBM_PEAK_GBS, 4),
                 "note": "two pre-map launches (Q, K of the linear heads) + the layer with the identity map"}
+        # Bidirectional variant (the encoder / image workloads of section IV): window centred on
+        # the token, linear heads over all keys.
+        params_bi = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=H0, bidirectional=1,
+                                   segment_len=args.segment_len)
+        need = gb.gformer_attn_workspace_bytes(wl.B, wl.H, wl.N, wl.d, wl.window, params_bi)
+        ws_bi = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        def layer_bi():
+            st_ = gb.gformer_attn_fwd_raw(tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), out.data_ptr(),
+                                          wl.B, wl.H, wl.N, wl.d, wl.window, params_bi,
+                                          ws_bi.data_ptr(), ws_bi.numel(), stream)
+            if st_ != gb.GF_OK:
+                raise gb.GformerError(st_, gb.gformer_status_string(st_))
+        s_bi = time_steps(layer_bi, max(5, args.steps // 2), 3)
+        modes["bidirectional"] = {"ms": round(s_bi * 1e3, 4), "tokens_per_s": round(wl.B * wl.N / s_bi, 1),
+                                  "pct_hbm_peak": round(100 * nbytes / s_bi / 1e9 / HBM_PEAK_GBS, 2)}
         result["modes"] = modes
 
     # ---- CPU baseline: the fp64 oracle on batch element 0 (all heads), host cores ---------

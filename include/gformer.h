@@ -88,7 +88,12 @@ typedef struct gformer_params {
   int32_t overlap;        /* 0: everything is enqueued on `hip_stream` one after another.    */
                           /* 1: the windowed heads run on a library-owned side stream that   */
                           /* forks from and joins `hip_stream`, next to the state pass.      */
-  int32_t reserved0;
+  int32_t bidirectional;  /* 0: causal (sections III-B, III-C).  1: the encoder / image form of  */
+                          /* section IV: windowed heads see the w tokens centred on the token */
+                          /* (w/2 to the left, w-1-w/2 to the right, cut at the ends; the     */
+                          /* paper does not say how w splits), linear heads see every key:    */
+                          /* out_i = phi(q_i)^T (sum_j phi(k_j) v_j^T) / (phi(q_i).sum_j      */
+                          /* phi(k_j) + eps), section II-B.                                   */
   float softmax_scale;    /* multiplies q.k on windowed heads; 1.0 when Q is pre-scaled      */
   float eps;              /* added to the linear denominator; 0 follows Algorithm 1          */
   int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3]; /* (b, h, n) element strides   */
@@ -116,7 +121,7 @@ typedef struct gformer_plan {
 } gformer_plan;
 
 /* Fills `p` with defaults: struct_size, dtype = GF_BF16, phi = GF_PHI_ELU1, H0 = 0, chunk,
- * segment_len, impl, launch_mask = 0, overlap = 0, softmax_scale = 1, eps = 0, dense
+ * segment_len, impl, launch_mask = 0, overlap = 0, bidirectional = 0, softmax_scale = 1, eps = 0, dense
  * strides. */
 void gformer_params_init(gformer_params* p);
 

@@ -30,7 +30,7 @@ class GformerParams(ctypes.Structure):
                 ("phi", ctypes.c_int32), ("n_sparse_heads", ctypes.c_int32),
                 ("chunk", ctypes.c_int32), ("segment_len", ctypes.c_int32),
                 ("impl", ctypes.c_int32), ("launch_mask", ctypes.c_int32),
-                ("overlap", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+                ("overlap", ctypes.c_int32), ("bidirectional", ctypes.c_int32),
                 ("softmax_scale", ctypes.c_float), ("eps", ctypes.c_float),
                 ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
                 ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3)]
@@ -104,12 +104,13 @@ def gformer_params_init() -> GformerParams:
 
 
 def make_params(dtype=GF_BF16, n_sparse_heads=0, phi=GF_PHI_ELU1, chunk=0, segment_len=0,
-                impl=GF_IMPL_AUTO, launch_mask=0, overlap=0, softmax_scale=1.0, eps=0.0,
-                q_stride=None, k_stride=None, v_stride=None, o_stride=None) -> GformerParams:
+                impl=GF_IMPL_AUTO, launch_mask=0, overlap=0, bidirectional=0, softmax_scale=1.0,
+                eps=0.0, q_stride=None, k_stride=None, v_stride=None, o_stride=None) -> GformerParams:
     p = gformer_params_init()
     p.dtype, p.n_sparse_heads, p.phi = int(dtype), int(n_sparse_heads), int(phi)
     p.chunk, p.segment_len, p.impl, p.launch_mask = int(chunk), int(segment_len), int(impl), int(launch_mask)
     p.overlap = int(overlap)
+    p.bidirectional = int(bidirectional)
     p.softmax_scale, p.eps = float(softmax_scale), float(eps)
     for name, val in (("q_stride", q_stride), ("k_stride", k_stride),
                       ("v_stride", v_stride), ("o_stride", o_stride)):
@@ -157,7 +158,8 @@ def _strides3(t):
 
 def gformer_attn_fwd(q, k, v, out, window: int, n_sparse_heads: int, *, phi=GF_PHI_ELU1,
                      chunk=0, segment_len=0, impl=GF_IMPL_AUTO, launch_mask=0, overlap=0,
-                     softmax_scale=1.0, eps=0.0, workspace=None, stream: Optional[int] = None):
+                     bidirectional=0, softmax_scale=1.0, eps=0.0, workspace=None,
+                     stream: Optional[int] = None):
     """GFormer attention forward on torch device tensors shaped [B, H, N, d] (any strides with
     a contiguous last dimension, e.g. a permuted [B, N, H, d] buffer).
 
@@ -182,7 +184,8 @@ def gformer_attn_fwd(q, k, v, out, window: int, n_sparse_heads: int, *, phi=GF_P
     B, H, N, d = (int(x) for x in q.shape)
     params = make_params(dtype=dtype, n_sparse_heads=n_sparse_heads, phi=phi, chunk=chunk,
                          segment_len=segment_len, impl=impl, launch_mask=launch_mask,
-                         overlap=overlap, softmax_scale=softmax_scale, eps=eps,
+                         overlap=overlap, bidirectional=bidirectional,
+                         softmax_scale=softmax_scale, eps=eps,
                          q_stride=_strides3(q), k_stride=_strides3(k),
                          v_stride=_strides3(v), o_stride=_strides3(out))
     need = gformer_attn_workspace_bytes(B, H, N, d, window, params)

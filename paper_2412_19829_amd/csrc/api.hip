@@ -89,6 +89,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   if (p->chunk < 0 || p->segment_len < 0) return GF_ERR_INVALID_ARG;
   if (p->launch_mask < 0 || p->launch_mask > 7) return GF_ERR_INVALID_ARG;
   if (p->overlap != 0 && p->overlap != 1) return GF_ERR_INVALID_ARG;
+  if (p->bidirectional != 0 && p->bidirectional != 1) return GF_ERR_INVALID_ARG;
   if (!(p->softmax_scale == p->softmax_scale) || !(p->eps >= 0.f)) return GF_ERR_INVALID_ARG;
   if (B > 65535 || H > 65535) return GF_ERR_UNSUPPORTED;  // grid y/z limits
   gf_status st;
@@ -123,8 +124,24 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   pl.chunk = p->chunk ? p->chunk : 64;
   const long cph = N > 0 ? (N + pl.chunk - 1) / pl.chunk : 0;  // real chunks per head
   long piece = 0, vcph = cph, pieces = 0, mid = 0, sub = 1;
-  if (p->segment_len != 0) {
-    if (p->segment_len % pl.chunk != 0) return GF_ERR_INVALID_ARG;
+  if (p->segment_len != 0 && p->segment_len % pl.chunk != 0) return GF_ERR_INVALID_ARG;
+  if (p->bidirectional && heads_lin > 0 && cph > 0) {
+    // Bidirectional linear heads: every piece needs the state of its whole head, so pieces never
+    // straddle heads (uniform segments per head) and every one of them is summed by the state
+    // pass.  Without a request: as many pieces per head as keep every compute unit at one piece.
+    if (p->segment_len != 0) {
+      piece = p->segment_len / pl.chunk;
+    } else {
+      long per = kComputeUnits / heads_lin;
+      if (per < 1) per = 1;
+      if (per > cph) per = cph;
+      piece = (cph + per - 1) / per;
+    }
+    const long per_head = (cph + piece - 1) / piece;
+    vcph = per_head * piece;
+    pieces = heads_lin * per_head;
+    mid = pieces;
+  } else if (p->segment_len != 0) {
     piece = p->segment_len / pl.chunk;
     const long per_head = cph > 0 ? (cph + piece - 1) / piece : 0;
     vcph = per_head * piece;
@@ -223,6 +240,9 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
   a.osb = r.os[0]; a.osh = r.os[1]; a.osn = r.os[2];
   a.B = B; a.H = H; a.N = N; a.d = d;
   a.window = window;
+  a.causal = p->bidirectional ? 0 : 1;
+  a.wleft = p->bidirectional ? window / 2 : window - 1;
+  a.wright = p->bidirectional ? window - 1 - window / 2 : 0;
   a.H0 = p->n_sparse_heads;
   a.phi = p->phi;
   a.scale = p->softmax_scale;

@@ -19,6 +19,8 @@ struct AttnArgs {
   int64_t osb, osh, osn;
   int B, H, N, d;
   int window;
+  int causal;        // 1: causal (window ends at the token, linear prefix); 0: bidirectional
+  int wleft, wright; // windowed heads: token i sees keys i - wleft .. i + wright (cut at the ends)
   int H0;            // heads [0,H0) windowed, [H0,H) linear
   int phi;           // gf_phi
   float scale;       // softmax scale (windowed heads)

@@ -270,16 +270,27 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs
   StateSmem<D>& sm = *reinterpret_cast<StateSmem<D>*>(smem_raw);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
-  const int q = blockIdx.x + 1;
   const int ls = a.piece_chunks / a.state_sub;
-  const int e = q * ls;                      // the boundary, as a global chunk index
-  if (e % a.vcph == 0) return;               // on a head boundary: nothing is carried
-  const int head = e / a.vcph;
-  const int next_main = (q + a.state_sub - 1) / a.state_sub * a.piece_chunks;
-  if (next_main >= (head + 1) * a.vcph || next_main >= a.n_pieces * a.piece_chunks)
-    return;                                  // no piece starts later in this head: nobody reads it
-  const int lc1 = e % a.vcph;                // chunks [lc0, lc1) of `head`
-  const int lc0 = max(lc1 - ls, 0);
+  int q, head, lc0, lc1;                     // workspace slot; chunks [lc0, lc1) of `head`
+  if (a.causal) {
+    q = blockIdx.x + 1;
+    const int e = q * ls;                    // the boundary, as a global chunk index
+    if (e % a.vcph == 0) return;             // on a head boundary: nothing is carried
+    head = e / a.vcph;
+    const int next_main = (q + a.state_sub - 1) / a.state_sub * a.piece_chunks;
+    if (next_main >= (head + 1) * a.vcph || next_main >= a.n_pieces * a.piece_chunks)
+      return;                                // no piece starts later in this head: nobody reads it
+    lc1 = e % a.vcph;
+    lc0 = max(lc1 - ls, 0);
+  } else {
+    // bidirectional: every sub-piece is summed (pieces never straddle heads in this mode);
+    // slot q holds the sum over sub-piece q itself
+    q = blockIdx.x;
+    head = q * ls / a.vcph;
+    lc0 = q * ls % a.vcph;
+    lc1 = min(lc0 + ls, a.cph);
+    if (lc0 >= lc1) return;                  // virtual padding only (the planner avoids it)
+  }
   const HeadPtrs<D> hp = head_ptrs<D>(a, head);
   const int N = a.N;
   const int nchunks = lc1 - lc0;
@@ -364,11 +375,19 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs
 //     Stops after the head's last piece boundary (later slots were not written and are not read).
 __global__ __launch_bounds__(256) void linear_prefix_kernel(float* ws, int n_heads, int vcph,
                                                              int sub_chunks, int n_sub, int state_sub,
-                                                             int state_floats) {
+                                                             int state_floats, int causal) {
   const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int head = blockIdx.y;
   if (x >= state_floats || head >= n_heads) return;
   const int64_t g_lo = (int64_t)head * vcph, g_hi = g_lo + vcph;
+  if (!causal) {
+    // bidirectional: the head's first slot receives the sum of all its slots
+    const int64_t j0 = g_lo / sub_chunks, j1 = g_hi / sub_chunks;
+    float tot = 0.f;
+    for (int64_t j = j0; j < j1; ++j) tot += ws[j * state_floats + x];
+    ws[j0 * state_floats + x] = tot;
+    return;
+  }
   const int64_t total = (int64_t)n_sub * sub_chunks;
   float run = 0.f;
   for (int64_t j = g_lo / sub_chunks + 1; j < n_sub && j * sub_chunks < g_hi; ++j) {
@@ -389,7 +408,10 @@ __global__ __launch_bounds__(256) void linear_prefix_kernel(float* ws, int n_hea
 //     of chunk n on every SIMD.  Two workgroup barriers per chunk: (a) masked products
 //     visible, (b) buffers change hands.
 // -----------------------------------------------------------------------------------------
-template <int D, bool ELU1>
+//     CAUSAL = false is the bidirectional read-out: the state is the sum over the whole head and
+//     never moves, K and V are not touched, and per chunk only the state read-out, phi(q).Z and
+//     the normalisation remain (same barriers, same producer/consumer split).
+template <int D, bool ELU1, bool CAUSAL>
 __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_kernel(AttnArgs a) {
   using C = LinCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -413,9 +435,11 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
     int nl = 0, no = 0;  // chunks loaded / written so far
     auto load_q = [&](u32x4 (&qr)[C::PIECES]) { load_chunk<D>(qr, cl.hp.q, cl.t0(), N, qo); };
     auto load_kv = [&](u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES]) {
-      const int t0 = cl.t0();
-      load_chunk<D>(kr, cl.hp.k, t0, N, ko);
-      load_chunk<D>(vr, cl.hp.v, t0, N, vo);
+      if constexpr (CAUSAL) {
+        const int t0 = cl.t0();
+        load_chunk<D>(kr, cl.hp.k, t0, N, ko);
+        load_chunk<D>(vr, cl.hp.v, t0, N, vo);
+      }
       ++nl;
       cl.next(a, nl < nchunks);
     };
@@ -441,21 +465,25 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
     // of barrier (a), where the producers would otherwise wait for the matrix waves
     constexpr int KEARLY = C::PIECES / 2;
     auto map_k_early = [&](u32x4 (&kr)[C::PIECES]) {
+      if constexpr (CAUSAL) {
 #pragma unroll
-      for (int i = 0; i < KEARLY; ++i) kr[i] = map_features<ELU1>(kr[i]);
+        for (int i = 0; i < KEARLY; ++i) kr[i] = map_features<ELU1>(kr[i]);
+      }
     };
     // phi(K) and V of the chunk at `cs` -> buf[n % 2]; rows past the head's end become zeros
     auto stage_kv = [&](const u32x4 (&kr)[C::PIECES], const u32x4 (&vr)[C::PIECES], int n) {
-      const int t0 = cs.t0();
-      ChunkTiles<D>& b = sm.buf[n & 1];
-      const bool full = t0 + CH <= N;  // uniform; only a head's last chunk can be ragged
+      if constexpr (CAUSAL) {
+        const int t0 = cs.t0();
+        ChunkTiles<D>& b = sm.buf[n & 1];
+        const bool full = t0 + CH <= N;  // uniform; only a head's last chunk can be ragged
 #pragma unroll
-      for (int i = 0; i < C::PIECES; ++i) {
-        const int row = st.r0 + i * C::RP;
-        const bool valid = full || t0 + row < N;
-        const u32x4 fk = i < KEARLY ? kr[i] : map_features<ELU1>(kr[i]);
-        *reinterpret_cast<u32x4*>(&b.fk[row * C::KROW + st.col]) = valid ? fk : kZero4;
-        *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = valid ? vr[i] : kZero4;
+        for (int i = 0; i < C::PIECES; ++i) {
+          const int row = st.r0 + i * C::RP;
+          const bool valid = full || t0 + row < N;
+          const u32x4 fk = i < KEARLY ? kr[i] : map_features<ELU1>(kr[i]);
+          *reinterpret_cast<u32x4*>(&b.fk[row * C::KROW + st.col]) = valid ? fk : kZero4;
+          *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = valid ? vr[i] : kZero4;
+        }
       }
       cs.next(a, n + 1 < nchunks);
     };
@@ -562,18 +590,28 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[ct][r] = 0.f;
   float z0 = 0.f;
-  if (lc > 0 && a.ws_states) {
-    // state carried into this piece: the running sum of its head's sub-piece sums up to here
+  if (CAUSAL ? (lc > 0 && a.ws_states) : a.ws_states != nullptr) {
     const int ls = a.piece_chunks / a.state_sub;
-    const int j_last = g0 / ls;
-    const int j_first = uses_prefix_kernel(a) ? j_last : (g0 - lc) / ls + 1;
+    int j_first, j_last;
+    if (CAUSAL) {
+      // state carried into this piece: the running sum of its head's sub-piece sums up to here
+      j_last = g0 / ls;
+      j_first = uses_prefix_kernel(a) ? j_last : (g0 - lc) / ls + 1;
+    } else {
+      // the state of the whole head: all of its sub-piece sums (or their total in its first slot)
+      j_first = (g0 - lc) / ls;
+      j_last = uses_prefix_kernel(a) ? j_first : j_first + a.vcph / ls - 1;
+    }
     for (int j = j_first; j <= j_last; ++j) {
       const float* src = a.ws_states + (int64_t)j * C::STATE;
       state_add<D>(sacc, src, wave, lane);
       z0 += src[D * D + 32 * wave + ln];
     }
   }
-  if (lh == 0) put_z(0, 32 * wave + kperm32(ln), z0);
+  if (lh == 0) {
+    put_z(0, 32 * wave + kperm32(ln), z0);
+    if (!CAUSAL) put_z(1, 32 * wave + kperm32(ln), z0);   // Z never moves: both buffers hold it
+  }
   // the product tile above the diagonal (keys 32.., queries ..31) is never computed: it stays 0
   for (int x = tid; x < 32 * 32 / 8; x += C::NTC)
     *reinterpret_cast<u32x4*>(&sm.pt[(x / 4) * C::PROW + 32 + 8 * (x % 4)]) = kZero4;
@@ -633,10 +671,12 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
       StepOps o;
       const int rep = i / KS, ks = i % KS;
       // k-slot 8*lh + 4*g + j of this step is feature 16*ks + 8*g + 4*lh + j
-      const uint16_t* kr = &b.fk[(32 * tk[rep] + ln) * C::KROW + 16 * ks + 4 * lh];
-      const u32x2 k0 = *reinterpret_cast<const u32x2*>(kr);
-      const u32x2 k1 = *reinterpret_cast<const u32x2*>(kr + 8);
-      o.kt = as_bf16x8(u32x4{k0[0], k0[1], k1[0], k1[1]});
+      if constexpr (CAUSAL) {
+        const uint16_t* kr = &b.fk[(32 * tk[rep] + ln) * C::KROW + 16 * ks + 4 * lh];
+        const u32x2 k0 = *reinterpret_cast<const u32x2*>(kr);
+        const u32x2 k1 = *reinterpret_cast<const u32x2*>(kr + 8);
+        o.kt = as_bf16x8(u32x4{k0[0], k0[1], k1[0], k1[1]});
+      }
       // phi(Q) rows 0..31 and 32..63, features of contraction step ks: the read-out step
       // 2*ct + kb = ks uses both, the product tile the one of its query half
       o.q0 = lds_read16(&b.fq[ln * C::QROW + 16 * ks + 8 * lh]);
@@ -644,9 +684,10 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
       return o;
     };
     constexpr int PD = 3;  // steps between an operand fetch and its use
-    StepOps ops[G1N];
+    constexpr int NSTEP = CAUSAL ? G1N : KS;   // without product tiles only the read-out steps remain
+    StepOps ops[NSTEP];
 #pragma unroll
-    for (int i = 0; i < PD && i < G1N; ++i) ops[i] = fetch(i);
+    for (int i = 0; i < PD && i < NSTEP; ++i) ops[i] = fetch(i);
     __builtin_amdgcn_sched_barrier(0);
     // rows of the previous chunk (at n = 0: zeros over den = 1, never written out), while the
     // first operands are on their way
@@ -660,10 +701,10 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
 #pragma unroll
       for (int r = 0; r < 16; ++r) p[rep][r] = 0.f;
 #pragma unroll
-    for (int i = 0; i < G1N; ++i) {
-      if (i + PD < G1N) ops[i + PD] = fetch(i + PD);
+    for (int i = 0; i < NSTEP; ++i) {
+      if (i + PD < NSTEP) ops[i + PD] = fetch(i + PD);
       const StepOps& cur = ops[i];
-      p[i / KS] = mfma32(cur.kt, tqa[i / KS] ? cur.q1 : cur.q0, p[i / KS]);
+      if constexpr (CAUSAL) p[i / KS] = mfma32(cur.kt, tqa[i / KS] ? cur.q1 : cur.q0, p[i / KS]);
       if (i / KS == 0) {
         // num^T = A^T phiQ^T with A straight from the state registers
         const int ct = i / 2, kb_ = i % 2;
@@ -678,7 +719,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
       __builtin_amdgcn_sched_barrier(0);  // keep the fetches PD steps ahead of their use
     }
 #pragma unroll
-    for (int rep = 0; rep < NTILE; ++rep) {
+    for (int rep = 0; CAUSAL && rep < NTILE; ++rep) {
       // on the diagonal tile key row 8*(r/4) + 4*lh + r%4 must not exceed query column ln
       const int top = (tk[rep] == tqa[rep] ? ln : CH) - 4 * lh;
 #pragma unroll
@@ -717,8 +758,8 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
         o.fz = lds_operand_tr(b.fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
         return o;
       };
-      constexpr int NK = CH / 16, PDB = 2;
-      TokOps tok[NK];
+      constexpr int NK = CAUSAL ? CH / 16 : 0, PDB = 2;   // no token work in the bidirectional read-out
+      TokOps tok[NK > 0 ? NK : 1];
 #pragma unroll
       for (int kk = 0; kk < PDB && kk < NK; ++kk) tok[kk] = fetch_tok(kk);
       __builtin_amdgcn_sched_barrier(0);
@@ -730,7 +771,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
         constexpr int CW = D / PPT;   // features per thread
         float s = 0.f;
 #pragma unroll
-        for (int x = 0; x < KW; x += 8) {  // the never-visible tile holds zeros
+        for (int x = 0; CAUSAL && x < KW; x += 8) {  // the never-visible tile holds zeros
           const u32x4 pv = *reinterpret_cast<const u32x4*>(&sm.pt[qrow * C::PROW + KW * part + x]);
 #pragma unroll
           for (int w = 0; w < 4; ++w) s = dot2_bf16(pv[w], kOnesBf16x2, s);
@@ -763,14 +804,16 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
         for (int ct = 0; ct < C::ET; ++ct) sacc[ct] = mfma32(cur.fa[ct], cur.vt, sacc[ct]);
         __builtin_amdgcn_sched_barrier(0);
       }
-      zs += __shfl_xor(zs, 32, 64);
-      const int zi = 32 * wave + kperm32(ln);
-      if (lh == 0) put_z(zc ^ 1, zi, head_ends ? 0.f : sm.z[zc][zi] + zs);
-      if (head_ends) {
+      if constexpr (CAUSAL) {
+        zs += __shfl_xor(zs, 32, 64);
+        const int zi = 32 * wave + kperm32(ln);
+        if (lh == 0) put_z(zc ^ 1, zi, head_ends ? 0.f : sm.z[zc][zi] + zs);
+        if (head_ends) {
 #pragma unroll
-        for (int ct = 0; ct < C::ET; ++ct)
+          for (int ct = 0; ct < C::ET; ++ct)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[ct][r] = 0.f;
+            for (int r = 0; r < 16; ++r) sacc[ct][r] = 0.f;
+        }
       }
     }
     lds_barrier();  // (b) denominators visible; this chunk's tiles are free again
@@ -788,7 +831,7 @@ template <int D> hipError_t launch_state_t(const AttnArgs& a, hipStream_t s) {
   using C = LinCfg<D>;
   const int heads = a.B * (a.H - a.H0);
   const int smem = (int)sizeof(StateSmem<D>);
-  const dim3 grid(a.n_pieces * a.state_sub - 1), block(C::NT);
+  const dim3 grid(a.n_pieces * a.state_sub - (a.causal ? 1 : 0)), block(C::NT);
   hipError_t e;
   if (a.phi == 0) {
     if ((e = allow_lds(linear_state_kernel<D, true>, smem)) != hipSuccess) return e;
@@ -801,7 +844,7 @@ template <int D> hipError_t launch_state_t(const AttnArgs& a, hipStream_t s) {
   if (uses_prefix_kernel(a)) {
     linear_prefix_kernel<<<dim3((C::STATE + 255) / 256, heads), dim3(256), 0, s>>>(
         a.ws_states, heads, a.vcph, a.piece_chunks / a.state_sub, a.n_pieces * a.state_sub,
-        a.state_sub, C::STATE);
+        a.state_sub, C::STATE, a.causal);
     e = hipGetLastError();
   }
   return e;
@@ -811,21 +854,26 @@ template <int D> hipError_t launch_main_t(const AttnArgs& a, hipStream_t s) {
   using C = LinCfg<D>;
   const int smem = (int)sizeof(LinSmem<D>);
   const dim3 grid(a.n_pieces), block(C::NT);
-  hipError_t e;
-  if (a.phi == 0) {
-    if ((e = allow_lds(linear_main_kernel<D, true>, smem)) != hipSuccess) return e;
-    linear_main_kernel<D, true><<<grid, block, smem, s>>>(a);
+  hipError_t e = hipSuccess;
+  auto launch = [&](auto kern) {
+    e = allow_lds(kern, smem);
+    if (e == hipSuccess) kern<<<grid, block, smem, s>>>(a);
+  };
+  if (a.causal) {
+    if (a.phi == 0) launch(linear_main_kernel<D, true, true>);
+    else launch(linear_main_kernel<D, false, true>);
   } else {
-    if ((e = allow_lds(linear_main_kernel<D, false>, smem)) != hipSuccess) return e;
-    linear_main_kernel<D, false><<<grid, block, smem, s>>>(a);
+    if (a.phi == 0) launch(linear_main_kernel<D, true, false>);
+    else launch(linear_main_kernel<D, false, false>);
   }
-  return hipGetLastError();
+  return e != hipSuccess ? e : hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_linear_state_mfma(const AttnArgs& a, hipStream_t s) {
-  if (a.H - a.H0 <= 0 || a.N <= 0 || a.B <= 0 || a.n_pieces <= 1 || !a.ws_states) return hipSuccess;
+  if (a.H - a.H0 <= 0 || a.N <= 0 || a.B <= 0 || !a.ws_states) return hipSuccess;
+  if (a.causal && a.n_pieces <= 1) return hipSuccess;
   return a.d == 64 ? launch_state_t<64>(a, s) : launch_state_t<128>(a, s);
 }
 

@@ -28,7 +28,7 @@ __device__ __forceinline__ float feature_map(float x, int phi) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Windowed causal softmax head (section III-B, Eq. 1).  One wave owns one query at a time;
+// Windowed softmax head (section III-B, Eq. 1), causal or centred.  One wave owns one query at a time;
 // lanes own keys for the scores and value columns for the weighted sum.
 // grid = (ceil(N / kScalarWindowRows), H0, B), block = 256.
 // ---------------------------------------------------------------------------------------
@@ -50,19 +50,20 @@ __global__ __launch_bounds__(kScalarThreads) void windowed_scalar_kernel(AttnArg
     float qreg[CPL];
 #pragma unroll
     for (int cc = 0; cc < CPL; ++cc) qreg[cc] = Storage<T>::load(a.q.base, qoff + i * a.q.sn + cc * 64 + lane);
-    const int lo = max(0, i - a.window + 1);
+    // visible keys lo..hi: the w tokens ending at i (causal) or centred on i (bidirectional)
+    const int lo = max(0, i - a.wleft), hi = min(a.N - 1, i + a.wright);
     float m = -INFINITY, l = 0.f;
     float acc[CPL];
 #pragma unroll
     for (int cc = 0; cc < CPL; ++cc) acc[cc] = 0.f;
 
-    for (int j0 = lo; j0 <= i; j0 += 64) {
+    for (int j0 = lo; j0 <= hi; j0 += 64) {
       const int j = j0 + lane;
-      const bool valid = j <= i;
+      const bool valid = j <= hi;
       float s = 0.f;
       {
-        // lanes past the diagonal read row i again (in bounds) and are masked below
-        const int64_t kr = koff + (int64_t)min(j, i) * a.k.sn;
+        // lanes past the last visible key read that key's row again (in bounds), masked below
+        const int64_t kr = koff + (int64_t)min(j, hi) * a.k.sn;
 #pragma unroll
         for (int cc = 0; cc < CPL; ++cc) {
 #pragma unroll
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(kScalarThreads) void windowed_scalar_kernel(AttnArg
       l = l * alpha + wave_sum(p);
 #pragma unroll
       for (int cc = 0; cc < CPL; ++cc) acc[cc] *= alpha;
-      const int cnt = min(64, i - j0 + 1);
+      const int cnt = min(64, hi - j0 + 1);
       for (int jj = 0; jj < cnt; ++jj) {
         const float pj = __shfl(p, jj, 64);
         const int64_t vr = voff + (int64_t)(j0 + jj) * a.v.sn;
@@ -199,6 +200,94 @@ __global__ __launch_bounds__(kScalarThreads) void linear_scalar_kernel(AttnArgs 
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Non-causal linear attention head (section II-B): S = phi(K)^T V and z = phi(K)^T 1 over the
+// whole sequence first, then out_i = phi(q_i)^T S / (phi(q_i).z + eps).  Same LDS layout and
+// launch geometry as the causal kernel; two passes over the head.
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kScalarThreads) void linear_scalar_bidir_kernel(AttnArgs a) {
+  constexpr int CH = kScalarChunk;
+  constexpr int G = kScalarThreads / D;
+  constexpr int NUM_T = CH / G;
+  constexpr int UPD_C = D / G;
+  extern __shared__ float smem[];
+  float* fq = smem;                 // [CH][D]
+  float* fk = fq + CH * D;          // [CH][D]
+  float* vv = fk + CH * D;          // [CH][D]
+  float* S = vv + CH * D;           // [D][D]
+  float* z = S + D * D;             // [D]
+  float* den = z + D;               // [CH]
+
+  const int tid = threadIdx.x;
+  const int h = a.H0 + blockIdx.x, b = blockIdx.y;
+  const int64_t qoff = b * a.q.sb + h * a.q.sh;
+  const int64_t koff = b * a.k.sb + h * a.k.sh;
+  const int64_t voff = b * a.v.sb + h * a.v.sh;
+  const int64_t ooff = b * a.osb + h * a.osh;
+  const int e = tid % D, g = tid / D;
+
+  for (int x = tid; x < D * D; x += kScalarThreads) S[x] = 0.f;
+  if (tid < D) z[tid] = 0.f;
+  // pass 1: the state of the whole head
+  for (int t0 = 0; t0 < a.N; t0 += CH) {
+    __syncthreads();
+    for (int x = tid; x < CH * D; x += kScalarThreads) {
+      const int n = t0 + x / D, c = x % D;
+      float kv = 0.f, v_ = 0.f;
+      if (n < a.N) {
+        kv = feature_map(Storage<T>::load(a.k.base, koff + (int64_t)n * a.k.sn + c), a.phi);
+        v_ = Storage<T>::load(a.v.base, voff + (int64_t)n * a.v.sn + c);
+      }
+      fk[x] = kv; vv[x] = v_;   // rows past N hold zeros and contribute nothing
+    }
+    __syncthreads();
+    float vcol[CH];
+#pragma unroll
+    for (int t = 0; t < CH; ++t) vcol[t] = vv[t * D + e];
+    for (int i = 0; i < UPD_C; ++i) {
+      const int c = g + G * i;
+      float s = S[c * D + e];
+#pragma unroll
+      for (int t = 0; t < CH; ++t) s = fmaf(fk[t * D + c], vcol[t], s);
+      S[c * D + e] = s;
+    }
+    if (tid < D) {
+      float s = z[tid];
+      for (int t = 0; t < CH; ++t) s += fk[t * D + tid];
+      z[tid] = s;
+    }
+  }
+  // pass 2: read-out of every token against the same state
+  for (int t0 = 0; t0 < a.N; t0 += CH) {
+    __syncthreads();  // state complete (first round) / previous chunk consumed
+    for (int x = tid; x < CH * D; x += kScalarThreads) {
+      const int n = t0 + x / D, c = x % D;
+      fq[x] = n < a.N ? feature_map(Storage<T>::load(a.q.base, qoff + (int64_t)n * a.q.sn + c), a.phi) : 0.f;
+    }
+    __syncthreads();
+    if (tid < CH) {
+      float zz = 0.f;
+      for (int c = 0; c < D; ++c) zz = fmaf(fq[tid * D + c], z[c], zz);
+      den[tid] = zz + a.eps;
+    }
+    float num[NUM_T];
+#pragma unroll
+    for (int i = 0; i < NUM_T; ++i) num[i] = 0.f;
+    for (int c = 0; c < D; ++c) {
+      const float sce = S[c * D + e];
+#pragma unroll
+      for (int i = 0; i < NUM_T; ++i) num[i] = fmaf(fq[(g + G * i) * D + c], sce, num[i]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NUM_T; ++i) {
+      const int n = t0 + g + G * i;
+      if (n < a.N) Storage<T>::store(a.out, ooff + (int64_t)n * a.osn + e, num[i] / den[g + G * i]);
+    }
+  }
+}
+
 template <int D> size_t linear_scalar_smem() {
   constexpr int CH = kScalarChunk;
   return sizeof(float) * (size_t)(3 * CH * D + D * D + D + CH * (CH + 1) + CH);
@@ -223,7 +312,7 @@ hipError_t launch_windowed_scalar(const AttnArgs& a, bool bf16, hipStream_t s) {
 template <typename T, int D>
 static hipError_t launch_linear_scalar_t(const AttnArgs& a, hipStream_t s) {
   const size_t smem = linear_scalar_smem<D>();
-  auto kern = linear_scalar_kernel<T, D>;
+  auto kern = a.causal ? linear_scalar_kernel<T, D> : linear_scalar_bidir_kernel<T, D>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;

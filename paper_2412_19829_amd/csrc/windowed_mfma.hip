@@ -1,4 +1,5 @@
-// Windowed causal softmax attention heads on bf16 matrix cores (section III-B, Eq. 1).
+// Windowed softmax attention heads on bf16 matrix cores (section III-B, Eq. 1): the causal window
+// ending at the token, or (bidirectional variant) the window centred on it.
 //
 // One workgroup (4 waves) owns 128 consecutive queries of one (batch, head); each wave owns 32
 // of them.  The band of keys those queries can see is walked in tiles of 64 keys; tiles outside
@@ -90,8 +91,11 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   float m_run = -INFINITY;  // running max of the scaled base-2 scores of this lane's query
   float l_run = 0.f;        // running sum over the keys this lane holds (half of each tile)
 
-  const int kfirst = max(0, i0 - w + 1) / BC;
-  const int klast = min(N - 1, i0 + BR - 1) / BC;
+  // token i sees keys i - wl .. i + wr (cut at the ends): wl = w - 1, wr = 0 for the causal window
+  // ending at the token, wl = w / 2, wr = w - 1 - wl for the window centred on it
+  const int wl = a.wleft, wr = a.wright;
+  const int kfirst = max(0, i0 - wl) / BC;
+  const int klast = min(N - 1, i0 + BR - 1 + wr) / BC;
   // base-2 logits = raw score * sc; a zero scale is nudged so that masked (infinite) scores
   // still map to weight 0 instead of NaN
   const float sc = (a.scale == 0.f ? 1e-30f : a.scale) * kLog2e;
@@ -142,9 +146,11 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
     if (t < klast) store_tile(sm.buf[(t - kfirst + 1) & 1]);
     if (t + 1 < klast) load_tile(t + 2);
     const int t0 = t * BC;
-    // keys visible to query i: i - w < j <= i; a tile with none for this wave's queries is skipped
-    if (!(t0 > q0 + WQ - 1 || t0 + BC - 1 <= q0 - w)) {
-      const bool need_mask = !(t0 + BC - 1 <= q0 && t0 > q0 + WQ - 1 - w);
+    // keys visible to query i: i - wl <= j <= min(i + wr, N - 1); a tile with none for this
+    // wave's queries is skipped, a tile every one of them sees in full needs no mask
+    if (!(t0 > q0 + WQ - 1 + wr || t0 + BC - 1 < q0 - wl)) {
+      const bool need_mask =
+          !(t0 + BC - 1 <= q0 + wr && t0 >= q0 + WQ - 1 - wl && t0 + BC <= N);
 
       // S^T = K Q^T for the two 32-key halves of the tile
       f32x16 s[2];
@@ -166,14 +172,17 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
       constexpr float worst = NEG ? INFINITY : -INFINITY;
       if (need_mask) {
         // register (kt, r) of this lane is key t0 + c + 4*lh, c = 32*kt + 8*(r/4) + r%4;
-        // visible iff 0 <= (qi - key) < w
-        const int rel = q0 + ln - t0 - 4 * lh;
+        // with hi = min(qi + wr, N - 1) the key is visible iff 0 <= hi - key <= hi - (qi - wl)
+        const int qi = q0 + ln;
+        const int hi = min(qi + wr, N - 1);
+        const int rel = hi - t0 - 4 * lh;
+        const int wv = hi - qi + wl + 1;   // visible keys of this query (<= 0: none, a row past N)
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int c = 32 * kt + 8 * (r / 4) + (r % 4);
-            s[kt][r] = ((unsigned)(rel - c) >= (unsigned)w) ? worst : s[kt][r];
+            s[kt][r] = ((unsigned)(rel - c) >= (unsigned)max(wv, 0)) ? worst : s[kt][r];
           }
       }
       float ext = worst;

@@ -104,6 +104,7 @@ def test_plan_modes_and_overrides():
     ((1, 2, 16, 64, 4), {"eps": float("nan")}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"launch_mask": 8}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"overlap": 2}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"bidirectional": 2}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"q_stride": (1024, 512, 60)}, gb.GF_ERR_INVALID_ARG),   # not 16-byte rows
     ((1, 2, 16, 64, 4), {"o_stride": (2048, 1024, 32)}, gb.GF_ERR_INVALID_ARG),  # rows overlap
     ((1, 2, 16, 64, 4), {"k_stride": (1 << 26, 1 << 25, (1 << 20) + 8)}, gb.GF_ERR_UNSUPPORTED),  # row stride limit
@@ -204,3 +205,18 @@ def test_feature_pointer_checks_and_empty_problems():
         import torch
         t = torch.zeros(1, 2, 16, 64)
         gb.gformer_random_features(t, torch.zeros(64, 64), t, 0, 2)   # host tensors: no CPU path
+
+
+def test_plan_bidirectional_pieces_never_straddle_heads():
+    """Every piece needs the state of its whole head: uniform segments per head, every piece
+    summed by the state pass, one piece per compute unit at most."""
+    st, pl = _plan(4, 32, 8192, 128, 256, n_sparse_heads=6, bidirectional=1)
+    assert st == gb.GF_OK
+    # 104 linear heads, 128 chunks each: two pieces of 64 chunks per head
+    assert pl["segment_len"] == 64 * 64 and pl["n_segments"] == 208 and pl["state_blocks"] == 208
+    assert pl["workspace_bytes"] == 208 * (128 * 128 + 128) * 4
+    st, pl = _plan(1, 3, 1100, 64, 40, n_sparse_heads=1, bidirectional=1, segment_len=64)
+    assert st == gb.GF_OK and pl["n_segments"] == 2 * 18 and pl["state_blocks"] == 36
+    # one short head: a single piece, still summed first
+    st, pl = _plan(1, 1, 100, 64, 8, n_sparse_heads=0, bidirectional=1)
+    assert st == gb.GF_OK and pl["n_segments"] == 2 and pl["state_blocks"] == 2 and pl["workspace_bytes"] > 0

@@ -244,10 +244,11 @@ def _full_size(name, H0, **kw):
     for (b, h) in gi.sample_heads(wl, H0):
         got = to_host(out[b, h])
         q, k, v = gi.make_head(wl, b, h)
+        bidir = bool(kw.get("bidirectional", 0))
         if h < H0:
-            ref = co.windowed_head(q, k, v, wl.window)
+            ref = co.windowed_head(q, k, v, wl.window, bidirectional=bidir)
         else:
-            ref = co.linear_head(q, k, v, form=co.LINEAR_RECURRENT)
+            ref = co.linear_head(q, k, v, form=co.LINEAR_RECURRENT, bidirectional=bidir)
         check(got, ref, "bf16", f"{name} head ({b},{h}) H0={H0}")
 
 
@@ -387,3 +388,69 @@ def test_layer_under_stream_capture_replays_bit_identically(overlap):
         gb.gformer_attn_fwd(tq, tk, tv, tmp, w, H0, overlap=overlap)
         torch.cuda.synchronize()
         assert torch.equal(tmp.view(torch.int16), eager.view(torch.int16))
+
+
+# ---------------------------------------------------------------------------------------
+# bidirectional variant: window centred on the token, linear heads over all keys
+# ---------------------------------------------------------------------------------------
+
+BIDIR_SHAPES = [
+    # (B, H, N, d, window, H0)
+    (1, 2, 1, 64, 4, 1),
+    (2, 3, 77, 64, 1, 2),
+    (1, 4, 333, 64, 33, 2),
+    (1, 2, 300, 128, 100, 1),
+    (1, 2, 200, 64, 1000, 1),     # window >= 2N: plain softmax attention over the whole sequence
+    (1, 3, 1025, 128, 256, 1),
+    (2, 2, 513, 128, 64, 0),
+    (1, 2, 640, 64, 129, 2),
+    (2, 8, 200, 64, 16, 0),
+    (3, 3, 1000, 64, 50, 1),
+]
+
+
+def _oracle_bidir(q, k, v, w, H0, **kw):
+    return co.attn_fwd(q, k, v, w, H0, bidirectional=True, **kw)
+
+
+@pytest.mark.parametrize("shape", BIDIR_SHAPES, ids=str)
+def test_bidirectional_f32_shapes(shape):
+    B, H, N, d, w, H0 = shape
+    q, k, v = synth(B, H, N, d, "f32", 51)
+    got = run_gpu(q, k, v, "f32", w, H0, bidirectional=1)
+    check(got, _oracle_bidir(q, k, v, w, H0), "f32", str(shape))
+
+
+@pytest.mark.parametrize("impl", [SCALAR, MFMA], ids=["scalar", "mfma"])
+@pytest.mark.parametrize("shape", BIDIR_SHAPES, ids=str)
+def test_bidirectional_bf16_shapes(shape, impl):
+    B, H, N, d, w, H0 = shape
+    q, k, v = synth(B, H, N, d, "bf16", 52)
+    got = run_gpu(q, k, v, "bf16", w, H0, impl=impl, bidirectional=1)
+    check(got, _oracle_bidir(q, k, v, w, H0), "bf16", str(shape))
+
+
+def test_bidirectional_segments_strides_and_options():
+    B, H, N, d, w, H0 = 1, 3, 1100, 64, 40, 1
+    q, k, v = synth(B, H, N, d, "bf16", 53, q_prescaled=False)
+    ref = _oracle_bidir(q, k, v, w, H0, softmax_scale=0.125, eps=0.25)
+    base = None
+    for seg in (0, 64, 128, 320, 1152):    # 64: 18 slots per head, summed by the totals kernel
+        got = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA, bidirectional=1, segment_len=seg,
+                      softmax_scale=0.125, eps=0.25)
+        check(got, ref, "bf16", f"seg={seg}")
+        base = got if base is None else base
+        assert float(row_rel_l2(got, base).max()) < 1e-2
+    got = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA, bidirectional=1, layout="bnhd",
+                  softmax_scale=0.125, eps=0.25)
+    check(got, ref, "bf16", "bnhd")
+    # key/value order does not matter to the linear heads; determinism of repeated runs
+    perm = np.random.default_rng(54).permutation(N)
+    a = run_gpu(q, k, v, "bf16", w, 0, impl=MFMA, bidirectional=1)
+    b = run_gpu(q, k[:, :, perm], v[:, :, perm], "bf16", w, 0, impl=MFMA, bidirectional=1)
+    assert float(row_rel_l2(a, b).max()) < 1e-2
+    assert np.array_equal(a, run_gpu(q, k, v, "bf16", w, 0, impl=MFMA, bidirectional=1))
+
+
+def test_bidirectional_llm7b_full_size_sampled_heads():
+    _full_size("llm7b", 6, bidirectional=1)
