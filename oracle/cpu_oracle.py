@@ -47,6 +47,12 @@ def lib():
             f.argtypes = L.gformer_oracle_linear_head_quadratic_f64.argtypes
         L.gformer_oracle_fwd_bidir_f64.restype = ctypes.c_int
         L.gformer_oracle_fwd_bidir_f64.argtypes = L.gformer_oracle_fwd_f64.argtypes
+        L.gformer_oracle_decode_windowed_f64.restype = ctypes.c_int
+        L.gformer_oracle_decode_windowed_f64.argtypes = [_dp] * 6 + [ctypes.c_int, ctypes.c_int,
+                                                                  ctypes.c_long, ctypes.c_double]
+        L.gformer_oracle_decode_linear_f64.restype = ctypes.c_int
+        L.gformer_oracle_decode_linear_f64.argtypes = [_dp] * 6 + [ctypes.c_int, ctypes.c_int,
+                                                                ctypes.c_double]
         L.gformer_oracle_max_threads.restype = ctypes.c_int
         L.gformer_oracle_random_features_f64.restype = ctypes.c_int
         L.gformer_oracle_random_features_f64.argtypes = [_dp, _dp, _dp, ctypes.c_long,
@@ -103,6 +109,38 @@ def attn_fwd(q, k, v, window, n_sparse_heads, phi=PHI_ELU1, softmax_scale=1.0, e
                                       int(threads))
     if rc:
         raise RuntimeError(f"oracle layer call failed: {rc}")
+    return out
+
+
+def _inplace(a):
+    if not (isinstance(a, np.ndarray) and a.dtype == np.float64 and a.flags.c_contiguous):
+        raise ValueError("state arrays must be C-contiguous float64 (they are updated in place)")
+    return a.ctypes.data_as(_dp)
+
+
+def decode_windowed(q, k, v, kring, vring, t, scale=1.0):
+    """One decode step of a windowed head: q, k, v are [d]; kring, vring [window, d] are updated
+    in place (slot t % window); returns row t of the causal windowed head."""
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v)
+    window, d = kring.shape
+    out = np.empty(d, np.float64)
+    rc = lib().gformer_oracle_decode_windowed_f64(qp, kp, vp, out.ctypes.data_as(_dp), _inplace(kring),
+                                                  _inplace(vring), d, window, int(t), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle windowed decode failed: {rc}")
+    return out
+
+
+def decode_linear(q, k, v, A, Z, phi=PHI_ELU1, eps=0.0):
+    """One decode step of a linear head (Algorithm 1's loop body): A [d, d] and Z [d] are updated
+    in place; returns H_t."""
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v)
+    d = q.shape[0]
+    out = np.empty(d, np.float64)
+    rc = lib().gformer_oracle_decode_linear_f64(qp, kp, vp, out.ctypes.data_as(_dp), _inplace(A),
+                                                _inplace(Z), d, int(phi), float(eps))
+    if rc:
+        raise RuntimeError(f"oracle linear decode failed: {rc}")
     return out
 
 

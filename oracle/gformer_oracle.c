@@ -328,6 +328,64 @@ int gformer_oracle_fwd_bidir_f64(const double *q, const double *k, const double 
 }
 
 /*
+ * Decode step (the inference setting the paper targets, one token at a time): what the causal
+ * layer computes for token t alone, from what it keeps between steps.
+ *   windowed head: the keys and values of the last `window` tokens in a ring (slot t % window);
+ *     row t of section III-B's head is the softmax over the min(t+1, window) rows in the ring.
+ *   linear head: Algorithm 1's loop body, once: A += phi(k_t) (x) v_t, Z += phi(k_t), then
+ *     H_t = phi(q_t)^T A / (phi(q_t).Z + eps).
+ * q, k, v, out: [d].  kring, vring: [window, d], read and written.  A: [d, d], Z: [d], read and
+ * written.  Decoding t = 0, 1, ... from empty rings / zero state reproduces the full forward.
+ */
+int gformer_oracle_decode_windowed_f64(const double *q, const double *k, const double *v,
+                                       double *out, double *kring, double *vring, int d,
+                                       int window, long t, double scale)
+{
+    if (!q || !k || !v || !out || !kring || !vring || d < 1 || window < 1 || t < 0) return 1;
+    const long slot = t % window;
+    memcpy(kring + (size_t)slot * d, k, sizeof(double) * (size_t)d);
+    memcpy(vring + (size_t)slot * d, v, sizeof(double) * (size_t)d);
+    const long cnt = t + 1 < window ? t + 1 : window;
+    double *s = (double *)malloc(sizeof(double) * (size_t)cnt);
+    if (!s) return 2;
+    double m = -INFINITY;
+    for (long r = 0; r < cnt; ++r) {   /* while t < window the ring is filled from slot 0 up */
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c) acc += q[c] * kring[(size_t)r * d + c];
+        s[r] = acc * scale;
+        if (s[r] > m) m = s[r];
+    }
+    double l = 0.0;
+    for (long r = 0; r < cnt; ++r) { s[r] = exp(s[r] - m); l += s[r]; }
+    for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (long r = 0; r < cnt; ++r) acc += s[r] * vring[(size_t)r * d + c];
+        out[c] = acc / l;
+    }
+    free(s);
+    return 0;
+}
+
+int gformer_oracle_decode_linear_f64(const double *q, const double *k, const double *v,
+                                     double *out, double *A, double *Z, int d, int phi, double eps)
+{
+    if (!q || !k || !v || !out || !A || !Z || d < 1) return 1;
+    for (int c = 0; c < d; ++c) {
+        const double f = feature_map(k[c], phi);
+        Z[c] += f;
+        for (int e = 0; e < d; ++e) A[(size_t)c * d + e] += f * v[e];
+    }
+    double den = eps;
+    for (int c = 0; c < d; ++c) den += feature_map(q[c], phi) * Z[c];
+    for (int e = 0; e < d; ++e) {
+        double num = 0.0;
+        for (int c = 0; c < d; ++c) num += feature_map(q[c], phi) * A[(size_t)c * d + e];
+        out[e] = num / den;
+    }
+    return 0;
+}
+
+/*
  * Positive random features (section III-A names them for the linear heads, Algorithm 1 calls
  * them "random feature maps"; neither prints a formula, so this is the construction of the work
  * they cite): for a projection matrix W of m rows w_i,

@@ -624,3 +624,39 @@ def test_bidirectional_linear_against_exact_rationals(seed):
     got = co.linear_head(qi.astype(float), ki.astype(float), vi.astype(float), phi=co.PHI_IDENTITY,
                          bidirectional=True)
     assert max_abs(got, np.array(want)) < 1e-14
+
+
+# ---------------------------------------------------------------------------------------
+# decode step: one token at a time reproduces the full causal forward
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N,d,w", [(40, 6, 7), (25, 4, 1), (30, 8, 64), (33, 5, 32)])
+def test_decode_steps_reproduce_the_full_forward(N, d, w):
+    rng = np.random.default_rng(800 + N + w)
+    q, k, v = (rng.standard_normal((N, d)) for _ in range(3))
+    full_w = co.windowed_head(q, k, v, w, scale=0.6)
+    full_l = co.linear_head(q, k, v, eps=0.125)
+    kring, vring = np.full((w, d), np.nan), np.full((w, d), np.nan)   # unused slots are never read
+    A, Z = np.zeros((d, d)), np.zeros(d)
+    for t in range(N):
+        ow = co.decode_windowed(q[t], k[t], v[t], kring, vring, t, scale=0.6)
+        ol = co.decode_linear(q[t], k[t], v[t], A, Z, eps=0.125)
+        assert max_abs(ow, full_w[t]) < 1e-12, t
+        assert max_abs(ol, full_l[t]) < 1e-12, t
+    # what is kept between steps: the last w keys in ring order, and Algorithm 1's running sums
+    for t in range(max(0, N - w), N):
+        assert np.array_equal(kring[t % w], k[t]) and np.array_equal(vring[t % w], v[t])
+    fk = np.where(k > 0, k + 1, np.exp(k))
+    assert max_abs(A, fk.T @ v) < 1e-12 and max_abs(Z, fk.sum(0)) < 1e-12
+
+
+def test_decode_linear_worked_example_and_identity_map():
+    g = load_golden("linear_4token.json")
+    q, k, v = (parse_matrix(g[n]) for n in "qkv")
+    d = q.shape[1]
+    A, Z = np.zeros((d, d)), np.zeros(d)
+    rows = [co.decode_linear(q[t], k[t], v[t], A, Z, phi=co.PHI_ELU1 if g.get("phi", "elu1") == "elu1" else co.PHI_IDENTITY)
+            for t in range(q.shape[0])]
+    assert max_abs(np.array(rows), co.linear_head(q, k, v)) < 1e-13
+    with pytest.raises(ValueError):
+        co.decode_linear(q[0], k[0], v[0], A.astype(np.float32), Z)
