@@ -254,6 +254,28 @@ def main() -> int:
         s_bi = time_steps(layer_bi, max(5, args.steps // 2), 3)
         modes["bidirectional"] = {"ms": round(s_bi * 1e3, 4), "tokens_per_s": round(wl.B * wl.N / s_bi, 1),
                                   "pct_hbm_peak": round(100 * nbytes / s_bi / 1e9 / HBM_PEAK_GBS, 2)}
+        # Decode step: one token of every (batch, head) against the rings / carried states
+        kc = torch.zeros((wl.B, H0, wl.window, wl.d), dtype=torch.bfloat16, device="cuda") if H0 > 0 else None
+        vc = torch.zeros_like(kc) if H0 > 0 else None
+        stt = torch.zeros((wl.B, wl.H - H0, wl.d * wl.d + wl.d), dtype=torch.float32, device="cuda") if H0 < wl.H else None
+        q1, k1, v1 = (x[:, :, 0].contiguous() for x in (tq, tk, tv))
+        o1 = torch.empty_like(q1)
+        pdec = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=H0)
+        ptr = lambda x: 0 if x is None else x.data_ptr()
+        tpos = [wl.window]   # a full ring
+        def decode():
+            st_ = gb.gformer_attn_decode_raw(q1.data_ptr(), k1.data_ptr(), v1.data_ptr(), o1.data_ptr(),
+                                             ptr(kc), ptr(vc), ptr(stt), wl.B, wl.H, wl.d, wl.window,
+                                             tpos[0], pdec, stream)
+            tpos[0] += 1
+            if st_ != gb.GF_OK:
+                raise gb.GformerError(st_, gb.gformer_status_string(st_))
+        ramp(decode)
+        t_dec = event_time(decode, 500)
+        dec_bytes = wl.B * (H0 * 2 * wl.window * wl.d * 2 + (wl.H - H0) * 2 * (wl.d * wl.d + wl.d) * 4)
+        modes["decode"] = {"us_per_step": round(t_dec * 1e6, 2), "tokens_per_s": round(wl.B / t_dec, 1),
+                           "gbs": round(dec_bytes / t_dec / 1e9, 1),
+                           "note": "full rings; bytes = rings read once + states read and written once"}
         result["modes"] = modes
 
     # ---- CPU baseline: the fp64 oracle on batch element 0 (all heads), host cores ---------

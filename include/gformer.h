@@ -144,6 +144,27 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
                            int N, int d, int window, const gformer_params* p, void* workspace,
                            size_t workspace_bytes, void* hip_stream);
 
+/* One decode step of the causal layer: token `t` of every (batch, head) from what the layer keeps
+ * between steps (autoregressive generation; the paper targets LLM inference, its evaluation runs
+ * whole sequences).  Windowed heads (section III-B, Eq. 1): the last `window` keys and values live
+ * in rings, slot t % window is overwritten with the new row and the min(t+1, window) filled slots
+ * are attended to.  Linear heads (Algorithm 1, one pass of its loop): A += phi(k) (x) v,
+ * Z += phi(k), out = phi(q)^T A / (phi(q).Z + eps).  Decoding t = 0, 1, ... from zeroed states
+ * reproduces gformer_attn_fwd row by row (fp32 arithmetic throughout; bf16 only as storage).
+ *   q, k, v : device, dense [B,H,d], the new token, read
+ *   out     : device, dense [B,H,d], written; must not alias q, k, v
+ *   kcache, vcache : device, dense [B,H0,window,d] rings of the same element type, read and
+ *             written; caller-owned, kept between steps; may be NULL when H0 == 0
+ *   state   : device, fp32 [B,H-H0,d*d+d]: A row-major [feature][value], then Z; read and
+ *             written; zero it before t = 0; may be NULL when H0 == H
+ * Of `p` only dtype, phi, n_sparse_heads, softmax_scale and eps are used; bidirectional must be
+ * 0.  d in {64,128}; window up to what fits 64 KB of LDS as fp32 scores (about 16,000), else
+ * GF_ERR_UNSUPPORTED.  No workspace; asynchronous on `hip_stream`; one step per call, steps of
+ * one sequence must be enqueued in order. */
+gf_status gformer_attn_decode(const void* q, const void* k, const void* v, void* out, void* kcache,
+                              void* vcache, float* state, int B, int H, int d, int window,
+                              int64_t t, const gformer_params* p, void* hip_stream);
+
 /* Positive random features as a pre-map of Q or K for the linear heads.  Section III-A names
  * "positive orthogonal random features" for the linear part and Algorithm 1 "random feature
  * maps"; neither prints them, so the formula is the construction of the work they cite:

@@ -21,7 +21,8 @@ GF_IMPL_AUTO, GF_IMPL_SCALAR, GF_IMPL_MFMA = 0, 1, 2
 GF_LAUNCH_WINDOWED, GF_LAUNCH_LINEAR_STATE, GF_LAUNCH_LINEAR_MAIN = 1, 2, 4
 
 EXPORTS = ("gformer_params_init", "gformer_attn_workspace_bytes", "gformer_attn_plan",
-           "gformer_attn_fwd", "gformer_feature_params_init", "gformer_random_features",
+           "gformer_attn_fwd", "gformer_attn_decode", "gformer_feature_params_init",
+           "gformer_random_features",
            "gformer_status_string", "gformer_version")
 
 
@@ -83,6 +84,9 @@ def lib():
         L.gformer_attn_fwd.restype = ctypes.c_int
         L.gformer_attn_fwd.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 5 + \
             [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.gformer_attn_decode.restype = ctypes.c_int
+        L.gformer_attn_decode.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_int] * 4 + \
+            [ctypes.c_int64, P, ctypes.c_void_p]
         FP = ctypes.POINTER(GformerFeatureParams)
         L.gformer_feature_params_init.restype = None
         L.gformer_feature_params_init.argtypes = [FP]
@@ -253,6 +257,52 @@ def gformer_random_features(x, w, out, head_begin: int, head_end: int, *, impl=G
         stream = torch.cuda.current_stream(x.device).cuda_stream
     st = gformer_random_features_raw(x.data_ptr(), w.data_ptr(), out.data_ptr(), B, H, N, d,
                                      int(w.shape[0]), params, stream)
+    if st != GF_OK:
+        raise GformerError(st, gformer_status_string(st))
+    return out
+
+
+def gformer_attn_decode_raw(q_ptr, k_ptr, v_ptr, out_ptr, kcache_ptr, vcache_ptr, state_ptr, B, H, d,
+                            window, t, params: GformerParams, stream=0) -> int:
+    """Direct call with integer device addresses; returns the gf_status."""
+    vp = lambda x: ctypes.c_void_p(x or None)
+    return int(lib().gformer_attn_decode(vp(q_ptr), vp(k_ptr), vp(v_ptr), vp(out_ptr), vp(kcache_ptr),
+                                         vp(vcache_ptr), vp(state_ptr), int(B), int(H), int(d),
+                                         int(window), ctypes.c_int64(int(t)), ctypes.byref(params),
+                                         vp(stream)))
+
+
+def gformer_attn_decode(q, k, v, out, kcache, vcache, state, window: int, n_sparse_heads: int, t: int,
+                        *, phi=GF_PHI_ELU1, softmax_scale=1.0, eps=0.0, stream: Optional[int] = None):
+    """One decode step on dense device tensors: q, k, v, out [B, H, d]; kcache, vcache
+    [B, H0, window, d] (or None when H0 == 0); state fp32 [B, H - H0, d*d + d] (or None)."""
+    import torch
+
+    ts = [x for x in (q, k, v, out, kcache, vcache, state) if x is not None]
+    if not all(x.is_cuda and x.is_contiguous() for x in ts):
+        raise ValueError("decode tensors must be dense device tensors: there is no CPU path")
+    if q.dtype == torch.bfloat16:
+        dtype = GF_BF16
+    elif q.dtype == torch.float32:
+        dtype = GF_F32
+    else:
+        raise ValueError(f"unsupported dtype {q.dtype}")
+    B, H, d = (int(x) for x in q.shape)
+    if any(x.shape != q.shape or x.dtype != q.dtype for x in (k, v, out)):
+        raise ValueError("q, k, v, out must all be [B, H, d] of one dtype")
+    H0 = int(n_sparse_heads)
+    if H0 > 0 and (kcache is None or vcache is None or kcache.dtype != q.dtype
+                   or tuple(kcache.shape) != (B, H0, window, d) or vcache.shape != kcache.shape):
+        raise ValueError("kcache, vcache must be [B, H0, window, d] of the same dtype")
+    if H0 < H and (state is None or state.dtype != torch.float32
+                   or tuple(state.shape) != (B, H - H0, d * d + d)):
+        raise ValueError("state must be fp32 [B, H - H0, d*d + d]")
+    params = make_params(dtype=dtype, n_sparse_heads=H0, phi=phi, softmax_scale=softmax_scale, eps=eps)
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    ptr = lambda x: 0 if x is None else x.data_ptr()
+    st = gformer_attn_decode_raw(ptr(q), ptr(k), ptr(v), ptr(out), ptr(kcache), ptr(vcache), ptr(state),
+                                 B, H, d, window, t, params, stream)
     if st != GF_OK:
         raise GformerError(st, gformer_status_string(st))
     return out

@@ -288,6 +288,41 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
   return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
 }
 
+gf_status gformer_attn_decode(const void* q, const void* k, const void* v, void* out, void* kcache,
+                              void* vcache, float* state, int B, int H, int d, int window,
+                              int64_t t, const gformer_params* p, void* hip_stream) {
+  if (!p || p->struct_size != sizeof(gformer_params)) return GF_ERR_INVALID_ARG;
+  if (B < 0 || H < 0 || d < 1 || window < 1 || t < 0) return GF_ERR_INVALID_ARG;
+  if (p->dtype != GF_F32 && p->dtype != GF_BF16) return GF_ERR_INVALID_ARG;
+  if (p->phi != GF_PHI_ELU1 && p->phi != GF_PHI_IDENTITY) return GF_ERR_INVALID_ARG;
+  if (p->n_sparse_heads < 0 || p->n_sparse_heads > H) return GF_ERR_INVALID_ARG;
+  if (!(p->softmax_scale == p->softmax_scale) || !(p->eps >= 0.f)) return GF_ERR_INVALID_ARG;
+  if (p->bidirectional != 0) return GF_ERR_INVALID_ARG;   // a token cannot see what is not there yet
+  if (B > 65535) return GF_ERR_UNSUPPORTED;
+  if (d != 64 && d != 128) return GF_ERR_UNSUPPORTED;
+  const int H0 = p->n_sparse_heads;
+  if (decode_smem_bytes(d, window, H0) > 64 * 1024) return GF_ERR_UNSUPPORTED;  // ring scores in LDS
+  if (B == 0 || H == 0) return GF_OK;
+  if (!q || !k || !v || !out) return GF_ERR_INVALID_ARG;
+  if (H0 > 0 && (!kcache || !vcache)) return GF_ERR_INVALID_ARG;
+  if (H0 < H && !state) return GF_ERR_INVALID_ARG;
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out | (uintptr_t)kcache |
+       (uintptr_t)vcache | (uintptr_t)state) & 15u)
+    return GF_ERR_INVALID_ARG;
+  if (out == q || out == k || out == v) return GF_ERR_INVALID_ARG;
+
+  DecodeArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = q; a.k = k; a.v = v; a.out = out;
+  a.kcache = kcache; a.vcache = vcache; a.state = state;
+  a.B = B; a.H = H; a.d = d; a.window = window; a.H0 = H0; a.phi = p->phi;
+  a.t = t;
+  a.scale = p->softmax_scale;
+  a.eps = p->eps;
+  const hipError_t e = launch_decode(a, p->dtype == GF_BF16, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
+}
+
 void gformer_feature_params_init(gformer_feature_params* p) {
   if (!p) return;
   memset(p, 0, sizeof(*p));

@@ -86,6 +86,18 @@ struct FeatureArgs {
   int head_begin, head_end;
 };
 
+// One decode step: the new token of every (batch, head), the windowed heads' key/value rings
+// and the linear heads' carried states.
+struct DecodeArgs {
+  const void *q, *k, *v;   // [B, H, d] dense
+  void* out;               // [B, H, d] dense
+  void *kcache, *vcache;   // [B, H0, window, d] dense rings
+  float* state;            // [B, H - H0, d*d + d] fp32: A row-major [feature][value], then Z
+  int B, H, d, window, H0, phi;
+  int64_t t;               // position of the token, 0-based
+  float scale, eps;
+};
+
 // Host-side launchers, one per kernel family.  Each returns the hipError_t of its launch.
 hipError_t launch_windowed_scalar(const AttnArgs& a, bool bf16, hipStream_t s);
 hipError_t launch_linear_scalar(const AttnArgs& a, bool bf16, hipStream_t s);
@@ -93,6 +105,8 @@ hipError_t launch_windowed_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_linear_state_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_linear_main_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_random_features(const FeatureArgs& a, bool bf16, bool mfma, hipStream_t s);
+hipError_t launch_decode(const DecodeArgs& a, bool bf16, hipStream_t s);
+size_t decode_smem_bytes(int d, int window, int H0);
 
 // Launch geometry shared by the planner and the launchers.
 constexpr int kScalarWindowRows = 16;   // query rows per workgroup, scalar windowed kernel

@@ -220,3 +220,38 @@ def test_plan_bidirectional_pieces_never_straddle_heads():
     # one short head: a single piece, still summed first
     st, pl = _plan(1, 1, 100, 64, 8, n_sparse_heads=0, bidirectional=1)
     assert st == gb.GF_OK and pl["n_segments"] == 2 and pl["state_blocks"] == 2 and pl["workspace_bytes"] > 0
+
+
+# ---------------------------------------------------------------------------------------
+# gformer_attn_decode: host-side checks
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("shape,kw,t,want", [
+    ((1, 2, 64, 4), {"n_sparse_heads": 3}, 0, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 64, 4), {"n_sparse_heads": 1, "bidirectional": 1}, 0, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 64, 4), {"n_sparse_heads": 1}, -1, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 64, 0), {"n_sparse_heads": 1}, 0, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 64, 4), {"n_sparse_heads": 1, "eps": -1.0}, 0, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 96, 4), {"n_sparse_heads": 1}, 0, gb.GF_ERR_UNSUPPORTED),
+    ((1, 2, 64, 1 << 20), {"n_sparse_heads": 1}, 0, gb.GF_ERR_UNSUPPORTED),   # ring scores do not fit LDS
+    ((70000, 2, 64, 4), {"n_sparse_heads": 1}, 0, gb.GF_ERR_UNSUPPORTED),
+])
+def test_decode_argument_errors_are_reported_on_the_host(shape, kw, t, want):
+    B, H, d, w = shape
+    p = gb.make_params(**kw)
+    got = gb.gformer_attn_decode_raw(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, B, H, d, w, t, p)
+    assert got == want
+
+
+def test_decode_pointer_checks_and_empty_problems():
+    p = gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1)
+    a = (1, 2, 64, 8, 5)
+    ok = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
+    for i in range(7):                      # every pointer is needed when both head kinds exist
+        bad = list(ok); bad[i] = 0
+        assert gb.gformer_attn_decode_raw(*bad, *a, p) == gb.GF_ERR_INVALID_ARG
+    mis = list(ok); mis[4] = 0x5008
+    assert gb.gformer_attn_decode_raw(*mis, *a, p) == gb.GF_ERR_INVALID_ARG
+    alias = list(ok); alias[3] = alias[1]
+    assert gb.gformer_attn_decode_raw(*alias, *a, p) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_attn_decode_raw(0, 0, 0, 0, 0, 0, 0, 0, 2, 64, 8, 5, p) == gb.GF_OK

@@ -454,3 +454,39 @@ def test_bidirectional_segments_strides_and_options():
 
 def test_bidirectional_llm7b_full_size_sampled_heads():
     _full_size("llm7b", 6, bidirectional=1)
+
+
+# ---------------------------------------------------------------------------------------
+# decode step: token by token against the full causal forward of the oracle
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 3, 150, 64, 40, 1), (1, 2, 90, 128, 200, 1), (1, 2, 70, 64, 1, 2),
+                                   (2, 2, 60, 128, 16, 0)], ids=str)
+def test_decode_steps_match_full_forward(dtype, shape):
+    import torch
+    B, H, T, d, w, H0 = shape
+    q, k, v = synth(B, H, T, d, dtype, 61)
+    ref = co.attn_fwd(q, k, v, w, H0, eps=0.125, softmax_scale=0.5)
+    tq, tk, tv = (to_device(x, dtype) for x in (q, k, v))
+    tdt = tq.dtype
+    kc = torch.full((B, H0, w, d), float("nan"), dtype=tdt, device="cuda") if H0 > 0 else None
+    vc = torch.full((B, H0, w, d), float("nan"), dtype=tdt, device="cuda") if H0 > 0 else None
+    st = torch.zeros((B, H - H0, d * d + d), dtype=torch.float32, device="cuda") if H0 < H else None
+    got = np.empty_like(ref)
+    out = torch.full((B, H, d), float("nan"), dtype=tdt, device="cuda")
+    for t in range(T):
+        gb.gformer_attn_decode(tq[:, :, t].contiguous(), tk[:, :, t].contiguous(), tv[:, :, t].contiguous(),
+                               out, kc, vc, st, w, H0, t, eps=0.125, softmax_scale=0.5)
+        got[:, :, t] = to_host(out)
+    check(got, ref, dtype, f"decode {shape}")
+    # what is kept between steps
+    if H0 < H:
+        fk = np.where(k[:, H0:] > 0, k[:, H0:].astype(np.float64) + 1, np.exp(k[:, H0:].astype(np.float64)))
+        A = np.einsum("bhnc,bhne->bhce", fk, v[:, H0:].astype(np.float64)).reshape(B, H - H0, d * d)
+        s = st.cpu().numpy().astype(np.float64)
+        assert float(np.abs(s[..., :d * d] - A).max()) <= 2e-4 * max(1.0, float(np.abs(A).max()))
+        assert float(np.abs(s[..., d * d:] - fk.sum(2)).max()) <= 2e-4 * float(fk.sum(2).max())
+    if H0 > 0:
+        for t in range(max(0, T - w), T):
+            assert np.array_equal(to_host(kc[:, :, t % w]), k[:, :H0, t].astype(np.float64))
