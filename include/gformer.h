@@ -165,6 +165,18 @@ gf_status gformer_attn_decode(const void* q, const void* k, const void* v, void*
                               void* vcache, float* state, int B, int H, int d, int window,
                               int64_t t, const gformer_params* p, void* hip_stream);
 
+/* gformer_attn_fwd (causal) that also leaves what gformer_attn_decode continues from: the last
+ * `window` keys and values of every windowed head in ring order (token t in slot t % window;
+ * slots of tokens that do not exist are left alone) and every linear head's (A, Z) after its last
+ * token.  Same arguments, conventions and errors as gformer_attn_fwd, plus
+ *   kcache, vcache : device, dense [B,H0,window,d], element type of q; may be NULL when H0 == 0
+ *   state          : device, fp32 dense [B,H-H0,d*d+d]; may be NULL when H0 == H
+ * params.bidirectional and params.launch_mask must be 0.  The next token to decode is t = N. */
+gf_status gformer_attn_prefill(const void* q, const void* k, const void* v, void* out, void* kcache,
+                               void* vcache, float* state, int B, int H, int N, int d, int window,
+                               const gformer_params* p, void* workspace, size_t workspace_bytes,
+                               void* hip_stream);
+
 /* Positive random features as a pre-map of Q or K for the linear heads.  Section III-A names
  * "positive orthogonal random features" for the linear part and Algorithm 1 "random feature
  * maps"; neither prints them, so the formula is the construction of the work they cite:

@@ -21,7 +21,8 @@ GF_IMPL_AUTO, GF_IMPL_SCALAR, GF_IMPL_MFMA = 0, 1, 2
 GF_LAUNCH_WINDOWED, GF_LAUNCH_LINEAR_STATE, GF_LAUNCH_LINEAR_MAIN = 1, 2, 4
 
 EXPORTS = ("gformer_params_init", "gformer_attn_workspace_bytes", "gformer_attn_plan",
-           "gformer_attn_fwd", "gformer_attn_decode", "gformer_feature_params_init",
+           "gformer_attn_fwd", "gformer_attn_prefill", "gformer_attn_decode",
+           "gformer_feature_params_init",
            "gformer_random_features",
            "gformer_status_string", "gformer_version")
 
@@ -83,6 +84,9 @@ def lib():
         L.gformer_attn_plan.argtypes = [ctypes.c_int] * 5 + [P, ctypes.POINTER(GformerPlan)]
         L.gformer_attn_fwd.restype = ctypes.c_int
         L.gformer_attn_fwd.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 5 + \
+            [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.gformer_attn_prefill.restype = ctypes.c_int
+        L.gformer_attn_prefill.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_int] * 5 + \
             [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.gformer_attn_decode.restype = ctypes.c_int
         L.gformer_attn_decode.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_int] * 4 + \
@@ -303,6 +307,51 @@ def gformer_attn_decode(q, k, v, out, kcache, vcache, state, window: int, n_spar
     ptr = lambda x: 0 if x is None else x.data_ptr()
     st = gformer_attn_decode_raw(ptr(q), ptr(k), ptr(v), ptr(out), ptr(kcache), ptr(vcache), ptr(state),
                                  B, H, d, window, t, params, stream)
+    if st != GF_OK:
+        raise GformerError(st, gformer_status_string(st))
+    return out
+
+
+def gformer_attn_prefill_raw(q_ptr, k_ptr, v_ptr, out_ptr, kcache_ptr, vcache_ptr, state_ptr, B, H, N, d,
+                             window, params: GformerParams, workspace_ptr=0, workspace_bytes=0,
+                             stream=0) -> int:
+    """Direct call with integer device addresses; returns the gf_status."""
+    vp = lambda x: ctypes.c_void_p(x or None)
+    return int(lib().gformer_attn_prefill(vp(q_ptr), vp(k_ptr), vp(v_ptr), vp(out_ptr), vp(kcache_ptr),
+                                          vp(vcache_ptr), vp(state_ptr), int(B), int(H), int(N), int(d),
+                                          int(window), ctypes.byref(params), vp(workspace_ptr),
+                                          ctypes.c_size_t(int(workspace_bytes)), vp(stream)))
+
+
+def gformer_attn_prefill(q, k, v, out, kcache, vcache, state, window: int, n_sparse_heads: int, *,
+                         phi=GF_PHI_ELU1, impl=GF_IMPL_AUTO, softmax_scale=1.0, eps=0.0,
+                         workspace=None, stream: Optional[int] = None):
+    """The causal layer on [B, H, N, d] device tensors that also fills the decode step's rings
+    (kcache, vcache: dense [B, H0, window, d]) and carried states (fp32 [B, H - H0, d*d + d])."""
+    import torch
+
+    if not all(x.is_cuda for x in (q, k, v, out)):
+        raise ValueError("q, k, v, out must be device tensors: there is no CPU path")
+    dtype = GF_BF16 if q.dtype == torch.bfloat16 else GF_F32
+    B, H, N, d = (int(x) for x in q.shape)
+    for x in (kcache, vcache, state):
+        if x is not None and not (x.is_cuda and x.is_contiguous()):
+            raise ValueError("rings and states must be dense device tensors")
+    params = make_params(dtype=dtype, n_sparse_heads=n_sparse_heads, phi=phi, impl=impl,
+                         softmax_scale=softmax_scale, eps=eps, q_stride=_strides3(q),
+                         k_stride=_strides3(k), v_stride=_strides3(v), o_stride=_strides3(out))
+    need = gformer_attn_workspace_bytes(B, H, N, d, window, params)
+    ws_ptr, ws_bytes = 0, 0
+    if need > 0:
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    ptr = lambda x: 0 if x is None else x.data_ptr()
+    st = gformer_attn_prefill_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), ptr(kcache),
+                                  ptr(vcache), ptr(state), B, H, N, d, window, params, ws_ptr, ws_bytes,
+                                  stream)
     if st != GF_OK:
         raise GformerError(st, gformer_status_string(st))
     return out

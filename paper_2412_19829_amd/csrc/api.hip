@@ -216,9 +216,15 @@ gf_status gformer_attn_plan(int B, int H, int N, int d, int window, const gforme
   return st;
 }
 
-gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int H,
-                           int N, int d, int window, const gformer_params* p, void* workspace,
-                           size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// The whole layer; with rings / final states it also leaves what a decode step continues from.
+gf_status attn_forward(const void* q, const void* k, const void* v, void* out, void* kring,
+                       void* vring, float* final_state, int B, int H, int N, int d, int window,
+                       const gformer_params* p, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
   Resolved r;
   gf_status st = resolve(B, H, N, d, window, p, &r);
   if (st != GF_OK) return st;
@@ -254,6 +260,9 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
   a.n_pieces = r.plan.n_segments;
   a.state_sub = r.state_sub;
   a.ws_states = r.plan.workspace_bytes > 0 ? reinterpret_cast<float*>(workspace) : nullptr;
+  a.final_state = final_state;
+  a.kring = kring;
+  a.vring = vring;
 
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   const int mask = p->launch_mask ? p->launch_mask : 7;
@@ -285,7 +294,35 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
     }
     if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_main_mfma(a, s);
   }
+  if (e == hipSuccess) e = launch_fill_rings(a, bf16, s);
   return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
+}
+
+}  // namespace
+
+extern "C" {
+
+gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int H,
+                           int N, int d, int window, const gformer_params* p, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  return attn_forward(q, k, v, out, nullptr, nullptr, nullptr, B, H, N, d, window, p, workspace,
+                      workspace_bytes, hip_stream);
+}
+
+gf_status gformer_attn_prefill(const void* q, const void* k, const void* v, void* out, void* kcache,
+                               void* vcache, float* state, int B, int H, int N, int d, int window,
+                               const gformer_params* p, void* workspace, size_t workspace_bytes,
+                               void* hip_stream) {
+  if (!p || p->struct_size != sizeof(gformer_params)) return GF_ERR_INVALID_ARG;
+  if (p->bidirectional != 0 || p->launch_mask != 0) return GF_ERR_INVALID_ARG;
+  if (B > 0 && H > 0 && N > 0) {
+    const int H0 = p->n_sparse_heads;
+    if (H0 > 0 && H0 <= H && (!kcache || !vcache)) return GF_ERR_INVALID_ARG;
+    if (H0 >= 0 && H0 < H && !state) return GF_ERR_INVALID_ARG;
+    if (((uintptr_t)kcache | (uintptr_t)vcache | (uintptr_t)state) & 15u) return GF_ERR_INVALID_ARG;
+  }
+  return attn_forward(q, k, v, out, kcache, vcache, state, B, H, N, d, window, p, workspace,
+                      workspace_bytes, hip_stream);
 }
 
 gf_status gformer_attn_decode(const void* q, const void* k, const void* v, void* out, void* kcache,

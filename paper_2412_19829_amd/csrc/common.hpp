@@ -36,6 +36,10 @@ struct AttnArgs {
   int piece_chunks;  // chunks per piece
   int n_pieces;      // pieces = workgroups of the read-out kernel
   int state_sub;     // the state pass cuts every piece into this many equal sub-pieces (1 or 2)
+  float* final_state; // optional [B*(H-H0), d*d + d] fp32: every linear head's (A, Z) after its last
+                     // token, A row-major [feature][value] (what the decode step carries on from)
+  void *kring, *vring; // optional [B, H0, window, d] rings: the last `window` keys / values of every
+                     // windowed head, token t in slot t % window
   float* ws_states;  // [n_pieces*state_sub, d*d + d] fp32: slot j = (A, Z) of its head just
                      // before global chunk j*piece_chunks/state_sub (piece p reads slot p*state_sub)
 };
@@ -104,6 +108,7 @@ hipError_t launch_linear_scalar(const AttnArgs& a, bool bf16, hipStream_t s);
 hipError_t launch_windowed_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_linear_state_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_linear_main_mfma(const AttnArgs& a, hipStream_t s);
+hipError_t launch_fill_rings(const AttnArgs& a, bool bf16, hipStream_t s);
 hipError_t launch_random_features(const FeatureArgs& a, bool bf16, bool mfma, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, bool bf16, hipStream_t s);
 size_t decode_smem_bytes(int d, int window, int H0);

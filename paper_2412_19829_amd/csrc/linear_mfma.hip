@@ -411,7 +411,9 @@ __global__ __launch_bounds__(256) void linear_prefix_kernel(float* ws, int n_hea
 //     CAUSAL = false is the bidirectional read-out: the state is the sum over the whole head and
 //     never moves, K and V are not touched, and per chunk only the state read-out, phi(q).Z and
 //     the normalisation remain (same barriers, same producer/consumer split).
-template <int D, bool ELU1, bool CAUSAL>
+//     EMIT (causal only): every head's (A, Z) after its last token is also written out, for a
+//     decode step to continue from; a separate instantiation so that the plain layer pays nothing.
+template <int D, bool ELU1, bool CAUSAL, bool EMIT>
 __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_kernel(AttnArgs a) {
   using C = LinCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -653,6 +655,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
     const int zc = n & 1;
     const ChunkTiles<D>& b = sm.buf[n & 1];
     const bool head_ends = (lc + 1 == a.vcph);  // the next chunk starts a new head from zero
+    const bool head_done = (lc + 1 == a.cph);   // this chunk holds the head's last token
     lc = head_ends ? 0 : lc + 1;
 
     f32x16 p[NTILE];
@@ -807,7 +810,19 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
       if constexpr (CAUSAL) {
         zs += __shfl_xor(zs, 32, 64);
         const int zi = 32 * wave + kperm32(ln);
-        if (lh == 0) put_z(zc ^ 1, zi, head_ends ? 0.f : sm.z[zc][zi] + zs);
+        const float znew = sm.z[zc][zi] + zs;
+        if (EMIT && head_done) {
+          // the state after the head's last token, for a decode step to continue from:
+          // A row-major [feature][value] (lane = value column, register = feature row), then Z
+          float* fs = a.final_state + (int64_t)((g0 + n) / a.vcph) * C::STATE;
+#pragma unroll
+          for (int ct = 0; ct < C::ET; ++ct)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              fs[(32 * ct + 8 * (r / 4) + 4 * lh + (r % 4)) * D + 32 * wave + ln] = sacc[ct][r];
+          if (lh == 0) fs[D * D + 32 * wave + ln] = znew;
+        }
+        if (lh == 0) put_z(zc ^ 1, zi, head_ends ? 0.f : znew);
         if (head_ends) {
 #pragma unroll
           for (int ct = 0; ct < C::ET; ++ct)
@@ -859,12 +874,15 @@ template <int D> hipError_t launch_main_t(const AttnArgs& a, hipStream_t s) {
     e = allow_lds(kern, smem);
     if (e == hipSuccess) kern<<<grid, block, smem, s>>>(a);
   };
-  if (a.causal) {
-    if (a.phi == 0) launch(linear_main_kernel<D, true, true>);
-    else launch(linear_main_kernel<D, false, true>);
+  if (a.causal && a.final_state) {
+    if (a.phi == 0) launch(linear_main_kernel<D, true, true, true>);
+    else launch(linear_main_kernel<D, false, true, true>);
+  } else if (a.causal) {
+    if (a.phi == 0) launch(linear_main_kernel<D, true, true, false>);
+    else launch(linear_main_kernel<D, false, true, false>);
   } else {
-    if (a.phi == 0) launch(linear_main_kernel<D, true, false>);
-    else launch(linear_main_kernel<D, false, false>);
+    if (a.phi == 0) launch(linear_main_kernel<D, true, false, false>);
+    else launch(linear_main_kernel<D, false, false, false>);
   }
   return e != hipSuccess ? e : hipGetLastError();
 }

@@ -198,6 +198,29 @@ __global__ __launch_bounds__(kScalarThreads) void linear_scalar_kernel(AttnArgs 
       z[tid] = s;
     }
   }
+  if (a.final_state) {   // (A, Z) after the last token, for a decode step to continue from
+    __syncthreads();
+    float* fs = a.final_state + ((int64_t)b * (a.H - a.H0) + blockIdx.x) * (D * D + D);
+    for (int x = tid; x < D * D; x += kScalarThreads) fs[x] = S[x];
+    if (tid < D) fs[D * D + tid] = z[tid];
+  }
+}
+
+// The last `window` keys and values of every windowed head, token t in ring slot t % window
+// (what the decode step attends to).  grid = (window rows, H0, B), block = d / 8 threads... one
+// thread per 8 elements of a row.
+template <typename T>
+__global__ void fill_rings_kernel(AttnArgs a) {
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int first = max(0, a.N - a.window);
+  const int t = first + blockIdx.x;
+  if (t >= a.N) return;
+  const int slot = t % a.window;
+  const int64_t ring = (((int64_t)b * a.H0 + h) * a.window + slot) * a.d;
+  for (int c = threadIdx.x; c < a.d; c += blockDim.x) {
+    Storage<T>::store(a.kring, ring + c, Storage<T>::load(a.k.base, b * a.k.sb + h * a.k.sh + (int64_t)t * a.k.sn + c));
+    Storage<T>::store(a.vring, ring + c, Storage<T>::load(a.v.base, b * a.v.sb + h * a.v.sh + (int64_t)t * a.v.sn + c));
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -318,6 +341,15 @@ static hipError_t launch_linear_scalar_t(const AttnArgs& a, hipStream_t s) {
   if (e != hipSuccess) return e;
   dim3 grid(a.H - a.H0, a.B);
   kern<<<grid, dim3(kScalarThreads), smem, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_rings(const AttnArgs& a, bool bf16, hipStream_t s) {
+  if (a.H0 <= 0 || a.N <= 0 || a.B <= 0 || !a.kring || !a.vring) return hipSuccess;
+  const int rows = a.N < a.window ? a.N : a.window;
+  const dim3 grid(rows, a.H0, a.B), block(64);
+  if (bf16) fill_rings_kernel<uint16_t><<<grid, block, 0, s>>>(a);
+  else fill_rings_kernel<float><<<grid, block, 0, s>>>(a);
   return hipGetLastError();
 }
 

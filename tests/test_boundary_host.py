@@ -255,3 +255,16 @@ def test_decode_pointer_checks_and_empty_problems():
     alias = list(ok); alias[3] = alias[1]
     assert gb.gformer_attn_decode_raw(*alias, *a, p) == gb.GF_ERR_INVALID_ARG
     assert gb.gformer_attn_decode_raw(0, 0, 0, 0, 0, 0, 0, 0, 2, 64, 8, 5, p) == gb.GF_OK
+
+
+def test_prefill_argument_checks_on_the_host():
+    p = gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1)
+    a = (1, 2, 16, 64, 4)
+    ok = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
+    for i in (4, 5, 6):                     # rings and states are needed when both head kinds exist
+        bad = list(ok); bad[i] = 0
+        assert gb.gformer_attn_prefill_raw(*bad, *a, p) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_attn_prefill_raw(*ok, *a, gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1, bidirectional=1)) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_attn_prefill_raw(*ok, *a, gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1, launch_mask=1)) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_attn_prefill_raw(*ok, 1, 2, 16, 96, 4, p) == gb.GF_ERR_UNSUPPORTED
+    assert gb.gformer_attn_prefill_raw(0, 0, 0, 0, 0, 0, 0, 1, 2, 0, 64, 4, p) == gb.GF_OK

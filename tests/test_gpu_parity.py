@@ -490,3 +490,34 @@ def test_decode_steps_match_full_forward(dtype, shape):
     if H0 > 0:
         for t in range(max(0, T - w), T):
             assert np.array_equal(to_host(kc[:, :, t % w]), k[:, :H0, t].astype(np.float64))
+
+
+@pytest.mark.parametrize("dtype,impl", [("f32", SCALAR), ("bf16", SCALAR), ("bf16", MFMA)],
+                         ids=["f32", "bf16-scalar", "bf16-mfma"])
+@pytest.mark.parametrize("shape", [(2, 3, 333, 64, 40, 1, 25), (1, 3, 700, 128, 1000, 1, 12),
+                                   (1, 8, 200, 64, 16, 2, 20)], ids=str)
+def test_prefill_then_decode_matches_one_long_forward(dtype, impl, shape):
+    """Prefill N tokens (the layer plus rings and carried states), then decode T more: every row
+    must match the oracle's forward over all N + T tokens."""
+    import torch
+    B, H, N, d, w, H0, T = shape
+    q, k, v = synth(B, H, N + T, d, dtype, 71)
+    ref = oracle(q, k, v, w, H0)
+    tq, tk, tv = (to_device(x, dtype) for x in (q, k, v))
+    tdt = tq.dtype
+    kc = torch.full((B, H0, w, d), float("nan"), dtype=tdt, device="cuda")
+    vc = torch.full((B, H0, w, d), float("nan"), dtype=tdt, device="cuda")
+    st = torch.full((B, H - H0, d * d + d), float("nan"), dtype=torch.float32, device="cuda")
+    out = torch.full((B, H, N, d), float("nan"), dtype=tdt, device="cuda")
+    gb.gformer_attn_prefill(tq[:, :, :N].contiguous(), tk[:, :, :N].contiguous(), tv[:, :, :N].contiguous(),
+                            out, kc, vc, st, w, H0, impl=impl)
+    torch.cuda.synchronize()
+    check(to_host(out), ref[:, :, :N], dtype, f"prefill {shape}")
+    assert bool(torch.isfinite(st).all())
+    got = np.empty((B, H, T, d))
+    o1 = torch.full((B, H, d), float("nan"), dtype=tdt, device="cuda")
+    for t in range(N, N + T):
+        gb.gformer_attn_decode(tq[:, :, t].contiguous(), tk[:, :, t].contiguous(), tv[:, :, t].contiguous(),
+                               o1, kc, vc, st, w, H0, t)
+        got[:, :, t - N] = to_host(o1)
+    check(got, ref[:, :, N:], dtype, f"decode after prefill {shape}")
