@@ -1,4 +1,5 @@
-// Causal linear attention heads on bf16 matrix cores (section III-C, Algorithm 1), chunked.
+// Linear attention heads on bf16 matrix cores, chunked: the causal form of section III-C,
+// Algorithm 1 (described first), and the bidirectional form of section II-B (end of this note).
 //
 // Algorithm 1 walks tokens one by one: A += phi(k_i) (x) v_i, Z += phi(k_i), then reads row i.
 // Here a head's sequence is cut into segments (one workgroup each) and segments into chunks of
@@ -18,10 +19,17 @@
 //
 // The chunks of all linear heads form one list that is cut into equal pieces, one workgroup
 // each, with no regard to head boundaries (or, on request, into uniform segments per head).
-// Pieces are stitched in three launches: (1) for every piece boundary that falls inside a
-// head, sum (A, Z) over the part of that head lying in the piece before it; (2) a tiny kernel
-// turns those sums into running sums inside each head; (3) the read-out kernel starts each
-// piece from the state carried to its first chunk and restarts from zero at head boundaries.
+// Pieces are stitched in stream-ordered launches: (1) for every (half-)piece boundary that
+// falls inside a head and is followed by a piece start in the same head, sum (A, Z) over the
+// part of that head lying in the (half-)piece before it; (2) only when a head holds many such
+// sums, a tiny kernel turns them into running sums; (3) the read-out kernel starts each piece
+// from the state carried to its first chunk (adding up the few sums itself otherwise) and
+// restarts from zero at head boundaries.
+//
+// Bidirectional form: out_i = phi(q_i)^T S / (phi(q_i).z + eps) with S, z summed over the whole
+// head.  Pieces are uniform segments per head, launch (1) sums every piece, and the read-out
+// kernel (CAUSAL = false) contracts phi(Q) with the head's total state only: K and V are read
+// once, by the state pass.
 #include "common.hpp"
 #include "mfma.hpp"
 

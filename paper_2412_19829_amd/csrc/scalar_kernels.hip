@@ -207,8 +207,7 @@ __global__ __launch_bounds__(kScalarThreads) void linear_scalar_kernel(AttnArgs 
 }
 
 // The last `window` keys and values of every windowed head, token t in ring slot t % window
-// (what the decode step attends to).  grid = (window rows, H0, B), block = d / 8 threads... one
-// thread per 8 elements of a row.
+// (what the decode step attends to).  grid = (min(window, N) rows, H0, B), block = 64.
 template <typename T>
 __global__ void fill_rings_kernel(AttnArgs a) {
   const int h = blockIdx.y, b = blockIdx.z;
