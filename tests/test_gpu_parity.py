@@ -521,3 +521,19 @@ def test_prefill_then_decode_matches_one_long_forward(dtype, impl, shape):
                                o1, kc, vc, st, w, H0, t)
         got[:, :, t - N] = to_host(o1)
     check(got, ref[:, :, N:], dtype, f"decode after prefill {shape}")
+
+
+def test_one_very_long_sequence():
+    """Few heads, many tokens: hundreds of pieces per head (running sums by the prefix kernel),
+    a ragged last chunk, and a window that is not a multiple of anything."""
+    B, H, N, d, w, H0 = 1, 2, 70_001, 64, 301, 1
+    q, k, v = synth(B, H, N, d, "bf16", 81)
+    got = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA)
+    ref = np.empty((B, H, N, d))
+    ref[0, 0] = co.windowed_head(q[0, 0], k[0, 0], v[0, 0], w)
+    ref[0, 1] = co.linear_head(q[0, 1], k[0, 1], v[0, 1], form=co.LINEAR_RECURRENT)
+    check(got, ref, "bf16", "70k tokens")
+    got_bi = run_gpu(q, k, v, "bf16", w, H0, impl=MFMA, bidirectional=1)
+    ref[0, 0] = co.windowed_head(q[0, 0], k[0, 0], v[0, 0], w, bidirectional=True)
+    ref[0, 1] = co.linear_head(q[0, 1], k[0, 1], v[0, 1], form=co.LINEAR_RECURRENT, bidirectional=True)
+    check(got_bi, ref, "bf16", "70k tokens, bidirectional")
