@@ -163,3 +163,63 @@ def random_features(x, w):
 
 def max_threads() -> int:
     return int(lib().gformer_oracle_max_threads())
+
+
+# ---- Head partition model (Section III-D) -------------------------------------------------
+# Plain Python floats (fp64).  The "find p'" step of Algorithm 2 is done here by bisection on
+# the share: latency0 grows and latency1 shrinks with it, so their difference crosses zero once.
+
+FLOPS_PAPER = 0      # linear heads counted as one contraction of width H1*E (the printed count)
+FLOPS_PER_HEAD = 1   # linear heads counted one by one
+
+
+def partition_latencies(p, size, flops_per0, flops_per1, perf0, perf1):
+    """The first four steps of Algorithm 2 at share p: FLOPs of each partition, then latency =
+    FLOPs / average performance."""
+    flops_p0 = p * size * flops_per0
+    flops_p1 = (1.0 - p) * size * flops_per1
+    latency0 = flops_p0 / perf0
+    latency1 = flops_p1 / perf1
+    return latency0, latency1
+
+
+def partition_balance(p, size, flops_per0, flops_per1, perf0, perf1, iters=200):
+    """Algorithm 2: the share p' of partition 0 at which latency0 == latency1.  `p` is the
+    initial share of the printed algorithm; the search does not depend on it."""
+    lo, hi = 0.0, 1.0
+    for _ in range(iters):
+        mid = 0.5 * (lo + hi)
+        l0, l1 = partition_latencies(mid, size, flops_per0, flops_per1, perf0, perf1)
+        if l0 < l1:
+            lo = mid
+        else:
+            hi = mid
+    return 0.5 * (lo + hi)
+
+
+def sparse_flops(B, H0, N, E, W):
+    """Section III-D: scores 2*B*H0*E*N*W plus softmax 3*B*H0*N*W (the two printed terms)."""
+    return 2.0 * B * H0 * E * N * W + 3.0 * B * H0 * N * W
+
+
+def linear_flops(B, H1, N, E, flop_model=FLOPS_PAPER):
+    """Section III-D: feature maps 4BN(H1 E)^2, phi(K)^T V 2BN(H1 E)^2, phi(Q) C 2BN(H1 E)^2."""
+    if flop_model == FLOPS_PAPER:
+        width2 = float(H1 * E) ** 2
+    else:
+        width2 = float(H1) * float(E) ** 2
+    return 4.0 * B * N * width2 + 2.0 * B * N * width2 + 2.0 * B * N * width2
+
+
+def partition_heads(B, H, N, E, W, perf_sparse, perf_linear, flop_model=FLOPS_PAPER):
+    """The head count H0 in [0,H] whose windowed latency (sparse FLOPs / perf_sparse) is closest
+    to the linear latency of the other H-H0 heads; the smaller count on a tie.  Returns
+    (H0, latency_sparse, latency_linear)."""
+    best = None
+    for h0 in range(H + 1):
+        ls = sparse_flops(B, h0, N, E, W) / perf_sparse
+        ll = linear_flops(B, H - h0, N, E, flop_model) / perf_linear
+        gap = abs(ls - ll)
+        if best is None or gap < best[0]:
+            best = (gap, h0, ls, ll)
+    return best[1], best[2], best[3]

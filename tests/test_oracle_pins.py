@@ -7,7 +7,10 @@ wrong readings (written here, on the CPU) must each be rejected by the goldens.
 """
 from __future__ import annotations
 
+import json
 import math
+import os
+import random
 from fractions import Fraction
 
 import numpy as np
@@ -660,3 +663,103 @@ def test_decode_linear_worked_example_and_identity_map():
     assert max_abs(np.array(rows), co.linear_head(q, k, v)) < 1e-13
     with pytest.raises(ValueError):
         co.decode_linear(q[0], k[0], v[0], A.astype(np.float32), Z)
+
+
+# ---- Head partition model (Section III-D, Algorithm 2) ---------------------------------------
+
+def _partition_golden():
+    with open(os.path.join(os.path.dirname(__file__), "golden", "partition_examples.json")) as f:
+        return json.load(f)
+
+
+def _fr(x):
+    return Fraction(x)
+
+
+@pytest.mark.parametrize("case", range(3))
+def test_partition_balance_worked_examples(case):
+    ex = _partition_golden()["balance"][case]
+    args = [float(_fr(ex[k])) for k in ("p", "size", "flops_per0", "flops_per1", "perf0", "perf1")]
+    pp = co.partition_balance(*args)
+    assert abs(pp - float(_fr(ex["p_prime"]))) <= 1e-14, ex["why"]
+    l0, l1 = co.partition_latencies(pp, *args[1:])
+    want = float(_fr(ex["latency_at_p_prime"]))
+    assert abs(l0 - want) <= 1e-12 * want and abs(l1 - want) <= 1e-12 * want
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_partition_balance_against_exact_rationals(seed):
+    """Equal latencies p' c0 = (1-p') c1 with c = FLOPs per unit / performance, solved in exact
+    rationals: p' = c1 / (c0 + c1).  Also: independent of size and of the initial share, and
+    swapping the two partitions gives 1 - p'."""
+    rng = random.Random(seed)
+    f0, f1 = Fraction(rng.randint(1, 999), rng.randint(1, 99)), Fraction(rng.randint(1, 999), rng.randint(1, 99))
+    g0, g1 = Fraction(rng.randint(1, 999), rng.randint(1, 99)), Fraction(rng.randint(1, 999), rng.randint(1, 99))
+    size = Fraction(rng.randint(1, 10 ** 6))
+    c0, c1 = f0 / g0, f1 / g1
+    want = c1 / (c0 + c1)
+    got = co.partition_balance(0.25, float(size), float(f0), float(f1), float(g0), float(g1))
+    assert abs(got - float(want)) <= 1e-13
+    assert abs(co.partition_balance(0.9, 3.0 * float(size), float(f0), float(f1), float(g0), float(g1)) - got) <= 1e-13
+    swapped = co.partition_balance(0.25, float(size), float(f1), float(f0), float(g1), float(g0))
+    assert abs(swapped - (1.0 - got)) <= 1e-13
+    # a dropped (1-p), a latency written as perf/FLOPs or a swapped performance would each move p'
+    wrong = [c0 / (c0 + c1), (f1 * g1) / (f0 * g0 + f1 * g1), (f1 / g0) / (f0 / g1 + f1 / g0)]
+    assert all(abs(float(wv) - got) > 1e-6 for wv in wrong if wv != want)
+
+
+def test_partition_latencies_follow_the_printed_steps():
+    # share 1/4 of 8 units at 6 FLOPs per unit and 4 FLOP/s: 12 FLOPs, 3 s; the rest: 6 units at 1 FLOP, 2 FLOP/s: 3 s
+    assert co.partition_latencies(0.25, 8.0, 6.0, 1.0, 4.0, 2.0) == (3.0, 3.0)
+    assert co.partition_latencies(1.0, 8.0, 6.0, 1.0, 4.0, 2.0) == (12.0, 0.0)
+    assert co.partition_latencies(0.0, 8.0, 6.0, 1.0, 4.0, 2.0) == (0.0, 4.0)
+
+
+def test_partition_flop_counts_are_the_printed_ones():
+    B, N, E, W = 3, 7, 5, 11
+    # windowed: 2 B H0 E N W + 3 B H0 N W
+    assert co.sparse_flops(B, 2, N, E, W) == 2 * B * 2 * E * N * W + 3 * B * 2 * N * W
+    # linear: (4 + 2 + 2) B N (H1 E)^2
+    assert co.linear_flops(B, 4, N, E, co.FLOPS_PAPER) == 8 * B * N * (4 * E) ** 2
+    assert co.linear_flops(B, 4, N, E, co.FLOPS_PER_HEAD) == 8 * B * N * 4 * E ** 2
+    assert co.linear_flops(B, 1, N, E, co.FLOPS_PAPER) == co.linear_flops(B, 1, N, E, co.FLOPS_PER_HEAD)
+    assert co.sparse_flops(B, 0, N, E, W) == 0 and co.linear_flops(B, 0, N, E) == 0
+
+
+@pytest.mark.parametrize("case", range(4))
+def test_partition_heads_worked_examples(case):
+    ex = _partition_golden()["heads"][case]
+    model = co.FLOPS_PAPER if ex["flop_model"] == "paper" else co.FLOPS_PER_HEAD
+    h0, ls, ll = co.partition_heads(ex["B"], ex["H"], ex["N"], ex["E"], ex["W"], float(_fr(ex["perf_sparse"])),
+                                    float(_fr(ex["perf_linear"])), model)
+    assert h0 == ex["H0"], ex["why"]
+    assert ls == float(_fr(ex["latency_sparse"])) and ll == float(_fr(ex["latency_linear"]))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_partition_heads_against_exact_rational_search(seed):
+    rng = random.Random(100 + seed)
+    B, H, N, E, W = rng.randint(1, 4), rng.randint(1, 40), rng.randint(1, 4096), rng.choice([16, 64, 128]), rng.randint(1, 512)
+    ps, pl = Fraction(rng.randint(1, 10 ** 6)), Fraction(rng.randint(1, 10 ** 6))
+    for model in (co.FLOPS_PAPER, co.FLOPS_PER_HEAD):
+        gaps = []
+        for h0 in range(H + 1):
+            fs = Fraction(2 * B * h0 * E * N * W + 3 * B * h0 * N * W)
+            h1 = H - h0
+            fl = Fraction(8 * B * N * ((h1 * E) ** 2 if model == co.FLOPS_PAPER else h1 * E * E))
+            gaps.append(abs(fs / ps - fl / pl))
+        want = min(range(H + 1), key=lambda h: (gaps[h], h))
+        got, ls, ll = co.partition_heads(B, H, N, E, W, float(ps), float(pl), model)
+        # the float search may only differ from the exact one on a near-tie
+        assert got == want or abs(float(gaps[got] - gaps[want])) <= 1e-9 * float(max(gaps))
+        assert abs(abs(ls - ll) - float(gaps[got])) <= 1e-9 * float(max(gaps))
+
+
+def test_partition_heads_follows_the_continuous_balance():
+    """With heads counted one by one both latencies are linear in the head count, so the head
+    search must land within one head of H times the share Algorithm 2 returns."""
+    B, H, N, E, W = 4, 32, 8192, 128, 256
+    ps, pl = 3.0e14, 2.0e14
+    pp = co.partition_balance(0.5, float(H), co.sparse_flops(B, 1, N, E, W), co.linear_flops(B, 1, N, E, co.FLOPS_PER_HEAD), ps, pl)
+    h0, _, _ = co.partition_heads(B, H, N, E, W, ps, pl, co.FLOPS_PER_HEAD)
+    assert abs(h0 - pp * H) <= 0.5 + 1e-9
