@@ -208,6 +208,28 @@ def main() -> int:
                            "tflops": round(fl / s / 1e12, 2),
                            "pct_mfma_peak": round(100 * fl / s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
                            "pct_hbm_peak": round(100 * by / s / 1e9 / HBM_PEAK_GBS, 2)}
+        # Section III-D's partition model re-fitted on this machine: the average performance of
+        # each head kind comes from the two runs above (under the section's own FLOP counts, heads
+        # counted one by one), Algorithm 2 over whole heads gives the split with equal latencies,
+        # and the layer is timed at that split.  The two kinds share one set of compute units
+        # here and run one after the other, so the step costs the SUM of the two latencies
+        # (checked below) and equal latencies are a description of the split, not an optimum.
+        f_sparse = 2.0 * wl.B * wl.H * wl.d * wl.N * wl.window + 3.0 * wl.B * wl.H * wl.N * wl.window
+        f_linear = 8.0 * wl.B * wl.N * wl.H * wl.d * wl.d
+        perf_s = f_sparse / (modes["all_windowed"]["ms"] * 1e-3)
+        perf_l = f_linear / (modes["all_linear"]["ms"] * 1e-3)
+        h0_bal, lat_bal = gb.gformer_partition_heads(wl.B, wl.H, wl.N, wl.d, wl.window, perf_s, perf_l,
+                                                     gb.GF_FLOPS_PER_HEAD)
+        c_bal, _, _w_bal = make_call(h0_bal)
+        s_bal = time_steps(c_bal, max(5, args.steps // 2), 3)
+        modes["partition"] = {"perf_sparse_tflops": round(perf_s / 1e12, 1),
+                              "perf_linear_tflops": round(perf_l / 1e12, 1),
+                              "flop_model": "per_head", "H0_balanced": h0_bal,
+                              "model_latency_ms": [round(x * 1e3, 4) for x in lat_bal],
+                              "model_ms_serial": round(sum(lat_bal) * 1e3, 4),
+                              "measured_ms": round(s_bal * 1e3, 4),
+                              "note": "Algorithm 2 over whole heads with performances measured in this run; "
+                                      "one engine runs both kinds in turn, so the step is the sum of the two"}
         # Section III-A's alternative feature map: Q and K of the linear heads mapped by the
         # random-feature kernel (two launches), then the same layer with the identity map.
         if H0 < wl.H:

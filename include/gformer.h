@@ -209,6 +209,47 @@ void gformer_feature_params_init(gformer_feature_params* p);
 gf_status gformer_random_features(const void* x, const void* w, void* out, int B, int H, int N,
                                   int d, int m, const gformer_feature_params* p, void* hip_stream);
 
+/* ---- Head partition model (Section III-D, Algorithm 2 and the two latency estimates) -------
+ * Host arithmetic only: no device is touched and no stream is taken.
+ *
+ * gformer_partition_balance is Algorithm 2 as printed: a share p of `size` units goes to
+ * partition 0 and 1-p to partition 1; each partition's latency is its FLOPs (share x size x
+ * FLOPs per unit) over its average performance; the result p' is the share at which the two
+ * latencies are equal,  p' = (flops_per1/perf1) / (flops_per0/perf0 + flops_per1/perf1).
+ *   in       : host, read.  size, perf0, perf1 > 0; flops_per0, flops_per1 >= 0 and not both 0;
+ *              p in [0,1] (the initial share; it only selects what latency[0..1] report)
+ *   p_prime  : host, written
+ *   latency  : host, 4 doubles written, or NULL: latency0(p), latency1(p), latency0(p'),
+ *              latency1(p') in seconds when perf is in FLOP/s
+ * GF_ERR_INVALID_ARG for a null pointer, a wrong struct_size, a non-finite or out-of-range field. */
+typedef struct gformer_partition_inputs {
+  uint32_t struct_size;   /* = sizeof(gformer_partition_inputs)                              */
+  int32_t reserved0;      /* 0                                                               */
+  double p;               /* initial share of partition 0                                    */
+  double size;            /* problem size, in the units the FLOP counts are per              */
+  double flops_per0, flops_per1; /* FLOPs per unit of partition 0 / 1                        */
+  double perf0, perf1;    /* average performance of partition 0 / 1, FLOP/s                  */
+} gformer_partition_inputs;
+
+gf_status gformer_partition_balance(const gformer_partition_inputs* in, double* p_prime,
+                                    double* latency);
+
+/* The same balance over whole heads, with the FLOP counts of Section III-D: H0 windowed heads
+ * cost 2*B*H0*E*N*W (scores) + 3*B*H0*N*W (softmax) FLOPs (the two terms as printed; the total
+ * printed under them drops the factor E of the first and is not used), H1 = H-H0 linear heads
+ * cost 8*B*N*(H1*E)^2 with GF_FLOPS_PAPER (the printed count, which treats the linear heads as
+ * one contraction of width H1*E) or 8*B*N*H1*E^2 with GF_FLOPS_PER_HEAD (heads independent, as
+ * the kernels of this library run them).  Returns in *H0 the head count in [0,H] whose two
+ * latencies are closest (the smaller count on a tie), and in latency[0..1] (may be NULL) the
+ * windowed and the linear latency at that count.
+ *   perf_sparse, perf_linear : measured average FLOP/s of the two head kinds under the same
+ *                              FLOP count, > 0
+ * GF_ERR_INVALID_ARG for null H0, sizes < 1, a bad flop_model or a non-positive performance. */
+typedef enum gf_flop_model { GF_FLOPS_PAPER = 0, GF_FLOPS_PER_HEAD = 1 } gf_flop_model;
+
+gf_status gformer_partition_heads(int B, int H, int N, int E, int W, double perf_sparse,
+                                  double perf_linear, int flop_model, int* H0, double* latency);
+
 const char* gformer_status_string(gf_status s);
 
 /* major*10000 + minor*100 + patch */

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(HERE, "libgformer_attn.so")
 GF_OK, GF_ERR_INVALID_ARG, GF_ERR_UNSUPPORTED, GF_ERR_WORKSPACE, GF_ERR_DEVICE = range(5)
 GF_F32, GF_BF16 = 0, 1
 GF_PHI_ELU1, GF_PHI_IDENTITY = 0, 1
+GF_FLOPS_PAPER, GF_FLOPS_PER_HEAD = 0, 1
 GF_IMPL_AUTO, GF_IMPL_SCALAR, GF_IMPL_MFMA = 0, 1, 2
 GF_LAUNCH_WINDOWED, GF_LAUNCH_LINEAR_STATE, GF_LAUNCH_LINEAR_MAIN = 1, 2, 4
 
@@ -24,6 +25,7 @@ EXPORTS = ("gformer_params_init", "gformer_attn_workspace_bytes", "gformer_attn_
            "gformer_attn_fwd", "gformer_attn_prefill", "gformer_attn_decode",
            "gformer_feature_params_init",
            "gformer_random_features",
+           "gformer_partition_balance", "gformer_partition_heads",
            "gformer_status_string", "gformer_version")
 
 
@@ -55,6 +57,13 @@ class GformerFeatureParams(ctypes.Structure):
                 ("head_begin", ctypes.c_int32), ("head_end", ctypes.c_int32),
                 ("impl", ctypes.c_int32), ("reserved0", ctypes.c_int32),
                 ("x_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3)]
+
+
+class GformerPartitionInputs(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("reserved0", ctypes.c_int32),
+                ("p", ctypes.c_double), ("size", ctypes.c_double),
+                ("flops_per0", ctypes.c_double), ("flops_per1", ctypes.c_double),
+                ("perf0", ctypes.c_double), ("perf1", ctypes.c_double)]
 
 
 class GformerError(RuntimeError):
@@ -97,6 +106,13 @@ def lib():
         L.gformer_random_features.restype = ctypes.c_int
         L.gformer_random_features.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 5 + \
             [FP, ctypes.c_void_p]
+        L.gformer_partition_balance.restype = ctypes.c_int
+        L.gformer_partition_balance.argtypes = [ctypes.POINTER(GformerPartitionInputs),
+                                                ctypes.POINTER(ctypes.c_double),
+                                                ctypes.POINTER(ctypes.c_double)]
+        L.gformer_partition_heads.restype = ctypes.c_int
+        L.gformer_partition_heads.argtypes = [ctypes.c_int] * 5 + [ctypes.c_double] * 2 + \
+            [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)]
         L.gformer_status_string.restype = ctypes.c_char_p
         L.gformer_status_string.argtypes = [ctypes.c_int]
         L.gformer_version.restype = ctypes.c_int
@@ -355,3 +371,28 @@ def gformer_attn_prefill(q, k, v, out, kcache, vcache, state, window: int, n_spa
     if st != GF_OK:
         raise GformerError(st, gformer_status_string(st))
     return out
+
+
+def gformer_partition_balance(p, size, flops_per0, flops_per1, perf0, perf1):
+    """Algorithm 2 through the C ABI (host arithmetic).  Returns (p', [latency0(p), latency1(p),
+    latency0(p'), latency1(p')])."""
+    inp = GformerPartitionInputs(ctypes.sizeof(GformerPartitionInputs), 0, p, size, flops_per0,
+                                 flops_per1, perf0, perf1)
+    pp = ctypes.c_double()
+    lat = (ctypes.c_double * 4)()
+    st = int(lib().gformer_partition_balance(ctypes.byref(inp), ctypes.byref(pp), lat))
+    if st != GF_OK:
+        raise GformerError(st, gformer_status_string(st))
+    return pp.value, list(lat)
+
+
+def gformer_partition_heads(B, H, N, E, W, perf_sparse, perf_linear, flop_model=GF_FLOPS_PAPER):
+    """The balance of Section III-D over whole heads.  Returns (H0, [windowed latency, linear
+    latency])."""
+    h0 = ctypes.c_int()
+    lat = (ctypes.c_double * 2)()
+    st = int(lib().gformer_partition_heads(int(B), int(H), int(N), int(E), int(W), float(perf_sparse),
+                                           float(perf_linear), int(flop_model), ctypes.byref(h0), lat))
+    if st != GF_OK:
+        raise GformerError(st, gformer_status_string(st))
+    return h0.value, list(lat)
