@@ -82,6 +82,11 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
     for (int ks = 0; ks < KS; ++ks)
       qreg[ks] = as_bf16x8(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qr + 16 * ks)));
   }
+  // Memory loads retire in issue order, so the wait for the first tile below also covers these
+  // loads, but only if they stay in front of it: were they to slip behind, every later use of Q
+  // would have to wait for whatever tile load is in flight at that point, and the prefetch
+  // distance of the loop would be lost.
+  __builtin_amdgcn_sched_barrier(0);
 
   f32x16 oacc[MT];
 #pragma unroll
