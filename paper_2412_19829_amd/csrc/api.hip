@@ -76,6 +76,11 @@ gf_status check_strides(const int64_t* in, int64_t* out, int H, int N, int d) {
 int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // Shared by gformer_attn_plan, gformer_attn_workspace_bytes and gformer_attn_fwd.
+// Token i of a windowed head sees keys i - left .. i + right (cut at the sequence ends): the w
+// tokens ending at i, or (bidirectional) the w tokens centred on it.
+int window_left(int window, int bidirectional) { return bidirectional ? window / 2 : window - 1; }
+int window_right(int window, int bidirectional) { return bidirectional ? window - 1 - window / 2 : 0; }
+
 gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* p, Resolved* r) {
   memset(r, 0, sizeof(*r));
   if (!p) return GF_ERR_INVALID_ARG;
@@ -83,7 +88,8 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   if (B < 0 || H < 0 || N < 0 || d < 1 || window < 1) return GF_ERR_INVALID_ARG;
   if (p->dtype != GF_F32 && p->dtype != GF_BF16) return GF_ERR_INVALID_ARG;
   if (p->phi != GF_PHI_ELU1 && p->phi != GF_PHI_IDENTITY) return GF_ERR_INVALID_ARG;
-  if (p->impl != GF_IMPL_AUTO && p->impl != GF_IMPL_SCALAR && p->impl != GF_IMPL_MFMA)
+  if (p->impl != GF_IMPL_AUTO && p->impl != GF_IMPL_SCALAR && p->impl != GF_IMPL_MFMA &&
+      p->impl != GF_IMPL_MFMA_BLOCKED)
     return GF_ERR_INVALID_ARG;
   if (p->n_sparse_heads < 0 || p->n_sparse_heads > H) return GF_ERR_INVALID_ARG;
   if (p->chunk < 0 || p->segment_len < 0) return GF_ERR_INVALID_ARG;
@@ -101,6 +107,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
 
   int impl = p->impl;
   if (impl == GF_IMPL_AUTO) impl = (p->dtype == GF_BF16) ? GF_IMPL_MFMA : GF_IMPL_SCALAR;
+  if (impl == GF_IMPL_MFMA_BLOCKED) impl = GF_IMPL_MFMA;   // differs only in the windowed launch
   if (impl == GF_IMPL_MFMA && p->dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
   if (p->chunk != 0 && p->chunk != 64) return GF_ERR_UNSUPPORTED;
 
@@ -175,6 +182,15 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   pl.n_segments = (int)pieces;
   pl.windowed_threads = kMfmaWindowThreads;
   pl.windowed_blocks = (H0 > 0 && N > 0) ? B * H0 * ((N + kMfmaWindowRows - 1) / kMfmaWindowRows) : 0;
+  if (p->impl != GF_IMPL_MFMA_BLOCKED) {
+    // windows of at most five key tiles go to the streaming kernel
+    const StreamPlan sp = windowed_stream_plan((int64_t)B * H0, N, window_left(window, p->bidirectional),
+                                               window_right(window, p->bidirectional));
+    if (sp.applies) {
+      pl.windowed_threads = sp.threads;
+      pl.windowed_blocks = (int)sp.blocks;
+    }
+  }
   pl.linear_threads = mfma_linear_threads(d);
   pl.linear_blocks = (int)pieces;
   pl.state_blocks = (int)mid;
@@ -247,8 +263,8 @@ gf_status attn_forward(const void* q, const void* k, const void* v, void* out, v
   a.B = B; a.H = H; a.N = N; a.d = d;
   a.window = window;
   a.causal = p->bidirectional ? 0 : 1;
-  a.wleft = p->bidirectional ? window / 2 : window - 1;
-  a.wright = p->bidirectional ? window - 1 - window / 2 : 0;
+  a.wleft = window_left(window, p->bidirectional);
+  a.wright = window_right(window, p->bidirectional);
   a.H0 = p->n_sparse_heads;
   a.phi = p->phi;
   a.scale = p->softmax_scale;
@@ -273,6 +289,12 @@ gf_status attn_forward(const void* q, const void* k, const void* v, void* out, v
     if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_scalar(a, bf16, s);
   } else {
     const bool win = (mask & GF_LAUNCH_WINDOWED) && a.H0 > 0;
+    // windows of at most five key tiles stream; wider ones go query block by query block
+    const bool stream = p->impl != GF_IMPL_MFMA_BLOCKED &&
+                        windowed_stream_plan((int64_t)a.B * a.H0, a.N, a.wleft, a.wright).applies;
+    auto launch_windowed = [&](hipStream_t on) {
+      return stream ? launch_windowed_stream(a, on) : launch_windowed_mfma(a, on);
+    };
     const bool lin = (mask & (GF_LAUNCH_LINEAR_STATE | GF_LAUNCH_LINEAR_MAIN)) && a.H0 < a.H;
     std::lock_guard<std::mutex> lock(g_enqueue_mutex);
     SideStream* side = nullptr;
@@ -281,7 +303,7 @@ gf_status attn_forward(const void* q, const void* k, const void* v, void* out, v
       // fork: the windowed heads wait for what is already in `s`, then run beside the linear ones
       e = hipEventRecord(side->fork, s);
       if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
-      if (e == hipSuccess) e = launch_windowed_mfma(a, side->stream);
+      if (e == hipSuccess) e = launch_windowed(side->stream);
       if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
     }
     // The read-out kernel wants every compute unit at once (one piece each), so only the state
@@ -290,7 +312,7 @@ gf_status attn_forward(const void* q, const void* k, const void* v, void* out, v
     if (side) {
       if (e == hipSuccess) e = hipStreamWaitEvent(s, side->join, 0);  // join
     } else if (win && e == hipSuccess) {
-      e = launch_windowed_mfma(a, s);
+      e = launch_windowed(s);
     }
     if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_main_mfma(a, s);
   }

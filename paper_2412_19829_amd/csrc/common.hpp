@@ -40,6 +40,9 @@ struct AttnArgs {
                      // token, A row-major [feature][value] (what the decode step carries on from)
   void *kring, *vring; // optional [B, H0, window, d] rings: the last `window` keys / values of every
                      // windowed head, token t in slot t % window
+  // Streaming windowed kernel: every (batch, windowed head) is cut into `win_pieces_per_head`
+  // pieces of `win_pairs_per_piece` pairs of 32-query groups (set by its launcher).
+  int win_pairs_per_piece, win_pieces_per_head;
   float* ws_states;  // [n_pieces*state_sub, d*d + d] fp32: slot j = (A, Z) of its head just
                      // before global chunk j*piece_chunks/state_sub (piece p reads slot p*state_sub)
 };
@@ -106,6 +109,17 @@ struct DecodeArgs {
 hipError_t launch_windowed_scalar(const AttnArgs& a, bool bf16, hipStream_t s);
 hipError_t launch_linear_scalar(const AttnArgs& a, bool bf16, hipStream_t s);
 hipError_t launch_windowed_mfma(const AttnArgs& a, hipStream_t s);
+// The streaming form of the same heads, for windows that span at most kStreamSlots key tiles.
+constexpr int kStreamSlots = 5;
+struct StreamPlan {
+  bool applies;          // the window fits the kernel
+  int pairs_per_piece;   // 64-query pairs one workgroup walks
+  int pieces_per_head;
+  int64_t blocks;        // workgroups = heads * pieces_per_head
+  int threads;
+};
+StreamPlan windowed_stream_plan(int64_t heads, int N, int wleft, int wright);
+hipError_t launch_windowed_stream(const AttnArgs& a, hipStream_t s);
 hipError_t launch_linear_state_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_linear_main_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_fill_rings(const AttnArgs& a, bool bf16, hipStream_t s);

@@ -58,6 +58,39 @@ __device__ __forceinline__ float dot2_ones_bf16(uint32_t a, float acc) {
   return dot2_bf16(a, kOnesBf16x2, acc);
 }
 
+// max(a, b, c) / min(a, b, c) in one instruction.  The library forms never see a NaN here (scores
+// are finite or the infinity a mask put there), and written this way the compiler does not add
+// the quieting moves it puts in front of every fmaxf / fminf.
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ float min3(float a, float b, float c) {
+  float r;
+  asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+// Lanes l and l^32 exchange a value (v_permlane32_swap): `a` and `b` come back as the lane's own
+// x and its partner's, in an order that depends on the half of the wave, so only symmetric
+// combinations (max, sum) of the two are meaningful.
+__device__ __forceinline__ void exchange_halves(float x, float& a, float& b) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  a = __uint_as_float(r[0]);
+  b = __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float max_over_halves(float x) {
+  float a, b;
+  exchange_halves(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_over_halves(float x) {
+  float a, b;
+  exchange_halves(x, a, b);
+  return a + b;
+}
+
 __host__ __device__ constexpr int kperm32(int k) {
   return 16 * (k / 16) + 8 * ((k / 4) % 2) + 4 * ((k / 8) % 2) + k % 4;
 }
@@ -89,6 +122,22 @@ __device__ __forceinline__ u32x2 lds_tr4(const uint16_t* p) {
 // gathered from a ROW-MAJOR tile whose rows are the contraction index: slots 0..3 come from
 // tile rows rowA .. rowA+3 and slots 4..7 from rows rowB .. rowB+3 (callers add their own
 // dependence on l/32).  `stride` is the tile's row stride in elements.
+// The lane-dependent part of lds_operand_tr's addresses, in elements: what is left is uniform.
+__device__ __forceinline__ int lds_operand_tr_lane_offset(int stride, int lane) {
+  const int p = lane & 15;
+  return (p >> 2) * stride + 16 * ((lane >> 4) & 1) + 4 * (p & 3);
+}
+// lds_operand_tr with the lane-dependent part precomputed: tile + lane_off points at this
+// lane's element of (row 0, column 0); rowA, rowB and col0 are uniform.
+__device__ __forceinline__ bf16x8 lds_operand_tr_at(const uint16_t* tile_lane, int stride, int rowA,
+                                                    int rowB, int col0) {
+  const u32x2 a = lds_tr4(tile_lane + rowA * stride + col0);
+  const u32x2 b = lds_tr4(tile_lane + rowB * stride + col0);
+  u32x4 r;
+  r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+  return as_bf16x8(r);
+}
+
 __device__ __forceinline__ bf16x8 lds_operand_tr(const uint16_t* tile, int stride, int rowA,
                                                  int rowB, int col0, int lane) {
   const int p = lane & 15;

@@ -53,7 +53,16 @@ def test_plan_headline_config():
     # 104 linear heads x 128 chunks cut into equal pieces, one per compute unit
     assert pl["chunk"] == 64 and pl["segment_len"] == 52 * 64
     assert pl["n_segments"] == 256 and pl["linear_blocks"] == 256
-    assert pl["windowed_blocks"] == 4 * 6 * (8192 // 128)
+    # window 256 spans five key tiles: the streaming kernel, 24 (batch, head) pairs cut into
+    # 256 // 24 = 10 pieces of ceil(128 / 10) = 13 pairs of 32-query groups each
+    assert pl["windowed_blocks"] == 24 * 10 and pl["windowed_threads"] == 768
+    st, blocked = _plan(4, 32, 8192, 128, 256, n_sparse_heads=6, impl=gb.GF_IMPL_MFMA_BLOCKED)
+    assert st == gb.GF_OK and blocked["impl"] == gb.GF_IMPL_MFMA
+    assert blocked["windowed_blocks"] == 4 * 6 * (8192 // 128) and blocked["windowed_threads"] == 256
+    st, wide = _plan(4, 32, 8192, 128, 258, n_sparse_heads=6)     # six tiles: query blocks
+    assert st == gb.GF_OK and wide["windowed_blocks"] == 4 * 6 * (8192 // 128)
+    st, centred = _plan(4, 32, 8192, 128, 257, n_sparse_heads=6, bidirectional=1)
+    assert st == gb.GF_OK and centred["windowed_threads"] == 768
     # The state pass works on half pieces (26 chunks).  A half-piece boundary e inside a head is
     # summed iff a piece boundary (multiple of 52) at or after e lies inside the same head.
     mid = 0
@@ -114,6 +123,8 @@ def test_plan_modes_and_overrides():
     ((1, 2, 16, 64, 4), {"chunk": 256}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 16, 64, 4), {"chunk": 128}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 16, 64, 4), {"dtype": gb.GF_F32, "impl": gb.GF_IMPL_MFMA}, gb.GF_ERR_UNSUPPORTED),
+    ((1, 2, 16, 64, 4), {"dtype": gb.GF_F32, "impl": gb.GF_IMPL_MFMA_BLOCKED}, gb.GF_ERR_UNSUPPORTED),
+    ((1, 2, 16, 64, 4), {"impl": 4}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 256, 64, 4), {"dtype": gb.GF_F32, "segment_len": 64}, gb.GF_ERR_UNSUPPORTED),
     ((70000, 2, 16, 64, 4), {}, gb.GF_ERR_UNSUPPORTED),
 ])
