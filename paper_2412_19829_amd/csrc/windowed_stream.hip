@@ -15,6 +15,8 @@
 // Per tile and consumer wave, as in the query-block kernel:  S^T = K Q^T  (keys x queries, one
 // lane owns one query column), online softmax in base 2 with lane-local running max / sum, then
 // O^T += V^T P^T with P^T taken straight from the score registers.
+#include <type_traits>
+
 #include "common.hpp"
 #include "mfma.hpp"
 
@@ -177,10 +179,9 @@ __global__ __launch_bounds__(NT, 1) void windowed_stream_kernel(AttnArgs a) {
       const uint16_t* qrow = &sm.q[s & 1][(WQ * hf + ln) * Smem::QROW + 8 * lh];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) qreg[ks] = lds_read16(qrow + 16 * ks);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[mt][r] = 0.f;
+      // The accumulators are not cleared here: with the running maximum back at -inf, the first
+      // visible key of a query triggers the rescale below with a factor of exactly 0, which
+      // clears them (they hold the previous pair's finite sums) before anything is added.
       m_run = -INFINITY;
       l_run = 0.f;
     }
@@ -193,6 +194,10 @@ __global__ __launch_bounds__(NT, 1) void windowed_stream_kernel(AttnArgs a) {
       const bool need_mask =
           !(t0 + BC - 1 <= q0 + wr && t0 >= q0 + WQ - 1 - wl && t0 + BC <= N);
 
+      // One copy of the tile body with the window mask and one without: left to itself the
+      // compiler turns the mask into selects that run on every tile.
+      auto tile_body = [&](auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
       // The two 32-key halves of the tile one after the other (scores of one half live at a
       // time): S^T = K Q^T, online softmax, O^T += V^T P^T.
       constexpr float worst = NEG ? INFINITY : -INFINITY;
@@ -202,18 +207,25 @@ __global__ __launch_bounds__(NT, 1) void windowed_stream_kernel(AttnArgs a) {
       const int hi = min(qi + wr, N - 1);
       const int rel = hi - t0 - 4 * lh;
       const int wv = max(hi - qi + wl + 1, 0);   // visible keys of this query (0: a row past N)
+      // both score products are issued before the first softmax, so that the second runs on the
+      // matrix core while the vector unit works on the first
+      f32x16 sboth[2];
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt) {
-        f32x16 sreg;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sreg[r] = 0.f;
+        for (int r = 0; r < 16; ++r) sboth[kt][r] = 0.f;
         const uint16_t* krow = &cur.k[(32 * kt + ln) * Smem::KROW + 8 * lh];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
           const bf16x8 ka = lds_read16(krow + 16 * ks);
-          sreg = mfma32(ka, qreg[ks], sreg);
+          sboth[kt] = mfma32(ka, qreg[ks], sboth[kt]);
         }
-        if (need_mask) {
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        f32x16& sreg = sboth[kt];
+        if (MASKED) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int c = 32 * kt + 8 * (r / 4) + (r % 4);
@@ -254,21 +266,36 @@ __global__ __launch_bounds__(NT, 1) void windowed_stream_kernel(AttnArgs a) {
           lsum = dot2_ones_bf16(pk, lsum);
         }
         l_run += lsum;
+        // O^T += V^T P^T: 8 products (2 groups of 16 keys x 4 row tiles of O^T); the V operand
+        // of product i + PDV is fetched from LDS before product i is issued, so that the wave
+        // does not sit through one LDS round trip per product
+        bf16x8 pbv[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
           u32x4 pw;
           pw[0] = pb[4 * kb + 0]; pw[1] = pb[4 * kb + 1];
           pw[2] = pb[4 * kb + 2]; pw[3] = pb[4 * kb + 3];
-          const bf16x8 pbv = as_bf16x8(pw);
+          pbv[kb] = as_bf16x8(pw);
+        }
+        constexpr int NPV = 2 * MT, PDV = 1;
+        // keys in the order the score registers hold them: 16*kb + 4*lh + j, then + 8
+        auto v_operand = [&](int i) {
+          const int r0 = 32 * kt + 16 * (i / MT);
+          return lds_operand_tr_at(cur.v + vlane, Smem::VROW, r0, r0 + 8, 32 * (i % MT));
+        };
+        bf16x8 vop[NPV];
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            // keys in the order the score registers hold them: 16*kb + 4*lh + j, then + 8
-            const int r0 = 32 * kt + 16 * kb;
-            const bf16x8 va_ = lds_operand_tr_at(cur.v + vlane, Smem::VROW, r0, r0 + 8, 32 * mt);
-            oacc[mt] = mfma32(va_, pbv, oacc[mt]);
-          }
+        for (int i = 0; i < PDV && i < NPV; ++i) vop[i] = v_operand(i);
+#pragma unroll
+        for (int i = 0; i < NPV; ++i) {
+          if (i + PDV < NPV) vop[i + PDV] = v_operand(i + PDV);
+          oacc[i % MT] = mfma32(vop[i], pbv[i / MT], oacc[i % MT]);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
+          };
+      if (need_mask) tile_body(std::true_type{});
+      else tile_body(std::false_type{});
     }
     if (mine && t == m_cur + dr) {
       // the pair ends: normalise; the 32 rows go through this group's LDS patch (only one pair
