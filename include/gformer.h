@@ -68,14 +68,17 @@ typedef enum { GF_PHI_ELU1 = 0, GF_PHI_IDENTITY = 1 } gf_phi;
 /* Which implementation runs.  GF_IMPL_AUTO picks the MFMA kernels for bf16 and the scalar
  * fp32 kernels for fp32.  GF_IMPL_SCALAR forces the plain-FMA kernels (fp32 arithmetic on
  * either storage type); GF_IMPL_MFMA with GF_F32 is GF_ERR_UNSUPPORTED.
- * GF_IMPL_MFMA_BLOCKED is GF_IMPL_MFMA with the windowed heads always run by the kernel that
- * gives each workgroup one block of 128 queries, also where the streaming kernel (windows of at
- * most 257 tokens) would be chosen: same results, kept selectable for comparison. */
+ * GF_IMPL_MFMA runs the windowed heads by one of two kernels with the same results: a streaming
+ * kernel (windows of at most 257 tokens; chosen when the call has at least 1024 blocks of 128
+ * queries over all windowed heads) or a kernel that gives each workgroup one block of 128
+ * queries (everything else).  GF_IMPL_MFMA_BLOCKED / GF_IMPL_MFMA_STREAM force one of them, for
+ * comparison and tests; GF_IMPL_MFMA_STREAM with a wider window is GF_ERR_UNSUPPORTED. */
 typedef enum {
   GF_IMPL_AUTO = 0,
   GF_IMPL_SCALAR = 1,
   GF_IMPL_MFMA = 2,
-  GF_IMPL_MFMA_BLOCKED = 3
+  GF_IMPL_MFMA_BLOCKED = 3,
+  GF_IMPL_MFMA_STREAM = 4
 } gf_impl;
 
 typedef struct gformer_params {

@@ -18,6 +18,7 @@ struct Resolved {
   gformer_plan plan;
   int64_t qs[3], ks[3], vs[3], os[3];
   int cph, vcph, piece_chunks, state_sub;
+  bool stream;   // MFMA path: the windowed heads go to the streaming kernel
 };
 
 constexpr long kComputeUnits = 256;  // MI355X
@@ -89,7 +90,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   if (p->dtype != GF_F32 && p->dtype != GF_BF16) return GF_ERR_INVALID_ARG;
   if (p->phi != GF_PHI_ELU1 && p->phi != GF_PHI_IDENTITY) return GF_ERR_INVALID_ARG;
   if (p->impl != GF_IMPL_AUTO && p->impl != GF_IMPL_SCALAR && p->impl != GF_IMPL_MFMA &&
-      p->impl != GF_IMPL_MFMA_BLOCKED)
+      p->impl != GF_IMPL_MFMA_BLOCKED && p->impl != GF_IMPL_MFMA_STREAM)
     return GF_ERR_INVALID_ARG;
   if (p->n_sparse_heads < 0 || p->n_sparse_heads > H) return GF_ERR_INVALID_ARG;
   if (p->chunk < 0 || p->segment_len < 0) return GF_ERR_INVALID_ARG;
@@ -107,7 +108,8 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
 
   int impl = p->impl;
   if (impl == GF_IMPL_AUTO) impl = (p->dtype == GF_BF16) ? GF_IMPL_MFMA : GF_IMPL_SCALAR;
-  if (impl == GF_IMPL_MFMA_BLOCKED) impl = GF_IMPL_MFMA;   // differs only in the windowed launch
+  // the last two differ from GF_IMPL_MFMA only in which kernel runs the windowed heads
+  if (impl == GF_IMPL_MFMA_BLOCKED || impl == GF_IMPL_MFMA_STREAM) impl = GF_IMPL_MFMA;
   if (impl == GF_IMPL_MFMA && p->dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
   if (p->chunk != 0 && p->chunk != 64) return GF_ERR_UNSUPPORTED;
 
@@ -182,11 +184,12 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   pl.n_segments = (int)pieces;
   pl.windowed_threads = kMfmaWindowThreads;
   pl.windowed_blocks = (H0 > 0 && N > 0) ? B * H0 * ((N + kMfmaWindowRows - 1) / kMfmaWindowRows) : 0;
-  if (p->impl != GF_IMPL_MFMA_BLOCKED) {
-    // windows of at most five key tiles go to the streaming kernel
+  {
     const StreamPlan sp = windowed_stream_plan((int64_t)B * H0, N, window_left(window, p->bidirectional),
                                                window_right(window, p->bidirectional));
-    if (sp.applies) {
+    if (p->impl == GF_IMPL_MFMA_STREAM && H0 > 0 && !sp.applies) return GF_ERR_UNSUPPORTED;
+    r->stream = p->impl == GF_IMPL_MFMA_STREAM || (p->impl != GF_IMPL_MFMA_BLOCKED && sp.preferred);
+    if (r->stream && H0 > 0 && N > 0) {
       pl.windowed_threads = sp.threads;
       pl.windowed_blocks = (int)sp.blocks;
     }
@@ -289,9 +292,9 @@ gf_status attn_forward(const void* q, const void* k, const void* v, void* out, v
     if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_scalar(a, bf16, s);
   } else {
     const bool win = (mask & GF_LAUNCH_WINDOWED) && a.H0 > 0;
-    // windows of at most five key tiles stream; wider ones go query block by query block
-    const bool stream = p->impl != GF_IMPL_MFMA_BLOCKED &&
-                        windowed_stream_plan((int64_t)a.B * a.H0, a.N, a.wleft, a.wright).applies;
+    // large problems with windows of at most five key tiles stream; the rest goes query block
+    // by query block
+    const bool stream = r.stream;
     auto launch_windowed = [&](hipStream_t on) {
       return stream ? launch_windowed_stream(a, on) : launch_windowed_mfma(a, on);
     };

@@ -113,6 +113,7 @@ hipError_t launch_windowed_mfma(const AttnArgs& a, hipStream_t s);
 constexpr int kStreamSlots = 5;
 struct StreamPlan {
   bool applies;          // the window fits the kernel
+  bool preferred;        // ... and the problem is large enough for it to beat the query-block kernel
   int pairs_per_piece;   // 64-query pairs one workgroup walks
   int pieces_per_head;
   int64_t blocks;        // workgroups = heads * pieces_per_head

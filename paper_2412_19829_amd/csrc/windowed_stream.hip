@@ -358,6 +358,10 @@ StreamPlan windowed_stream_plan(int64_t heads, int N, int wleft, int wright) {
   sp.pairs_per_piece = ppp;
   sp.pieces_per_head = (int)pph;
   sp.blocks = heads * pph;
+  // A piece is a serial walk of pairs + halo steps of about 1.5 us each: with little work per
+  // compute unit the query-block kernel's many short independent workgroups finish sooner.
+  // Measured crossover: about two full rounds of its 128-query workgroups (2 per CU).
+  sp.preferred = heads * ((N + 127) / 128) >= 4 * kComputeUnits;
   return sp;
 }
 

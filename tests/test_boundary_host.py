@@ -63,6 +63,14 @@ def test_plan_headline_config():
     assert st == gb.GF_OK and wide["windowed_blocks"] == 4 * 6 * (8192 // 128)
     st, centred = _plan(4, 32, 8192, 128, 257, n_sparse_heads=6, bidirectional=1)
     assert st == gb.GF_OK and centred["windowed_threads"] == 768
+    # a small call (192 blocks of 128 queries) goes query block by query block unless told otherwise
+    st, small = _plan(1, 12, 2048, 64, 128, n_sparse_heads=12)
+    assert st == gb.GF_OK and small["windowed_threads"] == 256 and small["windowed_blocks"] == 12 * 16
+    st, forced = _plan(1, 12, 2048, 64, 128, n_sparse_heads=12, impl=gb.GF_IMPL_MFMA_STREAM)
+    assert st == gb.GF_OK and forced["windowed_threads"] == 768 and forced["impl"] == gb.GF_IMPL_MFMA
+    # with no windowed head the forced streaming choice has nothing to refuse
+    st, _none = _plan(1, 2, 600, 64, 300, n_sparse_heads=0, impl=gb.GF_IMPL_MFMA_STREAM)
+    assert st == gb.GF_OK
     # The state pass works on half pieces (26 chunks).  A half-piece boundary e inside a head is
     # summed iff a piece boundary (multiple of 52) at or after e lies inside the same head.
     mid = 0
@@ -124,7 +132,8 @@ def test_plan_modes_and_overrides():
     ((1, 2, 16, 64, 4), {"chunk": 128}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 16, 64, 4), {"dtype": gb.GF_F32, "impl": gb.GF_IMPL_MFMA}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 16, 64, 4), {"dtype": gb.GF_F32, "impl": gb.GF_IMPL_MFMA_BLOCKED}, gb.GF_ERR_UNSUPPORTED),
-    ((1, 2, 16, 64, 4), {"impl": 4}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"impl": 5}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 600, 64, 258), {"impl": gb.GF_IMPL_MFMA_STREAM, "n_sparse_heads": 1}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 256, 64, 4), {"dtype": gb.GF_F32, "segment_len": 64}, gb.GF_ERR_UNSUPPORTED),
     ((70000, 2, 16, 64, 4), {}, gb.GF_ERR_UNSUPPORTED),
 ])

@@ -14,6 +14,7 @@ from tests.helpers import max_abs, row_rel_l2
 pytestmark = pytest.mark.gpu
 
 SCALAR, MFMA, BLOCKED = gb.GF_IMPL_SCALAR, gb.GF_IMPL_MFMA, gb.GF_IMPL_MFMA_BLOCKED
+STREAM = gb.GF_IMPL_MFMA_STREAM
 
 
 def check(gpu, ref, dtype, what=""):
@@ -50,7 +51,7 @@ def test_tiny_f32(H0):
     check(got, oracle(q, k, v, wl.window, H0), "f32", f"tiny_f32 H0={H0}")
 
 
-@pytest.mark.parametrize("impl", [SCALAR, MFMA, BLOCKED], ids=["scalar", "mfma", "mfma-blocked"])
+@pytest.mark.parametrize("impl", [SCALAR, MFMA, BLOCKED, STREAM], ids=["scalar", "mfma", "mfma-blocked", "mfma-stream"])
 @pytest.mark.parametrize("H0", [12, 0, 2])
 def test_gpt2_small_bf16(H0, impl):
     wl = gi.WORKLOADS["gpt2_small"]
@@ -88,10 +89,12 @@ def test_f32_shapes(shape):
     check(got, oracle(q, k, v, w, H0), "f32", str(shape))
 
 
-@pytest.mark.parametrize("impl", [SCALAR, MFMA, BLOCKED], ids=["scalar", "mfma", "mfma-blocked"])
+@pytest.mark.parametrize("impl", [SCALAR, MFMA, BLOCKED, STREAM], ids=["scalar", "mfma", "mfma-blocked", "mfma-stream"])
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_bf16_shapes(shape, impl):
     B, H, N, d, w, H0 = shape
+    if impl == STREAM and H0 > 0 and w > 257:
+        pytest.skip("the streaming kernel takes windows of at most 257 tokens")
     q, k, v = synth(B, H, N, d, "bf16", 12)
     got = run_gpu(q, k, v, "bf16", w, H0, impl=impl)
     check(got, oracle(q, k, v, w, H0), "bf16", str(shape))
@@ -548,7 +551,7 @@ WINDOW_KERNEL_CASES = [
     # B, H0, N, d, window, bidirectional
     (1, 3, 1000, 128, 256, 0),     # the headline window, ragged length
     (1, 2, 4097, 128, 257, 0),     # widest causal window that still streams; one token past a tile
-    (1, 2, 2000, 128, 258, 0),     # one wider: the automatic choice falls back to query blocks
+    (1, 2, 2000, 128, 258, 0),     # one wider: query blocks only
     (2, 2, 777, 64, 100, 0),
     (1, 2, 50, 128, 33, 0),        # shorter than one tile
     (1, 2, 300, 64, 1, 0),         # every token sees itself only
@@ -556,16 +559,19 @@ WINDOW_KERNEL_CASES = [
     (1, 2, 129, 64, 200, 0),       # window wider than the sequence
     (1, 3, 1000, 128, 256, 1),     # centred windows
     (1, 2, 2049, 64, 257, 1),
-    (1, 2, 700, 128, 258, 1),      # falls back
+    (1, 2, 700, 128, 258, 1),      # query blocks only
     (1, 2, 90, 64, 7, 1),
     (70, 4, 130, 64, 40, 0),       # more (batch, head) pairs than compute units: one piece per head
+    (2, 20, 3300, 64, 256, 0),     # large enough for the automatic choice to stream
 ]
 
 
-@pytest.mark.parametrize("impl", [MFMA, BLOCKED], ids=["auto", "blocked"])
+@pytest.mark.parametrize("impl", [MFMA, BLOCKED, STREAM], ids=["auto", "blocked", "stream"])
 @pytest.mark.parametrize("case", WINDOW_KERNEL_CASES, ids=lambda c: "x".join(map(str, c)))
 def test_windowed_kernels_against_oracle(case, impl):
     B, H0, N, d, w, bi = case
+    if impl == STREAM and w > 257:
+        pytest.skip("the streaming kernel takes windows of at most 257 tokens")
     q, k, v = synth(B, H0, N, d, "bf16", 91)
     got = run_gpu(q, k, v, "bf16", w, H0, impl=impl, bidirectional=bi)
     ref = np.empty((B, H0, N, d))
@@ -582,5 +588,5 @@ def test_windowed_kernels_on_the_long_stress_pattern():
     B, H0, N, d, w = 1, 2, 3000, wl.d, 256
     q, k, v = synth(B, H0, N, d, "bf16", 92, q_prescaled=False, sigma=0.5, outlier_every=64, outlier_gain=8.0)
     ref = np.stack([co.windowed_head(q[0, h], k[0, h], v[0, h], w) for h in range(H0)])[None]
-    for impl in (MFMA, BLOCKED):
+    for impl in (MFMA, BLOCKED, STREAM):
         check(run_gpu(q, k, v, "bf16", w, H0, impl=impl), ref, "bf16", f"stress impl={impl}")
