@@ -1,6 +1,9 @@
 // Windowed softmax attention heads on bf16 matrix cores (section III-B, Eq. 1): the causal window
 // ending at the token, or (bidirectional variant) the window centred on it.
 //
+// The query-block kernel: used for windows wider than five key tiles and for small calls (the
+// streaming kernel in windowed_stream.hip takes the rest).
+//
 // One workgroup (4 waves) owns 128 consecutive queries of one (batch, head); each wave owns 32
 // of them.  The band of keys those queries can see is walked in tiles of 64 keys; tiles outside
 // the band are never touched.  K and V tiles sit in LDS row-major, shared by the 4 waves; K is
