@@ -590,3 +590,35 @@ def test_windowed_kernels_on_the_long_stress_pattern():
     ref = np.stack([co.windowed_head(q[0, h], k[0, h], v[0, h], w) for h in range(H0)])[None]
     for impl in (MFMA, BLOCKED, STREAM):
         check(run_gpu(q, k, v, "bf16", w, H0, impl=impl), ref, "bf16", f"stress impl={impl}")
+
+
+# ---------------------------------------------------------------------------------------
+# seeded sweep over shapes, windows, head splits, layouts and kernel choices
+# ---------------------------------------------------------------------------------------
+
+def _sweep_cases():
+    rng = np.random.default_rng(2024)
+    cases = []
+    for _ in range(36):
+        d = int(rng.choice([64, 128]))
+        B = int(rng.integers(1, 4))
+        H = int(rng.integers(1, 6))
+        N = int(rng.choice([int(rng.integers(1, 70)), int(rng.integers(70, 700)), int(rng.integers(700, 2600))]))
+        w = int(rng.choice([1, int(rng.integers(2, 40)), int(rng.integers(40, 258)), int(rng.integers(258, 900))]))
+        H0 = int(rng.integers(0, H + 1))
+        bi = int(rng.integers(0, 2))
+        layout = "bnhd" if rng.integers(0, 3) == 0 else "bhnd"
+        impl = [MFMA, BLOCKED, STREAM, SCALAR][int(rng.integers(0, 4))]
+        if impl == STREAM and H0 > 0 and w > 257:
+            impl = MFMA
+        cases.append((B, H, N, d, w, H0, bi, layout, impl))
+    return cases
+
+
+@pytest.mark.parametrize("case", _sweep_cases(), ids=lambda c: "x".join(map(str, c)))
+def test_seeded_sweep(case):
+    B, H, N, d, w, H0, bi, layout, impl = case
+    q, k, v = synth(B, H, N, d, "bf16", 500 + N + w)
+    got = run_gpu(q, k, v, "bf16", w, H0, layout=layout, impl=impl, bidirectional=bi)
+    ref = co.attn_fwd(q, k, v, w, H0, linear_form=co.LINEAR_RECURRENT, bidirectional=bool(bi))
+    check(got, ref, "bf16", str(case))
