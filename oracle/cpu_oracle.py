@@ -53,6 +53,12 @@ def lib():
         L.gformer_oracle_decode_linear_f64.restype = ctypes.c_int
         L.gformer_oracle_decode_linear_f64.argtypes = [_dp] * 6 + [ctypes.c_int, ctypes.c_int,
                                                                 ctypes.c_double]
+        L.gformer_oracle_windowed_head_bwd_f64.restype = ctypes.c_int
+        L.gformer_oracle_windowed_head_bwd_f64.argtypes = [_dp] * 7 + [ctypes.c_int] * 3 + [ctypes.c_double]
+        L.gformer_oracle_linear_head_bwd_f64.restype = ctypes.c_int
+        L.gformer_oracle_linear_head_bwd_f64.argtypes = [_dp] * 7 + [ctypes.c_int] * 3 + [ctypes.c_double]
+        L.gformer_oracle_bwd_f64.restype = ctypes.c_int
+        L.gformer_oracle_bwd_f64.argtypes = [_dp] * 7 + [ctypes.c_int] * 7 + [ctypes.c_double] * 2
         L.gformer_oracle_max_threads.restype = ctypes.c_int
         L.gformer_oracle_random_features_f64.restype = ctypes.c_int
         L.gformer_oracle_random_features_f64.argtypes = [_dp, _dp, _dp, ctypes.c_long,
@@ -110,6 +116,45 @@ def attn_fwd(q, k, v, window, n_sparse_heads, phi=PHI_ELU1, softmax_scale=1.0, e
     if rc:
         raise RuntimeError(f"oracle layer call failed: {rc}")
     return out
+
+
+def windowed_head_bwd(q, k, v, dout, window, scale=1.0):
+    """Gradients (dq, dk, dv) of a causal windowed head, [N, d] each, for output gradient dout."""
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v); dout, dop = _c(dout)
+    N, d = q.shape
+    dq, dk, dv = (np.empty((N, d), np.float64) for _ in range(3))
+    rc = lib().gformer_oracle_windowed_head_bwd_f64(qp, kp, vp, dop, dq.ctypes.data_as(_dp),
+                                                    dk.ctypes.data_as(_dp), dv.ctypes.data_as(_dp),
+                                                    N, d, int(window), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle windowed backward failed: {rc}")
+    return dq, dk, dv
+
+
+def linear_head_bwd(q, k, v, dout, phi=PHI_ELU1, eps=0.0):
+    """Gradients (dq, dk, dv) of a causal linear head, [N, d] each, for output gradient dout."""
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v); dout, dop = _c(dout)
+    N, d = q.shape
+    dq, dk, dv = (np.empty((N, d), np.float64) for _ in range(3))
+    rc = lib().gformer_oracle_linear_head_bwd_f64(qp, kp, vp, dop, dq.ctypes.data_as(_dp),
+                                                  dk.ctypes.data_as(_dp), dv.ctypes.data_as(_dp),
+                                                  N, d, int(phi), float(eps))
+    if rc:
+        raise RuntimeError(f"oracle linear backward failed: {rc}")
+    return dq, dk, dv
+
+
+def attn_bwd(q, k, v, dout, window, n_sparse_heads, phi=PHI_ELU1, softmax_scale=1.0, eps=0.0):
+    """Backward of the causal layer over dense [B, H, N, d]: returns (dq, dk, dv)."""
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v); dout, dop = _c(dout)
+    B, H, N, d = q.shape
+    dq, dk, dv = (np.empty((B, H, N, d), np.float64) for _ in range(3))
+    rc = lib().gformer_oracle_bwd_f64(qp, kp, vp, dop, dq.ctypes.data_as(_dp), dk.ctypes.data_as(_dp),
+                                      dv.ctypes.data_as(_dp), B, H, N, d, int(window),
+                                      int(n_sparse_heads), int(phi), float(softmax_scale), float(eps))
+    if rc:
+        raise RuntimeError(f"oracle layer backward failed: {rc}")
+    return dq, dk, dv
 
 
 def _inplace(a):

@@ -763,3 +763,143 @@ def test_partition_heads_follows_the_continuous_balance():
     pp = co.partition_balance(0.5, float(H), co.sparse_flops(B, 1, N, E, W), co.linear_flops(B, 1, N, E, co.FLOPS_PER_HEAD), ps, pl)
     h0, _, _ = co.partition_heads(B, H, N, E, W, ps, pl, co.FLOPS_PER_HEAD)
     assert abs(h0 - pp * H) <= 0.5 + 1e-9
+
+
+# ---- Backward pass ---------------------------------------------------------------------------
+
+def _bwd_golden():
+    with open(os.path.join(os.path.dirname(__file__), "golden", "backward_2token.json")) as f:
+        return json.load(f)
+
+
+def _gval(x):
+    """'3/4', '-ln2', '3/4*ln3' -> float."""
+    x = x.replace("ln3", repr(math.log(3.0))).replace("ln2", repr(math.log(2.0)))
+    if "*" in x:
+        a, b = x.split("*")
+        return float(Fraction(a)) * float(b)
+    if x.startswith("-") and not x[1:].replace("/", "").replace(".", "").isdigit():
+        return -float(x[1:])
+    try:
+        return float(Fraction(x))
+    except ValueError:
+        return float(x)
+
+
+def _gcol(ex, key):
+    return np.array([[_gval(x)] for x in ex[key]], dtype=np.float64)
+
+
+def test_backward_worked_examples():
+    g = _bwd_golden()
+    ex = g["window"]
+    dq, dk, dv = co.windowed_head_bwd(_gcol(ex, "q"), _gcol(ex, "k"), _gcol(ex, "v"), _gcol(ex, "dout"), 2)
+    for got, key in ((dq, "dq"), (dk, "dk"), (dv, "dv")):
+        assert max_abs(got, _gcol(ex, key)) <= 1e-14, (key, ex["why"])
+    for name, phi in (("linear_identity", co.PHI_IDENTITY), ("linear_elu", co.PHI_ELU1)):
+        ex = g[name]
+        dq, dk, dv = co.linear_head_bwd(_gcol(ex, "q"), _gcol(ex, "k"), _gcol(ex, "v"), _gcol(ex, "dout"), phi=phi)
+        for got, key in ((dq, "dq"), (dk, "dk"), (dv, "dv")):
+            assert max_abs(got, _gcol(ex, key)) <= 1e-14, (name, key, ex["why"])
+
+
+def _central_differences(f, x, dout, h=1e-6):
+    """d/dx of sum(f(x) * dout) by central differences, every element of x."""
+    g = np.zeros_like(x)
+    it = np.nditer(x, flags=["multi_index"])
+    while not it.finished:
+        idx = it.multi_index
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        g[idx] = ((f(xp) - f(xm)) * dout).sum() / (2 * h)
+        it.iternext()
+    return g
+
+
+@pytest.mark.parametrize("N,d,w", [(9, 3, 4), (7, 4, 1), (6, 2, 50)])
+def test_windowed_backward_is_the_derivative_of_the_forward(N, d, w):
+    """Central differences of the (separately pinned) forward oracle, every input element."""
+    q, k, v, do = (_rand((N, d), 300 + s) for s in range(4))
+    dq, dk, dv = co.windowed_head_bwd(q, k, v, do, w, 0.7)
+    assert max_abs(dq, _central_differences(lambda x: co.windowed_head(x, k, v, w, 0.7), q, do)) <= 1e-7
+    assert max_abs(dk, _central_differences(lambda x: co.windowed_head(q, x, v, w, 0.7), k, do)) <= 1e-7
+    assert max_abs(dv, _central_differences(lambda x: co.windowed_head(q, k, x, w, 0.7), v, do)) <= 1e-7
+
+
+@pytest.mark.parametrize("phi", [co.PHI_ELU1, co.PHI_IDENTITY])
+@pytest.mark.parametrize("N,d", [(8, 3), (5, 4)])
+def test_linear_backward_is_the_derivative_of_the_forward(N, d, phi):
+    q, k, v, do = (_rand((N, d), 310 + s) for s in range(4))
+    if phi == co.PHI_IDENTITY:      # keep the denominators away from zero
+        q, k = np.abs(q) + 0.5, np.abs(k) + 0.5
+    eps = 0.25
+    f = lambda a, b, c: co.linear_head(a, b, c, phi=phi, eps=eps, form=co.LINEAR_QUADRATIC)
+    dq, dk, dv = co.linear_head_bwd(q, k, v, do, phi=phi, eps=eps)
+    assert max_abs(dq, _central_differences(lambda x: f(x, k, v), q, do)) <= 1e-7
+    assert max_abs(dk, _central_differences(lambda x: f(q, x, v), k, do)) <= 1e-7
+    assert max_abs(dv, _central_differences(lambda x: f(q, k, x), v, do)) <= 1e-7
+
+
+def test_backward_against_library_autograd():
+    """The two definitions written with library tensor routines (band-masked softmax; cumulative
+    sums for Algorithm 1) and differentiated by the library's reverse mode."""
+    N, d, w = 150, 8, 37
+    q, k, v, do = (torch.tensor(_rand((N, d), 320 + s)) for s in range(4))
+    idx = torch.arange(N)
+    band = (idx[None, :] <= idx[:, None]) & (idx[None, :] > idx[:, None] - w)
+    tq, tk, tv = (t.clone().requires_grad_(True) for t in (q, k, v))
+    s = (tq @ tk.T) * 0.3
+    o = torch.softmax(s.masked_fill(~band, float("-inf")), dim=-1) @ tv
+    (o * do).sum().backward()
+    dq, dk, dv = co.windowed_head_bwd(q.numpy(), k.numpy(), v.numpy(), do.numpy(), w, 0.3)
+    assert max_abs(dq, tq.grad.numpy()) <= 1e-12 and max_abs(dk, tk.grad.numpy()) <= 1e-12
+    assert max_abs(dv, tv.grad.numpy()) <= 1e-12
+    tq, tk, tv = (t.clone().requires_grad_(True) for t in (q, k, v))
+    fq, fk = torch.nn.functional.elu(tq) + 1, torch.nn.functional.elu(tk) + 1
+    A = torch.cumsum(fk[:, :, None] * tv[:, None, :], dim=0)        # Algorithm 1's running sums
+    Z = torch.cumsum(fk, dim=0)
+    o = torch.einsum("nc,nce->ne", fq, A) / ((fq * Z).sum(-1, keepdim=True) + 0.125)
+    (o * do).sum().backward()
+    dq, dk, dv = co.linear_head_bwd(q.numpy(), k.numpy(), v.numpy(), do.numpy(), eps=0.125)
+    assert max_abs(dq, tq.grad.numpy()) <= 1e-11 and max_abs(dk, tk.grad.numpy()) <= 1e-11
+    assert max_abs(dv, tv.grad.numpy()) <= 1e-11
+
+
+def test_backward_closed_forms():
+    N, d = 40, 6
+    q, k, v, do = (_rand((N, d), 330 + s) for s in range(4))
+    # window 1: every token returns its own value, so dv = dO and nothing depends on q or k
+    dq, dk, dv = co.windowed_head_bwd(q, k, v, do, 1)
+    assert max_abs(dq, 0 * q) == 0 and max_abs(dk, 0 * k) == 0 and max_abs(dv, do) <= 1e-15
+    # the softmax Jacobian annihilates constants: sum_j ds_ij = 0 for every query.  With one common
+    # query vector qc, dk_j = scale * qc * sum_i ds_ij, so the dk rows add up to zero
+    qc = np.tile(_rand((1, d), 340), (N, 1))
+    dq, dk, dv = co.windowed_head_bwd(qc, k, v, do, N)       # full causal attention
+    assert max_abs(dk.sum(axis=0), np.zeros(d)) <= 1e-12
+    # linear head: the ratio is unchanged when every phi(k_j) is scaled by one factor (identity
+    # map, eps = 0), so sum_j k_j . dk_j = 0; and likewise q_i . dq_i = 0 for every token
+    qp, kp = np.abs(q) + 0.5, np.abs(k) + 0.5
+    dq, dk, dv = co.linear_head_bwd(qp, kp, v, do, phi=co.PHI_IDENTITY)
+    assert abs((kp * dk).sum()) <= 1e-11
+    assert max_abs((qp * dq).sum(axis=1), np.zeros(N)) <= 1e-11
+    # first token of a linear head: out_0 = v_0 (eps = 0)
+    dq1, dk1, dv1 = co.linear_head_bwd(q[:1], k[:1], v[:1], do[:1])
+    assert max_abs(dv1, do[:1]) <= 1e-15 and max_abs(dq1, 0 * dq1) <= 1e-15 and max_abs(dk1, 0 * dk1) <= 1e-15
+
+
+def test_backward_is_linear_in_the_output_gradient_and_splits_by_head():
+    B, H, N, d, w, H0 = 2, 3, 30, 4, 7, 1
+    q, k, v, d1, d2 = (_rand((B, H, N, d), 350 + s) for s in range(5))
+    a = co.attn_bwd(q, k, v, d1, w, H0, softmax_scale=0.5, eps=0.1)
+    b = co.attn_bwd(q, k, v, d2, w, H0, softmax_scale=0.5, eps=0.1)
+    c = co.attn_bwd(q, k, v, 2 * d1 - 3 * d2, w, H0, softmax_scale=0.5, eps=0.1)
+    for x, y, z in zip(a, b, c):
+        assert max_abs(z, 2 * x - 3 * y) <= 1e-12
+    for bb in range(B):
+        ref = co.windowed_head_bwd(q[bb, 0], k[bb, 0], v[bb, 0], d1[bb, 0], w, 0.5)
+        for x, y in zip(a, ref):
+            assert max_abs(x[bb, 0], y) == 0
+        ref = co.linear_head_bwd(q[bb, 2], k[bb, 2], v[bb, 2], d1[bb, 2], eps=0.1)
+        for x, y in zip(a, ref):
+            assert max_abs(x[bb, 2], y) == 0
