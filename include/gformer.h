@@ -188,6 +188,30 @@ gf_status gformer_attn_prefill(const void* q, const void* k, const void* v, void
                                const gformer_params* p, void* workspace, size_t workspace_bytes,
                                void* hip_stream);
 
+/* Backward pass of the causal layer: the gradients of a scalar loss with respect to Q, K and V
+ * from its gradient with respect to the layer's output.  The paper trains its models (sections
+ * IV-B to IV-D) but prints no backward formulas: these are the derivatives of section III-B,
+ * Eq. 1 (softmax over the causal window) and of section II-B's ratio with Algorithm 1's running
+ * sums, the feature map's slope included.
+ *   q, k, v : device, as for gformer_attn_fwd, read
+ *   dout    : device, gradient with respect to the layer's output, layout of o_stride, read
+ *             (the forward result itself is not an input: what the derivatives need of it is
+ *             recomputed in fp32, since the stored result is rounded to the element type)
+ *   dq, dk, dv : device, written; laid out like q, k, v (their strides); must not overlap any
+ *             input or each other
+ *   workspace : device, gformer_attn_bwd_workspace_bytes bytes (8 per token and head), 256-byte
+ *             aligned; scratch for per-row softmax statistics / denominators
+ * Plain-FMA kernels only (fp32 arithmetic on either storage type): params.impl must be
+ * GF_IMPL_AUTO or GF_IMPL_SCALAR, the MFMA values are GF_ERR_UNSUPPORTED, and so is
+ * params.bidirectional = 1.  params.launch_mask must be 0; segment_len and overlap are ignored.
+ * Asynchronous on `hip_stream`; errors as for gformer_attn_fwd. */
+size_t gformer_attn_bwd_workspace_bytes(int B, int H, int N, int d, int window,
+                                        const gformer_params* p);
+gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq,
+                           void* dk, void* dv, int B, int H, int N, int d, int window,
+                           const gformer_params* p, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
 /* Positive random features as a pre-map of Q or K for the linear heads.  Section III-A names
  * "positive orthogonal random features" for the linear part and Algorithm 1 "random feature
  * maps"; neither prints them, so the formula is the construction of the work they cite:

@@ -23,6 +23,7 @@ GF_LAUNCH_WINDOWED, GF_LAUNCH_LINEAR_STATE, GF_LAUNCH_LINEAR_MAIN = 1, 2, 4
 
 EXPORTS = ("gformer_params_init", "gformer_attn_workspace_bytes", "gformer_attn_plan",
            "gformer_attn_fwd", "gformer_attn_prefill", "gformer_attn_decode",
+           "gformer_attn_bwd_workspace_bytes", "gformer_attn_bwd",
            "gformer_feature_params_init",
            "gformer_random_features",
            "gformer_partition_balance", "gformer_partition_heads",
@@ -96,6 +97,11 @@ def lib():
             [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.gformer_attn_prefill.restype = ctypes.c_int
         L.gformer_attn_prefill.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_int] * 5 + \
+            [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.gformer_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.gformer_attn_bwd_workspace_bytes.argtypes = [ctypes.c_int] * 5 + [P]
+        L.gformer_attn_bwd.restype = ctypes.c_int
+        L.gformer_attn_bwd.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_int] * 5 + \
             [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.gformer_attn_decode.restype = ctypes.c_int
         L.gformer_attn_decode.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_int] * 4 + \
@@ -371,6 +377,52 @@ def gformer_attn_prefill(q, k, v, out, kcache, vcache, state, window: int, n_spa
     if st != GF_OK:
         raise GformerError(st, gformer_status_string(st))
     return out
+
+
+def gformer_attn_bwd_workspace_bytes(B, H, N, d, window, params: GformerParams) -> int:
+    return int(lib().gformer_attn_bwd_workspace_bytes(B, H, N, d, window, ctypes.byref(params)))
+
+
+def gformer_attn_bwd_raw(q_ptr, k_ptr, v_ptr, dout_ptr, dq_ptr, dk_ptr, dv_ptr, B, H, N, d, window,
+                         params: GformerParams, workspace_ptr=0, workspace_bytes=0, stream=0) -> int:
+    """Direct call with integer device addresses; returns the gf_status."""
+    vp = lambda x: ctypes.c_void_p(x or None)
+    return int(lib().gformer_attn_bwd(vp(q_ptr), vp(k_ptr), vp(v_ptr), vp(dout_ptr), vp(dq_ptr),
+                                      vp(dk_ptr), vp(dv_ptr), int(B), int(H), int(N), int(d), int(window),
+                                      ctypes.byref(params), vp(workspace_ptr),
+                                      ctypes.c_size_t(int(workspace_bytes)), vp(stream)))
+
+
+def gformer_attn_bwd(q, k, v, dout, dq, dk, dv, window: int, n_sparse_heads: int, *,
+                     phi=GF_PHI_ELU1, impl=GF_IMPL_AUTO, softmax_scale=1.0, eps=0.0,
+                     workspace=None, stream: Optional[int] = None):
+    """Backward of the causal layer on [B, H, N, d] device tensors: fills dq, dk, dv (laid out
+    like q, k, v) from `dout`, the gradient with respect to the layer's output."""
+    import torch
+
+    if not all(x.is_cuda for x in (q, k, v, dout, dq, dk, dv)):
+        raise ValueError("all tensors must be device tensors: there is no CPU path")
+    if _strides3(dq) != _strides3(q) or _strides3(dk) != _strides3(k) or _strides3(dv) != _strides3(v):
+        raise ValueError("dq, dk, dv must be laid out like q, k, v")
+    dtype = GF_BF16 if q.dtype == torch.bfloat16 else GF_F32
+    B, H, N, d = (int(x) for x in q.shape)
+    params = make_params(dtype=dtype, n_sparse_heads=n_sparse_heads, phi=phi, impl=impl,
+                         softmax_scale=softmax_scale, eps=eps, q_stride=_strides3(q),
+                         k_stride=_strides3(k), v_stride=_strides3(v), o_stride=_strides3(dout))
+    need = gformer_attn_bwd_workspace_bytes(B, H, N, d, window, params)
+    ws_ptr, ws_bytes = 0, 0
+    if need > 0:
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    st = gformer_attn_bwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(),
+                              dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, H, N, d, window, params,
+                              ws_ptr, ws_bytes, stream)
+    if st != GF_OK:
+        raise GformerError(st, gformer_status_string(st))
+    return dq, dk, dv
 
 
 def gformer_partition_balance(p, size, flops_per0, flops_per1, perf0, perf1):

@@ -432,6 +432,65 @@ gf_status gformer_random_features(const void* x, const void* w, void* out, int B
   return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
 }
 
+size_t gformer_attn_bwd_workspace_bytes(int B, int H, int N, int d, int window,
+                                        const gformer_params* p) {
+  (void)d; (void)window; (void)p;
+  if (B <= 0 || H <= 0 || N <= 0) return 0;
+  return (size_t)B * H * N * 2 * sizeof(float);
+}
+
+gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq,
+                           void* dk, void* dv, int B, int H, int N, int d, int window,
+                           const gformer_params* p, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+  if (!p) return GF_ERR_INVALID_ARG;
+  if (p->struct_size != sizeof(gformer_params)) return GF_ERR_INVALID_ARG;
+  // the backward pass has plain-FMA kernels only, and only for the causal form
+  if (p->impl == GF_IMPL_MFMA || p->impl == GF_IMPL_MFMA_BLOCKED || p->impl == GF_IMPL_MFMA_STREAM)
+    return GF_ERR_UNSUPPORTED;
+  gformer_params pp = *p;
+  pp.impl = GF_IMPL_SCALAR;
+  pp.segment_len = 0;
+  Resolved r;
+  const gf_status st = resolve(B, H, N, d, window, &pp, &r);
+  if (st != GF_OK) return st;
+  if (p->bidirectional != 0) return GF_ERR_UNSUPPORTED;
+  if (p->launch_mask != 0) return GF_ERR_INVALID_ARG;
+  if (B == 0 || H == 0 || N == 0) return GF_OK;
+  if (!q || !k || !v || !dout || !dq || !dk || !dv) return GF_ERR_INVALID_ARG;
+  const void* ins[4] = {q, k, v, dout};
+  void* outs[3] = {dq, dk, dv};
+  for (const void* x : ins)
+    if ((uintptr_t)x & 15u) return GF_ERR_INVALID_ARG;
+  for (void* y : outs) {
+    if ((uintptr_t)y & 15u) return GF_ERR_INVALID_ARG;
+    for (const void* x : ins)
+      if (x == y) return GF_ERR_INVALID_ARG;
+  }
+  if (dq == dk || dq == dv || dk == dv) return GF_ERR_INVALID_ARG;
+  const size_t need = gformer_attn_bwd_workspace_bytes(B, H, N, d, window, p);
+  if (!workspace || workspace_bytes < need) return GF_ERR_WORKSPACE;
+  if ((uintptr_t)workspace & 255u) return GF_ERR_INVALID_ARG;
+
+  BwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = TensorView{q, r.qs[0], r.qs[1], r.qs[2]};
+  a.k = TensorView{k, r.ks[0], r.ks[1], r.ks[2]};
+  a.v = TensorView{v, r.vs[0], r.vs[1], r.vs[2]};
+  a.dout = TensorView{dout, r.os[0], r.os[1], r.os[2]};
+  a.dq = dq; a.dk = dk; a.dv = dv;
+  a.B = B; a.H = H; a.N = N; a.d = d;
+  a.window = window;
+  a.H0 = p->n_sparse_heads;
+  a.phi = p->phi;
+  a.scale = p->softmax_scale;
+  a.eps = p->eps;
+  a.ws = reinterpret_cast<float*>(workspace);
+  const hipError_t e = launch_backward_scalar(a, p->dtype == GF_BF16,
+                                              reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
+}
+
 const char* gformer_status_string(gf_status s) {
   switch (s) {
     case GF_OK: return "ok";

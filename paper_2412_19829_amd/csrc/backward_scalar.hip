@@ -1,0 +1,503 @@
+// Backward pass of the causal layer, plain-FMA kernels (fp32 arithmetic on fp32 or bf16 storage).
+//
+// The paper trains its models (sections IV-B to IV-D) but prints no backward formulas; these are
+// the derivatives of its two definitions.
+//
+// Nothing of the forward pass is taken as input: the forward result would arrive rounded to the
+// storage type, and the differences below cancel too strongly for that.
+//
+// Windowed head (section III-B, Eq. 1), s_ij = scale q_i.k_j, p_ij = softmax over the window,
+// o_i = sum_j p_ij v_j.  With D_i = dO_i.o_i = sum_j p_ij dO_i.v_j and ds_ij = p_ij (dO_i.v_j - D_i):
+//   dq_i = scale sum_j ds_ij k_j,  dk_j = scale sum_i ds_ij q_i,  dv_j = sum_i p_ij dO_i.
+// Two kernels: one wave per query row (recomputes the row's log-sum-exp, writes dq and leaves
+// (lse_i, D_i) in the workspace), then one wave per key row over the queries that see it.
+//
+// Linear head (section II-B's ratio, Algorithm 1's running sums), fq = phi(q), fk = phi(k),
+// den_i = fq_i.Z_i + eps, o_i = fq_i^T A_i / den_i.  With g_i = dO_i / den_i and
+// c_i = (dO_i.o_i) / den_i = g_i.(fq_i^T A_i) / den_i:
+//   dfq_i = A_i g_i - c_i Z_i                          (A_i, Z_i: sums over j <= i, forward scan)
+//   dfk_j = B_j v_j - Y_j,  dv_j = B_j^T fk_j          (B_j = sum_{i>=j} fq_i g_i^T,
+//                                                       Y_j = sum_{i>=j} c_i fq_i, reverse scan)
+//   dq = dfq * phi'(q),  dk = dfk * phi'(k).
+// Two kernels, one workgroup per head each, chunks of 32 tokens: inside a chunk the masked
+// quadratic form, across chunks the carried d x d state in LDS, as in the forward kernel.
+#include "common.hpp"
+#include "scalar_util.hpp"
+
+namespace gformer {
+
+namespace {
+
+constexpr int kBwdThreads = 256;
+constexpr int kBwdRows = 16;   // rows per workgroup in the windowed kernels (4 per wave)
+
+// ---------------------------------------------------------------------------------------
+// windowed heads, per query row: dq_i, and (lse_i, D_i) for the key-row kernel
+// grid = (ceil(N / kBwdRows), H0, B), block = 256
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kBwdThreads) void windowed_bwd_q_kernel(BwdArgs a) {
+  constexpr int CPL = D / 64;  // columns per lane
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int64_t qoff = b * a.q.sb + h * a.q.sh;
+  const int64_t koff = b * a.k.sb + h * a.k.sh;
+  const int64_t voff = b * a.v.sb + h * a.v.sh;
+  const int64_t ooff = b * a.dout.sb + h * a.dout.sh;
+  float* ws = a.ws + ((int64_t)b * a.H + h) * a.N * 2;
+  constexpr int rows_per_wave = kBwdRows / (kBwdThreads / 64);
+
+  for (int r = 0; r < rows_per_wave; ++r) {
+    const int i = blockIdx.x * kBwdRows + wave * rows_per_wave + r;
+    if (i >= a.N) break;  // uniform per wave
+    float qreg[CPL], doreg[CPL];
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) {
+      qreg[cc] = Storage<T>::load(a.q.base, qoff + i * a.q.sn + cc * 64 + lane);
+      doreg[cc] = Storage<T>::load(a.dout.base, ooff + i * a.dout.sn + cc * 64 + lane);
+    }
+    const int lo = max(0, i - a.window + 1), hi = i;
+    // lane j's score against this query; lanes past the last visible key read that key again
+    auto score = [&](int j) {
+      const int64_t kr = koff + (int64_t)min(j, hi) * a.k.sn;
+      float s = 0.f;
+#pragma unroll
+      for (int cc = 0; cc < CPL; ++cc)
+#pragma unroll
+        for (int c = 0; c < 64; ++c)
+          s = fmaf(lane_bcast(qreg[cc], c), Storage<T>::load(a.k.base, kr + cc * 64 + c), s);
+      return s * a.scale;
+    };
+    // the row's log-sum-exp
+    float m = -INFINITY, l = 0.f;
+    for (int j0 = lo; j0 <= hi; j0 += 64) {
+      const int j = j0 + lane;
+      const float s = j <= hi ? score(j) : -INFINITY;
+      const float m_new = fmaxf(m, wave_max(s));   // finite: key j0 is always visible
+      l = l * expf(m - m_new) + wave_sum(j <= hi ? expf(s - m_new) : 0.f);
+      m = m_new;
+    }
+    const float lse = m + logf(l);
+    // lane j's dO_i.v_j
+    auto dvalue = [&](int j) {
+      const int64_t vr = voff + (int64_t)min(j, hi) * a.v.sn;
+      float dp = 0.f;
+#pragma unroll
+      for (int cc = 0; cc < CPL; ++cc)
+#pragma unroll
+        for (int c = 0; c < 64; ++c)
+          dp = fmaf(lane_bcast(doreg[cc], c), Storage<T>::load(a.v.base, vr + cc * 64 + c), dp);
+      return dp;
+    };
+    // D_i = sum_j p_ij dO_i.v_j
+    float dsum = 0.f;
+    for (int j0 = lo; j0 <= hi; j0 += 64) {
+      const int j = j0 + lane;
+      if (j <= hi) dsum = fmaf(expf(score(j) - lse), dvalue(j), dsum);
+    }
+    const float Di = wave_sum(dsum);
+
+    float acc[CPL];
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) acc[cc] = 0.f;
+    for (int j0 = lo; j0 <= hi; j0 += 64) {
+      const int j = j0 + lane;
+      const bool valid = j <= hi;
+      const float p = valid ? expf(score(j) - lse) : 0.f;
+      const float dp = dvalue(j);
+      const float ds = p * (dp - Di);
+      const int cnt = min(64, hi - j0 + 1);
+      for (int jj = 0; jj < cnt; ++jj) {
+        const float dsj = __shfl(ds, jj, 64);
+        const int64_t kr = koff + (int64_t)(j0 + jj) * a.k.sn;
+#pragma unroll
+        for (int cc = 0; cc < CPL; ++cc)
+          acc[cc] = fmaf(dsj, Storage<T>::load(a.k.base, kr + cc * 64 + lane), acc[cc]);
+      }
+    }
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc)
+      Storage<T>::store(a.dq, qoff + i * a.q.sn + cc * 64 + lane, acc[cc] * a.scale);
+    if (lane == 0) {
+      ws[2 * (int64_t)i] = lse;
+      ws[2 * (int64_t)i + 1] = Di;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// windowed heads, per key row: dk_j and dv_j over the queries j .. j + w - 1 that see key j
+// grid = (ceil(N / kBwdRows), H0, B), block = 256; reads (lse_i, D_i) left by the kernel above
+// ---------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kBwdThreads) void windowed_bwd_kv_kernel(BwdArgs a) {
+  constexpr int CPL = D / 64;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int64_t qoff = b * a.q.sb + h * a.q.sh;
+  const int64_t koff = b * a.k.sb + h * a.k.sh;
+  const int64_t voff = b * a.v.sb + h * a.v.sh;
+  const int64_t ooff = b * a.dout.sb + h * a.dout.sh;
+  const float* ws = a.ws + ((int64_t)b * a.H + h) * a.N * 2;
+  constexpr int rows_per_wave = kBwdRows / (kBwdThreads / 64);
+
+  for (int r = 0; r < rows_per_wave; ++r) {
+    const int j = blockIdx.x * kBwdRows + wave * rows_per_wave + r;
+    if (j >= a.N) break;  // uniform per wave
+    float kreg[CPL], vreg[CPL], acck[CPL], accv[CPL];
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) {
+      kreg[cc] = Storage<T>::load(a.k.base, koff + j * a.k.sn + cc * 64 + lane);
+      vreg[cc] = Storage<T>::load(a.v.base, voff + j * a.v.sn + cc * 64 + lane);
+      acck[cc] = 0.f;
+      accv[cc] = 0.f;
+    }
+    const int ihi = (int)min((int64_t)a.N - 1, (int64_t)j + a.window - 1);
+    for (int i0 = j; i0 <= ihi; i0 += 64) {
+      const int i = i0 + lane;
+      const bool valid = i <= ihi;
+      const int ii = min(i, ihi);   // lanes past the last query read that query again
+      float s = 0.f, dp = 0.f;
+      {
+        const int64_t qr = qoff + (int64_t)ii * a.q.sn;
+        const int64_t dr = ooff + (int64_t)ii * a.dout.sn;
+#pragma unroll
+        for (int cc = 0; cc < CPL; ++cc)
+#pragma unroll
+          for (int c = 0; c < 64; ++c) {
+            s = fmaf(lane_bcast(kreg[cc], c), Storage<T>::load(a.q.base, qr + cc * 64 + c), s);
+            dp = fmaf(lane_bcast(vreg[cc], c), Storage<T>::load(a.dout.base, dr + cc * 64 + c), dp);
+          }
+      }
+      const float lse = ws[2 * (int64_t)ii], Di = ws[2 * (int64_t)ii + 1];
+      const float p = valid ? expf(s * a.scale - lse) : 0.f;
+      const float ds = p * (dp - Di);
+      const int cnt = min(64, ihi - i0 + 1);
+      for (int t = 0; t < cnt; ++t) {
+        const float pt = __shfl(p, t, 64), dst = __shfl(ds, t, 64);
+        const int64_t qr = qoff + (int64_t)(i0 + t) * a.q.sn;
+        const int64_t dr = ooff + (int64_t)(i0 + t) * a.dout.sn;
+#pragma unroll
+        for (int cc = 0; cc < CPL; ++cc) {
+          acck[cc] = fmaf(dst, Storage<T>::load(a.q.base, qr + cc * 64 + lane), acck[cc]);
+          accv[cc] = fmaf(pt, Storage<T>::load(a.dout.base, dr + cc * 64 + lane), accv[cc]);
+        }
+      }
+    }
+#pragma unroll
+    for (int cc = 0; cc < CPL; ++cc) {
+      Storage<T>::store(a.dk, koff + j * a.k.sn + cc * 64 + lane, acck[cc] * a.scale);
+      Storage<T>::store(a.dv, voff + j * a.v.sn + cc * 64 + lane, accv[cc]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// linear heads
+// ---------------------------------------------------------------------------------------
+constexpr int kBwdChunk = 32;
+
+template <int D> constexpr size_t linear_bwd_q_smem() {
+  return sizeof(float) * (5 * kBwdChunk * D + D * (D + 1) + D + 2 * kBwdChunk * (kBwdChunk + 1) + 2 * kBwdChunk);
+}
+template <int D> constexpr size_t linear_bwd_kv_smem() {
+  return sizeof(float) * (4 * kBwdChunk * D + D * (D + 1) + D + 2 * kBwdChunk * (kBwdChunk + 1) + kBwdChunk);
+}
+
+// Forward scan: dq, and (den_i, c_i) for the reverse scan.  grid = (H1, B), block = 256.
+template <typename T, int D>
+__global__ __launch_bounds__(kBwdThreads) void linear_bwd_q_kernel(BwdArgs a) {
+  constexpr int CH = kBwdChunk;
+  constexpr int G = kBwdThreads / D;   // thread groups along the token axis
+  constexpr int NUM_T = CH / G;        // tokens per thread
+  constexpr int UPD_C = D / G;         // state rows per thread in the update
+  constexpr int SR = D + 1;            // state row stride: rows and columns both conflict-free
+  extern __shared__ float smem[];
+  float* fq = smem;                   // [CH][D] phi(q)
+  float* fk = fq + CH * D;            // [CH][D] phi(k)
+  float* vv = fk + CH * D;            // [CH][D]
+  float* gg = vv + CH * D;            // [CH][D] dO, then g = dO / den
+  float* rr = gg + CH * D;            // [CH][D] r_t = A g_t (state before the chunk)
+  float* S = rr + CH * D;             // [D][SR]  A: rows = feature c, columns = value e
+  float* z = S + D * SR;              // [D]
+  float* am = z + D;                  // [CH][CH+1] a[t][u] = phi(q_t).phi(k_u), u <= t
+  float* gv = am + CH * (CH + 1);     // [CH][CH+1] g_t.v_u, then g_t.v_u - c_t, u <= t
+  float* den = gv + CH * (CH + 1);    // [CH]
+  float* cvec = den + CH;             // [CH]
+
+  const int tid = threadIdx.x;
+  const int h = a.H0 + blockIdx.x, b = blockIdx.y;
+  const int64_t qoff = b * a.q.sb + h * a.q.sh;
+  const int64_t koff = b * a.k.sb + h * a.k.sh;
+  const int64_t voff = b * a.v.sb + h * a.v.sh;
+  const int64_t ooff = b * a.dout.sb + h * a.dout.sh;   // layout of dO
+  float* ws = a.ws + ((int64_t)b * a.H + h) * a.N * 2;
+
+  for (int x = tid; x < D * SR; x += kBwdThreads) S[x] = 0.f;
+  if (tid < D) z[tid] = 0.f;
+  const int c = tid % D;   // the feature (or value) index this thread owns
+  const int g = tid / D;
+
+  for (int t0 = 0; t0 < a.N; t0 += CH) {
+    __syncthreads();  // previous chunk fully consumed (and the zero fill above is visible)
+    for (int x = tid; x < CH * D; x += kBwdThreads) {
+      const int t = x / D, cc = x % D;
+      const int n = t0 + t;
+      float qv = 0.f, kv = 0.f, v_ = 0.f, d_ = 0.f;
+      if (n < a.N) {
+        qv = feature_map(Storage<T>::load(a.q.base, qoff + (int64_t)n * a.q.sn + cc), a.phi);
+        kv = feature_map(Storage<T>::load(a.k.base, koff + (int64_t)n * a.k.sn + cc), a.phi);
+        v_ = Storage<T>::load(a.v.base, voff + (int64_t)n * a.v.sn + cc);
+        d_ = Storage<T>::load(a.dout.base, ooff + (int64_t)n * a.dout.sn + cc);
+      }
+      fq[x] = qv; fk[x] = kv; vv[x] = v_; gg[x] = d_;   // rows past N: zeros
+    }
+    __syncthreads();
+    // a[t][u] = phi(q_t).phi(k_u), u <= t
+    for (int x = tid; x < CH * CH; x += kBwdThreads) {
+      const int t = x / CH, u = x % CH;
+      float s = 0.f;
+      if (u <= t)
+        for (int cc = 0; cc < D; ++cc) s = fmaf(fq[t * D + cc], fk[u * D + cc], s);
+      am[t * (CH + 1) + u] = s;
+    }
+    __syncthreads();
+    if (tid < CH) {
+      float s = 0.f;
+      for (int u = 0; u <= tid; ++u) s += am[tid * (CH + 1) + u];
+      float zz = 0.f;
+      for (int cc = 0; cc < D; ++cc) zz = fmaf(fq[tid * D + cc], z[cc], zz);
+      // rows past N keep a harmless denominator of 1 (their dO is zero)
+      den[tid] = (t0 + tid < a.N) ? s + zz + a.eps : 1.f;
+    }
+    __syncthreads();
+    for (int x = tid; x < CH * D; x += kBwdThreads) gg[x] /= den[x / D];   // g = dO / den
+    __syncthreads();
+    // gv[t][u] = g_t.v_u, u <= t
+    for (int x = tid; x < CH * CH; x += kBwdThreads) {
+      const int t = x / CH, u = x % CH;
+      float s = 0.f;
+      if (u <= t)
+        for (int cc = 0; cc < D; ++cc) s = fmaf(gg[t * D + cc], vv[u * D + cc], s);
+      gv[t * (CH + 1) + u] = s;
+    }
+    // r[t][c] = sum_e A[c][e] g_t[e]
+    float acc[NUM_T];
+#pragma unroll
+    for (int i = 0; i < NUM_T; ++i) acc[i] = 0.f;
+    for (int e = 0; e < D; ++e) {
+      const float sce = S[c * SR + e];
+#pragma unroll
+      for (int i = 0; i < NUM_T; ++i) acc[i] = fmaf(sce, gg[(g + G * i) * D + e], acc[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < NUM_T; ++i) rr[(g + G * i) * D + c] = acc[i];
+    __syncthreads();
+    // c_t = g_t.num_t / den_t with g_t.num_t = phi(q_t).r_t + sum_{u<=t} a[t][u] g_t.v_u
+    if (tid < CH) {
+      float s = 0.f;
+      for (int cc = 0; cc < D; ++cc) s = fmaf(fq[tid * D + cc], rr[tid * D + cc], s);
+      for (int u = 0; u <= tid; ++u) s = fmaf(am[tid * (CH + 1) + u], gv[tid * (CH + 1) + u], s);
+      const float ct = s / den[tid];
+      cvec[tid] = ct;
+      if (t0 + tid < a.N) {
+        ws[2 * (int64_t)(t0 + tid)] = den[tid];
+        ws[2 * (int64_t)(t0 + tid) + 1] = ct;
+      }
+    }
+    __syncthreads();
+    // w[t][u] = g_t.v_u - c_t, u <= t
+    for (int x = tid; x < CH * CH; x += kBwdThreads) {
+      const int t = x / CH, u = x % CH;
+      if (u <= t) gv[t * (CH + 1) + u] -= cvec[t];
+    }
+    __syncthreads();
+    // dfq[t][c] = r_t[c] - c_t Z[c] + sum_{u<=t} w[t][u] phi(k_u)[c]
+#pragma unroll
+    for (int i = 0; i < NUM_T; ++i) acc[i] -= cvec[g + G * i] * z[c];
+    for (int u = 0; u < CH; ++u) {
+      const float fku = fk[u * D + c];
+#pragma unroll
+      for (int i = 0; i < NUM_T; ++i) acc[i] = fmaf(gv[(g + G * i) * (CH + 1) + u], fku, acc[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < NUM_T; ++i) {
+      const int t = g + G * i, n = t0 + t;
+      if (n < a.N)
+        Storage<T>::store(a.dq, qoff + (int64_t)n * a.q.sn + c,
+                          acc[i] * feature_map_slope(fq[t * D + c], a.phi));
+    }
+    __syncthreads();  // all reads of A and Z for this chunk are done
+    // state update: A[cc][e] += sum_t phi(k_t)[cc] v_t[e];  Z[cc] += sum_t phi(k_t)[cc]
+    {
+      const int e = c;
+      float vcol[CH];
+#pragma unroll
+      for (int t = 0; t < CH; ++t) vcol[t] = vv[t * D + e];
+      for (int i = 0; i < UPD_C; ++i) {
+        const int cc = g + G * i;
+        float s = S[cc * SR + e];
+#pragma unroll
+        for (int t = 0; t < CH; ++t) s = fmaf(fk[t * D + cc], vcol[t], s);
+        S[cc * SR + e] = s;
+      }
+      if (tid < D) {
+        float s = z[tid];
+        for (int t = 0; t < CH; ++t) s += fk[t * D + tid];
+        z[tid] = s;
+      }
+    }
+  }
+}
+
+// Reverse scan: dk and dv.  grid = (H1, B), block = 256; reads (den_i, c_i) left by the kernel above.
+template <typename T, int D>
+__global__ __launch_bounds__(kBwdThreads) void linear_bwd_kv_kernel(BwdArgs a) {
+  constexpr int CH = kBwdChunk;
+  constexpr int G = kBwdThreads / D;
+  constexpr int NUM_T = CH / G;
+  constexpr int UPD_C = D / G;
+  constexpr int SR = D + 1;
+  extern __shared__ float smem[];
+  float* fq = smem;                   // [CH][D]
+  float* fk = fq + CH * D;            // [CH][D]
+  float* vv = fk + CH * D;            // [CH][D]
+  float* gg = vv + CH * D;            // [CH][D] g = dO / den
+  float* Bm = gg + CH * D;            // [D][SR]  B: rows = feature c, columns = value e
+  float* y = Bm + D * SR;             // [D]
+  float* a1 = y + D;                  // [CH][CH+1] phi(q_t).phi(k_u), t >= u
+  float* a2 = a1 + CH * (CH + 1);     // [CH][CH+1] g_t.v_u - c_t, t >= u
+  float* cvec = a2 + CH * (CH + 1);   // [CH]
+
+  const int tid = threadIdx.x;
+  const int h = a.H0 + blockIdx.x, b = blockIdx.y;
+  const int64_t qoff = b * a.q.sb + h * a.q.sh;
+  const int64_t koff = b * a.k.sb + h * a.k.sh;
+  const int64_t voff = b * a.v.sb + h * a.v.sh;
+  const int64_t ooff = b * a.dout.sb + h * a.dout.sh;
+  const float* ws = a.ws + ((int64_t)b * a.H + h) * a.N * 2;
+
+  for (int x = tid; x < D * SR; x += kBwdThreads) Bm[x] = 0.f;
+  if (tid < D) y[tid] = 0.f;
+  const int c = tid % D;
+  const int g = tid / D;
+
+  const int nchunks = (a.N + CH - 1) / CH;
+  for (int ch = nchunks - 1; ch >= 0; --ch) {
+    const int t0 = ch * CH;
+    __syncthreads();  // previous chunk fully consumed (and the zero fill above is visible)
+    for (int x = tid; x < CH * D; x += kBwdThreads) {
+      const int t = x / D, cc = x % D;
+      const int n = t0 + t;
+      float qv = 0.f, kv = 0.f, v_ = 0.f, g_ = 0.f;
+      if (n < a.N) {
+        qv = feature_map(Storage<T>::load(a.q.base, qoff + (int64_t)n * a.q.sn + cc), a.phi);
+        kv = feature_map(Storage<T>::load(a.k.base, koff + (int64_t)n * a.k.sn + cc), a.phi);
+        v_ = Storage<T>::load(a.v.base, voff + (int64_t)n * a.v.sn + cc);
+        g_ = Storage<T>::load(a.dout.base, ooff + (int64_t)n * a.dout.sn + cc) / ws[2 * (int64_t)n];
+      }
+      fq[x] = qv; fk[x] = kv; vv[x] = v_; gg[x] = g_;   // rows past N: zeros, no contribution
+    }
+    if (tid < CH) cvec[tid] = (t0 + tid < a.N) ? ws[2 * (int64_t)(t0 + tid) + 1] : 0.f;
+    __syncthreads();
+    for (int x = tid; x < CH * CH; x += kBwdThreads) {
+      const int t = x / CH, u = x % CH;
+      float s1 = 0.f, s2 = 0.f;
+      if (t >= u) {
+        for (int cc = 0; cc < D; ++cc) {
+          s1 = fmaf(fq[t * D + cc], fk[u * D + cc], s1);
+          s2 = fmaf(gg[t * D + cc], vv[u * D + cc], s2);
+        }
+        s2 -= cvec[t];
+        if (t0 + t >= a.N) { s1 = 0.f; s2 = 0.f; }   // a row past N weighs nothing
+      }
+      a1[t * (CH + 1) + u] = s1;
+      a2[t * (CH + 1) + u] = s2;
+    }
+    __syncthreads();
+    // thread (c, g) owns value column e = c of dv and feature c of dk for tokens u = g + G*i
+    float accv[NUM_T], acck[NUM_T];
+#pragma unroll
+    for (int i = 0; i < NUM_T; ++i) { accv[i] = 0.f; acck[i] = -y[c]; }
+    for (int cc = 0; cc < D; ++cc) {
+      const float bce = Bm[cc * SR + c];   // B[cc][e = c]
+      const float bec = Bm[c * SR + cc];   // B[c][e = cc]
+#pragma unroll
+      for (int i = 0; i < NUM_T; ++i) {
+        accv[i] = fmaf(bce, fk[(g + G * i) * D + cc], accv[i]);   // dv_u[e] += B[cc][e] phi(k_u)[cc]
+        acck[i] = fmaf(bec, vv[(g + G * i) * D + cc], acck[i]);   // dfk_u[c] += B[c][cc] v_u[cc]
+      }
+    }
+    for (int t = 0; t < CH; ++t) {
+      const float gte = gg[t * D + c], fqt = fq[t * D + c];
+#pragma unroll
+      for (int i = 0; i < NUM_T; ++i) {
+        accv[i] = fmaf(a1[t * (CH + 1) + g + G * i], gte, accv[i]);   // zero where t < u
+        acck[i] = fmaf(a2[t * (CH + 1) + g + G * i], fqt, acck[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NUM_T; ++i) {
+      const int u = g + G * i, n = t0 + u;
+      if (n < a.N) {
+        Storage<T>::store(a.dv, voff + (int64_t)n * a.v.sn + c, accv[i]);
+        Storage<T>::store(a.dk, koff + (int64_t)n * a.k.sn + c,
+                          acck[i] * feature_map_slope(fk[u * D + c], a.phi));
+      }
+    }
+    __syncthreads();  // all reads of B and Y for this chunk are done
+    // state update: B[cc][e] += sum_t phi(q_t)[cc] g_t[e];  Y[cc] += sum_t c_t phi(q_t)[cc]
+    {
+      const int e = c;
+      float gcol[CH];
+#pragma unroll
+      for (int t = 0; t < CH; ++t) gcol[t] = gg[t * D + e];
+      for (int i = 0; i < UPD_C; ++i) {
+        const int cc = g + G * i;
+        float s = Bm[cc * SR + e];
+#pragma unroll
+        for (int t = 0; t < CH; ++t) s = fmaf(fq[t * D + cc], gcol[t], s);
+        Bm[cc * SR + e] = s;
+      }
+      if (tid < D) {
+        float s = y[tid];
+        for (int t = 0; t < CH; ++t) s = fmaf(cvec[t], fq[t * D + tid], s);
+        y[tid] = s;
+      }
+    }
+  }
+}
+
+template <typename T, int D>
+hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t s) {
+  if (a.H0 > 0) {
+    dim3 grid((a.N + kBwdRows - 1) / kBwdRows, a.H0, a.B);
+    windowed_bwd_q_kernel<T, D><<<grid, dim3(kBwdThreads), 0, s>>>(a);
+    windowed_bwd_kv_kernel<T, D><<<grid, dim3(kBwdThreads), 0, s>>>(a);
+  }
+  if (a.H0 < a.H) {
+    dim3 grid(a.H - a.H0, a.B);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_q_kernel<T, D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)linear_bwd_q_smem<D>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_kv_kernel<T, D>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)linear_bwd_kv_smem<D>());
+    if (e != hipSuccess) return e;
+    linear_bwd_q_kernel<T, D><<<grid, dim3(kBwdThreads), linear_bwd_q_smem<D>(), s>>>(a);
+    linear_bwd_kv_kernel<T, D><<<grid, dim3(kBwdThreads), linear_bwd_kv_smem<D>(), s>>>(a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_backward_scalar(const BwdArgs& a, bool bf16, hipStream_t s) {
+  if (a.B <= 0 || a.H <= 0 || a.N <= 0) return hipSuccess;
+  if (a.d == 64) return bf16 ? launch_bwd_t<uint16_t, 64>(a, s) : launch_bwd_t<float, 64>(a, s);
+  return bf16 ? launch_bwd_t<uint16_t, 128>(a, s) : launch_bwd_t<float, 128>(a, s);
+}
+
+}  // namespace gformer

@@ -83,6 +83,21 @@ template <> struct Storage<uint16_t> {  // bf16 bit patterns
   }
 };
 
+// One call of the backward pass: q, k, v and the gradient dout of the output in; dq, dk, dv out
+// (dq is laid out like q, dk like k, dv like v).
+struct BwdArgs {
+  TensorView q, k, v, dout;
+  void *dq, *dk, *dv;
+  int B, H, N, d;
+  int window;
+  int H0;
+  int phi;
+  float scale, eps;
+  float* ws;   // [B, H, N, 2] fp32: windowed heads (log-sum-exp, dO.o), linear heads (den, dO.o / den),
+               // written by the per-query kernels, read by the per-key kernels
+};
+hipError_t launch_backward_scalar(const BwdArgs& a, bool bf16, hipStream_t s);
+
 // One call of the random-feature pre-map: heads [head_begin, head_end) of x -> the same heads of out.
 struct FeatureArgs {
   TensorView x;

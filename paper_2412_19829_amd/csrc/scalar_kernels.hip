@@ -2,30 +2,11 @@
 // library (reduced-precision operands never reach a matrix core here) and are written for
 // clarity; the MFMA kernels carry the bf16 performance path.
 #include "common.hpp"
+#include "scalar_util.hpp"
 
 namespace gformer {
 
 namespace {
-
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
-  return x;
-}
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
-  return x;
-}
-__device__ __forceinline__ float lane_bcast(float x, int lane) {
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
-}
-
-// Feature map of section II-B: phi(x) = elu(x) + 1.
-__device__ __forceinline__ float feature_map(float x, int phi) {
-  if (phi != 0) return x;
-  return x > 0.f ? x + 1.f : expf(x);
-}
 
 // ---------------------------------------------------------------------------------------
 // Windowed softmax head (section III-B, Eq. 1), causal or centred.  One wave owns one query at a time;

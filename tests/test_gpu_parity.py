@@ -622,3 +622,99 @@ def test_seeded_sweep(case):
     got = run_gpu(q, k, v, "bf16", w, H0, layout=layout, impl=impl, bidirectional=bi)
     ref = co.attn_fwd(q, k, v, w, H0, linear_form=co.LINEAR_RECURRENT, bidirectional=bool(bi))
     check(got, ref, "bf16", str(case))
+
+
+# ---------------------------------------------------------------------------------------
+# backward pass (plain-FMA kernels) against the oracle's derivatives
+# ---------------------------------------------------------------------------------------
+
+def run_bwd(q, k, v, dout, dtype, w, H0, layout="bhnd", **kw):
+    """Returns float64 (dq, dk, dv)."""
+    import torch
+    tq, tk, tv, tdo = (to_device(x, dtype) for x in (q, k, v, dout))
+    if layout == "bnhd":
+        tq, tk, tv, tdo = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (tq, tk, tv, tdo))
+    dq, dk, dv = (torch.full_like(t, float("nan")) for t in (tq, tk, tv))
+    gb.gformer_attn_bwd(tq, tk, tv, tdo, dq, dk, dv, w, H0, **kw)
+    torch.cuda.synchronize()
+    return tuple(to_host(t) for t in (dq, dk, dv))
+
+
+def check_grad(got, ref, dtype, what, dout):
+    """fp32: max-abs error <= 1e-5 times the larger of the tensor's largest gradient magnitude
+    and a typical dO row norm (a gradient entry is a difference of terms of the size
+    |dO_i||v_j||k_j|, and fp32 rounding acts on those terms, not on the difference).  bf16: per-row L2 error <= 2e-2
+    of the row's norm, where rows that vanish by cancellation (the gradient with respect to q of
+    a token that sees one key is exactly 0) are measured against 1 % of a typical dO row instead
+    of against themselves."""
+    assert np.isfinite(got).all(), f"non-finite gradient {what}"
+    if dtype == "f32":
+        rown = float(np.median(np.sqrt((dout.astype(np.float64) ** 2).sum(-1))))
+        err, scale = max_abs(got, ref), max(1.0, float(np.abs(ref).max()), rown)
+        assert err <= F32_MAX_ABS * scale, f"{what}: max-abs {err:.3e} at scale {scale:.3g}"
+    else:
+        err = np.sqrt(((got - ref) ** 2).sum(-1))
+        floor = 1e-2 * float(np.median(np.sqrt((dout.astype(np.float64) ** 2).sum(-1))))
+        den = np.maximum(np.sqrt((ref ** 2).sum(-1)), floor)
+        worst = float((err / den).max())
+        assert worst <= BF16_ROW_REL_L2, f"{what}: worst row rel-L2 {worst:.3e}"
+
+
+BWD_SHAPES = [
+    # B, H, N, d, window, H0
+    (1, 2, 1, 64, 4, 1),
+    (2, 3, 77, 64, 1, 2),
+    (1, 4, 333, 64, 32, 2),
+    (1, 2, 300, 128, 100, 1),
+    (1, 2, 200, 64, 1000, 1),      # window >= N
+    (1, 3, 1025, 128, 256, 1),
+    (2, 2, 513, 128, 70, 0),
+    (1, 2, 640, 64, 129, 2),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", BWD_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_backward_shapes(shape, dtype):
+    B, H, N, d, w, H0 = shape
+    q, k, v = synth(B, H, N, d, dtype, 61)
+    dout = synth(B, H, N, d, dtype, 62)[2]
+    got = run_bwd(q, k, v, dout, dtype, w, H0)
+    ref = co.attn_bwd(q, k, v, dout, w, H0)
+    for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+        check_grad(g, r, dtype, f"{name} {shape}", dout)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_scale_eps_identity_map_and_strides(dtype):
+    B, H, N, d, w, H0 = 2, 4, 150, 64, 40, 2
+    q, k, v = synth(B, H, N, d, dtype, 63, q_prescaled=False)
+    dout = synth(B, H, N, d, dtype, 64)[2]
+    q[:, H0:] = np.abs(q[:, H0:]) + np.float32(0.125)
+    k[:, H0:] = np.abs(k[:, H0:]) + np.float32(0.125)
+    if dtype == "bf16":
+        q, k = gi.round_to_bf16(q), gi.round_to_bf16(k)
+    kw = dict(softmax_scale=0.125, eps=0.5, phi=gb.GF_PHI_IDENTITY)
+    got = run_bwd(q, k, v, dout, dtype, w, H0, layout="bnhd", **kw)
+    ref = co.attn_bwd(q, k, v, dout, w, H0, phi=co.PHI_IDENTITY, softmax_scale=0.125, eps=0.5)
+    for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+        check_grad(g, r, dtype, name, dout)
+
+
+def test_backward_refuses_what_it_does_not_cover():
+    import torch
+    t = [torch.zeros(1, 2, 64, 64, device="cuda", dtype=torch.bfloat16) for _ in range(7)]
+    with pytest.raises(gb.GformerError) as e:
+        gb.gformer_attn_bwd(*t, 8, 1, impl=MFMA)
+    assert e.value.status == gb.GF_ERR_UNSUPPORTED
+    p = gb.make_params(n_sparse_heads=1, bidirectional=1)
+    ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    st = gb.gformer_attn_bwd_raw(*(x.data_ptr() for x in t), 1, 2, 64, 64, 8, p, ws.data_ptr(), ws.numel(), 0)
+    assert st == gb.GF_ERR_UNSUPPORTED
+    p = gb.make_params(n_sparse_heads=1)
+    st = gb.gformer_attn_bwd_raw(*(x.data_ptr() for x in t), 1, 2, 64, 64, 8, p, 0, 0, 0)
+    assert st == gb.GF_ERR_WORKSPACE
+    ptrs = [x.data_ptr() for x in t]
+    ptrs[4] = ptrs[0]          # dq aliases q
+    st = gb.gformer_attn_bwd_raw(*ptrs, 1, 2, 64, 64, 8, p, ws.data_ptr(), ws.numel(), 0)
+    assert st == gb.GF_ERR_INVALID_ARG
