@@ -298,6 +298,24 @@ def main() -> int:
         modes["decode"] = {"us_per_step": round(t_dec * 1e6, 2), "tokens_per_s": round(wl.B / t_dec, 1),
                            "gbs": round(dec_bytes / t_dec / 1e9, 1),
                            "note": "full rings; bytes = rings read once + states read and written once"}
+        # Backward pass of the same layer (plain-FMA kernels; a few launches only: they are slow)
+        tdo = dev(v)
+        dq_, dk_, dv_ = (torch.empty_like(x) for x in (tq, tk, tv))
+        pb = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=H0)
+        need_b = gb.gformer_attn_bwd_workspace_bytes(wl.B, wl.H, wl.N, wl.d, wl.window, pb)
+        ws_b = torch.empty(need_b, dtype=torch.uint8, device=tq.device)
+
+        def backward():
+            st_ = gb.gformer_attn_bwd_raw(tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), tdo.data_ptr(),
+                                          dq_.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), wl.B, wl.H, wl.N,
+                                          wl.d, wl.window, pb, ws_b.data_ptr(), need_b, stream)
+            if st_ != gb.GF_OK:
+                raise gb.GformerError(st_, gb.gformer_status_string(st_))
+        backward()
+        torch.cuda.synchronize()
+        t_bwd = event_time(backward, 3)
+        modes["backward"] = {"ms": round(t_bwd * 1e3, 3), "tokens_per_s": round(wl.B * wl.N / t_bwd, 1),
+                             "note": "gformer_attn_bwd, fp32 plain-FMA kernels on bf16 storage"}
         result["modes"] = modes
 
     # ---- CPU baseline: the fp64 oracle on batch element 0 (all heads), host cores ---------

@@ -60,14 +60,7 @@ __global__ __launch_bounds__(kBwdThreads) void windowed_bwd_q_kernel(BwdArgs a) 
     const int lo = max(0, i - a.window + 1), hi = i;
     // lane j's score against this query; lanes past the last visible key read that key again
     auto score = [&](int j) {
-      const int64_t kr = koff + (int64_t)min(j, hi) * a.k.sn;
-      float s = 0.f;
-#pragma unroll
-      for (int cc = 0; cc < CPL; ++cc)
-#pragma unroll
-        for (int c = 0; c < 64; ++c)
-          s = fmaf(lane_bcast(qreg[cc], c), Storage<T>::load(a.k.base, kr + cc * 64 + c), s);
-      return s * a.scale;
+      return dot_row_with_spread<T, D>(a.k.base, koff + (int64_t)min(j, hi) * a.k.sn, qreg) * a.scale;
     };
     // the row's log-sum-exp
     float m = -INFINITY, l = 0.f;
@@ -81,14 +74,7 @@ __global__ __launch_bounds__(kBwdThreads) void windowed_bwd_q_kernel(BwdArgs a) 
     const float lse = m + logf(l);
     // lane j's dO_i.v_j
     auto dvalue = [&](int j) {
-      const int64_t vr = voff + (int64_t)min(j, hi) * a.v.sn;
-      float dp = 0.f;
-#pragma unroll
-      for (int cc = 0; cc < CPL; ++cc)
-#pragma unroll
-        for (int c = 0; c < 64; ++c)
-          dp = fmaf(lane_bcast(doreg[cc], c), Storage<T>::load(a.v.base, vr + cc * 64 + c), dp);
-      return dp;
+      return dot_row_with_spread<T, D>(a.v.base, voff + (int64_t)min(j, hi) * a.v.sn, doreg);
     };
     // D_i = sum_j p_ij dO_i.v_j
     float dsum = 0.f;
@@ -159,18 +145,8 @@ __global__ __launch_bounds__(kBwdThreads) void windowed_bwd_kv_kernel(BwdArgs a)
       const int i = i0 + lane;
       const bool valid = i <= ihi;
       const int ii = min(i, ihi);   // lanes past the last query read that query again
-      float s = 0.f, dp = 0.f;
-      {
-        const int64_t qr = qoff + (int64_t)ii * a.q.sn;
-        const int64_t dr = ooff + (int64_t)ii * a.dout.sn;
-#pragma unroll
-        for (int cc = 0; cc < CPL; ++cc)
-#pragma unroll
-          for (int c = 0; c < 64; ++c) {
-            s = fmaf(lane_bcast(kreg[cc], c), Storage<T>::load(a.q.base, qr + cc * 64 + c), s);
-            dp = fmaf(lane_bcast(vreg[cc], c), Storage<T>::load(a.dout.base, dr + cc * 64 + c), dp);
-          }
-      }
+      const float s = dot_row_with_spread<T, D>(a.q.base, qoff + (int64_t)ii * a.q.sn, kreg);
+      const float dp = dot_row_with_spread<T, D>(a.dout.base, ooff + (int64_t)ii * a.dout.sn, vreg);
       const float lse = ws[2 * (int64_t)ii], Di = ws[2 * (int64_t)ii + 1];
       const float p = valid ? expf(s * a.scale - lse) : 0.f;
       const float ds = p * (dp - Di);
@@ -198,29 +174,33 @@ __global__ __launch_bounds__(kBwdThreads) void windowed_bwd_kv_kernel(BwdArgs a)
 // linear heads
 // ---------------------------------------------------------------------------------------
 constexpr int kBwdChunk = 32;
+constexpr int kBwdLinThreads = 512;
 
+// Token rows in LDS are D + 1 floats apart: the chunk's CH x CH products read column cc of 32
+// different rows at once, which with a stride of D would all fall into one bank.
 template <int D> constexpr size_t linear_bwd_q_smem() {
-  return sizeof(float) * (5 * kBwdChunk * D + D * (D + 1) + D + 2 * kBwdChunk * (kBwdChunk + 1) + 2 * kBwdChunk);
+  return sizeof(float) * (5 * kBwdChunk * (D + 1) + D * (D + 1) + D + 2 * kBwdChunk * (kBwdChunk + 1) + 2 * kBwdChunk);
 }
 template <int D> constexpr size_t linear_bwd_kv_smem() {
-  return sizeof(float) * (4 * kBwdChunk * D + D * (D + 1) + D + 2 * kBwdChunk * (kBwdChunk + 1) + kBwdChunk);
+  return sizeof(float) * (4 * kBwdChunk * (D + 1) + D * (D + 1) + D + 2 * kBwdChunk * (kBwdChunk + 1) + kBwdChunk);
 }
 
-// Forward scan: dq, and (den_i, c_i) for the reverse scan.  grid = (H1, B), block = 256.
+// Forward scan: dq, and (den_i, c_i) for the reverse scan.  grid = (H1, B), block = 512.
 template <typename T, int D>
-__global__ __launch_bounds__(kBwdThreads) void linear_bwd_q_kernel(BwdArgs a) {
+__global__ __launch_bounds__(kBwdLinThreads) void linear_bwd_q_kernel(BwdArgs a) {
   constexpr int CH = kBwdChunk;
-  constexpr int G = kBwdThreads / D;   // thread groups along the token axis
+  constexpr int G = kBwdLinThreads / D;   // thread groups along the token axis
   constexpr int NUM_T = CH / G;        // tokens per thread
   constexpr int UPD_C = D / G;         // state rows per thread in the update
   constexpr int SR = D + 1;            // state row stride: rows and columns both conflict-free
+  constexpr int TR = D + 1;            // token row stride
   extern __shared__ float smem[];
   float* fq = smem;                   // [CH][D] phi(q)
-  float* fk = fq + CH * D;            // [CH][D] phi(k)
-  float* vv = fk + CH * D;            // [CH][D]
-  float* gg = vv + CH * D;            // [CH][D] dO, then g = dO / den
-  float* rr = gg + CH * D;            // [CH][D] r_t = A g_t (state before the chunk)
-  float* S = rr + CH * D;             // [D][SR]  A: rows = feature c, columns = value e
+  float* fk = fq + CH * TR;            // [CH][D] phi(k)
+  float* vv = fk + CH * TR;            // [CH][D]
+  float* gg = vv + CH * TR;            // [CH][D] dO, then g = dO / den
+  float* rr = gg + CH * TR;            // [CH][D] r_t = A g_t (state before the chunk)
+  float* S = rr + CH * TR;             // [D][SR]  A: rows = feature c, columns = value e
   float* z = S + D * SR;              // [D]
   float* am = z + D;                  // [CH][CH+1] a[t][u] = phi(q_t).phi(k_u), u <= t
   float* gv = am + CH * (CH + 1);     // [CH][CH+1] g_t.v_u, then g_t.v_u - c_t, u <= t
@@ -235,14 +215,14 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_q_kernel(BwdArgs a) {
   const int64_t ooff = b * a.dout.sb + h * a.dout.sh;   // layout of dO
   float* ws = a.ws + ((int64_t)b * a.H + h) * a.N * 2;
 
-  for (int x = tid; x < D * SR; x += kBwdThreads) S[x] = 0.f;
+  for (int x = tid; x < D * SR; x += kBwdLinThreads) S[x] = 0.f;
   if (tid < D) z[tid] = 0.f;
   const int c = tid % D;   // the feature (or value) index this thread owns
   const int g = tid / D;
 
   for (int t0 = 0; t0 < a.N; t0 += CH) {
     __syncthreads();  // previous chunk fully consumed (and the zero fill above is visible)
-    for (int x = tid; x < CH * D; x += kBwdThreads) {
+    for (int x = tid; x < CH * D; x += kBwdLinThreads) {
       const int t = x / D, cc = x % D;
       const int n = t0 + t;
       float qv = 0.f, kv = 0.f, v_ = 0.f, d_ = 0.f;
@@ -252,15 +232,16 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_q_kernel(BwdArgs a) {
         v_ = Storage<T>::load(a.v.base, voff + (int64_t)n * a.v.sn + cc);
         d_ = Storage<T>::load(a.dout.base, ooff + (int64_t)n * a.dout.sn + cc);
       }
-      fq[x] = qv; fk[x] = kv; vv[x] = v_; gg[x] = d_;   // rows past N: zeros
+      const int y = t * TR + cc;
+      fq[y] = qv; fk[y] = kv; vv[y] = v_; gg[y] = d_;   // rows past N: zeros
     }
     __syncthreads();
     // a[t][u] = phi(q_t).phi(k_u), u <= t
-    for (int x = tid; x < CH * CH; x += kBwdThreads) {
+    for (int x = tid; x < CH * CH; x += kBwdLinThreads) {
       const int t = x / CH, u = x % CH;
       float s = 0.f;
       if (u <= t)
-        for (int cc = 0; cc < D; ++cc) s = fmaf(fq[t * D + cc], fk[u * D + cc], s);
+        for (int cc = 0; cc < D; ++cc) s = fmaf(fq[t * TR + cc], fk[u * TR + cc], s);
       am[t * (CH + 1) + u] = s;
     }
     __syncthreads();
@@ -268,19 +249,19 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_q_kernel(BwdArgs a) {
       float s = 0.f;
       for (int u = 0; u <= tid; ++u) s += am[tid * (CH + 1) + u];
       float zz = 0.f;
-      for (int cc = 0; cc < D; ++cc) zz = fmaf(fq[tid * D + cc], z[cc], zz);
+      for (int cc = 0; cc < D; ++cc) zz = fmaf(fq[tid * TR + cc], z[cc], zz);
       // rows past N keep a harmless denominator of 1 (their dO is zero)
       den[tid] = (t0 + tid < a.N) ? s + zz + a.eps : 1.f;
     }
     __syncthreads();
-    for (int x = tid; x < CH * D; x += kBwdThreads) gg[x] /= den[x / D];   // g = dO / den
+    for (int x = tid; x < CH * D; x += kBwdLinThreads) gg[(x / D) * TR + x % D] /= den[x / D];   // g = dO / den
     __syncthreads();
     // gv[t][u] = g_t.v_u, u <= t
-    for (int x = tid; x < CH * CH; x += kBwdThreads) {
+    for (int x = tid; x < CH * CH; x += kBwdLinThreads) {
       const int t = x / CH, u = x % CH;
       float s = 0.f;
       if (u <= t)
-        for (int cc = 0; cc < D; ++cc) s = fmaf(gg[t * D + cc], vv[u * D + cc], s);
+        for (int cc = 0; cc < D; ++cc) s = fmaf(gg[t * TR + cc], vv[u * TR + cc], s);
       gv[t * (CH + 1) + u] = s;
     }
     // r[t][c] = sum_e A[c][e] g_t[e]
@@ -290,15 +271,15 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_q_kernel(BwdArgs a) {
     for (int e = 0; e < D; ++e) {
       const float sce = S[c * SR + e];
 #pragma unroll
-      for (int i = 0; i < NUM_T; ++i) acc[i] = fmaf(sce, gg[(g + G * i) * D + e], acc[i]);
+      for (int i = 0; i < NUM_T; ++i) acc[i] = fmaf(sce, gg[(g + G * i) * TR + e], acc[i]);
     }
 #pragma unroll
-    for (int i = 0; i < NUM_T; ++i) rr[(g + G * i) * D + c] = acc[i];
+    for (int i = 0; i < NUM_T; ++i) rr[(g + G * i) * TR + c] = acc[i];
     __syncthreads();
     // c_t = g_t.num_t / den_t with g_t.num_t = phi(q_t).r_t + sum_{u<=t} a[t][u] g_t.v_u
     if (tid < CH) {
       float s = 0.f;
-      for (int cc = 0; cc < D; ++cc) s = fmaf(fq[tid * D + cc], rr[tid * D + cc], s);
+      for (int cc = 0; cc < D; ++cc) s = fmaf(fq[tid * TR + cc], rr[tid * TR + cc], s);
       for (int u = 0; u <= tid; ++u) s = fmaf(am[tid * (CH + 1) + u], gv[tid * (CH + 1) + u], s);
       const float ct = s / den[tid];
       cvec[tid] = ct;
@@ -309,7 +290,7 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_q_kernel(BwdArgs a) {
     }
     __syncthreads();
     // w[t][u] = g_t.v_u - c_t, u <= t
-    for (int x = tid; x < CH * CH; x += kBwdThreads) {
+    for (int x = tid; x < CH * CH; x += kBwdLinThreads) {
       const int t = x / CH, u = x % CH;
       if (u <= t) gv[t * (CH + 1) + u] -= cvec[t];
     }
@@ -318,7 +299,7 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_q_kernel(BwdArgs a) {
 #pragma unroll
     for (int i = 0; i < NUM_T; ++i) acc[i] -= cvec[g + G * i] * z[c];
     for (int u = 0; u < CH; ++u) {
-      const float fku = fk[u * D + c];
+      const float fku = fk[u * TR + c];
 #pragma unroll
       for (int i = 0; i < NUM_T; ++i) acc[i] = fmaf(gv[(g + G * i) * (CH + 1) + u], fku, acc[i]);
     }
@@ -327,7 +308,7 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_q_kernel(BwdArgs a) {
       const int t = g + G * i, n = t0 + t;
       if (n < a.N)
         Storage<T>::store(a.dq, qoff + (int64_t)n * a.q.sn + c,
-                          acc[i] * feature_map_slope(fq[t * D + c], a.phi));
+                          acc[i] * feature_map_slope(fq[t * TR + c], a.phi));
     }
     __syncthreads();  // all reads of A and Z for this chunk are done
     // state update: A[cc][e] += sum_t phi(k_t)[cc] v_t[e];  Z[cc] += sum_t phi(k_t)[cc]
@@ -335,37 +316,38 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_q_kernel(BwdArgs a) {
       const int e = c;
       float vcol[CH];
 #pragma unroll
-      for (int t = 0; t < CH; ++t) vcol[t] = vv[t * D + e];
+      for (int t = 0; t < CH; ++t) vcol[t] = vv[t * TR + e];
       for (int i = 0; i < UPD_C; ++i) {
         const int cc = g + G * i;
         float s = S[cc * SR + e];
 #pragma unroll
-        for (int t = 0; t < CH; ++t) s = fmaf(fk[t * D + cc], vcol[t], s);
+        for (int t = 0; t < CH; ++t) s = fmaf(fk[t * TR + cc], vcol[t], s);
         S[cc * SR + e] = s;
       }
       if (tid < D) {
         float s = z[tid];
-        for (int t = 0; t < CH; ++t) s += fk[t * D + tid];
+        for (int t = 0; t < CH; ++t) s += fk[t * TR + tid];
         z[tid] = s;
       }
     }
   }
 }
 
-// Reverse scan: dk and dv.  grid = (H1, B), block = 256; reads (den_i, c_i) left by the kernel above.
+// Reverse scan: dk and dv.  grid = (H1, B), block = 512; reads (den_i, c_i) left by the kernel above.
 template <typename T, int D>
-__global__ __launch_bounds__(kBwdThreads) void linear_bwd_kv_kernel(BwdArgs a) {
+__global__ __launch_bounds__(kBwdLinThreads) void linear_bwd_kv_kernel(BwdArgs a) {
   constexpr int CH = kBwdChunk;
-  constexpr int G = kBwdThreads / D;
+  constexpr int G = kBwdLinThreads / D;
   constexpr int NUM_T = CH / G;
   constexpr int UPD_C = D / G;
   constexpr int SR = D + 1;
+  constexpr int TR = D + 1;
   extern __shared__ float smem[];
   float* fq = smem;                   // [CH][D]
-  float* fk = fq + CH * D;            // [CH][D]
-  float* vv = fk + CH * D;            // [CH][D]
-  float* gg = vv + CH * D;            // [CH][D] g = dO / den
-  float* Bm = gg + CH * D;            // [D][SR]  B: rows = feature c, columns = value e
+  float* fk = fq + CH * TR;            // [CH][D]
+  float* vv = fk + CH * TR;            // [CH][D]
+  float* gg = vv + CH * TR;            // [CH][D] g = dO / den
+  float* Bm = gg + CH * TR;            // [D][SR]  B: rows = feature c, columns = value e
   float* y = Bm + D * SR;             // [D]
   float* a1 = y + D;                  // [CH][CH+1] phi(q_t).phi(k_u), t >= u
   float* a2 = a1 + CH * (CH + 1);     // [CH][CH+1] g_t.v_u - c_t, t >= u
@@ -379,7 +361,7 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_kv_kernel(BwdArgs a) {
   const int64_t ooff = b * a.dout.sb + h * a.dout.sh;
   const float* ws = a.ws + ((int64_t)b * a.H + h) * a.N * 2;
 
-  for (int x = tid; x < D * SR; x += kBwdThreads) Bm[x] = 0.f;
+  for (int x = tid; x < D * SR; x += kBwdLinThreads) Bm[x] = 0.f;
   if (tid < D) y[tid] = 0.f;
   const int c = tid % D;
   const int g = tid / D;
@@ -388,7 +370,7 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_kv_kernel(BwdArgs a) {
   for (int ch = nchunks - 1; ch >= 0; --ch) {
     const int t0 = ch * CH;
     __syncthreads();  // previous chunk fully consumed (and the zero fill above is visible)
-    for (int x = tid; x < CH * D; x += kBwdThreads) {
+    for (int x = tid; x < CH * D; x += kBwdLinThreads) {
       const int t = x / D, cc = x % D;
       const int n = t0 + t;
       float qv = 0.f, kv = 0.f, v_ = 0.f, g_ = 0.f;
@@ -398,17 +380,18 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_kv_kernel(BwdArgs a) {
         v_ = Storage<T>::load(a.v.base, voff + (int64_t)n * a.v.sn + cc);
         g_ = Storage<T>::load(a.dout.base, ooff + (int64_t)n * a.dout.sn + cc) / ws[2 * (int64_t)n];
       }
-      fq[x] = qv; fk[x] = kv; vv[x] = v_; gg[x] = g_;   // rows past N: zeros, no contribution
+      const int y = t * TR + cc;
+      fq[y] = qv; fk[y] = kv; vv[y] = v_; gg[y] = g_;   // rows past N: zeros, no contribution
     }
     if (tid < CH) cvec[tid] = (t0 + tid < a.N) ? ws[2 * (int64_t)(t0 + tid) + 1] : 0.f;
     __syncthreads();
-    for (int x = tid; x < CH * CH; x += kBwdThreads) {
+    for (int x = tid; x < CH * CH; x += kBwdLinThreads) {
       const int t = x / CH, u = x % CH;
       float s1 = 0.f, s2 = 0.f;
       if (t >= u) {
         for (int cc = 0; cc < D; ++cc) {
-          s1 = fmaf(fq[t * D + cc], fk[u * D + cc], s1);
-          s2 = fmaf(gg[t * D + cc], vv[u * D + cc], s2);
+          s1 = fmaf(fq[t * TR + cc], fk[u * TR + cc], s1);
+          s2 = fmaf(gg[t * TR + cc], vv[u * TR + cc], s2);
         }
         s2 -= cvec[t];
         if (t0 + t >= a.N) { s1 = 0.f; s2 = 0.f; }   // a row past N weighs nothing
@@ -426,12 +409,12 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_kv_kernel(BwdArgs a) {
       const float bec = Bm[c * SR + cc];   // B[c][e = cc]
 #pragma unroll
       for (int i = 0; i < NUM_T; ++i) {
-        accv[i] = fmaf(bce, fk[(g + G * i) * D + cc], accv[i]);   // dv_u[e] += B[cc][e] phi(k_u)[cc]
-        acck[i] = fmaf(bec, vv[(g + G * i) * D + cc], acck[i]);   // dfk_u[c] += B[c][cc] v_u[cc]
+        accv[i] = fmaf(bce, fk[(g + G * i) * TR + cc], accv[i]);   // dv_u[e] += B[cc][e] phi(k_u)[cc]
+        acck[i] = fmaf(bec, vv[(g + G * i) * TR + cc], acck[i]);   // dfk_u[c] += B[c][cc] v_u[cc]
       }
     }
     for (int t = 0; t < CH; ++t) {
-      const float gte = gg[t * D + c], fqt = fq[t * D + c];
+      const float gte = gg[t * TR + c], fqt = fq[t * TR + c];
 #pragma unroll
       for (int i = 0; i < NUM_T; ++i) {
         accv[i] = fmaf(a1[t * (CH + 1) + g + G * i], gte, accv[i]);   // zero where t < u
@@ -444,7 +427,7 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_kv_kernel(BwdArgs a) {
       if (n < a.N) {
         Storage<T>::store(a.dv, voff + (int64_t)n * a.v.sn + c, accv[i]);
         Storage<T>::store(a.dk, koff + (int64_t)n * a.k.sn + c,
-                          acck[i] * feature_map_slope(fk[u * D + c], a.phi));
+                          acck[i] * feature_map_slope(fk[u * TR + c], a.phi));
       }
     }
     __syncthreads();  // all reads of B and Y for this chunk are done
@@ -453,17 +436,17 @@ __global__ __launch_bounds__(kBwdThreads) void linear_bwd_kv_kernel(BwdArgs a) {
       const int e = c;
       float gcol[CH];
 #pragma unroll
-      for (int t = 0; t < CH; ++t) gcol[t] = gg[t * D + e];
+      for (int t = 0; t < CH; ++t) gcol[t] = gg[t * TR + e];
       for (int i = 0; i < UPD_C; ++i) {
         const int cc = g + G * i;
         float s = Bm[cc * SR + e];
 #pragma unroll
-        for (int t = 0; t < CH; ++t) s = fmaf(fq[t * D + cc], gcol[t], s);
+        for (int t = 0; t < CH; ++t) s = fmaf(fq[t * TR + cc], gcol[t], s);
         Bm[cc * SR + e] = s;
       }
       if (tid < D) {
         float s = y[tid];
-        for (int t = 0; t < CH; ++t) s = fmaf(cvec[t], fq[t * D + tid], s);
+        for (int t = 0; t < CH; ++t) s = fmaf(cvec[t], fq[t * TR + tid], s);
         y[tid] = s;
       }
     }
@@ -486,8 +469,8 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t s) {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_kv_kernel<T, D>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)linear_bwd_kv_smem<D>());
     if (e != hipSuccess) return e;
-    linear_bwd_q_kernel<T, D><<<grid, dim3(kBwdThreads), linear_bwd_q_smem<D>(), s>>>(a);
-    linear_bwd_kv_kernel<T, D><<<grid, dim3(kBwdThreads), linear_bwd_kv_smem<D>(), s>>>(a);
+    linear_bwd_q_kernel<T, D><<<grid, dim3(kBwdLinThreads), linear_bwd_q_smem<D>(), s>>>(a);
+    linear_bwd_kv_kernel<T, D><<<grid, dim3(kBwdLinThreads), linear_bwd_kv_smem<D>(), s>>>(a);
   }
   return hipGetLastError();
 }
