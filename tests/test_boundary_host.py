@@ -288,3 +288,37 @@ def test_prefill_argument_checks_on_the_host():
     assert gb.gformer_attn_prefill_raw(*ok, *a, gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1, launch_mask=1)) == gb.GF_ERR_INVALID_ARG
     assert gb.gformer_attn_prefill_raw(*ok, 1, 2, 16, 96, 4, p) == gb.GF_ERR_UNSUPPORTED
     assert gb.gformer_attn_prefill_raw(0, 0, 0, 0, 0, 0, 0, 1, 2, 0, 64, 4, p) == gb.GF_OK
+
+
+def test_backward_argument_checks_on_the_host():
+    p = gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1)
+    a = (1, 2, 16, 64, 4)
+    ptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
+    ws = (0x10000, 1 << 20)
+    assert gb.gformer_attn_bwd_workspace_bytes(*a, p) == 1 * 2 * 16 * 2 * 4
+    assert gb.gformer_attn_bwd_workspace_bytes(0, 2, 16, 64, 4, p) == 0
+    for i in range(7):                      # any null pointer
+        bad = list(ptrs)
+        bad[i] = 0
+        assert gb.gformer_attn_bwd_raw(*bad, *a, p, *ws) == gb.GF_ERR_INVALID_ARG
+    mis = list(ptrs)
+    mis[3] += 8                             # misaligned dout
+    assert gb.gformer_attn_bwd_raw(*mis, *a, p, *ws) == gb.GF_ERR_INVALID_ARG
+    for i, j in ((4, 0), (5, 1), (6, 3), (4, 5), (5, 6)):   # an output on an input or on another output
+        al = list(ptrs)
+        al[i] = al[j]
+        assert gb.gformer_attn_bwd_raw(*al, *a, p, *ws) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_attn_bwd_raw(*ptrs, *a, p, 0, 0) == gb.GF_ERR_WORKSPACE
+    assert gb.gformer_attn_bwd_raw(*ptrs, *a, p, ws[0], 255) == gb.GF_ERR_WORKSPACE
+    assert gb.gformer_attn_bwd_raw(*ptrs, *a, p, ws[0] + 16, ws[1]) == gb.GF_ERR_INVALID_ARG
+    # what the backward pass does not cover
+    for impl in (gb.GF_IMPL_MFMA, gb.GF_IMPL_MFMA_BLOCKED, gb.GF_IMPL_MFMA_STREAM):
+        q = gb.make_params(n_sparse_heads=1, impl=impl)
+        assert gb.gformer_attn_bwd_raw(*ptrs, *a, q, *ws) == gb.GF_ERR_UNSUPPORTED
+    assert gb.gformer_attn_bwd_raw(*ptrs, *a, gb.make_params(n_sparse_heads=1, bidirectional=1), *ws) == gb.GF_ERR_UNSUPPORTED
+    assert gb.gformer_attn_bwd_raw(*ptrs, *a, gb.make_params(n_sparse_heads=1, launch_mask=1), *ws) == gb.GF_ERR_INVALID_ARG
+    assert gb.gformer_attn_bwd_raw(*ptrs, 1, 2, 16, 96, 4, p, *ws) == gb.GF_ERR_UNSUPPORTED     # head size
+    assert gb.gformer_attn_bwd_raw(*ptrs, 1, 2, 16, 64, 0, p, *ws) == gb.GF_ERR_INVALID_ARG     # window
+    assert gb.gformer_attn_bwd_raw(*ptrs, 1, 2, 16, 64, 4, gb.make_params(n_sparse_heads=3), *ws) == gb.GF_ERR_INVALID_ARG
+    # empty problems are a no-op even with null pointers
+    assert gb.gformer_attn_bwd_raw(0, 0, 0, 0, 0, 0, 0, 1, 2, 0, 64, 4, p) == gb.GF_OK
