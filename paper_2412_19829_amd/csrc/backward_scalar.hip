@@ -62,44 +62,77 @@ __global__ __launch_bounds__(kBwdThreads) void windowed_bwd_q_kernel(BwdArgs a) 
     auto score = [&](int j) {
       return dot_row_with_spread<T, D>(a.k.base, koff + (int64_t)min(j, hi) * a.k.sn, qreg) * a.scale;
     };
-    // the row's log-sum-exp
-    float m = -INFINITY, l = 0.f;
-    for (int j0 = lo; j0 <= hi; j0 += 64) {
-      const int j = j0 + lane;
-      const float s = j <= hi ? score(j) : -INFINITY;
-      const float m_new = fmaxf(m, wave_max(s));   // finite: key j0 is always visible
-      l = l * expf(m - m_new) + wave_sum(j <= hi ? expf(s - m_new) : 0.f);
-      m = m_new;
-    }
-    const float lse = m + logf(l);
     // lane j's dO_i.v_j
     auto dvalue = [&](int j) {
       return dot_row_with_spread<T, D>(a.v.base, voff + (int64_t)min(j, hi) * a.v.sn, doreg);
     };
-    // D_i = sum_j p_ij dO_i.v_j
-    float dsum = 0.f;
-    for (int j0 = lo; j0 <= hi; j0 += 64) {
-      const int j = j0 + lane;
-      if (j <= hi) dsum = fmaf(expf(score(j) - lse), dvalue(j), dsum);
-    }
-    const float Di = wave_sum(dsum);
-
+    // dq_i += sum over one tile of ds_j k_j (lanes own columns)
     float acc[CPL];
 #pragma unroll
     for (int cc = 0; cc < CPL; ++cc) acc[cc] = 0.f;
-    for (int j0 = lo; j0 <= hi; j0 += 64) {
-      const int j = j0 + lane;
-      const bool valid = j <= hi;
-      const float p = valid ? expf(score(j) - lse) : 0.f;
-      const float dp = dvalue(j);
-      const float ds = p * (dp - Di);
+    auto add_tile = [&](int j0, float ds) {
       const int cnt = min(64, hi - j0 + 1);
       for (int jj = 0; jj < cnt; ++jj) {
-        const float dsj = __shfl(ds, jj, 64);
+        const float dsj = lane_bcast(ds, jj);
         const int64_t kr = koff + (int64_t)(j0 + jj) * a.k.sn;
 #pragma unroll
         for (int cc = 0; cc < CPL; ++cc)
           acc[cc] = fmaf(dsj, Storage<T>::load(a.k.base, kr + cc * 64 + lane), acc[cc]);
+      }
+    };
+    float lse, Di;
+    constexpr int KT = 4;   // windows of up to 64*KT keys keep their scores and dO.v in registers
+    if (hi - lo < 64 * KT) {
+      float sv[KT], dpv[KT];
+      float m = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < KT; ++t) {
+        const int j = lo + 64 * t + lane;
+        sv[t] = j <= hi ? score(j) : -INFINITY;
+        dpv[t] = j <= hi ? dvalue(j) : 0.f;
+        m = fmaxf(m, sv[t]);
+      }
+      m = wave_max(m);   // finite: key lo is always visible
+      float l = 0.f;
+#pragma unroll
+      for (int t = 0; t < KT; ++t) {
+        sv[t] = expf(sv[t] - m);   // 0 for lanes past the window
+        l += sv[t];
+      }
+      l = wave_sum(l);
+      lse = m + logf(l);
+      const float inv = 1.f / l;
+      float dsum = 0.f;
+#pragma unroll
+      for (int t = 0; t < KT; ++t) {
+        sv[t] *= inv;              // p_ij
+        dsum = fmaf(sv[t], dpv[t], dsum);
+      }
+      Di = wave_sum(dsum);
+#pragma unroll
+      for (int t = 0; t < KT; ++t)
+        if (lo + 64 * t <= hi) add_tile(lo + 64 * t, sv[t] * (dpv[t] - Di));   // uniform condition
+    } else {
+      // wider windows: three walks over the window, recomputing the scores
+      float m = -INFINITY, l = 0.f;
+      for (int j0 = lo; j0 <= hi; j0 += 64) {
+        const int j = j0 + lane;
+        const float s = j <= hi ? score(j) : -INFINITY;
+        const float m_new = fmaxf(m, wave_max(s));   // finite: key j0 is always visible
+        l = l * expf(m - m_new) + wave_sum(j <= hi ? expf(s - m_new) : 0.f);
+        m = m_new;
+      }
+      lse = m + logf(l);
+      float dsum = 0.f;   // D_i = sum_j p_ij dO_i.v_j
+      for (int j0 = lo; j0 <= hi; j0 += 64) {
+        const int j = j0 + lane;
+        if (j <= hi) dsum = fmaf(expf(score(j) - lse), dvalue(j), dsum);
+      }
+      Di = wave_sum(dsum);
+      for (int j0 = lo; j0 <= hi; j0 += 64) {
+        const int j = j0 + lane;
+        const float p = j <= hi ? expf(score(j) - lse) : 0.f;
+        add_tile(j0, p * (dvalue(j) - Di));
       }
     }
 #pragma unroll
@@ -152,7 +185,7 @@ __global__ __launch_bounds__(kBwdThreads) void windowed_bwd_kv_kernel(BwdArgs a)
       const float ds = p * (dp - Di);
       const int cnt = min(64, ihi - i0 + 1);
       for (int t = 0; t < cnt; ++t) {
-        const float pt = __shfl(p, t, 64), dst = __shfl(ds, t, 64);
+        const float pt = lane_bcast(p, t), dst = lane_bcast(ds, t);
         const int64_t qr = qoff + (int64_t)(i0 + t) * a.q.sn;
         const int64_t dr = ooff + (int64_t)(i0 + t) * a.dout.sn;
 #pragma unroll
@@ -176,13 +209,14 @@ __global__ __launch_bounds__(kBwdThreads) void windowed_bwd_kv_kernel(BwdArgs a)
 constexpr int kBwdChunk = 32;
 constexpr int kBwdLinThreads = 512;
 
-// Token rows in LDS are D + 1 floats apart: the chunk's CH x CH products read column cc of 32
-// different rows at once, which with a stride of D would all fall into one bank.
+// Token rows in LDS are D + 4 floats apart: 16-byte aligned, so that a row can be read four
+// values at a time, and a column of 32 rows (the chunk's CH x CH products read those) spreads
+// over 8 banks instead of falling into one.
 template <int D> constexpr size_t linear_bwd_q_smem() {
-  return sizeof(float) * (5 * kBwdChunk * (D + 1) + D * (D + 1) + D + 2 * kBwdChunk * (kBwdChunk + 1) + 2 * kBwdChunk);
+  return sizeof(float) * (5 * kBwdChunk * (D + 4) + D * (D + 1) + D + 2 * kBwdChunk * (kBwdChunk + 1) + 2 * kBwdChunk);
 }
 template <int D> constexpr size_t linear_bwd_kv_smem() {
-  return sizeof(float) * (4 * kBwdChunk * (D + 1) + D * (D + 1) + D + 2 * kBwdChunk * (kBwdChunk + 1) + kBwdChunk);
+  return sizeof(float) * (4 * kBwdChunk * (D + 4) + D * (D + 1) + D + 2 * kBwdChunk * (kBwdChunk + 1) + kBwdChunk);
 }
 
 // Forward scan: dq, and (den_i, c_i) for the reverse scan.  grid = (H1, B), block = 512.
@@ -193,8 +227,8 @@ __global__ __launch_bounds__(kBwdLinThreads) void linear_bwd_q_kernel(BwdArgs a)
   constexpr int NUM_T = CH / G;        // tokens per thread
   constexpr int UPD_C = D / G;         // state rows per thread in the update
   constexpr int SR = D + 1;            // state row stride: rows and columns both conflict-free
-  constexpr int TR = D + 1;            // token row stride
-  extern __shared__ float smem[];
+  constexpr int TR = D + 4;            // token row stride
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   float* fq = smem;                   // [CH][D] phi(q)
   float* fk = fq + CH * TR;            // [CH][D] phi(k)
   float* vv = fk + CH * TR;            // [CH][D]
@@ -268,10 +302,13 @@ __global__ __launch_bounds__(kBwdLinThreads) void linear_bwd_q_kernel(BwdArgs a)
     float acc[NUM_T];
 #pragma unroll
     for (int i = 0; i < NUM_T; ++i) acc[i] = 0.f;
-    for (int e = 0; e < D; ++e) {
-      const float sce = S[c * SR + e];
+    for (int e = 0; e < D; e += 4) {
+      const float s0 = S[c * SR + e], s1 = S[c * SR + e + 1], s2 = S[c * SR + e + 2], s3 = S[c * SR + e + 3];
 #pragma unroll
-      for (int i = 0; i < NUM_T; ++i) acc[i] = fmaf(sce, gg[(g + G * i) * TR + e], acc[i]);
+      for (int i = 0; i < NUM_T; ++i) {
+        const float4 g4 = *reinterpret_cast<const float4*>(&gg[(g + G * i) * TR + e]);   // same for all lanes
+        acc[i] = fmaf(s0, g4.x, fmaf(s1, g4.y, fmaf(s2, g4.z, fmaf(s3, g4.w, acc[i]))));
+      }
     }
 #pragma unroll
     for (int i = 0; i < NUM_T; ++i) rr[(g + G * i) * TR + c] = acc[i];
@@ -317,12 +354,16 @@ __global__ __launch_bounds__(kBwdLinThreads) void linear_bwd_q_kernel(BwdArgs a)
       float vcol[CH];
 #pragma unroll
       for (int t = 0; t < CH; ++t) vcol[t] = vv[t * TR + e];
-      for (int i = 0; i < UPD_C; ++i) {
-        const int cc = g + G * i;
-        float s = S[cc * SR + e];
+      for (int i = 0; i < UPD_C / 4; ++i) {
+        const int cc = 4 * (g + G * i);   // four state rows at a time: one 16-byte read per token
+        float s0 = S[cc * SR + e], s1 = S[(cc + 1) * SR + e], s2 = S[(cc + 2) * SR + e], s3 = S[(cc + 3) * SR + e];
 #pragma unroll
-        for (int t = 0; t < CH; ++t) s = fmaf(fk[t * TR + cc], vcol[t], s);
-        S[cc * SR + e] = s;
+        for (int t = 0; t < CH; ++t) {
+          const float4 f4 = *reinterpret_cast<const float4*>(&fk[t * TR + cc]);
+          s0 = fmaf(f4.x, vcol[t], s0); s1 = fmaf(f4.y, vcol[t], s1);
+          s2 = fmaf(f4.z, vcol[t], s2); s3 = fmaf(f4.w, vcol[t], s3);
+        }
+        S[cc * SR + e] = s0; S[(cc + 1) * SR + e] = s1; S[(cc + 2) * SR + e] = s2; S[(cc + 3) * SR + e] = s3;
       }
       if (tid < D) {
         float s = z[tid];
@@ -341,8 +382,8 @@ __global__ __launch_bounds__(kBwdLinThreads) void linear_bwd_kv_kernel(BwdArgs a
   constexpr int NUM_T = CH / G;
   constexpr int UPD_C = D / G;
   constexpr int SR = D + 1;
-  constexpr int TR = D + 1;
-  extern __shared__ float smem[];
+  constexpr int TR = D + 4;
+  extern __shared__ __attribute__((aligned(16))) float smem[];
   float* fq = smem;                   // [CH][D]
   float* fk = fq + CH * TR;            // [CH][D]
   float* vv = fk + CH * TR;            // [CH][D]
@@ -404,13 +445,20 @@ __global__ __launch_bounds__(kBwdLinThreads) void linear_bwd_kv_kernel(BwdArgs a
     float accv[NUM_T], acck[NUM_T];
 #pragma unroll
     for (int i = 0; i < NUM_T; ++i) { accv[i] = 0.f; acck[i] = -y[c]; }
-    for (int cc = 0; cc < D; ++cc) {
-      const float bce = Bm[cc * SR + c];   // B[cc][e = c]
-      const float bec = Bm[c * SR + cc];   // B[c][e = cc]
+    for (int cc = 0; cc < D; cc += 4) {
+      float bce[4], bec[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        bce[r] = Bm[(cc + r) * SR + c];   // B[cc + r][e = c]
+        bec[r] = Bm[c * SR + cc + r];     // B[c][e = cc + r]
+      }
 #pragma unroll
       for (int i = 0; i < NUM_T; ++i) {
-        accv[i] = fmaf(bce, fk[(g + G * i) * TR + cc], accv[i]);   // dv_u[e] += B[cc][e] phi(k_u)[cc]
-        acck[i] = fmaf(bec, vv[(g + G * i) * TR + cc], acck[i]);   // dfk_u[c] += B[c][cc] v_u[cc]
+        const float4 k4 = *reinterpret_cast<const float4*>(&fk[(g + G * i) * TR + cc]);
+        const float4 v4 = *reinterpret_cast<const float4*>(&vv[(g + G * i) * TR + cc]);
+        // dv_u[e] += B[cc][e] phi(k_u)[cc];  dfk_u[c] += B[c][cc] v_u[cc]
+        accv[i] = fmaf(bce[0], k4.x, fmaf(bce[1], k4.y, fmaf(bce[2], k4.z, fmaf(bce[3], k4.w, accv[i]))));
+        acck[i] = fmaf(bec[0], v4.x, fmaf(bec[1], v4.y, fmaf(bec[2], v4.z, fmaf(bec[3], v4.w, acck[i]))));
       }
     }
     for (int t = 0; t < CH; ++t) {
@@ -437,12 +485,16 @@ __global__ __launch_bounds__(kBwdLinThreads) void linear_bwd_kv_kernel(BwdArgs a
       float gcol[CH];
 #pragma unroll
       for (int t = 0; t < CH; ++t) gcol[t] = gg[t * TR + e];
-      for (int i = 0; i < UPD_C; ++i) {
-        const int cc = g + G * i;
-        float s = Bm[cc * SR + e];
+      for (int i = 0; i < UPD_C / 4; ++i) {
+        const int cc = 4 * (g + G * i);   // four state rows at a time: one 16-byte read per token
+        float s0 = Bm[cc * SR + e], s1 = Bm[(cc + 1) * SR + e], s2 = Bm[(cc + 2) * SR + e], s3 = Bm[(cc + 3) * SR + e];
 #pragma unroll
-        for (int t = 0; t < CH; ++t) s = fmaf(fq[t * TR + cc], gcol[t], s);
-        Bm[cc * SR + e] = s;
+        for (int t = 0; t < CH; ++t) {
+          const float4 f4 = *reinterpret_cast<const float4*>(&fq[t * TR + cc]);
+          s0 = fmaf(f4.x, gcol[t], s0); s1 = fmaf(f4.y, gcol[t], s1);
+          s2 = fmaf(f4.z, gcol[t], s2); s3 = fmaf(f4.w, gcol[t], s3);
+        }
+        Bm[cc * SR + e] = s0; Bm[(cc + 1) * SR + e] = s1; Bm[(cc + 2) * SR + e] = s2; Bm[(cc + 3) * SR + e] = s3;
       }
       if (tid < D) {
         float s = y[tid];
