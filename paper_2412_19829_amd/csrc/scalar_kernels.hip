@@ -44,13 +44,7 @@ __global__ __launch_bounds__(kScalarThreads) void windowed_scalar_kernel(AttnArg
       float s = 0.f;
       {
         // lanes past the last visible key read that key's row again (in bounds), masked below
-        const int64_t kr = koff + (int64_t)min(j, hi) * a.k.sn;
-#pragma unroll
-        for (int cc = 0; cc < CPL; ++cc) {
-#pragma unroll
-          for (int c = 0; c < 64; ++c)
-            s = fmaf(lane_bcast(qreg[cc], c), Storage<T>::load(a.k.base, kr + cc * 64 + c), s);
-        }
+        s = dot_row_with_spread<T, D>(a.k.base, koff + (int64_t)min(j, hi) * a.k.sn, qreg);
       }
       s = valid ? s * a.scale : -INFINITY;
       const float m_new = fmaxf(m, wave_max(s));  // finite: key j0 is always valid
@@ -61,7 +55,7 @@ __global__ __launch_bounds__(kScalarThreads) void windowed_scalar_kernel(AttnArg
       for (int cc = 0; cc < CPL; ++cc) acc[cc] *= alpha;
       const int cnt = min(64, hi - j0 + 1);
       for (int jj = 0; jj < cnt; ++jj) {
-        const float pj = __shfl(p, jj, 64);
+        const float pj = lane_bcast(p, jj);
         const int64_t vr = voff + (int64_t)(j0 + jj) * a.v.sn;
 #pragma unroll
         for (int cc = 0; cc < CPL; ++cc)
@@ -82,6 +76,7 @@ __global__ __launch_bounds__(kScalarThreads) void windowed_scalar_kernel(AttnArg
 // One workgroup walks one head from token 0 to N-1.  grid = (H1, B), block = 256.
 // ---------------------------------------------------------------------------------------
 constexpr int kScalarChunk = 32;
+template <int D> constexpr int kScalarTokenRow = D + 4;   // LDS stride of a token row (causal kernel)
 
 template <typename T, int D>
 __global__ __launch_bounds__(kScalarThreads) void linear_scalar_kernel(AttnArgs a) {
@@ -89,11 +84,15 @@ __global__ __launch_bounds__(kScalarThreads) void linear_scalar_kernel(AttnArgs 
   constexpr int G = kScalarThreads / D;        // thread groups along the non-e axis
   constexpr int NUM_T = CH / G;                // tokens per thread in the read-out
   constexpr int UPD_C = D / G;                 // state rows per thread in the update
-  extern __shared__ float smem[];
-  float* fq = smem;                 // [CH][D]
-  float* fk = fq + CH * D;          // [CH][D]
-  float* vv = fk + CH * D;          // [CH][D]
-  float* S = vv + CH * D;           // [D][D]   A of Algorithm 1, rows = feature c, cols = e
+  // Token rows are D + 4 floats apart: 16-byte aligned, so that a row broadcast to a wave is read
+  // four values at a time, and a column of 32 rows (the masked products read those) spreads over
+  // 8 banks instead of falling into one.
+  constexpr int TR = kScalarTokenRow<D>;
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  float* fq = smem;                 // [CH][TR]
+  float* fk = fq + CH * TR;         // [CH][TR]
+  float* vv = fk + CH * TR;         // [CH][TR]
+  float* S = vv + CH * TR;          // [D][D]   A of Algorithm 1, rows = feature c, cols = e
   float* z = S + D * D;             // [D]
   float* am = z + D;                // [CH][CH+1] masked feature products
   float* den = am + CH * (CH + 1);  // [CH]
@@ -122,7 +121,8 @@ __global__ __launch_bounds__(kScalarThreads) void linear_scalar_kernel(AttnArgs 
         kv = feature_map(Storage<T>::load(a.k.base, koff + (int64_t)n * a.k.sn + c), a.phi);
         v_ = Storage<T>::load(a.v.base, voff + (int64_t)n * a.v.sn + c);
       }
-      fq[x] = qv; fk[x] = kv; vv[x] = v_;   // rows past N hold zeros and contribute nothing
+      const int y = t * TR + c;
+      fq[y] = qv; fk[y] = kv; vv[y] = v_;   // rows past N hold zeros and contribute nothing
     }
     __syncthreads();
     // masked products a[t][u] = phi(q_t).phi(k_u) for u <= t
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kScalarThreads) void linear_scalar_kernel(AttnArgs 
       const int t = x / CH, u = x % CH;
       float s = 0.f;
       if (u <= t) {
-        for (int c = 0; c < D; ++c) s = fmaf(fq[t * D + c], fk[u * D + c], s);
+        for (int c = 0; c < D; ++c) s = fmaf(fq[t * TR + c], fk[u * TR + c], s);
       }
       am[t * (CH + 1) + u] = s;
     }
@@ -139,20 +139,23 @@ __global__ __launch_bounds__(kScalarThreads) void linear_scalar_kernel(AttnArgs 
       float s = 0.f;
       for (int u = 0; u <= tid; ++u) s += am[tid * (CH + 1) + u];
       float zz = 0.f;
-      for (int c = 0; c < D; ++c) zz = fmaf(fq[tid * D + c], z[c], zz);
+      for (int c = 0; c < D; ++c) zz = fmaf(fq[tid * TR + c], z[c], zz);
       den[tid] = s + zz + a.eps;
     }
     // read-out: num[t][e] = sum_u a[t][u] v[u][e] + sum_c phi(q_t)[c] A[c][e]
     float num[NUM_T];
 #pragma unroll
     for (int i = 0; i < NUM_T; ++i) num[i] = 0.f;
-    for (int c = 0; c < D; ++c) {
-      const float sce = S[c * D + e];
+    for (int c = 0; c < D; c += 4) {
+      const float s0 = S[c * D + e], s1 = S[(c + 1) * D + e], s2 = S[(c + 2) * D + e], s3 = S[(c + 3) * D + e];
 #pragma unroll
-      for (int i = 0; i < NUM_T; ++i) num[i] = fmaf(fq[(g + G * i) * D + c], sce, num[i]);
+      for (int i = 0; i < NUM_T; ++i) {
+        const float4 f4 = *reinterpret_cast<const float4*>(&fq[(g + G * i) * TR + c]);   // same for all lanes
+        num[i] = fmaf(f4.x, s0, fmaf(f4.y, s1, fmaf(f4.z, s2, fmaf(f4.w, s3, num[i]))));
+      }
     }
     for (int u = 0; u < CH; ++u) {
-      const float vue = vv[u * D + e];
+      const float vue = vv[u * TR + e];
 #pragma unroll
       for (int i = 0; i < NUM_T; ++i) num[i] = fmaf(am[(g + G * i) * (CH + 1) + u], vue, num[i]);
     }
@@ -165,17 +168,21 @@ __global__ __launch_bounds__(kScalarThreads) void linear_scalar_kernel(AttnArgs 
     // state update: A[c][e] += sum_t phi(k_t)[c] v_t[e];  Z[c] += sum_t phi(k_t)[c]
     float vcol[CH];
 #pragma unroll
-    for (int t = 0; t < CH; ++t) vcol[t] = vv[t * D + e];
-    for (int i = 0; i < UPD_C; ++i) {
-      const int c = g + G * i;
-      float s = S[c * D + e];
+    for (int t = 0; t < CH; ++t) vcol[t] = vv[t * TR + e];
+    for (int i = 0; i < UPD_C / 4; ++i) {
+      const int c = 4 * (g + G * i);   // four state rows at a time: one 16-byte read per token
+      float s0 = S[c * D + e], s1 = S[(c + 1) * D + e], s2 = S[(c + 2) * D + e], s3 = S[(c + 3) * D + e];
 #pragma unroll
-      for (int t = 0; t < CH; ++t) s = fmaf(fk[t * D + c], vcol[t], s);
-      S[c * D + e] = s;
+      for (int t = 0; t < CH; ++t) {
+        const float4 f4 = *reinterpret_cast<const float4*>(&fk[t * TR + c]);
+        s0 = fmaf(f4.x, vcol[t], s0); s1 = fmaf(f4.y, vcol[t], s1);
+        s2 = fmaf(f4.z, vcol[t], s2); s3 = fmaf(f4.w, vcol[t], s3);
+      }
+      S[c * D + e] = s0; S[(c + 1) * D + e] = s1; S[(c + 2) * D + e] = s2; S[(c + 3) * D + e] = s3;
     }
     if (tid < D) {
       float s = z[tid];
-      for (int t = 0; t < CH; ++t) s += fk[t * D + tid];
+      for (int t = 0; t < CH; ++t) s += fk[t * TR + tid];
       z[tid] = s;
     }
   }
@@ -293,7 +300,7 @@ __global__ __launch_bounds__(kScalarThreads) void linear_scalar_bidir_kernel(Att
 
 template <int D> size_t linear_scalar_smem() {
   constexpr int CH = kScalarChunk;
-  return sizeof(float) * (size_t)(3 * CH * D + D * D + D + CH * (CH + 1) + CH);
+  return sizeof(float) * (size_t)(3 * CH * kScalarTokenRow<D> + D * D + D + CH * (CH + 1) + CH);
 }
 
 }  // namespace
