@@ -73,8 +73,9 @@ def main() -> int:
     ap.add_argument("--no-modes", action="store_true", help="skip the pure-windowed / pure-linear runs")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path shards by head/batch with no "
-              "communication; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (every batch element and head is "
+              "independent, so the path shards by head or batch with no communication). "
+              "Run with --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np
