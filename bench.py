@@ -299,6 +299,30 @@ def main() -> int:
         modes["decode"] = {"us_per_step": round(t_dec * 1e6, 2), "tokens_per_s": round(wl.B / t_dec, 1),
                            "gbs": round(dec_bytes / t_dec / 1e9, 1),
                            "note": "full rings; bytes = rings read once + states read and written once"}
+        # The paper's own timing shapes (section IV-A and IV-D: batch 4, 16 heads of size 64, 3 of
+        # them windowed, sequence 1k-6k, window 128), for context next to its Gaudi figures.
+        # These working sets (8-50 MB) sit in the caches: times only, no HBM fraction.
+        shapes = {}
+        for n_p in (1024, 2048, 4096, 6144):
+            pq, pk, pv = (torch.randn(4, 16, n_p, 64, device="cuda", generator=torch.Generator("cuda").manual_seed(n_p + i))
+                          .to(torch.bfloat16) for i in range(3))
+            pq = (pq.float() / 8.0).to(torch.bfloat16)
+            po = torch.empty_like(pq)
+            pp = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=3)
+            pneed = gb.gformer_attn_workspace_bytes(4, 16, n_p, 64, 128, pp)
+            pws = torch.empty(max(pneed, 256), dtype=torch.uint8, device="cuda")
+
+            def paper_call():
+                st_ = gb.gformer_attn_fwd_raw(pq.data_ptr(), pk.data_ptr(), pv.data_ptr(), po.data_ptr(), 4, 16,
+                                              n_p, 64, 128, pp, pws.data_ptr(), pws.numel(), stream)
+                if st_ != gb.GF_OK:
+                    raise gb.GformerError(st_, gb.gformer_status_string(st_))
+            for _ in range(20):
+                paper_call()
+            torch.cuda.synchronize()
+            shapes[str(n_p)] = round(event_time(paper_call, 200) * 1e6, 1)
+        modes["paper_shapes"] = {"us_by_seq_len": shapes,
+                                 "note": "B=4 H=16 d=64 window=128 n_sparse_heads=3 bf16, cache-resident"}
         # Backward pass of the same layer (plain-FMA kernels; a few launches only: they are slow)
         tdo = dev(v)
         dq_, dk_, dv_ = (torch.empty_like(x) for x in (tq, tk, tv))
