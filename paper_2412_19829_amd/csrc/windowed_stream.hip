@@ -267,8 +267,8 @@ __global__ __launch_bounds__(NT, 1) void windowed_stream_kernel(AttnArgs a) {
         }
         l_run += lsum;
         // O^T += V^T P^T: 8 products (2 groups of 16 keys x 4 row tiles of O^T); the V operand
-        // of product i + PDV is fetched from LDS before product i is issued, so that the wave
-        // does not sit through one LDS round trip per product
+        // of product i + PDV is fetched from LDS before product i is issued (deeper than one
+        // ahead costs registers the 168-register budget does not have, and measured no gain)
         bf16x8 pbv[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
