@@ -670,6 +670,8 @@ BWD_SHAPES = [
     (1, 3, 1025, 128, 256, 1),
     (2, 2, 513, 128, 70, 0),
     (1, 2, 640, 64, 129, 2),
+    (1, 2, 700, 64, 300, 1),       # more than 256 visible keys: the per-query kernel's general walk
+    (1, 2, 600, 128, 600, 2),      # full causal attention over 600 tokens
 ]
 
 
