@@ -506,13 +506,13 @@ __global__ __launch_bounds__(kBwdLinThreads) void linear_bwd_kv_kernel(BwdArgs a
 }
 
 template <typename T, int D>
-hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t s) {
-  if (a.H0 > 0) {
+hipError_t launch_bwd_t(const BwdArgs& a, bool windowed_heads, bool linear_heads, hipStream_t s) {
+  if (windowed_heads && a.H0 > 0) {
     dim3 grid((a.N + kBwdRows - 1) / kBwdRows, a.H0, a.B);
     windowed_bwd_q_kernel<T, D><<<grid, dim3(kBwdThreads), 0, s>>>(a);
     windowed_bwd_kv_kernel<T, D><<<grid, dim3(kBwdThreads), 0, s>>>(a);
   }
-  if (a.H0 < a.H) {
+  if (linear_heads && a.H0 < a.H) {
     dim3 grid(a.H - a.H0, a.B);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_q_kernel<T, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -529,10 +529,14 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_backward_scalar(const BwdArgs& a, bool bf16, hipStream_t s) {
+hipError_t launch_backward_scalar(const BwdArgs& a, bool bf16, bool windowed_heads, bool linear_heads,
+                                  hipStream_t s) {
   if (a.B <= 0 || a.H <= 0 || a.N <= 0) return hipSuccess;
-  if (a.d == 64) return bf16 ? launch_bwd_t<uint16_t, 64>(a, s) : launch_bwd_t<float, 64>(a, s);
-  return bf16 ? launch_bwd_t<uint16_t, 128>(a, s) : launch_bwd_t<float, 128>(a, s);
+  if (a.d == 64)
+    return bf16 ? launch_bwd_t<uint16_t, 64>(a, windowed_heads, linear_heads, s)
+                : launch_bwd_t<float, 64>(a, windowed_heads, linear_heads, s);
+  return bf16 ? launch_bwd_t<uint16_t, 128>(a, windowed_heads, linear_heads, s)
+              : launch_bwd_t<float, 128>(a, windowed_heads, linear_heads, s);
 }
 
 }  // namespace gformer

@@ -96,7 +96,11 @@ struct BwdArgs {
   float* ws;   // [B, H, N, 2] fp32: windowed heads (log-sum-exp, dO.o), linear heads (den, dO.o / den),
                // written by the per-query kernels, read by the per-key kernels
 };
-hipError_t launch_backward_scalar(const BwdArgs& a, bool bf16, hipStream_t s);
+// plain-FMA kernels: the windowed heads, the linear heads, or both
+hipError_t launch_backward_scalar(const BwdArgs& a, bool bf16, bool windowed_heads, bool linear_heads,
+                                  hipStream_t s);
+// bf16 matrix-core kernels for the windowed heads
+hipError_t launch_windowed_backward_mfma(const BwdArgs& a, hipStream_t s);
 
 // One call of the random-feature pre-map: heads [head_begin, head_end) of x -> the same heads of out.
 struct FeatureArgs {

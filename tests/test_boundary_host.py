@@ -312,9 +312,11 @@ def test_backward_argument_checks_on_the_host():
     assert gb.gformer_attn_bwd_raw(*ptrs, *a, p, ws[0], 255) == gb.GF_ERR_WORKSPACE
     assert gb.gformer_attn_bwd_raw(*ptrs, *a, p, ws[0] + 16, ws[1]) == gb.GF_ERR_INVALID_ARG
     # what the backward pass does not cover
-    for impl in (gb.GF_IMPL_MFMA, gb.GF_IMPL_MFMA_BLOCKED, gb.GF_IMPL_MFMA_STREAM):
+    for impl in (gb.GF_IMPL_MFMA_BLOCKED, gb.GF_IMPL_MFMA_STREAM):     # forward-only kernel choices
         q = gb.make_params(n_sparse_heads=1, impl=impl)
         assert gb.gformer_attn_bwd_raw(*ptrs, *a, q, *ws) == gb.GF_ERR_UNSUPPORTED
+    q = gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1, impl=gb.GF_IMPL_MFMA)   # matrix cores: bf16 only
+    assert gb.gformer_attn_bwd_raw(*ptrs, *a, q, *ws) == gb.GF_ERR_UNSUPPORTED
     assert gb.gformer_attn_bwd_raw(*ptrs, *a, gb.make_params(n_sparse_heads=1, bidirectional=1), *ws) == gb.GF_ERR_UNSUPPORTED
     assert gb.gformer_attn_bwd_raw(*ptrs, *a, gb.make_params(n_sparse_heads=1, launch_mask=1), *ws) == gb.GF_ERR_INVALID_ARG
     assert gb.gformer_attn_bwd_raw(*ptrs, 1, 2, 16, 96, 4, p, *ws) == gb.GF_ERR_UNSUPPORTED     # head size

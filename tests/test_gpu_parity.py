@@ -15,6 +15,7 @@ pytestmark = pytest.mark.gpu
 
 SCALAR, MFMA, BLOCKED = gb.GF_IMPL_SCALAR, gb.GF_IMPL_MFMA, gb.GF_IMPL_MFMA_BLOCKED
 STREAM = gb.GF_IMPL_MFMA_STREAM
+AUTO = gb.GF_IMPL_AUTO
 
 
 def check(gpu, ref, dtype, what=""):
@@ -675,13 +676,19 @@ BWD_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+# dtype and kernels: AUTO takes the matrix-core kernels for the windowed heads of a bf16 call
+BWD_PATHS = [("f32", AUTO), ("bf16", AUTO), ("bf16", SCALAR)]
+BWD_PATH_IDS = ["f32", "bf16", "bf16-scalar"]
+
+
+@pytest.mark.parametrize("path", BWD_PATHS, ids=BWD_PATH_IDS)
 @pytest.mark.parametrize("shape", BWD_SHAPES, ids=lambda s: "x".join(map(str, s)))
-def test_backward_shapes(shape, dtype):
+def test_backward_shapes(shape, path):
+    dtype, impl = path
     B, H, N, d, w, H0 = shape
     q, k, v = synth(B, H, N, d, dtype, 61)
     dout = synth(B, H, N, d, dtype, 62)[2]
-    got = run_bwd(q, k, v, dout, dtype, w, H0)
+    got = run_bwd(q, k, v, dout, dtype, w, H0, impl=impl)
     ref = co.attn_bwd(q, k, v, dout, w, H0)
     for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
         check_grad(g, r, dtype, f"{name} {shape}", dout)
@@ -707,7 +714,11 @@ def test_backward_refuses_what_it_does_not_cover():
     import torch
     t = [torch.zeros(1, 2, 64, 64, device="cuda", dtype=torch.bfloat16) for _ in range(7)]
     with pytest.raises(gb.GformerError) as e:
-        gb.gformer_attn_bwd(*t, 8, 1, impl=MFMA)
+        gb.gformer_attn_bwd(*t, 8, 1, impl=STREAM)
+    assert e.value.status == gb.GF_ERR_UNSUPPORTED
+    f = [torch.zeros(1, 2, 64, 64, device="cuda") for _ in range(7)]
+    with pytest.raises(gb.GformerError) as e:
+        gb.gformer_attn_bwd(*f, 8, 1, impl=MFMA)      # matrix-core kernels are bf16 only
     assert e.value.status == gb.GF_ERR_UNSUPPORTED
     p = gb.make_params(n_sparse_heads=1, bidirectional=1)
     ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
