@@ -445,8 +445,8 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
                            void* hip_stream) {
   if (!p) return GF_ERR_INVALID_ARG;
   if (p->struct_size != sizeof(gformer_params)) return GF_ERR_INVALID_ARG;
-  // matrix-core kernels exist for the windowed heads of a bf16 call (AUTO and MFMA take them);
-  // everything else runs on the plain-FMA kernels.  Causal form only.
+  // a bf16 call runs on the matrix-core kernels (AUTO, MFMA) unless SCALAR asks for the plain-FMA
+  // kernels, which are also the fp32 path.  Causal form only.
   if (p->impl == GF_IMPL_MFMA_BLOCKED || p->impl == GF_IMPL_MFMA_STREAM) return GF_ERR_UNSUPPORTED;
   if (p->impl == GF_IMPL_MFMA && p->dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
   gformer_params pp = *p;
@@ -489,10 +489,14 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
   a.ws = reinterpret_cast<float*>(workspace);
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   const bool bf16 = p->dtype == GF_BF16;
-  const bool mfma_windowed = bf16 && p->impl != GF_IMPL_SCALAR;
+  const bool mfma = bf16 && p->impl != GF_IMPL_SCALAR;
   hipError_t e = hipSuccess;
-  if (mfma_windowed) e = launch_windowed_backward_mfma(a, stream);
-  if (e == hipSuccess) e = launch_backward_scalar(a, bf16, !mfma_windowed, true, stream);
+  if (mfma) {
+    e = launch_windowed_backward_mfma(a, stream);
+    if (e == hipSuccess) e = launch_linear_backward_mfma(a, stream);
+  } else {
+    e = launch_backward_scalar(a, bf16, true, true, stream);
+  }
   return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
 }
 

@@ -99,8 +99,9 @@ struct BwdArgs {
 // plain-FMA kernels: the windowed heads, the linear heads, or both
 hipError_t launch_backward_scalar(const BwdArgs& a, bool bf16, bool windowed_heads, bool linear_heads,
                                   hipStream_t s);
-// bf16 matrix-core kernels for the windowed heads
+// bf16 matrix-core kernels for the windowed heads and for the linear heads
 hipError_t launch_windowed_backward_mfma(const BwdArgs& a, hipStream_t s);
+hipError_t launch_linear_backward_mfma(const BwdArgs& a, hipStream_t s);
 
 // One call of the random-feature pre-map: heads [head_begin, head_end) of x -> the same heads of out.
 struct FeatureArgs {

@@ -694,6 +694,20 @@ def test_backward_shapes(shape, path):
         check_grad(g, r, dtype, f"{name} {shape}", dout)
 
 
+@pytest.mark.parametrize("shape", [(1, 2, 8192, 128, 256, 1), (2, 3, 2117, 64, 128, 1), (1, 2, 4099, 128, 64, 0)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_backward_long_sequences_bf16(shape):
+    """The bench workload's sequence length (one windowed and one linear head of it) and ragged
+    multi-chunk lengths: the carried sums of the linear heads run over the whole sequence."""
+    B, H, N, d, w, H0 = shape
+    q, k, v = synth(B, H, N, d, "bf16", 71)
+    dout = synth(B, H, N, d, "bf16", 72)[2]
+    got = run_bwd(q, k, v, dout, "bf16", w, H0)
+    ref = co.attn_bwd(q, k, v, dout, w, H0)
+    for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+        check_grad(g, r, "bf16", f"{name} {shape}", dout)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_backward_scale_eps_identity_map_and_strides(dtype):
     B, H, N, d, w, H0 = 2, 4, 150, 64, 40, 2
