@@ -112,6 +112,7 @@ template <int D> __device__ __forceinline__ HeadCtx<D> head_ctx(const BwdArgs& a
   return c;
 }
 
+
 // ---------------------------------------------------------------------------------------
 // forward scan: dq, and (den_i, c_i) into the workspace.  grid = (H - H0, B)
 // ---------------------------------------------------------------------------------------
@@ -126,29 +127,49 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
   const HeadCtx<D> hc = head_ctx<D>(a, b, h);
   uint16_t* dqp = reinterpret_cast<uint16_t*>(a.dq) + b * a.q.sb + h * a.q.sh;
   const int N = a.N, nchunks = (N + CH - 1) / CH;
+  // this workgroup writes the chunks [cb, ce) of its head; the chunks in front of them are only
+  // summed (light rounds: the state update alone)
+  const int segc = (nchunks + a.lin_segments - 1) / a.lin_segments;
+  const int cb = blockIdx.z * segc, ce = min(nchunks, cb + segc);
+  if (cb >= ce) return;
   const int trl = lds_operand_tr_lane_offset(R, lane) + 8 * lh * R;
 
   u32x4 rq[PCS], rk[PCS], rv[PCS], rdo[PCS];
   auto load_chunk = [&](int n) {
+    const bool full = n >= cb;   // uniform
 #pragma unroll
     for (int i = 0; i < PCS; ++i) {
       const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
       const int64_t tok = min(n * CH + row, N - 1);
-      rq[i] = *reinterpret_cast<const u32x4*>(hc.q + tok * a.q.sn + col);
       rk[i] = *reinterpret_cast<const u32x4*>(hc.k + tok * a.k.sn + col);
       rv[i] = *reinterpret_cast<const u32x4*>(hc.v + tok * a.v.sn + col);
-      rdo[i] = *reinterpret_cast<const u32x4*>(hc.dout + tok * a.dout.sn + col);
+      if (full) {
+        rq[i] = *reinterpret_cast<const u32x4*>(hc.q + tok * a.q.sn + col);
+        rdo[i] = *reinterpret_cast<const u32x4*>(hc.dout + tok * a.dout.sn + col);
+      }
+    }
+  };
+  // the feature map, in place in the staging registers (light rounds: only the tensor they read)
+  auto map_chunk = [&](int n) {
+    const bool full = n >= cb;
+#pragma unroll
+    for (int i = 0; i < PCS; ++i) {
+      rk[i] = map8<ELU1>(rk[i]);
+      if (full) rq[i] = map8<ELU1>(rq[i]);
     }
   };
   auto stage_chunk = [&](int n) {
+    const bool full = n >= cb;
 #pragma unroll
     for (int i = 0; i < PCS; ++i) {
       const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
       const bool valid = n * CH + row < N;   // rows past the end become zeros: they contribute nothing
-      *reinterpret_cast<u32x4*>(&sm.fq[row * R + col]) = valid ? map8<ELU1>(rq[i]) : kZero4;
-      *reinterpret_cast<u32x4*>(&sm.fk[row * R + col]) = valid ? map8<ELU1>(rk[i]) : kZero4;
+      *reinterpret_cast<u32x4*>(&sm.fk[row * R + col]) = valid ? rk[i] : kZero4;
       *reinterpret_cast<u32x4*>(&sm.v[row * R + col]) = valid ? rv[i] : kZero4;
-      *reinterpret_cast<u32x4*>(&sm.g[row * R + col]) = valid ? rdo[i] : kZero4;   // dO until den is known
+      if (full) {
+        *reinterpret_cast<u32x4*>(&sm.fq[row * R + col]) = valid ? rq[i] : kZero4;
+        *reinterpret_cast<u32x4*>(&sm.g[row * R + col]) = valid ? rdo[i] : kZero4;   // dO until den is known
+      }
     }
   };
 
@@ -162,18 +183,21 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
   if (tid < D) sm.z[tid] = 0.f;
 
   load_chunk(0);
+  map_chunk(0);
   stage_chunk(0);
-  if (nchunks > 1) load_chunk(1);
+  if (ce > 1) load_chunk(1);
   lds_barrier();
 
   const int ti = wave & 3, jt = ti & 1, it = ti >> 1;   // 32 x 32 tile of the 64 x 64 products
   const bool do_s = NW == 4 || wave < 4, do_t = NW == 4 || wave >= 4;
   const int ot = wave % MT, it2 = wave / MT;            // output tile of the 64 x d products
 
-  for (int n = 0; n < nchunks; ++n) {
+  for (int n = 0; n < ce; ++n) {
     const int t0 = n * CH;
-    // ---- (a) S^T and (dO v^T)^T tiles: rows j, columns i (a lane owns one token i) ----
+    const bool full = n >= cb;   // uniform over the workgroup
     f32x16 traw;
+    if (full) {
+    // ---- (a) S^T and (dO v^T)^T tiles: rows j, columns i (a lane owns one token i) ----
     if (do_s) {
       f32x16 s;
 #pragma unroll
@@ -300,9 +324,10 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
       }
     }
     lds_barrier();
+    }  // full
 
     // ---- (d) dfq^T tile (feature block ot, token block it2), then the carried sums ----
-    {
+    if (full) {
       f32x16 dacc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) dacc[r] = 0.f;
@@ -359,16 +384,21 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
       for (int pz = 0; pz < C::ZP; ++pz) zz += sm.zpart[pz][tid];
       sm.z[tid] = zz;
     }
+    if (full) {
 #pragma unroll
-    for (int i = 0; i < PCS; ++i) {
-      const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
-      if (t0 + row < N)
-        *reinterpret_cast<u32x4*>(dqp + (int64_t)(t0 + row) * a.q.sn + col) =
-            *reinterpret_cast<const u32x4*>(&sm.fq[row * R + col]);
+      for (int i = 0; i < PCS; ++i) {
+        const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
+        if (t0 + row < N)
+          *reinterpret_cast<u32x4*>(dqp + (int64_t)(t0 + row) * a.q.sn + col) =
+              *reinterpret_cast<const u32x4*>(&sm.fq[row * R + col]);
+      }
     }
-    if (n + 1 < nchunks) stage_chunk(n + 1);   // the same thread overwrites the pieces it has just read
-    if (n + 2 < nchunks) load_chunk(n + 2);
-    lds_barrier();
+    if (n + 1 < ce) {
+      map_chunk(n + 1);
+      stage_chunk(n + 1);   // the same thread overwrites the pieces it has just read
+    }
+    if (n + 2 < ce) load_chunk(n + 2);
+      lds_barrier();
   }
 }
 
@@ -387,34 +417,52 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
   uint16_t* dkp = reinterpret_cast<uint16_t*>(a.dk) + b * a.k.sb + h * a.k.sh;
   uint16_t* dvp = reinterpret_cast<uint16_t*>(a.dv) + b * a.v.sb + h * a.v.sh;
   const int N = a.N, nchunks = (N + CH - 1) / CH;
+  // this workgroup writes the chunks [cb, ce) of its head; the chunks behind them are only summed
+  const int segc = (nchunks + a.lin_segments - 1) / a.lin_segments;
+  const int cb = blockIdx.z * segc, ce = min(nchunks, cb + segc);
+  if (cb >= ce) return;
   const int trl = lds_operand_tr_lane_offset(R, lane) + 8 * lh * R;
 
   u32x4 rq[PCS], rk[PCS], rv[PCS], rdo[PCS];
   float rden[PCS];
   float2 rstat = {1.f, 0.f};
   auto load_chunk = [&](int n) {
+    const bool full = n < ce;   // uniform
 #pragma unroll
     for (int i = 0; i < PCS; ++i) {
       const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
       const int64_t tok = min(n * CH + row, N - 1);
       rq[i] = *reinterpret_cast<const u32x4*>(hc.q + tok * a.q.sn + col);
-      rk[i] = *reinterpret_cast<const u32x4*>(hc.k + tok * a.k.sn + col);
-      rv[i] = *reinterpret_cast<const u32x4*>(hc.v + tok * a.v.sn + col);
       rdo[i] = *reinterpret_cast<const u32x4*>(hc.dout + tok * a.dout.sn + col);
       rden[i] = hc.ws[2 * tok];
+      if (full) {
+        rk[i] = *reinterpret_cast<const u32x4*>(hc.k + tok * a.k.sn + col);
+        rv[i] = *reinterpret_cast<const u32x4*>(hc.v + tok * a.v.sn + col);
+      }
     }
     if (tid < CH) rstat = *reinterpret_cast<const float2*>(&hc.ws[2 * (int64_t)min(n * CH + tid, N - 1)]);
   };
+  auto map_chunk = [&](int n) {
+    const bool full = n < ce;
+#pragma unroll
+    for (int i = 0; i < PCS; ++i) {
+      rq[i] = map8<ELU1>(rq[i]);
+      if (full) rk[i] = map8<ELU1>(rk[i]);
+    }
+  };
   auto stage_chunk = [&](int n) {
+    const bool full = n < ce;
 #pragma unroll
     for (int i = 0; i < PCS; ++i) {
       const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
       const bool valid = n * CH + row < N;
-      *reinterpret_cast<u32x4*>(&sm.fq[row * R + col]) = valid ? map8<ELU1>(rq[i]) : kZero4;
-      *reinterpret_cast<u32x4*>(&sm.fk[row * R + col]) = valid ? map8<ELU1>(rk[i]) : kZero4;
-      *reinterpret_cast<u32x4*>(&sm.v[row * R + col]) = valid ? rv[i] : kZero4;
+      *reinterpret_cast<u32x4*>(&sm.fq[row * R + col]) = valid ? rq[i] : kZero4;
       *reinterpret_cast<u32x4*>(&sm.g[row * R + col]) = valid ? scale8(rdo[i], 1.f / rden[i]) : kZero4;
-      *reinterpret_cast<u32x4*>(&sm.dout[row * R + col]) = valid ? rdo[i] : kZero4;
+      if (full) {
+        *reinterpret_cast<u32x4*>(&sm.fk[row * R + col]) = valid ? rk[i] : kZero4;
+        *reinterpret_cast<u32x4*>(&sm.v[row * R + col]) = valid ? rv[i] : kZero4;
+        *reinterpret_cast<u32x4*>(&sm.dout[row * R + col]) = valid ? rdo[i] : kZero4;
+      }
     }
     if (tid < CH) {
       const bool valid = n * CH + tid < N;
@@ -432,18 +480,20 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
   if (tid < D) sm.z[tid] = 0.f;
 
   load_chunk(nchunks - 1);
+  map_chunk(nchunks - 1);
   stage_chunk(nchunks - 1);
-  if (nchunks > 1) load_chunk(nchunks - 2);
+  if (nchunks - 2 >= cb) load_chunk(nchunks - 2);
   lds_barrier();
 
   const int ti = wave & 3, it = ti & 1, jt = ti >> 1;   // here rows are i, columns j (a lane owns a key j)
   const bool do_s = NW == 4 || wave < 4, do_t = NW == 4 || wave >= 4;
   const int ot = wave % MT, jt2 = wave / MT;
 
-  for (int n = nchunks - 1; n >= 0; --n) {
+  for (int n = nchunks - 1; n >= cb; --n) {
     const int t0 = n * CH;
+    const bool full = n < ce;   // uniform over the workgroup
     // ---- (a) S and T' tiles, stored transposed ([j][i]); column sums for Y ----
-    if (do_s) {
+    if (full && do_s) {
       f32x16 s;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -462,7 +512,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
         put4(&sm.sm[j * SR + 32 * it + 8 * g4 + 4 * lh], x[0], x[1], x[2], x[3]);
       }
     }
-    if (do_t) {
+    if (full && do_t) {
       f32x16 tr;
 #pragma unroll
       for (int r = 0; r < 16; ++r) tr[r] = 0.f;
@@ -501,6 +551,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
     f32x16 kacc, vacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { kacc[r] = 0.f; vacc[r] = 0.f; }
+    if (full) {
 #pragma unroll
     for (int kk = 0; kk < CH / 16; ++kk)
       kacc = mfma32(col_op(sm.fq + trl, R, 16 * kk, 32 * ot), row_op(sm.tp, SR, 32 * jt2, kk, ln, lh), kacc);
@@ -513,6 +564,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
       vacc = mfma32(col_op(sm.st + trl, R, 16 * ks, 32 * ot), row_op(sm.fk, R, 32 * jt2, ks, ln, lh), vacc);
+    }  // full
 #pragma unroll
     for (int u = 0; u < TPW; ++u) {
       const int stile = wave * TPW + u, vt = stile / MT, ft = stile % MT;
@@ -523,7 +575,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
     lds_barrier();   // every read of the phi(k) and v tiles is done
 
     // ---- (c) dk replaces phi(k), dv replaces v ----
-    {
+    if (full) {
       const int j = 32 * jt2 + ln;
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
@@ -554,24 +606,31 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
       for (int pz = 0; pz < C::ZP; ++pz) yy += sm.zpart[pz][tid];
       sm.z[tid] = yy;
     }
+    if (full) {
 #pragma unroll
-    for (int i = 0; i < PCS; ++i) {
-      const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
-      if (t0 + row < N) {
-        *reinterpret_cast<u32x4*>(dkp + (int64_t)(t0 + row) * a.k.sn + col) =
-            *reinterpret_cast<const u32x4*>(&sm.fk[row * R + col]);
-        *reinterpret_cast<u32x4*>(dvp + (int64_t)(t0 + row) * a.v.sn + col) =
-            *reinterpret_cast<const u32x4*>(&sm.v[row * R + col]);
+      for (int i = 0; i < PCS; ++i) {
+        const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
+        if (t0 + row < N) {
+          *reinterpret_cast<u32x4*>(dkp + (int64_t)(t0 + row) * a.k.sn + col) =
+              *reinterpret_cast<const u32x4*>(&sm.fk[row * R + col]);
+          *reinterpret_cast<u32x4*>(dvp + (int64_t)(t0 + row) * a.v.sn + col) =
+              *reinterpret_cast<const u32x4*>(&sm.v[row * R + col]);
+        }
       }
     }
-    if (n >= 1) stage_chunk(n - 1);
-    if (n >= 2) load_chunk(n - 2);
-    lds_barrier();
+    if (n - 1 >= cb) {
+      map_chunk(n - 1);
+      stage_chunk(n - 1);
+    }
+    if (n - 2 >= cb) load_chunk(n - 2);
+      lds_barrier();
   }
 }
 
+constexpr int kComputeUnitsBwd = 256;
+
 template <int D, bool ELU1> hipError_t launch_lin_bwd_t(const BwdArgs& a, hipStream_t s) {
-  const dim3 grid(a.H - a.H0, a.B), block(LbCfg<D>::NT);
+  const dim3 grid(a.H - a.H0, a.B, a.lin_segments), block(LbCfg<D>::NT);
   const int smem = (int)sizeof(LbSmem<D>), smem_kv = (int)sizeof(LbSmemKv<D>);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_bwd_q_mfma_kernel<D, ELU1>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -587,8 +646,14 @@ template <int D, bool ELU1> hipError_t launch_lin_bwd_t(const BwdArgs& a, hipStr
 }  // namespace
 
 // Linear heads [H0, H) of a bf16 call; the workspace receives (den_i, c_i) per token.
-hipError_t launch_linear_backward_mfma(const BwdArgs& a, hipStream_t s) {
-  if (a.H - a.H0 <= 0 || a.N <= 0 || a.B <= 0) return hipSuccess;
+hipError_t launch_linear_backward_mfma(const BwdArgs& args, hipStream_t s) {
+  if (args.H - args.H0 <= 0 || args.N <= 0 || args.B <= 0) return hipSuccess;
+  // A head is one sequential scan.  With fewer heads than compute units each head is cut into
+  // segments, one workgroup per segment: it first sums the chunks in front of (behind) its
+  // segment in light rounds, then scans the segment.
+  BwdArgs a = args;
+  const int heads = (a.H - a.H0) * a.B, nchunks = (a.N + CH - 1) / CH;
+  a.lin_segments = std::max(1, std::min(std::min(4, kComputeUnitsBwd / heads), nchunks / 4));
   const bool elu1 = a.phi == 0;
   if (a.d == 64) return elu1 ? launch_lin_bwd_t<64, true>(a, s) : launch_lin_bwd_t<64, false>(a, s);
   return elu1 ? launch_lin_bwd_t<128, true>(a, s) : launch_lin_bwd_t<128, false>(a, s);

@@ -93,6 +93,7 @@ struct BwdArgs {
   int H0;
   int phi;
   float scale, eps;
+  int lin_segments;   // workgroups per linear head in the matrix-core scans (set by their launcher)
   float* ws;   // [B, H, N, 2] fp32: windowed heads (log-sum-exp, dO.o), linear heads (den, dO.o / den),
                // written by the per-query kernels, read by the per-key kernels
 };
