@@ -201,9 +201,12 @@ gf_status gformer_attn_prefill(const void* q, const void* k, const void* v, void
  *             input or each other
  *   workspace : device, gformer_attn_bwd_workspace_bytes bytes (8 per token and head), 256-byte
  *             aligned; scratch for per-row softmax statistics / denominators
- * Plain-FMA kernels only (fp32 arithmetic on either storage type): params.impl must be
- * GF_IMPL_AUTO or GF_IMPL_SCALAR, the MFMA values are GF_ERR_UNSUPPORTED, and so is
- * params.bidirectional = 1.  params.launch_mask must be 0; segment_len and overlap are ignored.
+ * Kernels: a bf16 call runs on the matrix cores (params.impl GF_IMPL_AUTO or GF_IMPL_MFMA: bf16
+ * products, fp32 accumulation, softmax statistics, denominators and carried sums in fp32);
+ * GF_IMPL_SCALAR and every fp32 call run on plain-FMA kernels (fp32 arithmetic on either
+ * storage type).  GF_IMPL_MFMA with fp32 storage, GF_IMPL_MFMA_BLOCKED, GF_IMPL_MFMA_STREAM and
+ * params.bidirectional = 1 are GF_ERR_UNSUPPORTED.  params.launch_mask must be 0; segment_len
+ * and overlap are ignored.
  * Asynchronous on `hip_stream`; errors as for gformer_attn_fwd. */
 size_t gformer_attn_bwd_workspace_bytes(int B, int H, int N, int d, int window,
                                         const gformer_params* p);
