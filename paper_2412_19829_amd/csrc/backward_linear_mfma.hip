@@ -129,8 +129,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
   const int N = a.N, nchunks = (N + CH - 1) / CH;
   // this workgroup writes the chunks [cb, ce) of its head; the chunks in front of them are only
   // summed (light rounds: the state update alone)
-  const int segc = (nchunks + a.lin_segments - 1) / a.lin_segments;
-  const int cb = blockIdx.z * segc, ce = min(nchunks, cb + segc);
+  const int cb = a.lin_bounds[blockIdx.z], ce = a.lin_bounds[blockIdx.z + 1];
   if (cb >= ce) return;
   const int trl = lds_operand_tr_lane_offset(R, lane) + 8 * lh * R;
 
@@ -370,6 +369,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
     lds_barrier();
 
     // ---- (e) hand the sums to the next chunk; dq rows out; next chunk in ----
+    if (n + 1 >= cb) {   // light rounds do not read the operand copy
 #pragma unroll
     for (int u = 0; u < TPW; ++u) {
       const int stile = wave * TPW + u, vt = stile / MT, ft = stile % MT;
@@ -377,6 +377,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
       for (int g4 = 0; g4 < 4; ++g4)
         put4(&sm.st[(32 * ft + ln) * R + 32 * vt + 8 * g4 + 4 * lh], sacc[u][4 * g4 + 0], sacc[u][4 * g4 + 1],
              sacc[u][4 * g4 + 2], sacc[u][4 * g4 + 3]);
+    }
     }
     if (tid < D) {
       float zz = sm.z[tid];
@@ -418,8 +419,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
   uint16_t* dvp = reinterpret_cast<uint16_t*>(a.dv) + b * a.v.sb + h * a.v.sh;
   const int N = a.N, nchunks = (N + CH - 1) / CH;
   // this workgroup writes the chunks [cb, ce) of its head; the chunks behind them are only summed
-  const int segc = (nchunks + a.lin_segments - 1) / a.lin_segments;
-  const int cb = blockIdx.z * segc, ce = min(nchunks, cb + segc);
+  const int cb = nchunks - a.lin_bounds[blockIdx.z + 1], ce = nchunks - a.lin_bounds[blockIdx.z];
   if (cb >= ce) return;
   const int trl = lds_operand_tr_lane_offset(R, lane) + 8 * lh * R;
 
@@ -592,6 +592,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
     lds_barrier();
 
     // ---- (d) hand the sums on; dk, dv rows out; next (earlier) chunk in ----
+    if (n - 1 < ce) {   // light rounds do not read the operand copy
 #pragma unroll
     for (int u = 0; u < TPW; ++u) {
       const int stile = wave * TPW + u, vt = stile / MT, ft = stile % MT;
@@ -599,6 +600,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
       for (int g4 = 0; g4 < 4; ++g4)
         put4(&sm.st[(32 * ft + ln) * R + 32 * vt + 8 * g4 + 4 * lh], sacc[u][4 * g4 + 0], sacc[u][4 * g4 + 1],
              sacc[u][4 * g4 + 2], sacc[u][4 * g4 + 3]);
+    }
     }
     if (tid < D) {
       float yy = sm.z[tid];
@@ -654,6 +656,20 @@ hipError_t launch_linear_backward_mfma(const BwdArgs& args, hipStream_t s) {
   BwdArgs a = args;
   const int heads = (a.H - a.H0) * a.B, nchunks = (a.N + CH - 1) / CH;
   a.lin_segments = std::max(1, std::min(std::min(4, kComputeUnitsBwd / heads), nchunks / 4));
+  // A light round costs about 0.45 of a full one (measured), and segment s runs the light rounds
+  // of everything in front of it: lengths in the ratio (1 - 0.45)^s finish together.  The reverse
+  // scan uses the same cut mirrored.
+  {
+    double wsum = 0.0, w = 1.0;
+    for (int sgm = 0; sgm < a.lin_segments; ++sgm, w *= 0.55) wsum += w;
+    double acc = 0.0;
+    w = 1.0;
+    a.lin_bounds[0] = 0;
+    for (int sgm = 1; sgm <= a.lin_segments; ++sgm, w *= 0.55) {
+      acc += w;
+      a.lin_bounds[sgm] = sgm == a.lin_segments ? nchunks : std::min(nchunks, (int)(nchunks * acc / wsum + 0.5));
+    }
+  }
   const bool elu1 = a.phi == 0;
   if (a.d == 64) return elu1 ? launch_lin_bwd_t<64, true>(a, s) : launch_lin_bwd_t<64, false>(a, s);
   return elu1 ? launch_lin_bwd_t<128, true>(a, s) : launch_lin_bwd_t<128, false>(a, s);

@@ -94,6 +94,7 @@ struct BwdArgs {
   int phi;
   float scale, eps;
   int lin_segments;   // workgroups per linear head in the matrix-core scans (set by their launcher)
+  int lin_bounds[5];  // segment s covers chunks [lin_bounds[s], lin_bounds[s+1]) (reverse scan: mirrored)
   float* ws;   // [B, H, N, 2] fp32: windowed heads (log-sum-exp, dO.o), linear heads (den, dO.o / den),
                // written by the per-query kernels, read by the per-key kernels
 };
