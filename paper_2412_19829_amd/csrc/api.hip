@@ -74,7 +74,6 @@ gf_status check_strides(const int64_t* in, int64_t* out, int H, int N, int d) {
   return GF_OK;
 }
 
-int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // Shared by gformer_attn_plan, gformer_attn_workspace_bytes and gformer_attn_fwd.
 // Token i of a windowed head sees keys i - left .. i + right (cut at the sequence ends): the w

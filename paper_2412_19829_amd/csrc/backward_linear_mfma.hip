@@ -126,7 +126,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
   const int h = a.H0 + blockIdx.x, b = blockIdx.y;
   const HeadCtx<D> hc = head_ctx<D>(a, b, h);
   uint16_t* dqp = reinterpret_cast<uint16_t*>(a.dq) + b * a.q.sb + h * a.q.sh;
-  const int N = a.N, nchunks = (N + CH - 1) / CH;
+  const int N = a.N;
   // this workgroup writes the chunks [cb, ce) of its head; the chunks in front of them are only
   // summed (light rounds: the state update alone)
   const int cb = a.lin_bounds[blockIdx.z], ce = a.lin_bounds[blockIdx.z + 1];

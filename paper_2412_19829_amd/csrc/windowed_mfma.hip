@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   const int h = (lb / nqb) % a.H0, b = lb / (nqb * a.H0);
   const int i0 = qb * BR;
   const int q0 = i0 + wave * WQ;
-  const int N = a.N, w = a.window;
+  const int N = a.N;
 
   const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q.base) + b * a.q.sb + h * a.q.sh;
   const uint16_t* kp = reinterpret_cast<const uint16_t*>(a.k.base) + b * a.k.sb + h * a.k.sh;
