@@ -724,6 +724,33 @@ def test_backward_scale_eps_identity_map_and_strides(dtype):
         check_grad(g, r, dtype, name, dout)
 
 
+@pytest.mark.parametrize("path", BWD_PATHS, ids=BWD_PATH_IDS)
+def test_backward_negative_scale(path):
+    """A negative softmax scale turns the ordering of the logits around; the statistics pass must
+    still pick the largest logit as its reference."""
+    dtype, impl = path
+    B, H, N, d, w, H0 = 1, 3, 260, 64, 90, 2
+    q, k, v = synth(B, H, N, d, dtype, 65, q_prescaled=False, sigma=0.5)
+    dout = synth(B, H, N, d, dtype, 66)[2]
+    got = run_bwd(q, k, v, dout, dtype, w, H0, impl=impl, softmax_scale=-0.3)
+    ref = co.attn_bwd(q, k, v, dout, w, H0, softmax_scale=-0.3)
+    for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+        check_grad(g, r, dtype, name, dout)
+
+
+def test_backward_outlier_scores_bf16():
+    """Unscaled queries with a large row every 64 tokens: logits in the tens, nearly one-hot
+    softmax rows next to flat ones.  Both kernel families against the oracle."""
+    B, H, N, d, w, H0 = 1, 2, 1000, 128, 256, 2
+    q, k, v = synth(B, H, N, d, "bf16", 93, q_prescaled=False, sigma=0.5, outlier_every=64, outlier_gain=8.0)
+    dout = synth(B, H, N, d, "bf16", 94)[2]
+    ref = co.attn_bwd(q, k, v, dout, w, H0)
+    for impl in (AUTO, SCALAR):
+        got = run_bwd(q, k, v, dout, "bf16", w, H0, impl=impl)
+        for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+            check_grad(g, r, "bf16", f"{name} impl={impl}", dout)
+
+
 def test_backward_refuses_what_it_does_not_cover():
     import torch
     t = [torch.zeros(1, 2, 64, 64, device="cuda", dtype=torch.bfloat16) for _ in range(7)]
