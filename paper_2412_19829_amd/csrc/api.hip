@@ -75,6 +75,20 @@ gf_status check_strides(const int64_t* in, int64_t* out, int H, int N, int d) {
 }
 
 
+// Chunks per piece when every linear head is cut into the same whole number of pieces (one
+// workgroup per piece, at most one per compute unit, pieces of 8 chunks or more), or 0 when that
+// would leave more than a fifth of the compute units without a piece.
+long aligned_piece(long heads_lin, long cph) {
+  if (heads_lin <= 0 || cph <= 0) return 0;
+  long k = kComputeUnits / heads_lin;
+  if (k > cph / 8) k = cph / 8;
+  if (k < 1) return 0;
+  const long piece = (cph + k - 1) / k;
+  const long per_head = (cph + piece - 1) / piece;
+  if (heads_lin * per_head * 5 < (long)kComputeUnits * 4) return 0;
+  return piece;
+}
+
 // Shared by gformer_attn_plan, gformer_attn_workspace_bytes and gformer_attn_fwd.
 // Token i of a windowed head sees keys i - left .. i + right (cut at the sequence ends): the w
 // tokens ending at i, or (bidirectional) the w tokens centred on it.
@@ -149,12 +163,21 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
     vcph = per_head * piece;
     pieces = heads_lin * per_head;
     mid = pieces;
-  } else if (p->segment_len != 0) {
-    piece = p->segment_len / pl.chunk;
+  } else if (p->segment_len != 0 || aligned_piece(heads_lin, cph) > 0) {
+    // Uniform segments per head: asked for, or chosen because a whole number of them per head
+    // keeps at least 4 of 5 compute units busy.  Pieces that never straddle heads leave the state
+    // pass the least to re-read (a head's last segment is never summed).
+    piece = p->segment_len != 0 ? p->segment_len / pl.chunk : aligned_piece(heads_lin, cph);
     const long per_head = cph > 0 ? (cph + piece - 1) / piece : 0;
     vcph = per_head * piece;
     pieces = heads_lin * per_head;
-    mid = heads_lin * (per_head > 0 ? per_head - 1 : 0);
+    // The state pass walks a head's segments but the last one.  A workgroup of it is bound by
+    // its own chunk-by-chunk walk, so segments are cut into up to four sub-pieces as long as the
+    // sub-pieces stay 4 chunks or longer and fit two workgroups per compute unit.
+    const long carried = heads_lin * (per_head > 0 ? per_head - 1 : 0);
+    for (sub = 4; sub > 1; sub /= 2)
+      if (piece % sub == 0 && piece / sub >= 4 && carried * sub <= 2 * kComputeUnits) break;
+    mid = carried * sub;
   } else if (heads_lin > 0 && cph > 0) {
     // One workgroup per compute unit (its LDS holds one), each with the same number of chunks;
     // pieces no shorter than 8 chunks so the carried state (d*d fp32 in, d*d out) stays a small

@@ -35,7 +35,7 @@ struct AttnArgs {
   int vcph;          // virtual chunks per head
   int piece_chunks;  // chunks per piece
   int n_pieces;      // pieces = workgroups of the read-out kernel
-  int state_sub;     // the state pass cuts every piece into this many equal sub-pieces (1 or 2)
+  int state_sub;     // the state pass cuts every piece into this many equal sub-pieces (1, 2 or 4)
   float* final_state; // optional [B*(H-H0), d*d + d] fp32: every linear head's (A, Z) after its last
                      // token, A row-major [feature][value] (what the decode step carries on from)
   void *kring, *vring; // optional [B, H0, window, d] rings: the last `window` keys / values of every
@@ -51,7 +51,12 @@ struct AttnArgs {
 // itself (independent loads, no extra launch); with many, a prefix kernel runs first and the
 // read-out kernel reads a single slot.
 __host__ __device__ inline bool uses_prefix_kernel(const AttnArgs& a) {
-  return a.vcph / (a.piece_chunks / a.state_sub) > 6;
+  const int ls = a.piece_chunks / a.state_sub;
+  if (!a.causal) return a.vcph / ls > 6;   // every piece adds up its whole head
+  // a causal piece adds up the sub-pieces in front of it inside its head; the latest start is
+  // the head's last piece when pieces never straddle heads, else the head's last chunk
+  const int last_start = a.vcph % a.piece_chunks == 0 ? a.vcph - a.piece_chunks : a.vcph - 1;
+  return last_start / ls > 6;
 }
 
 // bf16 storage helpers (round to nearest even on store).

@@ -279,9 +279,20 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
   const int ls = a.piece_chunks / a.state_sub;
+  // Workgroups are dealt round-robin to the 8 XCDs.  Which sub-pieces have something to sum is
+  // periodic in the block index (with two segments per head every second group of state_sub
+  // blocks is idle), and a period that divides 8 would leave whole XCDs without work: give each
+  // XCD one contiguous run of the logical block order instead.
+  int lb = blockIdx.x;
+  {
+    constexpr int kXcds = 8;
+    const int total = gridDim.x, per = total / kXcds, rem = total % kXcds;
+    const int xcd = lb % kXcds, slot = lb / kXcds;
+    lb = xcd * per + min(xcd, rem) + slot;
+  }
   int q, head, lc0, lc1;                     // workspace slot; chunks [lc0, lc1) of `head`
   if (a.causal) {
-    q = blockIdx.x + 1;
+    q = lb + 1;
     const int e = q * ls;                    // the boundary, as a global chunk index
     if (e % a.vcph == 0) return;             // on a head boundary: nothing is carried
     head = e / a.vcph;
@@ -293,7 +304,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT, 2) void linear_state_kernel(AttnArgs
   } else {
     // bidirectional: every sub-piece is summed (pieces never straddle heads in this mode);
     // slot q holds the sum over sub-piece q itself
-    q = blockIdx.x;
+    q = lb;
     head = q * ls / a.vcph;
     lc0 = q * ls % a.vcph;
     lc1 = min(lc0 + ls, a.cph);
@@ -612,10 +623,35 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
       j_first = (g0 - lc) / ls;
       j_last = uses_prefix_kernel(a) ? j_first : j_first + a.vcph / ls - 1;
     }
-    for (int j = j_first; j <= j_last; ++j) {
-      const float* src = a.ws_states + (int64_t)j * C::STATE;
-      state_add<D>(sacc, src, wave, lane);
-      z0 += src[D * D + 32 * wave + ln];
+    // two sums at a time: their loads are all in flight before the first is added, which halves
+    // the number of trips to memory this prologue waits for (an odd one out is read twice and
+    // counted once)
+    for (int j = j_first; j <= j_last; j += 2) {
+      const bool pair = j + 1 <= j_last;
+      const float* s0 = a.ws_states + (int64_t)j * C::STATE;
+      const float* s1 = a.ws_states + (int64_t)(pair ? j + 1 : j) * C::STATE;
+      const float w1 = pair ? 1.f : 0.f;
+      float4 t0[C::ET][4], t1[C::ET][4];
+#pragma unroll
+      for (int ct = 0; ct < C::ET; ++ct) {
+        const int off = state_tile_offset<D>(ct, wave, lane);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          t0[ct][g] = reinterpret_cast<const float4*>(s0 + off)[g];
+          t1[ct][g] = reinterpret_cast<const float4*>(s1 + off)[g];
+        }
+      }
+      const float za = s0[D * D + 32 * wave + ln], zb = s1[D * D + 32 * wave + ln];
+#pragma unroll
+      for (int ct = 0; ct < C::ET; ++ct)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          sacc[ct][4 * g + 0] += t0[ct][g].x + w1 * t1[ct][g].x;
+          sacc[ct][4 * g + 1] += t0[ct][g].y + w1 * t1[ct][g].y;
+          sacc[ct][4 * g + 2] += t0[ct][g].z + w1 * t1[ct][g].z;
+          sacc[ct][4 * g + 3] += t0[ct][g].w + w1 * t1[ct][g].w;
+        }
+      z0 += za + w1 * zb;
     }
   }
   if (lh == 0) {

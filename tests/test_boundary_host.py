@@ -50,9 +50,10 @@ def _plan(B, H, N, d, w, **kw):
 def test_plan_headline_config():
     st, pl = _plan(4, 32, 8192, 128, 256, n_sparse_heads=6)
     assert st == gb.GF_OK and pl["impl"] == gb.GF_IMPL_MFMA
-    # 104 linear heads x 128 chunks cut into equal pieces, one per compute unit
-    assert pl["chunk"] == 64 and pl["segment_len"] == 52 * 64
-    assert pl["n_segments"] == 256 and pl["linear_blocks"] == 256
+    # 104 linear heads x 128 chunks: two pieces per head (208 of 256 compute units busy, no piece
+    # straddles a head)
+    assert pl["chunk"] == 64 and pl["segment_len"] == 64 * 64
+    assert pl["n_segments"] == 208 and pl["linear_blocks"] == 208
     # window 256 spans five key tiles: the streaming kernel, 24 (batch, head) pairs cut into
     # 256 // 24 = 10 pieces of ceil(128 / 10) = 13 pairs of 32-query groups each
     assert pl["windowed_blocks"] == 24 * 10 and pl["windowed_threads"] == 768
@@ -71,17 +72,16 @@ def test_plan_headline_config():
     # with no windowed head the forced streaming choice has nothing to refuse
     st, _none = _plan(1, 2, 600, 64, 300, n_sparse_heads=0, impl=gb.GF_IMPL_MFMA_STREAM)
     assert st == gb.GF_OK
-    # The state pass works on half pieces (26 chunks).  A half-piece boundary e inside a head is
-    # summed iff a piece boundary (multiple of 52) at or after e lies inside the same head.
-    mid = 0
-    for j in range(1, 512):
-        e = 26 * j
-        nxt = -(-e // 52) * 52
-        mid += (e % 128 != 0) and nxt < (e // 128 + 1) * 128 and nxt < 104 * 128
-    assert pl["state_blocks"] == mid == 448
-    want_ws = 512 * (128 * 128 + 128) * 4
+    # The state pass sums the first piece of every head, in four sub-pieces of 16 chunks.
+    assert pl["state_blocks"] == 104 * 4
+    want_ws = 208 * 4 * (128 * 128 + 128) * 4
     assert pl["workspace_bytes"] == want_ws
     assert gb.gformer_attn_workspace_bytes(4, 32, 8192, 128, 256, gb.make_params(n_sparse_heads=6)) == want_ws
+    # 7 heads x 128 chunks: no whole number of pieces per head fills the chip (16 per head would be
+    # the limit of 8 chunks a piece: 112 pieces), so the chunk list is cut into 256 equal pieces of
+    # ceil(896 / 256) = 4 -> 8 chunks (the minimum), half pieces of 4 in the state pass
+    st, eq = _plan(1, 7, 8192, 128, 256, n_sparse_heads=0)
+    assert st == gb.GF_OK and eq["segment_len"] == 8 * 64 and eq["n_segments"] == 112
 
 
 def test_plan_modes_and_overrides():
