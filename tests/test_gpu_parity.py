@@ -156,6 +156,32 @@ def test_linear_chunk_and_segment_invariance(d):
     assert float(row_rel_l2(outs[(64, 64)], outs[(64, 1280)]).max()) < 1e-2
 
 
+# B, H (all linear), N, pieces the planner must choose, state-pass blocks with work
+LINEAR_PLAN_CASES = [
+    (2, 64, 1050, 256, 128),    # two pieces of 9 chunks per head (the second holds a virtual chunk), summed whole
+    (2, 64, 1500, 256, 256),    # two pieces of 12 chunks per head, summed in halves
+    (1, 80, 1600, 240, 160),    # three pieces of 9 chunks per head (27 >= 25 chunks), odd pieces are summed whole
+    (2, 64, 2048, 256, 512),    # two pieces of 16 chunks per head, summed in four sub-pieces
+    (1, 50, 1900, 188, None),   # no whole number per head fills the chip: 188 equal pieces of 8 chunks that straddle heads
+]
+
+
+@pytest.mark.parametrize("case", LINEAR_PLAN_CASES, ids=lambda c: "x".join(map(str, c[:3])))
+def test_linear_plans_with_many_heads(case):
+    """Every way the planner cuts the linear heads into pieces, at sizes the oracle does in full."""
+    B, H, N, pieces, state_blocks = case
+    d, w = 64, 8
+    st, plan = gb.gformer_attn_plan(B, H, N, d, w, gb.make_params(n_sparse_heads=0))
+    plan = plan.as_dict()
+    assert st == gb.GF_OK and plan["n_segments"] == pieces
+    if state_blocks is not None:
+        assert plan["state_blocks"] == state_blocks
+    q, k, v = synth(B, H, N, d, "bf16", 17)
+    got = run_gpu(q, k, v, "bf16", w, 0)
+    ref = oracle(q, k, v, w, 0)
+    check(got, ref, "bf16", f"plan case {case}")
+
+
 @pytest.mark.parametrize("dtype,impl", [("f32", SCALAR), ("bf16", MFMA)], ids=["f32", "bf16-mfma"])
 def test_causality_is_bit_exact(dtype, impl):
     """Changing token t's key, value and query leaves every earlier output row bit-identical,
