@@ -87,10 +87,12 @@ typedef struct gformer_params {
   int32_t phi;            /* gf_phi, linear heads only                                       */
   int32_t n_sparse_heads; /* H0: heads [0,H0) windowed softmax, heads [H0,H) causal linear   */
   int32_t chunk;          /* linear-attention chunk C: 64, or 0 = library picks               */
-  int32_t segment_len;    /* 0 = library picks: the chunks of all linear heads are cut into  */
-                          /* equal pieces with no regard to head boundaries, one workgroup   */
-                          /* each.  > 0 (multiple of chunk): every head is cut into segments */
-                          /* of this many tokens.  Either way pieces run in parallel and are */
+  int32_t segment_len;    /* 0 = library picks: every linear head is cut into the same whole */
+                          /* number of pieces when that fills most of the chip, else the     */
+                          /* chunks of all linear heads are cut into equal pieces with no    */
+                          /* regard to head boundaries; one workgroup per piece.  > 0        */
+                          /* (multiple of chunk): every head is cut into segments of this    */
+                          /* many tokens.  Either way pieces run in parallel and are         */
                           /* stitched with a prefix over their (A, Z) states.                */
   int32_t impl;           /* gf_impl                                                         */
   int32_t launch_mask;    /* 0 = everything.  Otherwise a bit set of GF_LAUNCH_*: only those */

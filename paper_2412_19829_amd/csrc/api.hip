@@ -188,7 +188,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
     if (piece > total) piece = total;
     if (piece % 2 != 0 && piece < total) ++piece;  // even, so the state pass can halve it
     pieces = (total + piece - 1) / piece;
-    // The state pass works on half pieces (two workgroups per compute unit fit there), which
+    // Here the state pass works on half pieces (two workgroups per compute unit fit there), which
     // evens out its load: a sub-piece is summed iff a piece boundary follows it inside its head.
     sub = piece % 2 == 0 ? 2 : 1;
     const long ls = piece / sub;

@@ -17,11 +17,12 @@
 // and V sit row-major in LDS and are read through the LDS transpose read wherever the
 // contraction runs over tokens.
 //
-// The chunks of all linear heads form one list that is cut into equal pieces, one workgroup
-// each, with no regard to head boundaries (or, on request, into uniform segments per head).
-// Pieces are stitched in stream-ordered launches: (1) for every (half-)piece boundary that
-// falls inside a head and is followed by a piece start in the same head, sum (A, Z) over the
-// part of that head lying in the (half-)piece before it; (2) only when a head holds many such
+// The chunks of all linear heads form one list that is cut into pieces, one workgroup each:
+// uniform segments per head (chosen by the planner when a whole number per head fills most of
+// the chip, or on request), else equal pieces with no regard to head boundaries.
+// Pieces are stitched in stream-ordered launches: (1) for every sub-piece boundary (a piece is
+// cut into 1, 2 or 4 sub-pieces) that falls inside a head and is followed by a piece start in
+// the same head, sum (A, Z) over the part of that head lying in the sub-piece before it; (2) only when a head holds many such
 // sums, a tiny kernel turns them into running sums; (3) the read-out kernel starts each piece
 // from the state carried to its first chunk (adding up the few sums itself otherwise) and
 // restarts from zero at head boundaries.
