@@ -241,32 +241,27 @@ __global__ __launch_bounds__(NT, 2) void windowed_bwd_band_kernel(BwdArgs a) {
         } else {
           // weights of the output product, packed bf16 in accumulator-register order
           uint32_t wb[8];
-          float lse_r[16], dd_r[16];
-          if (!RES_Q) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
+          for (int g = 0; g < 4; ++g) {
+            // statistics of the four streamed queries this group of registers belongs to
+            float lse4[4] = {lse_q, lse_q, lse_q, lse_q}, dd4[4] = {dd_q, dd_q, dd_q, dd_q};
+            if (!RES_Q) {
               const float4 l4 = *reinterpret_cast<const float4*>(&cur.lse[32 * half + 8 * g + 4 * lh]);
-              lse_r[4 * g + 0] = l4.x; lse_r[4 * g + 1] = l4.y; lse_r[4 * g + 2] = l4.z; lse_r[4 * g + 3] = l4.w;
+              lse4[0] = l4.x; lse4[1] = l4.y; lse4[2] = l4.z; lse4[3] = l4.w;
               if (HAS_DP) {
                 const float4 d4 = *reinterpret_cast<const float4*>(&cur.dd[32 * half + 8 * g + 4 * lh]);
-                dd_r[4 * g + 0] = d4.x; dd_r[4 * g + 1] = d4.y; dd_r[4 * g + 2] = d4.z; dd_r[4 * g + 3] = d4.w;
+                dd4[0] = d4.x; dd4[1] = d4.y; dd4[2] = d4.z; dd4[3] = d4.w;
               }
             }
-          }
-          float wv[16];
+            float wv[4];
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float lse = RES_Q ? lse_q : lse_r[r];
-            const float p = __builtin_amdgcn_exp2f(x[r] - lse);
-            if (HAS_DP) {
-              const float dd = RES_Q ? dd_q : dd_r[r];
-              wv[r] = p * (dp[r] - dd);
-            } else {
-              wv[r] = p;
+            for (int e = 0; e < 4; ++e) {
+              const float p = __builtin_amdgcn_exp2f(x[4 * g + e] - lse4[e]);
+              wv[e] = HAS_DP ? p * (dp[4 * g + e] - dd4[e]) : p;
             }
+            wb[2 * g] = pack_bf16(wv[0], wv[1]);
+            wb[2 * g + 1] = pack_bf16(wv[2], wv[3]);
           }
-#pragma unroll
-          for (int r = 0; r < 16; r += 2) wb[r / 2] = pack_bf16(wv[r], wv[r + 1]);
           // acc^T[column, resident row] += Y^T[column, streamed row] * weight[streamed row, resident row]
           const uint16_t* ytile = (PASS == kDv) ? cur.y : cur.x;
 #pragma unroll
