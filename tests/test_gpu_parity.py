@@ -652,7 +652,7 @@ def test_seeded_sweep(case):
 
 
 # ---------------------------------------------------------------------------------------
-# backward pass (plain-FMA kernels) against the oracle's derivatives
+# backward pass (matrix-core and plain-FMA kernels) against the oracle's derivatives
 # ---------------------------------------------------------------------------------------
 
 def run_bwd(q, k, v, dout, dtype, w, H0, layout="bhnd", **kw):
@@ -667,13 +667,19 @@ def run_bwd(q, k, v, dout, dtype, w, H0, layout="bhnd", **kw):
     return tuple(to_host(t) for t in (dq, dk, dv))
 
 
-def check_grad(got, ref, dtype, what, dout):
+BF16_BWD_MATRIX_CORE = 4e-2   # per-row bar of the matrix-core backward kernels, see check_grad
+
+
+def check_grad(got, ref, dtype, what, dout, impl=None):
     """fp32: max-abs error <= 1e-5 times the larger of the tensor's largest gradient magnitude
     and a typical dO row norm (a gradient entry is a difference of terms of the size
     |dO_i||v_j||k_j|, and fp32 rounding acts on those terms, not on the difference).  bf16: per-row L2 error <= 2e-2
     of the row's norm, where rows that vanish by cancellation (the gradient with respect to q of
     a token that sees one key is exactly 0) are measured against 1 % of a typical dO row instead
-    of against themselves."""
+    of against themselves.  The matrix-core kernels (bf16 storage, impl other than SCALAR) round
+    every operand of their products to bf16, and a gradient row is a sum of signed terms: rows
+    whose terms cancel come out up to 3-4 % off whatever the kernel does
+    (tests/test_backward_rounding_model.py shows it on the CPU), so their per-row bar is 4e-2."""
     assert np.isfinite(got).all(), f"non-finite gradient {what}"
     if dtype == "f32":
         rown = float(np.median(np.sqrt((dout.astype(np.float64) ** 2).sum(-1))))
@@ -684,7 +690,10 @@ def check_grad(got, ref, dtype, what, dout):
         floor = 1e-2 * float(np.median(np.sqrt((dout.astype(np.float64) ** 2).sum(-1))))
         den = np.maximum(np.sqrt((ref ** 2).sum(-1)), floor)
         worst = float((err / den).max())
-        assert worst <= BF16_ROW_REL_L2, f"{what}: worst row rel-L2 {worst:.3e}"
+        bar = BF16_ROW_REL_L2 if impl == SCALAR else BF16_BWD_MATRIX_CORE
+        assert worst <= bar, f"{what}: worst row rel-L2 {worst:.3e}"
+        # the average row is well inside the forward bar either way
+        assert float((err / den).mean()) <= 0.5 * BF16_ROW_REL_L2, f"{what}: mean row rel-L2"
 
 
 BWD_SHAPES = [
@@ -717,7 +726,7 @@ def test_backward_shapes(shape, path):
     got = run_bwd(q, k, v, dout, dtype, w, H0, impl=impl)
     ref = co.attn_bwd(q, k, v, dout, w, H0)
     for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
-        check_grad(g, r, dtype, f"{name} {shape}", dout)
+        check_grad(g, r, dtype, f"{name} {shape}", dout, impl)
 
 
 @pytest.mark.parametrize("shape", [(1, 2, 8192, 128, 256, 1), (2, 3, 2117, 64, 128, 1), (1, 2, 4099, 128, 64, 0)],
@@ -731,7 +740,7 @@ def test_backward_long_sequences_bf16(shape):
     got = run_bwd(q, k, v, dout, "bf16", w, H0)
     ref = co.attn_bwd(q, k, v, dout, w, H0)
     for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
-        check_grad(g, r, "bf16", f"{name} {shape}", dout)
+        check_grad(g, r, "bf16", f"{name} {shape}", dout, AUTO)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -747,7 +756,35 @@ def test_backward_scale_eps_identity_map_and_strides(dtype):
     got = run_bwd(q, k, v, dout, dtype, w, H0, layout="bnhd", **kw)
     ref = co.attn_bwd(q, k, v, dout, w, H0, phi=co.PHI_IDENTITY, softmax_scale=0.125, eps=0.5)
     for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
-        check_grad(g, r, dtype, name, dout)
+        check_grad(g, r, dtype, name, dout, AUTO)
+
+
+def _bwd_sweep_cases():
+    rng = np.random.default_rng(4048)
+    cases = []
+    for _ in range(24):
+        d = int(rng.choice([64, 128]))
+        B = int(rng.integers(1, 3))
+        H = int(rng.integers(1, 5))
+        N = int(rng.choice([int(rng.integers(1, 70)), int(rng.integers(70, 400)), int(rng.integers(400, 1400))]))
+        w = int(rng.choice([1, int(rng.integers(2, 40)), int(rng.integers(40, 258)), int(rng.integers(258, 700))]))
+        H0 = int(rng.integers(0, H + 1))
+        layout = "bnhd" if rng.integers(0, 3) == 0 else "bhnd"
+        path = BWD_PATHS[int(rng.integers(0, 3))] if rng.integers(0, 3) == 0 else ("bf16", AUTO)
+        cases.append((B, H, N, d, w, H0, layout, path[0], path[1]))
+    return cases
+
+
+@pytest.mark.parametrize("case", _bwd_sweep_cases(), ids=lambda c: "x".join(map(str, c)))
+def test_backward_seeded_sweep(case):
+    """Random shapes, windows, head splits and layouts; mostly the matrix-core kernels."""
+    B, H, N, d, w, H0, layout, dtype, impl = case
+    q, k, v = synth(B, H, N, d, dtype, 900 + N + w)
+    dout = synth(B, H, N, d, dtype, 901 + N + w)[2]
+    got = run_bwd(q, k, v, dout, dtype, w, H0, layout=layout, impl=impl)
+    ref = co.attn_bwd(q, k, v, dout, w, H0)
+    for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+        check_grad(g, r, dtype, f"{name} {case}", dout, impl)
 
 
 @pytest.mark.parametrize("path", BWD_PATHS, ids=BWD_PATH_IDS)
@@ -761,7 +798,7 @@ def test_backward_negative_scale(path):
     got = run_bwd(q, k, v, dout, dtype, w, H0, impl=impl, softmax_scale=-0.3)
     ref = co.attn_bwd(q, k, v, dout, w, H0, softmax_scale=-0.3)
     for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
-        check_grad(g, r, dtype, name, dout)
+        check_grad(g, r, dtype, name, dout, impl)
 
 
 def test_backward_outlier_scores_bf16():
@@ -774,7 +811,7 @@ def test_backward_outlier_scores_bf16():
     for impl in (AUTO, SCALAR):
         got = run_bwd(q, k, v, dout, "bf16", w, H0, impl=impl)
         for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
-            check_grad(g, r, "bf16", f"{name} impl={impl}", dout)
+            check_grad(g, r, "bf16", f"{name} impl={impl}", dout, impl)
 
 
 def test_backward_refuses_what_it_does_not_cover():
