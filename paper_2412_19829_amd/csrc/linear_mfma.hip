@@ -48,8 +48,10 @@ template <int D> struct LinCfg {
   static constexpr int NTC = NWC * 64;        // compute threads
   static constexpr int NT = 2 * NTC;          // + as many producer threads
   static constexpr int QROW = D + 8;          // phi(Q): 128-bit row reads   (stride = 4 dw mod 64)
-  static constexpr int KROW = D == 64 ? D + 8 : D + 16;  // phi(K): 64-bit row reads + transpose
-                                              // reads (D = 64: 8 keeps two workgroups' LDS under 160 KB)
+  static constexpr int KROW = D == 64 ? D + 8 : D + 24;  // phi(K): 64-bit row reads + transpose
+                                              // reads.  Measured per wave instruction at d = 128: stride
+                                              // D+24 (12 dwords mod 64) 4.2 / 4.5 cycles, D+16 8.0 / 4.5,
+                                              // D+32 16 / 2.5 (D = 64: 8 keeps two workgroups' LDS under 160 KB)
   static constexpr int VROW = D + 32;         // V: transpose reads only     (stride = 16 dw mod 64)
   static constexpr int PROW = CH + 8;         // masked products, [query][key]
   static constexpr int OROW = D + 8;          // normalised output rows on their way to memory
@@ -801,9 +803,12 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
 #pragma unroll
         for (int ct = 0; ct < C::ET; ++ct)
           o.fa[ct] = lds_operand_tr(b.fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * ct, lane);
-        // the wave's own feature tile once more, for colsum(phiK): a second read costs less than
-        // picking it out of fa[] with a wave-dependent branch or select
-        o.fz = lds_operand_tr(b.fk, C::KROW, 16 * kk + 8 * lh, 16 * kk + 8 * lh + 4, 32 * wave, lane);
+        // the wave's own feature tile, for colsum(phiK): picked out of fa[] with wave-uniform
+        // selects (a dozen vector moves; the LDS pipeline is the busier unit, a second read of the
+        // tile costs it 9 cycles per wave)
+        o.fz = o.fa[0];
+#pragma unroll
+        for (int ct = 1; ct < C::ET; ++ct) o.fz = wave == ct ? o.fa[ct] : o.fz;
         return o;
       };
       constexpr int NK = CAUSAL ? CH / 16 : 0, PDB = 2;   // no token work in the bidirectional read-out
