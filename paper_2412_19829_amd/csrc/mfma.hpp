@@ -12,9 +12,12 @@
 // An accumulator tile can thus feed the next MFMA straight from registers as long as the other
 // operand supplies its k-index in the same permuted order.
 //
-// LDS on this chip (measured): ds_read_b128 reaches ~220 B/clk/CU when 16 consecutive lanes
-// touch 64 distinct banks (row stride = 4 dwords mod 64); 64-bit reads, ds_read_b64_tr_b16
-// included, top out near 128 B/clk/CU; stores near 64-74 B/clk/CU.
+// LDS on this chip, measured with eight waves issuing independent accesses, in cycles per wave
+// instruction: ds_read_b128 4.5 when 16 consecutive lanes touch 64 distinct banks (lane = row,
+// row stride 4 or 12 dwords mod 64) and 8 when the 16 lanes read one contiguous 256-byte row;
+// ds_read_b64 2.7 contiguous, 4.2 with lane = row at stride 4 or 12 dwords mod 64, 8 at stride 8,
+// 16 at stride 16; ds_read_b64_tr_b16 2.4 at row stride 16 dwords mod 64, 4.5 at 8 or 12, 8 at 4;
+// ds_write_b64 8 (16 at row stride 8 dwords mod 64, 32 at 16), ds_write_b128 13.
 #pragma once
 
 #include <hip/hip_runtime.h>
