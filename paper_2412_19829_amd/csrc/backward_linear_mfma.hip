@@ -11,7 +11,10 @@
 //   forward scan:  num = S v + fq A,  den = rowsum(S) + fq.Z + eps,  c = rowdot(dO, num) / den^2,
 //                  dfq = T' fk + g A^T - c Z^T;           then A += fk^T v, Z += colsum(fk)
 //   reverse scan:  dfk = T'^T fq + v B^T - 1 Y^T,  dv = S^T g + fk B;   then B += fq^T g, Y += fq^T c
-// One workgroup per (batch, head) and scan.  Every product is a 32x32 MFMA tile job handed out
+// One workgroup per (batch, head), segment and scan: with fewer heads than compute units a head
+// is cut into up to four segments, and a workgroup first sums the chunks in front of (behind)
+// its segment in light rounds (the update of the carried sums alone) before it scans the segment.
+// Every product is a 32x32 MFMA tile job handed out
 // over the waves; the chunk's tiles sit in LDS row-major with a row stride that serves both the
 // row read (contraction over the feature/value index) and the transpose read (contraction over
 // tokens); the carried d x d sum lives in fp32 accumulators spread over the waves, with a bf16
