@@ -6,6 +6,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2412_19829_amd import binding as gb
@@ -324,3 +325,41 @@ def test_backward_argument_checks_on_the_host():
     assert gb.gformer_attn_bwd_raw(*ptrs, 1, 2, 16, 64, 4, gb.make_params(n_sparse_heads=3), *ws) == gb.GF_ERR_INVALID_ARG
     # empty problems are a no-op even with null pointers
     assert gb.gformer_attn_bwd_raw(0, 0, 0, 0, 0, 0, 0, 1, 2, 0, 64, 4, p) == gb.GF_OK
+
+
+def test_plan_invariants_over_random_shapes():
+    """Whatever way the planner cuts the linear heads, the pieces must cover every chunk of every
+    head, the workspace must hold one (A, Z) per state-pass slot, and the launch must stay at one
+    workgroup per compute unit unless the pieces are already at their minimum length."""
+    rng = np.random.default_rng(77)
+    for _ in range(400):
+        d = int(rng.choice([64, 128]))
+        B = int(rng.integers(1, 9))
+        H = int(rng.integers(1, 65))
+        H0 = int(rng.integers(0, H + 1))
+        N = int(rng.choice([int(rng.integers(1, 300)), int(rng.integers(300, 5000)), int(rng.integers(5000, 40000))]))
+        bidir = int(rng.integers(0, 4) == 0)
+        st, pl = _plan(B, H, N, d, 64, n_sparse_heads=H0, bidirectional=bidir)
+        assert st == gb.GF_OK, (B, H, N, d, H0, bidir)
+        heads, cph = B * (H - H0), -(-N // 64)
+        if heads == 0:
+            assert pl["linear_blocks"] == 0 and pl["workspace_bytes"] == 0
+            continue
+        assert pl["chunk"] == 64 and pl["segment_len"] % 64 == 0 and pl["segment_len"] > 0
+        piece = pl["segment_len"] // 64
+        assert pl["linear_blocks"] == pl["n_segments"] >= 1
+        assert pl["n_segments"] * piece >= heads * cph                      # every chunk is in a piece
+        assert (pl["n_segments"] - 1) * piece < heads * -(-cph // piece) * piece   # and no piece is idle
+        assert pl["n_segments"] <= 256 or piece <= 8 or heads > 256, (B, H, N, H0, pl)
+        state = (d * d + d) * 4
+        if pl["state_blocks"] == 0:
+            assert pl["workspace_bytes"] == 0
+        else:
+            assert pl["workspace_bytes"] % (pl["n_segments"] * state) == 0
+            sub = pl["workspace_bytes"] // (pl["n_segments"] * state)
+            assert sub in (1, 2, 4) and piece % sub == 0
+            assert pl["state_blocks"] <= pl["n_segments"] * sub
+            # causal: nothing is carried into the very first piece
+            assert bidir or pl["state_blocks"] <= pl["n_segments"] * sub - 1
+        assert gb.gformer_attn_workspace_bytes(B, H, N, d, 64, gb.make_params(n_sparse_heads=H0, bidirectional=bidir)) \
+            == pl["workspace_bytes"]
