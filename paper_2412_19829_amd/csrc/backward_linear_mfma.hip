@@ -184,17 +184,85 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
   for (int i = tid; i < D * R / 2; i += NT) reinterpret_cast<uint32_t*>(sm.st)[i] = 0u;
   if (tid < D) sm.z[tid] = 0.f;
 
-  load_chunk(0);
-  map_chunk(0);
-  stage_chunk(0);
-  if (ce > 1) load_chunk(1);
+  // Light rounds, two chunks at a time: the chunks in front of the segment only feed the carried
+  // sums, so phi(K) and V of chunk n go to the fk / v tiles and those of chunk n + 1 to the fq / g
+  // tiles (and travel in the q / dO staging registers), one barrier pair for both.
+  auto load_pair = [&](int n) {
+#pragma unroll
+    for (int i = 0; i < PCS; ++i) {
+      const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
+      const int64_t t0 = min(n * CH + row, N - 1), t1 = min((n + 1) * CH + row, N - 1);
+      rk[i] = *reinterpret_cast<const u32x4*>(hc.k + t0 * a.k.sn + col);
+      rv[i] = *reinterpret_cast<const u32x4*>(hc.v + t0 * a.v.sn + col);
+      rq[i] = *reinterpret_cast<const u32x4*>(hc.k + t1 * a.k.sn + col);
+      rdo[i] = *reinterpret_cast<const u32x4*>(hc.v + t1 * a.v.sn + col);
+    }
+  };
+  int n0 = 0;   // first chunk of the round-by-round loop below
+  if (cb >= 2) {
+    load_pair(0);
+    for (; n0 + 2 <= cb; n0 += 2) {
+      // chunks in front of a segment are whole: no rows past the end here
+#pragma unroll
+      for (int i = 0; i < PCS; ++i) {
+        const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
+        *reinterpret_cast<u32x4*>(&sm.fk[row * R + col]) = map8<ELU1>(rk[i]);
+        *reinterpret_cast<u32x4*>(&sm.v[row * R + col]) = rv[i];
+        *reinterpret_cast<u32x4*>(&sm.fq[row * R + col]) = map8<ELU1>(rq[i]);
+        *reinterpret_cast<u32x4*>(&sm.g[row * R + col]) = rdo[i];
+      }
+      if (n0 + 4 <= cb) load_pair(n0 + 2);
+      lds_barrier();
+#pragma unroll
+      for (int u = 0; u < TPW; ++u) {
+        const int stile = wave * TPW + u, vt = stile / MT, ft = stile % MT;
+#pragma unroll
+        for (int kk = 0; kk < CH / 16; ++kk) {
+          sacc[u] = mfma32(col_op(sm.v + trl, R, 16 * kk, 32 * vt), col_op(sm.fk + trl, R, 16 * kk, 32 * ft), sacc[u]);
+          sacc[u] = mfma32(col_op(sm.g + trl, R, 16 * kk, 32 * vt), col_op(sm.fq + trl, R, 16 * kk, 32 * ft), sacc[u]);
+        }
+      }
+      {
+        const int f = tid % D, part = tid / D;
+        constexpr int RPP = CH / C::ZP;
+        float acc = 0.f;
+#pragma unroll
+        for (int r = 0; r < RPP; ++r)
+          acc += __uint_as_float((uint32_t)sm.fk[(part * RPP + r) * R + f] << 16) +
+                 __uint_as_float((uint32_t)sm.fq[(part * RPP + r) * R + f] << 16);
+        sm.zpart[part][f] = acc;
+      }
+      lds_barrier();
+      if (tid < D) {
+        float zz = sm.z[tid];
+#pragma unroll
+        for (int pz = 0; pz < C::ZP; ++pz) zz += sm.zpart[pz][tid];
+        sm.z[tid] = zz;
+      }
+    }
+    if (n0 >= cb) {   // the next round scans: it reads the operand copy of the carried sum
+#pragma unroll
+      for (int u = 0; u < TPW; ++u) {
+        const int stile = wave * TPW + u, vt = stile / MT, ft = stile % MT;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+          put4(&sm.st[(32 * ft + ln) * R + 32 * vt + 8 * g4 + 4 * lh], sacc[u][4 * g4 + 0], sacc[u][4 * g4 + 1],
+               sacc[u][4 * g4 + 2], sacc[u][4 * g4 + 3]);
+      }
+    }
+  }
+
+  load_chunk(n0);
+  map_chunk(n0);
+  stage_chunk(n0);
+  if (n0 + 1 < ce) load_chunk(n0 + 1);
   lds_barrier();
 
   const int ti = wave & 3, jt = ti & 1, it = ti >> 1;   // 32 x 32 tile of the 64 x 64 products
   const bool do_s = NW == 4 || wave < 4, do_t = NW == 4 || wave >= 4;
   const int ot = wave % MT, it2 = wave / MT;            // output tile of the 64 x d products
 
-  for (int n = 0; n < ce; ++n) {
+  for (int n = n0; n < ce; ++n) {
     const int t0 = n * CH;
     const bool full = n >= cb;   // uniform over the workgroup
     f32x16 traw;
@@ -482,17 +550,99 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
   for (int i = tid; i < D * R / 2; i += NT) reinterpret_cast<uint32_t*>(sm.st)[i] = 0u;
   if (tid < D) sm.z[tid] = 0.f;
 
-  load_chunk(nchunks - 1);
-  map_chunk(nchunks - 1);
-  stage_chunk(nchunks - 1);
-  if (nchunks - 2 >= cb) load_chunk(nchunks - 2);
+  // Light rounds, two chunks at a time (the chunks behind the segment only feed the carried
+  // sums): phi(q), g and c of chunk n go to the fq / g tiles and cc, those of chunk n - 1 to the
+  // fk / v tiles and dz (and travel in the k / v staging registers).
+  float rden2[PCS];
+  float2 rstat2 = {1.f, 0.f};
+  auto load_pair = [&](int n) {
+#pragma unroll
+    for (int i = 0; i < PCS; ++i) {
+      const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
+      const int64_t t0 = min(n * CH + row, N - 1), t1 = (n - 1) * CH + row;
+      rq[i] = *reinterpret_cast<const u32x4*>(hc.q + t0 * a.q.sn + col);
+      rdo[i] = *reinterpret_cast<const u32x4*>(hc.dout + t0 * a.dout.sn + col);
+      rden[i] = hc.ws[2 * t0];
+      rk[i] = *reinterpret_cast<const u32x4*>(hc.q + t1 * a.q.sn + col);
+      rv[i] = *reinterpret_cast<const u32x4*>(hc.dout + t1 * a.dout.sn + col);
+      rden2[i] = hc.ws[2 * t1];
+    }
+    if (tid < CH) {
+      rstat = *reinterpret_cast<const float2*>(&hc.ws[2 * (int64_t)min(n * CH + tid, N - 1)]);
+      rstat2 = *reinterpret_cast<const float2*>(&hc.ws[2 * (int64_t)((n - 1) * CH + tid)]);
+    }
+  };
+  int n1 = nchunks - 1;   // first chunk of the round-by-round loop below
+  if (nchunks - ce >= 2) {
+    load_pair(n1);
+    for (; n1 - 1 >= ce; n1 -= 2) {
+#pragma unroll
+      for (int i = 0; i < PCS; ++i) {
+        const int p = tid + i * NT, row = p / C::C8, col = 8 * (p % C::C8);
+        const bool valid = n1 * CH + row < N;   // only the head's last chunk can be ragged
+        *reinterpret_cast<u32x4*>(&sm.fq[row * R + col]) = valid ? map8<ELU1>(rq[i]) : kZero4;
+        *reinterpret_cast<u32x4*>(&sm.g[row * R + col]) = valid ? scale8(rdo[i], 1.f / rden[i]) : kZero4;
+        *reinterpret_cast<u32x4*>(&sm.fk[row * R + col]) = map8<ELU1>(rk[i]);
+        *reinterpret_cast<u32x4*>(&sm.v[row * R + col]) = scale8(rv[i], 1.f / rden2[i]);
+      }
+      if (tid < CH) {
+        sm.cc[tid] = (n1 * CH + tid < N) ? rstat.y : 0.f;
+        sm.dz[tid] = rstat2.y;
+      }
+      if (n1 - 3 >= ce) load_pair(n1 - 2);
+      lds_barrier();
+#pragma unroll
+      for (int u = 0; u < TPW; ++u) {
+        const int stile = wave * TPW + u, vt = stile / MT, ft = stile % MT;
+#pragma unroll
+        for (int kk = 0; kk < CH / 16; ++kk) {
+          sacc[u] = mfma32(col_op(sm.g + trl, R, 16 * kk, 32 * vt), col_op(sm.fq + trl, R, 16 * kk, 32 * ft), sacc[u]);
+          sacc[u] = mfma32(col_op(sm.v + trl, R, 16 * kk, 32 * vt), col_op(sm.fk + trl, R, 16 * kk, 32 * ft), sacc[u]);
+        }
+      }
+      {
+        const int f = tid % D, part = tid / D;
+        constexpr int RPP = CH / C::ZP;
+        float acc = 0.f;
+#pragma unroll
+        for (int r = 0; r < RPP; ++r) {
+          const int i = part * RPP + r;
+          acc = fmaf(sm.cc[i], __uint_as_float((uint32_t)sm.fq[i * R + f] << 16), acc);
+          acc = fmaf(sm.dz[i], __uint_as_float((uint32_t)sm.fk[i * R + f] << 16), acc);
+        }
+        sm.zpart[part][f] = acc;
+      }
+      lds_barrier();
+      if (tid < D) {
+        float yy = sm.z[tid];
+#pragma unroll
+        for (int pz = 0; pz < C::ZP; ++pz) yy += sm.zpart[pz][tid];
+        sm.z[tid] = yy;
+      }
+    }
+    if (n1 < ce) {   // the next round scans: it reads the operand copy of the carried sum
+#pragma unroll
+      for (int u = 0; u < TPW; ++u) {
+        const int stile = wave * TPW + u, vt = stile / MT, ft = stile % MT;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+          put4(&sm.st[(32 * ft + ln) * R + 32 * vt + 8 * g4 + 4 * lh], sacc[u][4 * g4 + 0], sacc[u][4 * g4 + 1],
+               sacc[u][4 * g4 + 2], sacc[u][4 * g4 + 3]);
+      }
+    }
+  }
+
+  load_chunk(n1);
+  map_chunk(n1);
+  stage_chunk(n1);
+  if (n1 - 1 >= cb) load_chunk(n1 - 1);
   lds_barrier();
 
   const int ti = wave & 3, it = ti & 1, jt = ti >> 1;   // here rows are i, columns j (a lane owns a key j)
   const bool do_s = NW == 4 || wave < 4, do_t = NW == 4 || wave >= 4;
   const int ot = wave % MT, jt2 = wave / MT;
 
-  for (int n = nchunks - 1; n >= cb; --n) {
+  for (int n = n1; n >= cb; --n) {
     const int t0 = n * CH;
     const bool full = n < ce;   // uniform over the workgroup
     // ---- (a) S and T' tiles, stored transposed ([j][i]); column sums for Y ----
@@ -659,16 +809,17 @@ hipError_t launch_linear_backward_mfma(const BwdArgs& args, hipStream_t s) {
   BwdArgs a = args;
   const int heads = (a.H - a.H0) * a.B, nchunks = (a.N + CH - 1) / CH;
   a.lin_segments = std::max(1, std::min(std::min(4, kComputeUnitsBwd / heads), nchunks / 4));
-  // A light round costs about 0.45 of a full one (measured), and segment s runs the light rounds
-  // of everything in front of it: lengths in the ratio (1 - 0.45)^s finish together.  The reverse
-  // scan uses the same cut mirrored.
+  // A chunk of a light round costs about a quarter of a chunk of a full round (measured: the
+  // step is flat between 0.7 and 0.8 below), and segment s runs the light rounds of everything in
+  // front of it: lengths in the ratio 0.75^s finish together.  The reverse scan uses the same cut
+  // mirrored.
   {
     double wsum = 0.0, w = 1.0;
-    for (int sgm = 0; sgm < a.lin_segments; ++sgm, w *= 0.55) wsum += w;
+    for (int sgm = 0; sgm < a.lin_segments; ++sgm, w *= 0.75) wsum += w;
     double acc = 0.0;
     w = 1.0;
     a.lin_bounds[0] = 0;
-    for (int sgm = 1; sgm <= a.lin_segments; ++sgm, w *= 0.55) {
+    for (int sgm = 1; sgm <= a.lin_segments; ++sgm, w *= 0.75) {
       acc += w;
       a.lin_bounds[sgm] = sgm == a.lin_segments ? nchunks : std::min(nchunks, (int)(nchunks * acc / wsum + 0.5));
     }
