@@ -865,11 +865,17 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
           // the state after the head's last token, for a decode step to continue from:
           // A row-major [feature][value] (lane = value column, register = feature row), then Z
           float* fs = a.final_state + (int64_t)((g0 + n) / a.vcph) * C::STATE;
+          // four stores at a time: left to itself the scheduler forms all 64 addresses first and
+          // spills half of the kernel's registers around this rarely taken block
 #pragma unroll
           for (int ct = 0; ct < C::ET; ++ct)
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-              fs[(32 * ct + 8 * (r / 4) + 4 * lh + (r % 4)) * D + 32 * wave + ln] = sacc[ct][r];
+            for (int g = 0; g < 4; ++g) {
+              float* row = fs + (32 * ct + 8 * g + 4 * lh) * D + 32 * wave + ln;
+#pragma unroll
+              for (int x = 0; x < 4; ++x) row[x * D] = sacc[ct][4 * g + x];
+              __builtin_amdgcn_sched_barrier(0);
+            }
           if (lh == 0) fs[D * D + 32 * wave + ln] = znew;
         }
         if (lh == 0) put_z(zc ^ 1, zi, head_ends ? 0.f : znew);
