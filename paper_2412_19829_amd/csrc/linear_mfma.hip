@@ -733,7 +733,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
       o.q1 = lds_read16(&b.fq[(32 + ln) * C::QROW + 16 * ks + 8 * lh]);
       return o;
     };
-    constexpr int PD = 3;  // steps between an operand fetch and its use
+    constexpr int PD = 2;  // steps between an operand fetch and its use (measured: 2 beats 1, 3 and 4)
     constexpr int NSTEP = CAUSAL ? G1N : KS;   // without product tiles only the read-out steps remain
     StepOps ops[NSTEP];
 #pragma unroll
