@@ -467,31 +467,15 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
       ++nl;
       cl.next(a, nl < nchunks);
     };
-    // phi(Q) of the first QPRE pieces, in place in their registers, one phase before they are
-    // staged: spreads the feature map's vector work over both phases of a chunk
-    constexpr int QPRE = C::PIECES / 2;
-    auto map_q_pre = [&](u32x4 (&qr)[C::PIECES]) {
-#pragma unroll
-      for (int i = 0; i < QPRE; ++i) qr[i] = map_features<ELU1>(qr[i]);
-    };
     // phi(Q) of the chunk at `cs` -> buf[n % 2]
     auto stage_q = [&](const u32x4 (&qr)[C::PIECES], int n) {
       ChunkTiles<D>& b = sm.buf[n & 1];
 #pragma unroll
       for (int i = 0; i < C::PIECES; ++i) {
-        const u32x4 fqv = i < QPRE ? qr[i] : map_features<ELU1>(qr[i]);
+        const u32x4 fqv = map_features<ELU1>(qr[i]);
         uint16_t* qd = &b.fq[(st.r0 + i * C::RP) * C::QROW + st.qcol];
         *reinterpret_cast<u32x2*>(qd) = u32x2{fqv[0], fqv[1]};
         *reinterpret_cast<u32x2*>(qd + 8) = u32x2{fqv[2], fqv[3]};
-      }
-    };
-    // phi(K) of the first KEARLY pieces, in place in their registers: vector work moved in front
-    // of barrier (a), where the producers would otherwise wait for the matrix waves
-    constexpr int KEARLY = C::PIECES / 2;
-    auto map_k_early = [&](u32x4 (&kr)[C::PIECES]) {
-      if constexpr (CAUSAL) {
-#pragma unroll
-        for (int i = 0; i < KEARLY; ++i) kr[i] = map_features<ELU1>(kr[i]);
       }
     };
     // phi(K) and V of the chunk at `cs` -> buf[n % 2]; rows past the head's end become zeros
@@ -504,7 +488,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
         for (int i = 0; i < C::PIECES; ++i) {
           const int row = st.r0 + i * C::RP;
           const bool valid = full || t0 + row < N;
-          const u32x4 fk = i < KEARLY ? kr[i] : map_features<ELU1>(kr[i]);
+          const u32x4 fk = map_features<ELU1>(kr[i]);
           *reinterpret_cast<u32x4*>(&b.fk[row * C::KROW + st.col]) = valid ? fk : kZero4;
           *reinterpret_cast<u32x4*>(&b.v[row * C::VROW + st.col]) = valid ? vr[i] : kZero4;
         }
@@ -526,10 +510,11 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
       co.next(a, no < nchunks);
     };
     // Per chunk n the consumers run [products, state read-out] (a) [denominators, in-chunk
-    // part, state update] (b).  The producers' work for chunk n+1 is split the same way so that
-    // neither side idles at a barrier: phi(Q) and half of phi(K) before (a); after (a) the
-    // write-out of chunk n-1, the rest of phi(K) and V; each set's reload (chunk n+3) follows
-    // its staging.  Two chunks per round (one per register set).
+    // part, state update] (b).  The producers' work for chunk n+1 is split the same way: phi(Q)
+    // and its staging before (a); after (a) the write-out of chunk n-1, then phi(K), V and their
+    // staging; each set's reload (chunk n+3) follows its staging.  The feature map is applied
+    // where a tensor is staged: mapping parts of Q and K one phase early, in their registers, was
+    // measured and is 2 % slower.  Two chunks per round (one per register set).
     //
     // The wait counters the compiler derives for a load that sits behind a condition assume it
     // may not have been issued, which makes the waits for older loads cover the newest ones as
@@ -545,42 +530,33 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
         load_q(q1);
         load_kv(k1, v1);
       }
-      map_q_pre(q0);
       stage_q(q0, 0);
-      map_k_early(k0);
       stage_kv(k0, v0, 0);
       if (S || nchunks > 2) {
         load_q(q0);
         load_kv(k0, v0);
       }
-      if (S || nchunks > 1) map_q_pre(q1);
       lds_barrier();  // chunk 0 staged
     };
     auto round2 = [&](int n, auto mode) {
       constexpr int M = decltype(mode)::value;
       constexpr bool S = M != kGeneral;
-      if (S || n + 1 < nchunks) {
-        stage_q(q1, n + 1);
-        map_k_early(k1);
-      }
+      if (S || n + 1 < nchunks) stage_q(q1, n + 1);
       if (S || n + 3 < nchunks) load_q(q1);
       lds_barrier();  // (a)
       if (M == kSteady || (M == kGeneral && n > 0)) store_out();
       if (S || n + 1 < nchunks) stage_kv(k1, v1, n + 1);
       if (S || n + 3 < nchunks) load_kv(k1, v1);
-      if (S || n + 2 < nchunks) map_q_pre(q0);
       lds_barrier();  // (b)
       if (!S && n + 1 >= nchunks) return false;
       if (S || n + 2 < nchunks) {
         stage_q(q0, n + 2);
-        map_k_early(k0);
-      }
+        }
       if (S || n + 4 < nchunks) load_q(q0);
       lds_barrier();  // (a)
       store_out();
       if (S || n + 2 < nchunks) stage_kv(k0, v0, n + 2);
       if (S || n + 4 < nchunks) load_kv(k0, v0);
-      if (S || n + 3 < nchunks) map_q_pre(q1);
       lds_barrier();  // (b)
       return true;
     };
