@@ -549,9 +549,7 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
       if (S || n + 3 < nchunks) load_kv(k1, v1);
       lds_barrier();  // (b)
       if (!S && n + 1 >= nchunks) return false;
-      if (S || n + 2 < nchunks) {
-        stage_q(q0, n + 2);
-        }
+      if (S || n + 2 < nchunks) stage_q(q0, n + 2);
       if (S || n + 4 < nchunks) load_q(q0);
       lds_barrier();  // (a)
       store_out();
