@@ -835,3 +835,50 @@ def test_backward_refuses_what_it_does_not_cover():
     ptrs[4] = ptrs[0]          # dq aliases q
     st = gb.gformer_attn_bwd_raw(*ptrs, 1, 2, 64, 64, 8, p, ws.data_ptr(), ws.numel(), 0)
     assert st == gb.GF_ERR_INVALID_ARG
+
+
+# ---------------------------------------------------------------------------------------
+# stream capture: the calls record kernels only, so a captured graph must reproduce them
+# ---------------------------------------------------------------------------------------
+
+def test_forward_and_backward_replay_from_a_captured_graph():
+    """Capture one forward and one backward call of the layer in a graph on a side stream, then
+    replay it several times with eager work and synchronisations of the program in between: every
+    replay must give the eager result bit for bit (the calls enqueue kernels and nothing else)."""
+    import torch
+    B, H, N, d, w, H0 = 2, 6, 1500, 64, 100, 2
+    q, k, v = synth(B, H, N, d, "bf16", 81)
+    dout = synth(B, H, N, d, "bf16", 82)[2]
+    tq, tk, tv, tdo = (to_device(x, "bf16") for x in (q, k, v, dout))
+    p = gb.make_params(n_sparse_heads=H0)
+    need_f = gb.gformer_attn_workspace_bytes(B, H, N, d, w, p)
+    need_b = gb.gformer_attn_bwd_workspace_bytes(B, H, N, d, w, p)
+    ws_f = torch.zeros(max(need_f, 256), dtype=torch.uint8, device="cuda")
+    ws_b = torch.zeros(max(need_b, 256), dtype=torch.uint8, device="cuda")
+    out, dq, dk, dv = (torch.empty_like(tq) for _ in range(4))
+
+    def calls(stream):
+        st = gb.gformer_attn_fwd_raw(tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), out.data_ptr(), B, H, N, d, w, p,
+                                     ws_f.data_ptr(), ws_f.numel(), stream)
+        assert st == gb.GF_OK
+        st = gb.gformer_attn_bwd_raw(tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), tdo.data_ptr(), dq.data_ptr(),
+                                     dk.data_ptr(), dv.data_ptr(), B, H, N, d, w, p, ws_b.data_ptr(), ws_b.numel(),
+                                     stream)
+        assert st == gb.GF_OK
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        calls(side.cuda_stream)          # eager, also loads every kernel before the capture
+        side.synchronize()
+        want = [t.clone() for t in (out, dq, dk, dv)]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            calls(side.cuda_stream)
+        for rep in range(3):
+            for t in (out, dq, dk, dv):
+                t.fill_(float("nan"))    # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for name, got, ref in zip(("out", "dq", "dk", "dv"), (out, dq, dk, dv), want):
+                assert torch.equal(got.view(torch.int16), ref.view(torch.int16)), f"replay {rep}: {name} differs"
