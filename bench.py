@@ -339,7 +339,12 @@ def main() -> int:
         backward()
         torch.cuda.synchronize()
         t_bwd = event_time(backward, 20)
+        pb.overlap = 1      # the windowed heads' passes beside the linear heads' scans
+        backward()
+        torch.cuda.synchronize()
+        t_bwd_overlap = event_time(backward, 20)
         modes["backward"] = {"ms": round(t_bwd * 1e3, 3), "tokens_per_s": round(wl.B * wl.N / t_bwd, 1),
+                             "ms_overlap_1": round(t_bwd_overlap * 1e3, 3),
                              "note": "gformer_attn_bwd, bf16 matrix-core kernels: four band passes over the "
                                      "windowed heads, a forward and a reverse chunk scan over the linear heads"}
         result["modes"] = modes

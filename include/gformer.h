@@ -100,7 +100,8 @@ typedef struct gformer_params {
                           /* is taken as already present in the workspace).                  */
   int32_t overlap;        /* 0: everything is enqueued on `hip_stream` one after another.    */
                           /* 1: the windowed heads run on a library-owned side stream that   */
-                          /* forks from and joins `hip_stream`, next to the state pass.      */
+                          /* forks from and joins `hip_stream`, next to the state pass (in   */
+                          /* gformer_attn_bwd: next to the linear heads' scans).             */
   int32_t bidirectional;  /* 0: causal (sections III-B, III-C).  1: the encoder / image form of  */
                           /* section IV: windowed heads see the w tokens centred on the token */
                           /* (w/2 to the left, w-1-w/2 to the right, cut at the ends; the     */
@@ -208,7 +209,10 @@ gf_status gformer_attn_prefill(const void* q, const void* k, const void* v, void
  * GF_IMPL_SCALAR and every fp32 call run on plain-FMA kernels (fp32 arithmetic on either
  * storage type).  GF_IMPL_MFMA with fp32 storage, GF_IMPL_MFMA_BLOCKED, GF_IMPL_MFMA_STREAM and
  * params.bidirectional = 1 are GF_ERR_UNSUPPORTED.  params.launch_mask must be 0; segment_len
- * and overlap are ignored.
+ * is ignored.  params.overlap = 1 (matrix-core kernels, both head groups present): the windowed
+ * heads' passes run on the library's side stream beside the linear heads' scans, which leave
+ * compute units idle when there are fewer heads than units; same fork/join as in
+ * gformer_attn_fwd, same results.
  * Asynchronous on `hip_stream`; errors as for gformer_attn_fwd. */
 size_t gformer_attn_bwd_workspace_bytes(int B, int H, int N, int d, int window,
                                         const gformer_params* p);

@@ -514,8 +514,26 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
   const bool mfma = bf16 && p->impl != GF_IMPL_SCALAR;
   hipError_t e = hipSuccess;
   if (mfma) {
-    e = launch_windowed_backward_mfma(a, stream);
-    if (e == hipSuccess) e = launch_linear_backward_mfma(a, stream);
+    // The linear scans are one workgroup per head and segment: with fewer of those than compute
+    // units the rest of the chip is idle for their whole duration.  With overlap = 1 the windowed
+    // heads' passes therefore run beside them on the library's side stream (forked from and
+    // joined to the caller's stream by events), and the scans are enqueued first so that their
+    // workgroups get their compute units.
+    const bool both = a.H0 > 0 && a.H0 < a.H;
+    std::lock_guard<std::mutex> lock(g_enqueue_mutex);
+    SideStream* side = nullptr;
+    if (both && p->overlap) e = side_stream_for_current_device(&side);
+    if (side && e == hipSuccess) {
+      e = hipEventRecord(side->fork, stream);
+      if (e == hipSuccess) e = launch_linear_backward_mfma(a, stream);
+      if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
+      if (e == hipSuccess) e = launch_windowed_backward_mfma(a, side->stream);
+      if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
+      if (e == hipSuccess) e = hipStreamWaitEvent(stream, side->join, 0);
+    } else if (e == hipSuccess) {
+      e = launch_windowed_backward_mfma(a, stream);
+      if (e == hipSuccess) e = launch_linear_backward_mfma(a, stream);
+    }
   } else {
     e = launch_backward_scalar(a, bf16, true, true, stream);
   }

@@ -814,6 +814,21 @@ def test_backward_outlier_scores_bf16():
             check_grad(g, r, "bf16", f"{name} impl={impl}", dout, impl)
 
 
+def test_backward_overlap_gives_the_same_bits():
+    """overlap = 1 only moves the windowed heads' passes to the library's side stream."""
+    B, H, N, d, w, H0 = 2, 5, 900, 128, 200, 2
+    q, k, v = synth(B, H, N, d, "bf16", 67)
+    dout = synth(B, H, N, d, "bf16", 68)[2]
+    plain = run_bwd(q, k, v, dout, "bf16", w, H0)
+    for _ in range(2):
+        side = run_bwd(q, k, v, dout, "bf16", w, H0, overlap=1)
+        for a_, b_, name in zip(plain, side, ("dq", "dk", "dv")):
+            assert np.array_equal(a_, b_), name
+    ref = co.attn_bwd(q, k, v, dout, w, H0)
+    for g, r, name in zip(side, ref, ("dq", "dk", "dv")):
+        check_grad(g, r, "bf16", name, dout, AUTO)
+
+
 def test_backward_refuses_what_it_does_not_cover():
     import torch
     t = [torch.zeros(1, 2, 64, 64, device="cuda", dtype=torch.bfloat16) for _ in range(7)]
