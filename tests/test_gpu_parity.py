@@ -856,16 +856,18 @@ def test_backward_refuses_what_it_does_not_cover():
 # stream capture: the calls record kernels only, so a captured graph must reproduce them
 # ---------------------------------------------------------------------------------------
 
-def test_forward_and_backward_replay_from_a_captured_graph():
+@pytest.mark.parametrize("overlap", [0, 1], ids=["one-stream", "overlap"])
+def test_forward_and_backward_replay_from_a_captured_graph(overlap):
     """Capture one forward and one backward call of the layer in a graph on a side stream, then
     replay it several times with eager work and synchronisations of the program in between: every
-    replay must give the eager result bit for bit (the calls enqueue kernels and nothing else)."""
+    replay must give the eager result bit for bit (the calls enqueue kernels and nothing else;
+    with overlap = 1 also the event fork and join of the library's own stream)."""
     import torch
     B, H, N, d, w, H0 = 2, 6, 1500, 64, 100, 2
     q, k, v = synth(B, H, N, d, "bf16", 81)
     dout = synth(B, H, N, d, "bf16", 82)[2]
     tq, tk, tv, tdo = (to_device(x, "bf16") for x in (q, k, v, dout))
-    p = gb.make_params(n_sparse_heads=H0)
+    p = gb.make_params(n_sparse_heads=H0, overlap=overlap)
     need_f = gb.gformer_attn_workspace_bytes(B, H, N, d, w, p)
     need_b = gb.gformer_attn_bwd_workspace_bytes(B, H, N, d, w, p)
     ws_f = torch.zeros(max(need_f, 256), dtype=torch.uint8, device="cuda")
