@@ -8,9 +8,31 @@
 
 #include "common.hpp"
 
+#include <atomic>
+
 namespace gformer {
 
 int mfma_linear_threads(int d) { return d == 128 ? 512 : 256; }
+
+// Compute units of the current device, asked once per device; a process without a device (the
+// planner is host arithmetic and is also called there) plans for an MI355X.
+int device_compute_units() {
+  constexpr int kDefault = 256, kSlots = 64;
+  static std::atomic<int> cached[kSlots];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kSlots) {
+    (void)hipGetLastError();
+    return kDefault;
+  }
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+    (void)hipGetLastError();
+    return kDefault;
+  }
+  cached[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
 
 namespace {
 
@@ -20,8 +42,6 @@ struct Resolved {
   int cph, vcph, piece_chunks, state_sub;
   bool stream;   // MFMA path: the windowed heads go to the streaming kernel
 };
-
-constexpr long kComputeUnits = 256;  // MI355X
 
 // One side stream and a fork/join event pair per device, created on first use and kept for the
 // life of the process.  Default priority on purpose.
@@ -78,7 +98,7 @@ gf_status check_strides(const int64_t* in, int64_t* out, int H, int N, int d) {
 // Chunks per piece when every linear head is cut into the same whole number of pieces (one
 // workgroup per piece, at most one per compute unit, pieces of 8 chunks or more), or 0 when that
 // would leave more than a fifth of the compute units without a piece.
-long aligned_piece(long heads_lin, long cph) {
+long aligned_piece(long heads_lin, long cph, long kComputeUnits) {
   if (heads_lin <= 0 || cph <= 0) return 0;
   long k = kComputeUnits / heads_lin;
   if (k > cph / 8) k = cph / 8;
@@ -92,8 +112,18 @@ long aligned_piece(long heads_lin, long cph) {
 // Shared by gformer_attn_plan, gformer_attn_workspace_bytes and gformer_attn_fwd.
 // Token i of a windowed head sees keys i - left .. i + right (cut at the sequence ends): the w
 // tokens ending at i, or (bidirectional) the w tokens centred on it.
-int window_left(int window, int bidirectional) { return bidirectional ? window / 2 : window - 1; }
-int window_right(int window, int bidirectional) { return bidirectional ? window - 1 - window / 2 : 0; }
+// Both reaches are cut at N - 1 here, once: a token cannot see further than the sequence, and
+// the tile arithmetic of the kernels and planners (reach + tile size, row + reach) then stays far
+// from the end of the int range for any window up to INT_MAX (the natural way to ask for full
+// attention).
+int window_left(int window, int bidirectional, int N) {
+  const int reach = bidirectional ? window / 2 : window - 1;
+  return reach < N - 1 ? reach : (N > 1 ? N - 1 : 0);
+}
+int window_right(int window, int bidirectional, int N) {
+  const int reach = bidirectional ? window - 1 - window / 2 : 0;
+  return reach < N - 1 ? reach : (N > 1 ? N - 1 : 0);
+}
 
 gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* p, Resolved* r) {
   memset(r, 0, sizeof(*r));
@@ -128,6 +158,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
 
   gformer_plan& pl = r->plan;
   pl.impl = impl;
+  const long kComputeUnits = device_compute_units();
   const int H0 = p->n_sparse_heads, H1 = H - H0;
   const long heads_lin = (long)B * H1;
   if (impl == GF_IMPL_SCALAR) {
@@ -163,11 +194,11 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
     vcph = per_head * piece;
     pieces = heads_lin * per_head;
     mid = pieces;
-  } else if (p->segment_len != 0 || aligned_piece(heads_lin, cph) > 0) {
+  } else if (p->segment_len != 0 || aligned_piece(heads_lin, cph, kComputeUnits) > 0) {
     // Uniform segments per head: asked for, or chosen because a whole number of them per head
     // keeps at least 4 of 5 compute units busy.  Pieces that never straddle heads leave the state
     // pass the least to re-read (a head's last segment is never summed).
-    piece = p->segment_len != 0 ? p->segment_len / pl.chunk : aligned_piece(heads_lin, cph);
+    piece = p->segment_len != 0 ? p->segment_len / pl.chunk : aligned_piece(heads_lin, cph, kComputeUnits);
     const long per_head = cph > 0 ? (cph + piece - 1) / piece : 0;
     vcph = per_head * piece;
     pieces = heads_lin * per_head;
@@ -207,8 +238,8 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   pl.windowed_threads = kMfmaWindowThreads;
   pl.windowed_blocks = (H0 > 0 && N > 0) ? B * H0 * ((N + kMfmaWindowRows - 1) / kMfmaWindowRows) : 0;
   {
-    const StreamPlan sp = windowed_stream_plan((int64_t)B * H0, N, window_left(window, p->bidirectional),
-                                               window_right(window, p->bidirectional));
+    const StreamPlan sp = windowed_stream_plan((int64_t)B * H0, N, window_left(window, p->bidirectional, N),
+                                               window_right(window, p->bidirectional, N));
     if (p->impl == GF_IMPL_MFMA_STREAM && H0 > 0 && !sp.applies) return GF_ERR_UNSUPPORTED;
     r->stream = p->impl == GF_IMPL_MFMA_STREAM || (p->impl != GF_IMPL_MFMA_BLOCKED && sp.preferred);
     if (r->stream && H0 > 0 && N > 0) {
@@ -288,8 +319,8 @@ gf_status attn_forward(const void* q, const void* k, const void* v, void* out, v
   a.B = B; a.H = H; a.N = N; a.d = d;
   a.window = window;
   a.causal = p->bidirectional ? 0 : 1;
-  a.wleft = window_left(window, p->bidirectional);
-  a.wright = window_right(window, p->bidirectional);
+  a.wleft = window_left(window, p->bidirectional, N);
+  a.wright = window_right(window, p->bidirectional, N);
   a.H0 = p->n_sparse_heads;
   a.phi = p->phi;
   a.scale = p->softmax_scale;
@@ -503,7 +534,7 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
   a.dout = TensorView{dout, r.os[0], r.os[1], r.os[2]};
   a.dq = dq; a.dk = dk; a.dv = dv;
   a.B = B; a.H = H; a.N = N; a.d = d;
-  a.window = window;
+  a.window = window < N ? window : N;   // a wider window sees no more keys; keeps row + window in range
   a.H0 = p->n_sparse_heads;
   a.phi = p->phi;
   a.scale = p->softmax_scale;

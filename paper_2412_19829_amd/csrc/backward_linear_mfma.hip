@@ -782,8 +782,6 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
   }
 }
 
-constexpr int kComputeUnitsBwd = 256;
-
 template <int D, bool ELU1> hipError_t launch_lin_bwd_t(const BwdArgs& a, hipStream_t s) {
   const dim3 grid(a.H - a.H0, a.B, a.lin_segments), block(LbCfg<D>::NT);
   const int smem = (int)sizeof(LbSmem<D>), smem_kv = (int)sizeof(LbSmemKv<D>);
@@ -808,7 +806,7 @@ hipError_t launch_linear_backward_mfma(const BwdArgs& args, hipStream_t s) {
   // segment in light rounds, then scans the segment.
   BwdArgs a = args;
   const int heads = (a.H - a.H0) * a.B, nchunks = (a.N + CH - 1) / CH;
-  a.lin_segments = std::max(1, std::min(std::min(4, kComputeUnitsBwd / heads), nchunks / 4));
+  a.lin_segments = std::max(1, std::min(std::min(4, device_compute_units() / heads), nchunks / 4));
   // A chunk of a light round costs about a quarter of a chunk of a full round (measured: the
   // step is flat between 0.7 and 0.8 below), and segment s runs the light rounds of everything in
   // front of it: lengths in the ratio 0.75^s finish together.  The reverse scan uses the same cut

@@ -161,5 +161,6 @@ constexpr int kScalarThreads = 256;
 constexpr int kMfmaWindowRows = 128;    // query rows per workgroup, MFMA windowed kernel
 constexpr int kMfmaWindowThreads = 256;
 int mfma_linear_threads(int d);
+int device_compute_units();   // of the current device; 256 (MI355X) in a process without one
 
 }  // namespace gformer

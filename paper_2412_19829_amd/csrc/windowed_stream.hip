@@ -350,7 +350,7 @@ StreamPlan windowed_stream_plan(int64_t heads, int N, int wleft, int wright) {
   // Pieces: one per compute unit where the heads allow it, never shorter than the halo a piece
   // has to walk on top of its own pairs.
   const int npairs = (N + PQ - 1) / PQ;
-  constexpr int64_t kComputeUnits = 256;   // MI355X
+  const int64_t kComputeUnits = device_compute_units();
   int64_t pph = heads >= kComputeUnits ? 1 : kComputeUnits / heads;
   int ppp = (int)((npairs + pph - 1) / pph);
   ppp = std::max(ppp, std::min(npairs, NS - 1));

@@ -59,6 +59,11 @@ WORKLOADS = {
     "long32k": Workload("long32k", 1, 32, 32768, 128, 512, "bf16", 1004, sigma=0.5,
                         q_prescaled=False, outlier_every=64, outlier_gain=8.0,
                         n_sparse_heads=6),
+    # the same stress pattern with Q multiplied by 1/sqrt(d) like the other workloads (the contract's
+    # text does not say whether Q is pre-scaled there; both readings are run)
+    "long32k_prescaled": Workload("long32k_prescaled", 1, 32, 32768, 128, 512, "bf16", 1004, sigma=0.5,
+                                  q_prescaled=True, outlier_every=64, outlier_gain=8.0,
+                                  n_sparse_heads=6),
     # the paper's own timing shape (section IV-A, IV-D): B=4, H=16, E=64, 3 sparse heads
     "paper_gpt_4k": Workload("paper_gpt_4k", 4, 16, 4096, 64, 128, "bf16", 1006,
                              n_sparse_heads=3),

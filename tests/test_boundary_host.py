@@ -363,3 +363,23 @@ def test_plan_invariants_over_random_shapes():
             assert bidir or pl["state_blocks"] <= pl["n_segments"] * sub - 1
         assert gb.gformer_attn_workspace_bytes(B, H, N, d, 64, gb.make_params(n_sparse_heads=H0, bidirectional=bidir)) \
             == pl["workspace_bytes"]
+
+
+@pytest.mark.parametrize("bidirectional", [0, 1])
+@pytest.mark.parametrize("shape", [(4, 32, 8192, 128, 6), (1, 12, 2048, 64, 12), (2, 3, 100, 64, 2)])
+def test_plan_of_a_window_at_the_end_of_the_int_range(shape, bidirectional):
+    """A window no sequence can fill (INT_MAX is the natural way to ask for full attention) is
+    planned exactly like a window of the whole sequence: the reach is cut at N - 1 on the host,
+    before any tile arithmetic could leave the int range."""
+    B, H, N, d, H0 = shape
+    full = 2 * N if bidirectional else N
+    st, want = _plan(B, H, N, d, full, n_sparse_heads=H0, bidirectional=bidirectional)
+    assert st == gb.GF_OK
+    for w in (2 ** 31 - 1, 2 ** 31 - 40, 2 ** 30, full + 1):
+        st, got = _plan(B, H, N, d, w, n_sparse_heads=H0, bidirectional=bidirectional)
+        assert st == gb.GF_OK and got == want, (w, got, want)
+    # such a window never fits the streaming kernel (five key tiles) once N is larger than that
+    if N > 400:
+        st, _pl = _plan(B, H, N, d, 2 ** 31 - 1, n_sparse_heads=H0, bidirectional=bidirectional,
+                        impl=gb.GF_IMPL_MFMA_STREAM)
+        assert st == gb.GF_ERR_UNSUPPORTED

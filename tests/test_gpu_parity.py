@@ -292,8 +292,28 @@ def test_llm7b_segment_sweep_sampled_heads(seg):
     _full_size("llm7b", 6, chunk=64, segment_len=seg)
 
 
-def test_long32k_full_size_sampled_heads():
-    _full_size("long32k", 6)
+@pytest.mark.parametrize("H0", [6, 32, 0])
+@pytest.mark.parametrize("name", ["long32k", "long32k_prescaled"])
+def test_long32k_full_size_sampled_heads(name, H0):
+    """The long-sequence stress workload at its full size, with the queries as drawn (logits of a
+    few units, outlier keys eight times that) and with the 1/sqrt(d) pre-scaling of the other
+    workloads; the paper's head split, all heads windowed, all heads linear."""
+    _full_size(name, H0)
+
+
+def test_window_at_the_end_of_the_int_range_is_full_causal_attention():
+    """window = INT_MAX on a call large enough for the planner to prefer the streaming kernel
+    when the window fits it: must run the query-block kernel over the whole prefix."""
+    B, H, N, d, H0 = 2, 20, 3300, 64, 20
+    q, k, v = synth(B, H, N, d, "bf16", 93)
+    ref = oracle(q, k, v, N, H0)
+    for w in (2 ** 31 - 1, 2 ** 31 - 30):
+        check(run_gpu(q, k, v, "bf16", w, H0), ref, "bf16", f"window={w}")
+    q, k, v = synth(1, 3, 333, 64, "f32", 94)
+    check(run_gpu(q, k, v, "f32", 2 ** 31 - 1, 2), oracle(q, k, v, 333, 2), "f32", "f32 window=INT_MAX")
+    qb, kb, vb = synth(1, 2, 700, 128, "bf16", 95)
+    got = run_gpu(qb, kb, vb, "bf16", 2 ** 31 - 1, 1, bidirectional=1)
+    check(got, co.attn_fwd(qb, kb, vb, 2 * 700, 1, bidirectional=True), "bf16", "bidirectional window=INT_MAX")
 
 
 # ---------------------------------------------------------------------------------------
@@ -727,6 +747,21 @@ def test_backward_shapes(shape, path):
     ref = co.attn_bwd(q, k, v, dout, w, H0)
     for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
         check_grad(g, r, dtype, f"{name} {shape}", dout, impl)
+
+
+@pytest.mark.parametrize("path", BWD_PATHS, ids=BWD_PATH_IDS)
+def test_backward_window_at_the_end_of_the_int_range(path):
+    """window = INT_MAX is full causal attention in the backward pass too (row + window must not
+    leave the int range in the key-resident passes)."""
+    dtype, impl = path
+    B, H, N, d, H0 = 1, 3, 450, 64, 2
+    q, k, v = synth(B, H, N, d, dtype, 65)
+    dout = synth(B, H, N, d, dtype, 66)[2]
+    ref = co.attn_bwd(q, k, v, dout, N, H0)
+    for w in (2 ** 31 - 1, 2 ** 31 - 100):
+        got = run_bwd(q, k, v, dout, dtype, w, H0, impl=impl)
+        for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+            check_grad(g, r, dtype, f"{name} window={w}", dout, impl)
 
 
 @pytest.mark.parametrize("shape", [(1, 2, 8192, 128, 256, 1), (2, 3, 2117, 64, 128, 1), (1, 2, 4099, 128, 64, 0)],
