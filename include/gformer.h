@@ -158,6 +158,28 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
                            int N, int d, int window, const gformer_params* p, void* workspace,
                            size_t workspace_bytes, void* hip_stream);
 
+/* gformer_attn_fwd for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results (bit for bit), conventions and errors as gformer_attn_fwd, without
+ * `workspace`: the carried linear-attention states go to a device array of
+ * GFORMER_NOALLOC_SCRATCH_BYTES that is part of the library's code object (every device that
+ * loads the library holds its own copy until the process ends).  The call allocates and frees
+ * nothing, on the host or on the device, and creates no stream or event.
+ *   - gformer_attn_workspace_bytes(...) > GFORMER_NOALLOC_SCRATCH_BYTES: GF_ERR_WORKSPACE, before
+ *     anything is launched (the headline layer B=4 H=32 N=8192 d=128 needs 52.4 MiB, 64.5 MiB with all heads linear).
+ *   - params.overlap = 1 (library-owned side stream, created on first use): GF_ERR_UNSUPPORTED.
+ *   - Call it with the device of `hip_stream` current.  The first call on a device looks up that
+ *     device's address of the array (hipGetSymbolAddress, no allocation); make that first call
+ *     outside stream capture.
+ *   - All calls on one device share the one array, which keeps the last call's contents: nothing
+ *     in it has to start at zero (every slot a call reads was written by that same call), but two
+ *     calls that overlap in time on one device (different streams, or graph branches) race.
+ *     Calls on one stream, one after another, are safe. */
+#define GFORMER_NOALLOC_SCRATCH_BYTES ((size_t)72 << 20)
+gf_status gformer_attn_fwd_noalloc(const void* q, const void* k, const void* v, void* out, int B,
+                                   int H, int N, int d, int window, const gformer_params* p,
+                                   void* hip_stream);
+
 /* One decode step of the causal layer: token `t` of every (batch, head) from what the layer keeps
  * between steps (autoregressive generation; the paper targets LLM inference, its evaluation runs
  * whole sequences).  Windowed heads (section III-B, Eq. 1): the last `window` keys and values live

@@ -22,7 +22,7 @@ GF_IMPL_AUTO, GF_IMPL_SCALAR, GF_IMPL_MFMA, GF_IMPL_MFMA_BLOCKED, GF_IMPL_MFMA_S
 GF_LAUNCH_WINDOWED, GF_LAUNCH_LINEAR_STATE, GF_LAUNCH_LINEAR_MAIN = 1, 2, 4
 
 EXPORTS = ("gformer_params_init", "gformer_attn_workspace_bytes", "gformer_attn_plan",
-           "gformer_attn_fwd", "gformer_attn_prefill", "gformer_attn_decode",
+           "gformer_attn_fwd", "gformer_attn_fwd_noalloc", "gformer_attn_prefill", "gformer_attn_decode",
            "gformer_attn_bwd_workspace_bytes", "gformer_attn_bwd",
            "gformer_feature_params_init",
            "gformer_random_features",
@@ -95,6 +95,9 @@ def lib():
         L.gformer_attn_fwd.restype = ctypes.c_int
         L.gformer_attn_fwd.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 5 + \
             [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.gformer_attn_fwd_noalloc.restype = ctypes.c_int
+        L.gformer_attn_fwd_noalloc.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 5 + \
+            [P, ctypes.c_void_p]
         L.gformer_attn_prefill.restype = ctypes.c_int
         L.gformer_attn_prefill.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_int] * 5 + \
             [P, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
@@ -176,6 +179,19 @@ def gformer_attn_fwd_raw(q_ptr, k_ptr, v_ptr, out_ptr, B, H, N, d, window, param
         ctypes.c_void_p(v_ptr or None), ctypes.c_void_p(out_ptr or None),
         int(B), int(H), int(N), int(d), int(window), ctypes.byref(params),
         ctypes.c_void_p(workspace_ptr or None), ctypes.c_size_t(int(workspace_bytes)),
+        ctypes.c_void_p(stream or None)))
+
+
+GFORMER_NOALLOC_SCRATCH_BYTES = 72 << 20
+
+
+def gformer_attn_fwd_noalloc_raw(q_ptr, k_ptr, v_ptr, out_ptr, B, H, N, d, window,
+                                 params: GformerParams, stream=0) -> int:
+    """Direct call with integer device addresses; returns the gf_status."""
+    return int(lib().gformer_attn_fwd_noalloc(
+        ctypes.c_void_p(q_ptr or None), ctypes.c_void_p(k_ptr or None),
+        ctypes.c_void_p(v_ptr or None), ctypes.c_void_p(out_ptr or None),
+        int(B), int(H), int(N), int(d), int(window), ctypes.byref(params),
         ctypes.c_void_p(stream or None)))
 
 

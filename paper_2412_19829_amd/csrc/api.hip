@@ -70,6 +70,31 @@ hipError_t side_stream_for_current_device(SideStream** out) {
   return hipSuccess;
 }
 
+// Scratch of the entry point that allocates nothing: the carried linear-attention states live in
+// this file-scope device array instead of a caller's workspace.  Every device the library runs
+// on holds its own copy, at its own address, from the moment the code object is loaded until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// address that kernels receive is looked up once per device, with that device current.
+constexpr size_t kScratchBytes = GFORMER_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+hipError_t scratch_for_current_device(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return hipSuccess;
+}
+
 constexpr int64_t kMaxRowStride = 1 << 20;  // elements
 
 bool strides_all_zero(const int64_t* s) { return s[0] == 0 && s[1] == 0 && s[2] == 0; }
@@ -385,6 +410,27 @@ gf_status gformer_attn_fwd(const void* q, const void* k, const void* v, void* ou
                            size_t workspace_bytes, void* hip_stream) {
   return attn_forward(q, k, v, out, nullptr, nullptr, nullptr, B, H, N, d, window, p, workspace,
                       workspace_bytes, hip_stream);
+}
+
+gf_status gformer_attn_fwd_noalloc(const void* q, const void* k, const void* v, void* out, int B,
+                                   int H, int N, int d, int window, const gformer_params* p,
+                                   void* hip_stream) {
+  Resolved r;
+  const gf_status st = resolve(B, H, N, d, window, p, &r);
+  if (st != GF_OK) return st;
+  if (p->overlap != 0) return GF_ERR_UNSUPPORTED;   // the side stream is created on first use
+  if (r.plan.workspace_bytes > kScratchBytes) return GF_ERR_WORKSPACE;
+  if (B == 0 || H == 0 || N == 0) return GF_OK;
+  void* ws = nullptr;
+  if (r.plan.workspace_bytes > 0) {
+    std::lock_guard<std::mutex> lock(g_enqueue_mutex);
+    if (scratch_for_current_device(&ws) != hipSuccess) {
+      (void)hipGetLastError();
+      return GF_ERR_DEVICE;
+    }
+  }
+  return attn_forward(q, k, v, out, nullptr, nullptr, nullptr, B, H, N, d, window, p, ws,
+                      ws ? kScratchBytes : 0, hip_stream);
 }
 
 gf_status gformer_attn_prefill(const void* q, const void* k, const void* v, void* out, void* kcache,
