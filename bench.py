@@ -107,9 +107,9 @@ def main() -> int:
     out = torch.empty_like(tq)
     stream = torch.cuda.current_stream().cuda_stream
 
-    def make_call(h0, mask=0):
+    def make_call(h0, mask=0, chunk=0, impl=gb.GF_IMPL_AUTO):
         params = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=h0, segment_len=args.segment_len,
-                                launch_mask=mask, overlap=int(args.overlap))
+                                launch_mask=mask, overlap=int(args.overlap), chunk=chunk, impl=impl)
         need = gb.gformer_attn_workspace_bytes(wl.B, wl.H, wl.N, wl.d, wl.window, params)
         ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
         ptrs = (tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), out.data_ptr())
@@ -186,6 +186,28 @@ def main() -> int:
                 "mfma_tflops": round(dom_flops / kern[dominant] / 1e12, 1),
                 "mfma_frac": round(dom_flops / kern[dominant] / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
+    # ---- linear-attention chunk size swept over {64, 128, 256} (the contract's sweep) -----
+    # 64 runs the kernel specialised for it (the timed step above); "64_general" is the same chunk
+    # on the general-chunk kernel that 128 and 256 use, so that the three sizes compare on one
+    # kernel.  A size the library refuses for this head size is reported with its status.
+    chunk_sweep = {}
+    if H0 < wl.H:
+        for label, ch, impl in (("64", 64, gb.GF_IMPL_AUTO), ("64_general", 64, gb.GF_IMPL_MFMA_CHUNK),
+                                ("128", 128, gb.GF_IMPL_AUTO), ("256", 256, gb.GF_IMPL_AUTO)):
+            p_ch = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=H0, chunk=ch, impl=impl)
+            st_ch, _pl = gb.gformer_attn_plan(wl.B, wl.H, wl.N, wl.d, wl.window, p_ch)
+            if st_ch != gb.GF_OK:
+                chunk_sweep[label] = {"status": gb.gformer_status_string(st_ch)}
+                continue
+            c_all, _, _w1 = make_call(H0, 0, ch, impl)
+            c_main, _, _w2 = make_call(H0, gb.GF_LAUNCH_LINEAR_MAIN, ch, impl)
+            ramp(c_all)
+            t_all = event_time(c_all, 100)
+            t_main = event_time(c_main, 100)
+            chunk_sweep[label] = {"ms_per_step": round(t_all * 1e3, 4),
+                                  "linear_readout_us": round(t_main * 1e6, 2),
+                                  "tokens_per_s": round(wl.B * wl.N / t_all, 1)}
+
     result = {
         "metric": "GFormer attention fwd tokens/s",
         "value": round(wl.B * wl.N / sec, 1),
@@ -204,6 +226,7 @@ def main() -> int:
         "gbs": round(nbytes / sec / 1e9, 1),
         "pct_hbm_peak": round(100 * nbytes / sec / 1e9 / HBM_PEAK_GBS, 2),
         "kernel_us": {k_: round(v_ * 1e6, 2) for k_, v_ in kern.items()},
+        "chunk_sweep": chunk_sweep,
         "roofline": roofline,
     }
 
@@ -220,6 +243,31 @@ def main() -> int:
                            "tflops": round(fl / s / 1e12, 2),
                            "pct_mfma_peak": round(100 * fl / s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
                            "pct_hbm_peak": round(100 * by / s / 1e9 / HBM_PEAK_GBS, 2)}
+        # The chunk sweep at head size 64 (where 256 exists too): the headline layer's shape with
+        # d = 64, same head split.
+        sweep64 = {}
+        g64 = torch.Generator("cuda").manual_seed(wl.seed + 64)
+        sq, sk, sv = (torch.randn(wl.B, wl.H, wl.N, 64, device="cuda", generator=g64).to(torch.bfloat16)
+                      for _ in range(3))
+        sq = (sq.float() / 8.0).to(torch.bfloat16)
+        so = torch.empty_like(sq)
+        for label, ch, impl in (("64", 64, gb.GF_IMPL_AUTO), ("64_general", 64, gb.GF_IMPL_MFMA_CHUNK),
+                                ("128", 128, gb.GF_IMPL_AUTO), ("256", 256, gb.GF_IMPL_AUTO)):
+            p64 = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=H0, chunk=ch, impl=impl)
+            n64 = gb.gformer_attn_workspace_bytes(wl.B, wl.H, wl.N, 64, wl.window, p64)
+            w64 = torch.empty(max(n64, 256), dtype=torch.uint8, device="cuda")
+
+            def call64():
+                st_ = gb.gformer_attn_fwd_raw(sq.data_ptr(), sk.data_ptr(), sv.data_ptr(), so.data_ptr(),
+                                              wl.B, wl.H, wl.N, 64, wl.window, p64, w64.data_ptr(),
+                                              w64.numel(), stream)
+                if st_ != gb.GF_OK:
+                    raise gb.GformerError(st_, gb.gformer_status_string(st_))
+            ramp(call64)
+            sweep64[label] = {"ms_per_step": round(event_time(call64, 100) * 1e3, 4)}
+        modes["chunk_sweep_d64"] = {"shape": f"B={wl.B} H={wl.H} N={wl.N} d=64 window={wl.window} n_sparse_heads={H0}",
+                                    "by_chunk": sweep64}
+        del sq, sk, sv, so
         # The long-sequence stress workload (B=1 H=32 N=32768 d=128 w=512, one key in 64 scaled by
         # 8, queries as drawn): at w = 512 arithmetic intensity is 256 FLOP/B, so the all-windowed
         # split is the shape where the matrix cores, not HBM, should bind.  Also the variant with

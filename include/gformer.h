@@ -41,8 +41,8 @@
  *     anything is launched and reported through gf_status.
  *   - Supported: d in {64, 128}; any N >= 0 (N == 0 or B*H == 0 is a no-op); any window >= 1
  *     (window >= N is full causal attention); 0 <= n_sparse_heads <= H;
- *     chunk in {0, 64}.  Everything else returns GF_ERR_UNSUPPORTED; nothing falls back
- *     silently.
+ *     chunk in {0, 64, 128, 256} (256 only with d = 64).  Everything else returns
+ *     GF_ERR_UNSUPPORTED; nothing falls back silently.
  */
 #ifndef GFORMER_H
 #define GFORMER_H
@@ -78,7 +78,9 @@ typedef enum {
   GF_IMPL_SCALAR = 1,
   GF_IMPL_MFMA = 2,
   GF_IMPL_MFMA_BLOCKED = 3,
-  GF_IMPL_MFMA_STREAM = 4
+  GF_IMPL_MFMA_STREAM = 4,
+  GF_IMPL_MFMA_CHUNK = 5 /* as GF_IMPL_MFMA, with the causal linear heads read out by the kernel */
+                         /* that takes any chunk size, also at chunk 64 (for comparison)        */
 } gf_impl;
 
 typedef struct gformer_params {
@@ -86,7 +88,14 @@ typedef struct gformer_params {
   int32_t dtype;          /* gf_dtype                                                        */
   int32_t phi;            /* gf_phi, linear heads only                                       */
   int32_t n_sparse_heads; /* H0: heads [0,H0) windowed softmax, heads [H0,H) causal linear   */
-  int32_t chunk;          /* linear-attention chunk C: 64, or 0 = library picks               */
+  int32_t chunk;          /* linear-attention chunk C of Algorithm 1's chunked form: 64, 128  */
+                          /* or 256 tokens, 0 = library picks (64).  The result does not      */
+                          /* depend on it.  64 runs a kernel specialised for it; 128 and 256  */
+                          /* (256: d = 64 only, a larger tile set does not fit the LDS of a   */
+                          /* compute unit) run the general-chunk kernel, causal layers only   */
+                          /* in the sense that the bidirectional read-out has no in-chunk     */
+                          /* part (there the chunk only sets the granularity of segment_len). */
+                          /* The fp32 kernels work in chunks of 32 whatever is asked.         */
   int32_t segment_len;    /* 0 = library picks: every linear head is cut into the same whole */
                           /* number of pieces when that fills most of the chip, else the     */
                           /* chunks of all linear heads are cut into equal pieces with no    */

@@ -19,6 +19,7 @@ GF_F32, GF_BF16 = 0, 1
 GF_PHI_ELU1, GF_PHI_IDENTITY = 0, 1
 GF_FLOPS_PAPER, GF_FLOPS_PER_HEAD = 0, 1
 GF_IMPL_AUTO, GF_IMPL_SCALAR, GF_IMPL_MFMA, GF_IMPL_MFMA_BLOCKED, GF_IMPL_MFMA_STREAM = 0, 1, 2, 3, 4
+GF_IMPL_MFMA_CHUNK = 5
 GF_LAUNCH_WINDOWED, GF_LAUNCH_LINEAR_STATE, GF_LAUNCH_LINEAR_MAIN = 1, 2, 4
 
 EXPORTS = ("gformer_params_init", "gformer_attn_workspace_bytes", "gformer_attn_plan",

@@ -41,6 +41,7 @@ struct Resolved {
   int64_t qs[3], ks[3], vs[3], os[3];
   int cph, vcph, piece_chunks, state_sub;
   bool stream;   // MFMA path: the windowed heads go to the streaming kernel
+  bool general_chunk;  // MFMA path, causal: the linear read-out goes to the general-chunk kernel
 };
 
 // One side stream and a fork/join event pair per device, created on first use and kept for the
@@ -158,7 +159,8 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   if (p->dtype != GF_F32 && p->dtype != GF_BF16) return GF_ERR_INVALID_ARG;
   if (p->phi != GF_PHI_ELU1 && p->phi != GF_PHI_IDENTITY) return GF_ERR_INVALID_ARG;
   if (p->impl != GF_IMPL_AUTO && p->impl != GF_IMPL_SCALAR && p->impl != GF_IMPL_MFMA &&
-      p->impl != GF_IMPL_MFMA_BLOCKED && p->impl != GF_IMPL_MFMA_STREAM)
+      p->impl != GF_IMPL_MFMA_BLOCKED && p->impl != GF_IMPL_MFMA_STREAM &&
+      p->impl != GF_IMPL_MFMA_CHUNK)
     return GF_ERR_INVALID_ARG;
   if (p->n_sparse_heads < 0 || p->n_sparse_heads > H) return GF_ERR_INVALID_ARG;
   if (p->chunk < 0 || p->segment_len < 0) return GF_ERR_INVALID_ARG;
@@ -176,10 +178,12 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
 
   int impl = p->impl;
   if (impl == GF_IMPL_AUTO) impl = (p->dtype == GF_BF16) ? GF_IMPL_MFMA : GF_IMPL_SCALAR;
-  // the last two differ from GF_IMPL_MFMA only in which kernel runs the windowed heads
-  if (impl == GF_IMPL_MFMA_BLOCKED || impl == GF_IMPL_MFMA_STREAM) impl = GF_IMPL_MFMA;
+  // the others differ from GF_IMPL_MFMA only in which kernel runs the windowed heads or the
+  // linear read-out
+  if (impl == GF_IMPL_MFMA_BLOCKED || impl == GF_IMPL_MFMA_STREAM || impl == GF_IMPL_MFMA_CHUNK)
+    impl = GF_IMPL_MFMA;
   if (impl == GF_IMPL_MFMA && p->dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
-  if (p->chunk != 0 && p->chunk != 64) return GF_ERR_UNSUPPORTED;
+  if (p->chunk != 0 && p->chunk != 64 && p->chunk != 128 && p->chunk != 256) return GF_ERR_UNSUPPORTED;
 
   gformer_plan& pl = r->plan;
   pl.impl = impl;
@@ -200,7 +204,16 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
     return GF_OK;
   }
   pl.chunk = p->chunk ? p->chunk : 64;
-  const long cph = N > 0 ? (N + pl.chunk - 1) / pl.chunk : 0;  // real chunks per head
+  // Everything below counts in strips of 64 tokens (the tile every kernel works in); a chunk is
+  // one, two or four of them.  Chunks of more than one strip (and GF_IMPL_MFMA_CHUNK at any
+  // size) take the causal read-out to the general-chunk kernel, whose pieces are whole chunks of
+  // one head.  The bidirectional read-out has no in-chunk part: there the chunk only sets the
+  // granularity of segment_len.
+  constexpr long kStrip = 64;
+  const long cm = pl.chunk / kStrip;
+  r->general_chunk = !p->bidirectional && (cm > 1 || p->impl == GF_IMPL_MFMA_CHUNK);
+  if (r->general_chunk && H1 > 0 && !linear_chunk_supported(d, pl.chunk)) return GF_ERR_UNSUPPORTED;
+  const long cph = N > 0 ? (N + kStrip - 1) / kStrip : 0;  // real strips per head
   long piece = 0, vcph = cph, pieces = 0, mid = 0, sub = 1;
   if (p->segment_len != 0 && p->segment_len % pl.chunk != 0) return GF_ERR_INVALID_ARG;
   if (p->bidirectional && heads_lin > 0 && cph > 0) {
@@ -208,7 +221,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
     // straddle heads (uniform segments per head) and every one of them is summed by the state
     // pass.  Without a request: as many pieces per head as keep every compute unit at one piece.
     if (p->segment_len != 0) {
-      piece = p->segment_len / pl.chunk;
+      piece = p->segment_len / kStrip;
     } else {
       long per = kComputeUnits / heads_lin;
       if (per < 1) per = 1;
@@ -219,11 +232,23 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
     vcph = per_head * piece;
     pieces = heads_lin * per_head;
     mid = pieces;
-  } else if (p->segment_len != 0 || aligned_piece(heads_lin, cph, kComputeUnits) > 0) {
-    // Uniform segments per head: asked for, or chosen because a whole number of them per head
-    // keeps at least 4 of 5 compute units busy.  Pieces that never straddle heads leave the state
-    // pass the least to re-read (a head's last segment is never summed).
-    piece = p->segment_len != 0 ? p->segment_len / pl.chunk : aligned_piece(heads_lin, cph, kComputeUnits);
+  } else if (p->segment_len != 0 ||
+             (heads_lin > 0 && cph > 0 &&
+              (r->general_chunk || aligned_piece(heads_lin, cph, kComputeUnits) > 0))) {
+    // Uniform segments per head: asked for, needed by the general-chunk kernel, or chosen
+    // because a whole number of them per head keeps at least 4 of 5 compute units busy.  Pieces
+    // that never straddle heads leave the state pass the least to re-read (a head's last segment
+    // is never summed).
+    piece = p->segment_len != 0 ? p->segment_len / kStrip : aligned_piece(heads_lin, cph, kComputeUnits);
+    if (piece == 0) {
+      // general-chunk kernel with too few or too many heads for a good whole-number cut: as many
+      // pieces per head as there are compute units for, none shorter than 8 strips
+      long k = kComputeUnits / heads_lin;
+      if (k > cph / 8) k = cph / 8;
+      if (k < 1) k = 1;
+      piece = (cph + k - 1) / k;
+    }
+    if (r->general_chunk) piece = (piece + cm - 1) / cm * cm;   // whole chunks
     const long per_head = cph > 0 ? (cph + piece - 1) / piece : 0;
     vcph = per_head * piece;
     pieces = heads_lin * per_head;
@@ -258,7 +283,7 @@ gf_status resolve(int B, int H, int N, int d, int window, const gformer_params* 
   r->vcph = (int)vcph;
   r->piece_chunks = (int)piece;
   r->state_sub = (int)sub;
-  pl.segment_len = (int)(piece * pl.chunk);
+  pl.segment_len = (int)(piece * kStrip);
   pl.n_segments = (int)pieces;
   pl.windowed_threads = kMfmaWindowThreads;
   pl.windowed_blocks = (H0 > 0 && N > 0) ? B * H0 * ((N + kMfmaWindowRows - 1) / kMfmaWindowRows) : 0;
@@ -333,6 +358,8 @@ gf_status attn_forward(const void* q, const void* k, const void* v, void* out, v
     if (!workspace || workspace_bytes < r.plan.workspace_bytes) return GF_ERR_WORKSPACE;
     if ((uintptr_t)workspace & 255u) return GF_ERR_INVALID_ARG;
   }
+  // only the kernel specialised for chunks of 64 writes the states a decode step continues from
+  if (final_state && r.general_chunk && p->n_sparse_heads < H) return GF_ERR_UNSUPPORTED;
 
   AttnArgs a;
   memset(&a, 0, sizeof(a));
@@ -395,7 +422,8 @@ gf_status attn_forward(const void* q, const void* k, const void* v, void* out, v
     } else if (win && e == hipSuccess) {
       e = launch_windowed(s);
     }
-    if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess) e = launch_linear_main_mfma(a, s);
+    if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess)
+      e = r.general_chunk ? launch_linear_chunk(a, s) : launch_linear_main_mfma(a, s);
   }
   if (e == hipSuccess) e = launch_fill_rings(a, bf16, s);
   return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
@@ -546,7 +574,9 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
   if (p->struct_size != sizeof(gformer_params)) return GF_ERR_INVALID_ARG;
   // a bf16 call runs on the matrix-core kernels (AUTO, MFMA) unless SCALAR asks for the plain-FMA
   // kernels, which are also the fp32 path.  Causal form only.
-  if (p->impl == GF_IMPL_MFMA_BLOCKED || p->impl == GF_IMPL_MFMA_STREAM) return GF_ERR_UNSUPPORTED;
+  if (p->impl == GF_IMPL_MFMA_BLOCKED || p->impl == GF_IMPL_MFMA_STREAM ||
+      p->impl == GF_IMPL_MFMA_CHUNK)
+    return GF_ERR_UNSUPPORTED;
   if (p->impl == GF_IMPL_MFMA && p->dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
   gformer_params pp = *p;
   pp.impl = GF_IMPL_SCALAR;

@@ -30,8 +30,9 @@ struct AttnArgs {
   // list is cut into `n_pieces` pieces of `piece_chunks` chunks; one workgroup walks one piece.
   // vcph == cph: pieces are cut with no regard to head boundaries (balanced);
   // vcph  > cph: every head is padded to a whole number of pieces (uniform segments per head).
-  int chunk;         // tokens per chunk
-  int cph;           // real chunks per head = ceil(N / chunk)
+  int chunk;         // tokens per chunk of the causal read-out (64, 128, 256)
+  // the four counts below are in strips of 64 tokens whatever the chunk ("chunks" of the fixed-64 kernels)
+  int cph;           // real strips per head = ceil(N / 64)
   int vcph;          // virtual chunks per head
   int piece_chunks;  // chunks per piece
   int n_pieces;      // pieces = workgroups of the read-out kernel
@@ -150,6 +151,9 @@ StreamPlan windowed_stream_plan(int64_t heads, int N, int wleft, int wright);
 hipError_t launch_windowed_stream(const AttnArgs& a, hipStream_t s);
 hipError_t launch_linear_state_mfma(const AttnArgs& a, hipStream_t s);
 hipError_t launch_linear_main_mfma(const AttnArgs& a, hipStream_t s);
+// The causal read-out for chunks of 64, 128 or 256 tokens (the general form of the kernel above).
+bool linear_chunk_supported(int d, int chunk);
+hipError_t launch_linear_chunk(const AttnArgs& a, hipStream_t s);
 hipError_t launch_fill_rings(const AttnArgs& a, bool bf16, hipStream_t s);
 hipError_t launch_random_features(const FeatureArgs& a, bool bf16, bool mfma, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, bool bf16, hipStream_t s);

@@ -129,11 +129,13 @@ def test_plan_modes_and_overrides():
     ((1, 2, 256, 64, 4), {"chunk": 64, "segment_len": 96}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 96, 4), {}, gb.GF_ERR_UNSUPPORTED),               # head size
     ((1, 2, 16, 64, 4), {"chunk": 48}, gb.GF_ERR_UNSUPPORTED),
-    ((1, 2, 16, 64, 4), {"chunk": 256}, gb.GF_ERR_UNSUPPORTED),
-    ((1, 2, 16, 64, 4), {"chunk": 128}, gb.GF_ERR_UNSUPPORTED),
+    ((1, 2, 16, 64, 4), {"chunk": 512}, gb.GF_ERR_UNSUPPORTED),
+    ((1, 2, 16, 128, 4), {"chunk": 256}, gb.GF_ERR_UNSUPPORTED),   # its tiles do not fit the LDS
+    ((1, 2, 256, 64, 4), {"chunk": 128, "segment_len": 192}, gb.GF_ERR_INVALID_ARG),
     ((1, 2, 16, 64, 4), {"dtype": gb.GF_F32, "impl": gb.GF_IMPL_MFMA}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 16, 64, 4), {"dtype": gb.GF_F32, "impl": gb.GF_IMPL_MFMA_BLOCKED}, gb.GF_ERR_UNSUPPORTED),
-    ((1, 2, 16, 64, 4), {"impl": 5}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"impl": 6}, gb.GF_ERR_INVALID_ARG),
+    ((1, 2, 16, 64, 4), {"dtype": gb.GF_F32, "impl": gb.GF_IMPL_MFMA_CHUNK}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 600, 64, 258), {"impl": gb.GF_IMPL_MFMA_STREAM, "n_sparse_heads": 1}, gb.GF_ERR_UNSUPPORTED),
     ((1, 2, 256, 64, 4), {"dtype": gb.GF_F32, "segment_len": 64}, gb.GF_ERR_UNSUPPORTED),
     ((70000, 2, 16, 64, 4), {}, gb.GF_ERR_UNSUPPORTED),
@@ -383,3 +385,28 @@ def test_plan_of_a_window_at_the_end_of_the_int_range(shape, bidirectional):
         st, _pl = _plan(B, H, N, d, 2 ** 31 - 1, n_sparse_heads=H0, bidirectional=bidirectional,
                         impl=gb.GF_IMPL_MFMA_STREAM)
         assert st == gb.GF_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("d,chunk", [(64, 64), (64, 128), (64, 256), (128, 64), (128, 128)])
+def test_plan_of_the_general_chunk_kernel(d, chunk):
+    """Chunks of 128 and 256 tokens (and GF_IMPL_MFMA_CHUNK at 64) go to the general-chunk kernel,
+    whose pieces are whole chunks of one head: uniform segments per head, a multiple of the chunk
+    long, whatever the head count."""
+    impl = gb.GF_IMPL_MFMA_CHUNK if chunk == 64 else gb.GF_IMPL_MFMA
+    for (B, H, N, H0) in [(4, 32, 8192, 6), (1, 3, 5000, 0), (2, 7, 333, 2), (40, 9, 700, 1), (1, 1, 64, 0)]:
+        st, pl = _plan(B, H, N, d, 256, n_sparse_heads=H0, chunk=chunk, impl=impl)
+        assert st == gb.GF_OK and pl["chunk"] == chunk
+        seg = pl["segment_len"]
+        assert seg % chunk == 0 and seg > 0
+        per_head = -(-N // seg)
+        assert pl["n_segments"] == B * (H - H0) * per_head == pl["linear_blocks"]
+        # asked-for segments keep their length when it is a multiple of the chunk
+        st, pl2 = _plan(B, H, N, d, 256, n_sparse_heads=H0, chunk=chunk, impl=impl, segment_len=2 * chunk)
+        assert st == gb.GF_OK and pl2["segment_len"] == 2 * chunk
+    # the headline layer: two segments of 64 strips per head, as with the specialised kernel
+    st, pl = _plan(4, 32, 8192, d, 256, n_sparse_heads=6, chunk=chunk, impl=impl)
+    assert pl["segment_len"] == 4096 and pl["n_segments"] == 208
+    # the bidirectional read-out has no in-chunk part: any chunk plans like 64
+    st, bi = _plan(4, 32, 8192, d, 256, n_sparse_heads=6, chunk=chunk, bidirectional=1)
+    st, bi64 = _plan(4, 32, 8192, d, 256, n_sparse_heads=6, chunk=64, bidirectional=1)
+    assert {k: v for k, v in bi.items() if k != "chunk"} == {k: v for k, v in bi64.items() if k != "chunk"}

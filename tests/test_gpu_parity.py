@@ -156,6 +156,59 @@ def test_linear_chunk_and_segment_invariance(d):
     assert float(row_rel_l2(outs[(64, 64)], outs[(64, 1280)]).max()) < 1e-2
 
 
+CHUNK = gb.GF_IMPL_MFMA_CHUNK
+CHUNK_KERNELS = [(64, 64), (64, 128), (64, 256), (128, 64), (128, 128)]   # (d, chunk)
+CHUNK_SHAPES = [
+    # B, H, N, window, H0, segment_len in chunks (0: the planner's cut)
+    (1, 2, 1, 4, 1, 0),          # one token
+    (2, 3, 77, 8, 1, 0),         # shorter than any chunk
+    (1, 2, 64, 8, 0, 0),         # exactly one strip
+    (1, 3, 1100, 16, 0, 0),      # ragged: the last chunk holds fewer strips than a whole one
+    (1, 3, 1100, 16, 1, 1),      # one chunk per piece: every piece after the first starts from a carried state
+    (2, 2, 1537, 50, 0, 2),      # two chunks per piece, one token past a strip
+    (1, 130, 700, 8, 2, 0),      # more heads than compute units: one piece per head
+    (1, 2, 9000, 64, 0, 0),      # many pieces per head: the carried sums come from the prefix kernel
+]
+
+
+@pytest.mark.parametrize("kernel", CHUNK_KERNELS, ids=lambda k: f"d{k[0]}-C{k[1]}")
+@pytest.mark.parametrize("shape", CHUNK_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_linear_chunk_sizes_against_oracle(shape, kernel):
+    """Algorithm 1 by chunks of 64, 128 and 256 tokens (the general-chunk kernel; 64 is forced onto
+    it): the chunk size moves work between the masked in-chunk product and the carried state and
+    must not move the result."""
+    d, chunk = kernel
+    B, H, N, w, H0, seg = shape
+    q, k, v = synth(B, H, N, d, "bf16", 18)
+    ref = co.attn_fwd(q, k, v, w, H0, linear_form=co.LINEAR_RECURRENT)
+    got = run_gpu(q, k, v, "bf16", w, H0, impl=CHUNK if chunk == 64 else MFMA, chunk=chunk,
+                  segment_len=seg * chunk)
+    check(got, ref, "bf16", f"d={d} chunk={chunk} {shape}")
+
+
+@pytest.mark.parametrize("kernel", CHUNK_KERNELS, ids=lambda k: f"d{k[0]}-C{k[1]}")
+def test_linear_chunk_sizes_options_and_layout(kernel):
+    """Identity feature map with eps, the paper's [B, N, H, E] storage, outlier keys."""
+    d, chunk = kernel
+    B, H, N, w, H0 = 2, 3, 900, 40, 1
+    q, k, v = synth(B, H, N, d, "bf16", 19, q_prescaled=False, sigma=0.5, outlier_every=64, outlier_gain=8.0)
+    impl = CHUNK if chunk == 64 else MFMA
+    got = run_gpu(q, k, v, "bf16", w, H0, impl=impl, chunk=chunk, layout="bnhd")
+    check(got, co.attn_fwd(q, k, v, w, H0, linear_form=co.LINEAR_RECURRENT), "bf16", "outliers, bnhd")
+    q[:, H0:] = gi.round_to_bf16(np.abs(q[:, H0:]) + np.float32(0.125))
+    k[:, H0:] = gi.round_to_bf16(np.abs(k[:, H0:]) + np.float32(0.125))
+    got = run_gpu(q, k, v, "bf16", w, H0, impl=impl, chunk=chunk, phi=gb.GF_PHI_IDENTITY, eps=0.5)
+    ref = co.attn_fwd(q, k, v, w, H0, phi=co.PHI_IDENTITY, eps=0.5, linear_form=co.LINEAR_RECURRENT)
+    check(got, ref, "bf16", "identity map, eps")
+
+
+@pytest.mark.parametrize("chunk", [64, 128])
+def test_llm7b_chunk_sweep_sampled_heads(chunk):
+    """The headline layer with the chunk sizes of the benchmark contract's sweep that exist at
+    d = 128 (64 on the general-chunk kernel; 256 does not fit the LDS at this head size)."""
+    _full_size("llm7b", 6, chunk=chunk, impl=CHUNK if chunk == 64 else MFMA)
+
+
 # B, H (all linear), N, pieces the planner must choose, state-pass blocks with work
 LINEAR_PLAN_CASES = [
     (2, 64, 1050, 256, 128),    # two pieces of 9 chunks per head (the second holds a virtual chunk), summed whole
