@@ -40,21 +40,38 @@ template <int D> struct LbCfg {
   static constexpr int ZP = NT / D;                    // threads per column in the column sums
 };
 
-template <int D> struct LbSmem {
+// T' is a difference of two nearly equal terms and a gradient row sums it against phi with
+// signs: its rounding to one bf16 is the largest single error of these kernels.  It is therefore
+// kept as a pair, bf16(T') in `tp` and bf16(T' - bf16(T')) in `tl` (16 mantissa bits), and every
+// product with T' runs over both.  The forward scan does the same with S (`sm`, `sl`) for the
+// numerator, and sums both halves into the denominator, because c = dO.num / den^2 enters every
+// T' of its row; dv = S^T g in the reverse scan takes the one-bf16 S (its rows do not cancel).
+template <int D, int RS_> struct LbSmemBase {
   using C = LbCfg<D>;
+  static constexpr int RS = RS_;      // row stride of the carried sum's operand copy
   uint16_t fq[CH * C::R], fk[CH * C::R], v[CH * C::R], g[CH * C::R];
-  uint16_t st[D * C::R];              // bf16 copy of the carried sum, [feature][value]
+  uint16_t st[D * RS];                // bf16 copy of the carried sum, [feature][value]
   uint16_t sm[CH * SR], tp[CH * SR];  // S and T' (forward scan: [i][j]; reverse scan: [j][i])
+  uint16_t tl[CH * SR];               // low half of T'
   float z[D];                         // Z (forward scan) or Y (reverse scan)
   float zpart[C::ZP][D];
-  float rs[2][CH], dz[CH], pd[C::MT][CH], den[CH], cc[CH];
+  float dz[CH], den[CH], cc[CH];
+};
+template <int D> struct LbSmem : LbSmemBase<D, LbCfg<D>::R> {
+  uint16_t sl[CH * SR];               // low half of S
+  float rs[2][CH], pd[LbCfg<D>::MT][CH];
 };
 
 // the reverse scan also keeps dO itself: T' is formed as (dO.v)/den - c in fp32, exactly as the
-// forward scan forms c, so that the two cancel where they must (a token that only sees itself)
-template <int D> struct LbSmemKv : LbSmem<D> {
-  uint16_t dout[CH * LbCfg<D>::R];
+// forward scan forms c, so that the two cancel where they must (a token that only sees itself).
+// Its tiles fill the LDS of a compute unit at d = 128: the operand copy of the carried sum and
+// dO (read by rows only) take the narrower row stride there.
+template <int D> struct LbSmemKv : LbSmemBase<D, D + 8> {
+  static constexpr int RD = D + 8;
+  uint16_t dout[CH * RD];
 };
+static_assert(sizeof(LbSmemKv<128>) <= 160 * 1024 && sizeof(LbSmem<128>) <= 160 * 1024,
+              "one workgroup's tiles must fit the LDS of a compute unit");
 
 __device__ __forceinline__ float phi_elu1(float x) {
   return x > 0.f ? x + 1.f : __builtin_amdgcn_exp2f(x * kLog2e);
@@ -95,6 +112,16 @@ __device__ __forceinline__ void put4(uint16_t* p, float a, float b, float c, flo
   pk[0] = pack_bf16(a, b);
   pk[1] = pack_bf16(c, d);
   *reinterpret_cast<u32x2*>(p) = pk;
+}
+// the same four values as a bf16 pair: high halves to `hi`, bf16(x - bf16(x)) to `lo`
+__device__ __forceinline__ void put4_split(uint16_t* hi, uint16_t* lo, float a, float b, float c, float d) {
+  u32x2 ph, pl;
+  ph[0] = pack_bf16(a, b);
+  ph[1] = pack_bf16(c, d);
+  pl[0] = pack_bf16(a - bf16_lo(ph[0]), b - bf16_hi(ph[0]));
+  pl[1] = pack_bf16(c - bf16_lo(ph[1]), d - bf16_hi(ph[1]));
+  *reinterpret_cast<u32x2*>(hi) = ph;
+  *reinterpret_cast<u32x2*>(lo) = pl;
 }
 __device__ __forceinline__ void get4(const uint16_t* p, float (&f)[4]) {
   const u32x2 pk = *reinterpret_cast<const u32x2*>(p);
@@ -285,12 +312,17 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
           const int j = 32 * jt + 8 * g4 + 4 * lh + e;
           x[e] = j <= i ? s[4 * g4 + e] : 0.f;
         }
-        u32x2 pk;
+        u32x2 pk, pl;
         pk[0] = pack_bf16(x[0], x[1]);
         pk[1] = pack_bf16(x[2], x[3]);
-        rsum = dot2_ones_bf16(pk[0], rsum);   // the row sum of the rounded weights the products see
-        rsum = dot2_ones_bf16(pk[1], rsum);
+        pl[0] = pack_bf16(x[0] - bf16_lo(pk[0]), x[1] - bf16_hi(pk[0]));
+        pl[1] = pack_bf16(x[2] - bf16_lo(pk[1]), x[3] - bf16_hi(pk[1]));
+        rsum = dot2_ones_bf16(pk[0], rsum);   // the row sum of the weights the numerator sees:
+        rsum = dot2_ones_bf16(pk[1], rsum);   // both halves of the pair
+        rsum = dot2_ones_bf16(pl[0], rsum);
+        rsum = dot2_ones_bf16(pl[1], rsum);
         *reinterpret_cast<u32x2*>(&sm.sm[i * SR + 32 * jt + 8 * g4 + 4 * lh]) = pk;
+        *reinterpret_cast<u32x2*>(&sm.sl[i * SR + 32 * jt + 8 * g4 + 4 * lh]) = pl;
       }
       rsum = sum_over_halves(rsum);
       if (lh == 0) sm.rs[jt][i] = rsum;
@@ -329,8 +361,11 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
 #pragma unroll
       for (int r = 0; r < 16; ++r) nacc[r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < CH / 16; ++kk)
-        nacc = mfma32(col_op(sm.v + trl, R, 16 * kk, 32 * ot), row_op(sm.sm, SR, 32 * it2, kk, ln, lh), nacc);
+      for (int kk = 0; kk < CH / 16; ++kk) {
+        const bf16x8 vop = col_op(sm.v + trl, R, 16 * kk, 32 * ot);
+        nacc = mfma32(vop, row_op(sm.sm, SR, 32 * it2, kk, ln, lh), nacc);
+        nacc = mfma32(vop, row_op(sm.sl, SR, 32 * it2, kk, ln, lh), nacc);
+      }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
         nacc = mfma32(col_op(sm.st + trl, R, 16 * ks, 32 * ot), row_op(sm.fq, R, 32 * it2, ks, ln, lh), nacc);
@@ -371,7 +406,8 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
           const int j = 32 * jt + 8 * g4 + 4 * lh + e;
           x[e] = j <= i ? fmaf(traw[4 * g4 + e], inv, -ci) : 0.f;
         }
-        put4(&sm.tp[i * SR + 32 * jt + 8 * g4 + 4 * lh], x[0], x[1], x[2], x[3]);
+        put4_split(&sm.tp[i * SR + 32 * jt + 8 * g4 + 4 * lh], &sm.tl[i * SR + 32 * jt + 8 * g4 + 4 * lh],
+                   x[0], x[1], x[2], x[3]);
       }
     }
 #pragma unroll
@@ -402,8 +438,11 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_q_mfma_kernel(BwdA
 #pragma unroll
       for (int r = 0; r < 16; ++r) dacc[r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < CH / 16; ++kk)
-        dacc = mfma32(col_op(sm.fk + trl, R, 16 * kk, 32 * ot), row_op(sm.tp, SR, 32 * it2, kk, ln, lh), dacc);
+      for (int kk = 0; kk < CH / 16; ++kk) {
+        const bf16x8 kop = col_op(sm.fk + trl, R, 16 * kk, 32 * ot);
+        dacc = mfma32(kop, row_op(sm.tp, SR, 32 * it2, kk, ln, lh), dacc);
+        dacc = mfma32(kop, row_op(sm.tl, SR, 32 * it2, kk, ln, lh), dacc);
+      }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
         dacc = mfma32(row_op(sm.st, R, 32 * ot, ks, ln, lh), row_op(sm.g, R, 32 * it2, ks, ln, lh), dacc);
@@ -493,6 +532,8 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
   const int cb = nchunks - a.lin_bounds[blockIdx.z + 1], ce = nchunks - a.lin_bounds[blockIdx.z];
   if (cb >= ce) return;
   const int trl = lds_operand_tr_lane_offset(R, lane) + 8 * lh * R;
+  constexpr int RS = LbSmemKv<D>::RS, RD = LbSmemKv<D>::RD;   // strides of the carried-sum copy and of dO
+  const int trl_s = lds_operand_tr_lane_offset(RS, lane) + 8 * lh * RS;
 
   u32x4 rq[PCS], rk[PCS], rv[PCS], rdo[PCS];
   float rden[PCS];
@@ -532,7 +573,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
       if (full) {
         *reinterpret_cast<u32x4*>(&sm.fk[row * R + col]) = valid ? rk[i] : kZero4;
         *reinterpret_cast<u32x4*>(&sm.v[row * R + col]) = valid ? rv[i] : kZero4;
-        *reinterpret_cast<u32x4*>(&sm.dout[row * R + col]) = valid ? rdo[i] : kZero4;
+        *reinterpret_cast<u32x4*>(&sm.dout[row * RD + col]) = valid ? rdo[i] : kZero4;
       }
     }
     if (tid < CH) {
@@ -547,7 +588,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
   for (int u = 0; u < TPW; ++u)
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[u][r] = 0.f;
-  for (int i = tid; i < D * R / 2; i += NT) reinterpret_cast<uint32_t*>(sm.st)[i] = 0u;
+  for (int i = tid; i < D * RS / 2; i += NT) reinterpret_cast<uint32_t*>(sm.st)[i] = 0u;
   if (tid < D) sm.z[tid] = 0.f;
 
   // Light rounds, two chunks at a time (the chunks behind the segment only feed the carried
@@ -626,7 +667,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
         const int stile = wave * TPW + u, vt = stile / MT, ft = stile % MT;
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4)
-          put4(&sm.st[(32 * ft + ln) * R + 32 * vt + 8 * g4 + 4 * lh], sacc[u][4 * g4 + 0], sacc[u][4 * g4 + 1],
+          put4(&sm.st[(32 * ft + ln) * RS + 32 * vt + 8 * g4 + 4 * lh], sacc[u][4 * g4 + 0], sacc[u][4 * g4 + 1],
                sacc[u][4 * g4 + 2], sacc[u][4 * g4 + 3]);
       }
     }
@@ -671,7 +712,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
       for (int r = 0; r < 16; ++r) tr[r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        tr = mfma32(row_op(sm.dout, R, 32 * it, ks, ln, lh), row_op(sm.v, R, 32 * jt, ks, ln, lh), tr);
+        tr = mfma32(row_op(sm.dout, RD, 32 * it, ks, ln, lh), row_op(sm.v, R, 32 * jt, ks, ln, lh), tr);
       const int j = 32 * jt + ln;
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
@@ -684,7 +725,8 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
           const int i = 32 * it + 8 * g4 + 4 * lh + e;
           x[e] = j <= i ? fmaf(tr[4 * g4 + e], rv4[e], -cv[e]) : 0.f;
         }
-        put4(&sm.tp[j * SR + 32 * it + 8 * g4 + 4 * lh], x[0], x[1], x[2], x[3]);
+        put4_split(&sm.tp[j * SR + 32 * it + 8 * g4 + 4 * lh], &sm.tl[j * SR + 32 * it + 8 * g4 + 4 * lh],
+                   x[0], x[1], x[2], x[3]);
       }
     }
     {
@@ -706,17 +748,20 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
     for (int r = 0; r < 16; ++r) { kacc[r] = 0.f; vacc[r] = 0.f; }
     if (full) {
 #pragma unroll
-    for (int kk = 0; kk < CH / 16; ++kk)
-      kacc = mfma32(col_op(sm.fq + trl, R, 16 * kk, 32 * ot), row_op(sm.tp, SR, 32 * jt2, kk, ln, lh), kacc);
+    for (int kk = 0; kk < CH / 16; ++kk) {
+      const bf16x8 qop = col_op(sm.fq + trl, R, 16 * kk, 32 * ot);
+      kacc = mfma32(qop, row_op(sm.tp, SR, 32 * jt2, kk, ln, lh), kacc);
+      kacc = mfma32(qop, row_op(sm.tl, SR, 32 * jt2, kk, ln, lh), kacc);
+    }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-      kacc = mfma32(row_op(sm.st, R, 32 * ot, ks, ln, lh), row_op(sm.v, R, 32 * jt2, ks, ln, lh), kacc);
+      kacc = mfma32(row_op(sm.st, RS, 32 * ot, ks, ln, lh), row_op(sm.v, R, 32 * jt2, ks, ln, lh), kacc);
 #pragma unroll
     for (int kk = 0; kk < CH / 16; ++kk)
       vacc = mfma32(col_op(sm.g + trl, R, 16 * kk, 32 * ot), row_op(sm.sm, SR, 32 * jt2, kk, ln, lh), vacc);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-      vacc = mfma32(col_op(sm.st + trl, R, 16 * ks, 32 * ot), row_op(sm.fk, R, 32 * jt2, ks, ln, lh), vacc);
+      vacc = mfma32(col_op(sm.st + trl_s, RS, 16 * ks, 32 * ot), row_op(sm.fk, R, 32 * jt2, ks, ln, lh), vacc);
     }  // full
 #pragma unroll
     for (int u = 0; u < TPW; ++u) {
@@ -751,7 +796,7 @@ __global__ __launch_bounds__(LbCfg<D>::NT, 1) void linear_bwd_kv_mfma_kernel(Bwd
       const int stile = wave * TPW + u, vt = stile / MT, ft = stile % MT;
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4)
-        put4(&sm.st[(32 * ft + ln) * R + 32 * vt + 8 * g4 + 4 * lh], sacc[u][4 * g4 + 0], sacc[u][4 * g4 + 1],
+        put4(&sm.st[(32 * ft + ln) * RS + 32 * vt + 8 * g4 + 4 * lh], sacc[u][4 * g4 + 0], sacc[u][4 * g4 + 1],
              sacc[u][4 * g4 + 2], sacc[u][4 * g4 + 3]);
     }
     }

@@ -740,31 +740,25 @@ def run_bwd(q, k, v, dout, dtype, w, H0, layout="bhnd", **kw):
     return tuple(to_host(t) for t in (dq, dk, dv))
 
 
-BF16_BWD_MATRIX_CORE = 4e-2   # per-row bar of the matrix-core backward kernels, see check_grad
-
-
 def check_grad(got, ref, dtype, what, dout, impl=None):
-    """fp32: max-abs error <= 1e-5 times the larger of the tensor's largest gradient magnitude
-    and a typical dO row norm (a gradient entry is a difference of terms of the size
-    |dO_i||v_j||k_j|, and fp32 rounding acts on those terms, not on the difference).  bf16: per-row L2 error <= 2e-2
+    """fp32: max-abs error <= 1e-5 times the tensor's largest gradient magnitude (at least 1): the
+    forward pass's bar taken relative to the size of the numbers, since gradient entries reach
+    the tens here and one fp32 ulp of 60 is already 4e-6.  bf16: per-row L2 error <= 2e-2
     of the row's norm, where rows that vanish by cancellation (the gradient with respect to q of
     a token that sees one key is exactly 0) are measured against 1 % of a typical dO row instead
-    of against themselves.  The matrix-core kernels (bf16 storage, impl other than SCALAR) round
-    every operand of their products to bf16, and a gradient row is a sum of signed terms: rows
-    whose terms cancel come out up to 3-4 % off whatever the kernel does
-    (tests/test_backward_rounding_model.py shows it on the CPU), so their per-row bar is 4e-2."""
+    of against themselves.  The same bar holds for the plain-FMA and the matrix-core kernels (the
+    latter carry the two operands whose rounding would break it as bf16 pairs;
+    tests/test_backward_rounding_model.py shows on the CPU which and why)."""
     assert np.isfinite(got).all(), f"non-finite gradient {what}"
     if dtype == "f32":
-        rown = float(np.median(np.sqrt((dout.astype(np.float64) ** 2).sum(-1))))
-        err, scale = max_abs(got, ref), max(1.0, float(np.abs(ref).max()), rown)
+        err, scale = max_abs(got, ref), max(1.0, float(np.abs(ref).max()))
         assert err <= F32_MAX_ABS * scale, f"{what}: max-abs {err:.3e} at scale {scale:.3g}"
     else:
         err = np.sqrt(((got - ref) ** 2).sum(-1))
         floor = 1e-2 * float(np.median(np.sqrt((dout.astype(np.float64) ** 2).sum(-1))))
         den = np.maximum(np.sqrt((ref ** 2).sum(-1)), floor)
         worst = float((err / den).max())
-        bar = BF16_ROW_REL_L2 if impl == SCALAR else BF16_BWD_MATRIX_CORE
-        assert worst <= bar, f"{what}: worst row rel-L2 {worst:.3e}"
+        assert worst <= BF16_ROW_REL_L2, f"{what}: worst row rel-L2 {worst:.3e}"
         # the average row is well inside the forward bar either way
         assert float((err / den).mean()) <= 0.5 * BF16_ROW_REL_L2, f"{what}: mean row rel-L2"
 
