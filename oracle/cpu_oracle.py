@@ -59,6 +59,12 @@ def lib():
         L.gformer_oracle_linear_head_bwd_f64.argtypes = [_dp] * 7 + [ctypes.c_int] * 3 + [ctypes.c_double]
         L.gformer_oracle_bwd_f64.restype = ctypes.c_int
         L.gformer_oracle_bwd_f64.argtypes = [_dp] * 7 + [ctypes.c_int] * 7 + [ctypes.c_double] * 2
+        for name, like in (("gformer_oracle_windowed_head_bidir_bwd_f64", L.gformer_oracle_windowed_head_bwd_f64),
+                           ("gformer_oracle_linear_head_bidir_bwd_f64", L.gformer_oracle_linear_head_bwd_f64),
+                           ("gformer_oracle_bwd_bidir_f64", L.gformer_oracle_bwd_f64)):
+            f = getattr(L, name)
+            f.restype = ctypes.c_int
+            f.argtypes = like.argtypes
         L.gformer_oracle_max_threads.restype = ctypes.c_int
         L.gformer_oracle_random_features_f64.restype = ctypes.c_int
         L.gformer_oracle_random_features_f64.argtypes = [_dp, _dp, _dp, ctypes.c_long,
@@ -118,12 +124,15 @@ def attn_fwd(q, k, v, window, n_sparse_heads, phi=PHI_ELU1, softmax_scale=1.0, e
     return out
 
 
-def windowed_head_bwd(q, k, v, dout, window, scale=1.0):
-    """Gradients (dq, dk, dv) of a causal windowed head, [N, d] each, for output gradient dout."""
+def windowed_head_bwd(q, k, v, dout, window, scale=1.0, bidirectional=False):
+    """Gradients (dq, dk, dv) of a windowed head (causal window, or the window centred on the
+    token), [N, d] each, for output gradient dout."""
     q, qp = _c(q); k, kp = _c(k); v, vp = _c(v); dout, dop = _c(dout)
     N, d = q.shape
     dq, dk, dv = (np.empty((N, d), np.float64) for _ in range(3))
-    rc = lib().gformer_oracle_windowed_head_bwd_f64(qp, kp, vp, dop, dq.ctypes.data_as(_dp),
+    fn = lib().gformer_oracle_windowed_head_bidir_bwd_f64 if bidirectional else \
+        lib().gformer_oracle_windowed_head_bwd_f64
+    rc = fn(qp, kp, vp, dop, dq.ctypes.data_as(_dp),
                                                     dk.ctypes.data_as(_dp), dv.ctypes.data_as(_dp),
                                                     N, d, int(window), float(scale))
     if rc:
@@ -131,12 +140,15 @@ def windowed_head_bwd(q, k, v, dout, window, scale=1.0):
     return dq, dk, dv
 
 
-def linear_head_bwd(q, k, v, dout, phi=PHI_ELU1, eps=0.0):
-    """Gradients (dq, dk, dv) of a causal linear head, [N, d] each, for output gradient dout."""
+def linear_head_bwd(q, k, v, dout, phi=PHI_ELU1, eps=0.0, bidirectional=False):
+    """Gradients (dq, dk, dv) of a linear head (causal, or over all keys), [N, d] each, for output
+    gradient dout."""
     q, qp = _c(q); k, kp = _c(k); v, vp = _c(v); dout, dop = _c(dout)
     N, d = q.shape
     dq, dk, dv = (np.empty((N, d), np.float64) for _ in range(3))
-    rc = lib().gformer_oracle_linear_head_bwd_f64(qp, kp, vp, dop, dq.ctypes.data_as(_dp),
+    fn = lib().gformer_oracle_linear_head_bidir_bwd_f64 if bidirectional else \
+        lib().gformer_oracle_linear_head_bwd_f64
+    rc = fn(qp, kp, vp, dop, dq.ctypes.data_as(_dp),
                                                   dk.ctypes.data_as(_dp), dv.ctypes.data_as(_dp),
                                                   N, d, int(phi), float(eps))
     if rc:
@@ -144,12 +156,14 @@ def linear_head_bwd(q, k, v, dout, phi=PHI_ELU1, eps=0.0):
     return dq, dk, dv
 
 
-def attn_bwd(q, k, v, dout, window, n_sparse_heads, phi=PHI_ELU1, softmax_scale=1.0, eps=0.0):
-    """Backward of the causal layer over dense [B, H, N, d]: returns (dq, dk, dv)."""
+def attn_bwd(q, k, v, dout, window, n_sparse_heads, phi=PHI_ELU1, softmax_scale=1.0, eps=0.0,
+             bidirectional=False):
+    """Backward of the layer (causal or bidirectional) over dense [B, H, N, d]: (dq, dk, dv)."""
     q, qp = _c(q); k, kp = _c(k); v, vp = _c(v); dout, dop = _c(dout)
     B, H, N, d = q.shape
     dq, dk, dv = (np.empty((B, H, N, d), np.float64) for _ in range(3))
-    rc = lib().gformer_oracle_bwd_f64(qp, kp, vp, dop, dq.ctypes.data_as(_dp), dk.ctypes.data_as(_dp),
+    fn = lib().gformer_oracle_bwd_bidir_f64 if bidirectional else lib().gformer_oracle_bwd_f64
+    rc = fn(qp, kp, vp, dop, dq.ctypes.data_as(_dp), dk.ctypes.data_as(_dp),
                                       dv.ctypes.data_as(_dp), B, H, N, d, int(window),
                                       int(n_sparse_heads), int(phi), float(softmax_scale), float(eps))
     if rc:

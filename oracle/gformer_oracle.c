@@ -558,6 +558,133 @@ int gformer_oracle_bwd_f64(const double *q, const double *k, const double *v, co
     return rc;
 }
 
+/* ---- backward pass of the bidirectional variant -------------------------------------------
+ * The same derivatives with the other index sets: the windowed head's softmax runs over the w
+ * tokens centred on token i (cut at the ends, as in gformer_oracle_windowed_head_bidir_f64), the
+ * linear head's sums run over ALL j (section II-B without the causal restriction). */
+int gformer_oracle_windowed_head_bidir_bwd_f64(const double *q, const double *k, const double *v,
+                                               const double *dout, double *dq, double *dk, double *dv,
+                                               int N, int d, int window, double scale)
+{
+    if (N < 0 || d < 1 || window < 1) return 1;
+    memset(dq, 0, sizeof(double) * (size_t)N * d);
+    memset(dk, 0, sizeof(double) * (size_t)N * d);
+    memset(dv, 0, sizeof(double) * (size_t)N * d);
+    double *p = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+    double *dp = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+    if (!p || !dp) { free(p); free(dp); return 2; }
+    const long left = window / 2, right = (long)window - 1 - left;
+    for (int i = 0; i < N; ++i) {
+        long lo = (long)i - left, hi = (long)i + right;
+        if (lo < 0) lo = 0;
+        if (hi > N - 1) hi = N - 1;
+        const long cnt = hi - lo + 1;
+        double m = -INFINITY;
+        for (long t = 0; t < cnt; ++t) {
+            double s = 0.0;
+            for (int c = 0; c < d; ++c) s += q[(size_t)i * d + c] * k[(size_t)(lo + t) * d + c];
+            p[t] = s * scale;
+            if (p[t] > m) m = p[t];
+        }
+        double l = 0.0;
+        for (long t = 0; t < cnt; ++t) { p[t] = exp(p[t] - m); l += p[t]; }
+        double mean_dp = 0.0;
+        for (long t = 0; t < cnt; ++t) {
+            p[t] /= l;
+            double x = 0.0;
+            for (int c = 0; c < d; ++c) x += dout[(size_t)i * d + c] * v[(size_t)(lo + t) * d + c];
+            dp[t] = x;
+            mean_dp += p[t] * x;
+        }
+        for (long t = 0; t < cnt; ++t) {
+            const long j = lo + t;
+            const double ds = p[t] * (dp[t] - mean_dp);
+            for (int c = 0; c < d; ++c) {
+                dv[(size_t)j * d + c] += p[t] * dout[(size_t)i * d + c];
+                dq[(size_t)i * d + c] += scale * ds * k[(size_t)j * d + c];
+                dk[(size_t)j * d + c] += scale * ds * q[(size_t)i * d + c];
+            }
+        }
+    }
+    free(p); free(dp);
+    return 0;
+}
+
+/* Non-causal linear head: a_ij = phi(q_i).phi(k_j) for every j, den_i = sum_j a_ij + eps,
+ * o_i = sum_j a_ij v_j / den_i; the same three lines as the causal head, summed over all j. */
+int gformer_oracle_linear_head_bidir_bwd_f64(const double *q, const double *k, const double *v,
+                                             const double *dout, double *dq, double *dk, double *dv,
+                                             int N, int d, int phi, double eps)
+{
+    if (N < 0 || d < 1) return 1;
+    const size_t nd = (size_t)N * d;
+    double *fq = (double *)malloc(sizeof(double) * (nd ? nd : 1));
+    double *fk = (double *)malloc(sizeof(double) * (nd ? nd : 1));
+    double *a = (double *)malloc(sizeof(double) * (size_t)(N ? N : 1));
+    double *o = (double *)malloc(sizeof(double) * (size_t)d);
+    if (!fq || !fk || !a || !o) { free(fq); free(fk); free(a); free(o); return 2; }
+    for (size_t x = 0; x < nd; ++x) { fq[x] = feature_map(q[x], phi); fk[x] = feature_map(k[x], phi); }
+    memset(dq, 0, sizeof(double) * nd);
+    memset(dk, 0, sizeof(double) * nd);
+    memset(dv, 0, sizeof(double) * nd);
+    for (int i = 0; i < N; ++i) {
+        double den = eps;
+        for (int c = 0; c < d; ++c) o[c] = 0.0;
+        for (int j = 0; j < N; ++j) {
+            double s = 0.0;
+            for (int c = 0; c < d; ++c) s += fq[(size_t)i * d + c] * fk[(size_t)j * d + c];
+            a[j] = s;
+            den += s;
+            for (int c = 0; c < d; ++c) o[c] += s * v[(size_t)j * d + c];
+        }
+        double do_o = 0.0;
+        for (int c = 0; c < d; ++c) { o[c] /= den; do_o += dout[(size_t)i * d + c] * o[c]; }
+        for (int j = 0; j < N; ++j) {
+            double do_v = 0.0;
+            for (int c = 0; c < d; ++c) do_v += dout[(size_t)i * d + c] * v[(size_t)j * d + c];
+            const double da = (do_v - do_o) / den;
+            for (int c = 0; c < d; ++c) {
+                dv[(size_t)j * d + c] += a[j] * dout[(size_t)i * d + c] / den;
+                dq[(size_t)i * d + c] += da * fk[(size_t)j * d + c];   /* still d/dphi(q) */
+                dk[(size_t)j * d + c] += da * fq[(size_t)i * d + c];   /* still d/dphi(k) */
+            }
+        }
+    }
+    for (size_t x = 0; x < nd; ++x) {
+        dq[x] *= feature_map_slope(q[x], phi);
+        dk[x] *= feature_map_slope(k[x], phi);
+    }
+    free(fq); free(fk); free(a); free(o);
+    return 0;
+}
+
+/* The bidirectional layer: heads [0, H0) windowed, [H0, H) linear, dense [B, H, N, d]. */
+int gformer_oracle_bwd_bidir_f64(const double *q, const double *k, const double *v, const double *dout,
+                                 double *dq, double *dk, double *dv, int B, int H, int N, int d,
+                                 int window, int n_sparse_heads, int phi, double scale, double eps)
+{
+    if (B < 0 || H < 0 || n_sparse_heads < 0 || n_sparse_heads > H) return 1;
+    int rc = 0;
+    const long heads = (long)B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long x = 0; x < heads; ++x) {
+        const int h = (int)(x % H);
+        const size_t off = (size_t)x * N * d;
+        int r;
+        if (h < n_sparse_heads)
+            r = gformer_oracle_windowed_head_bidir_bwd_f64(q + off, k + off, v + off, dout + off, dq + off,
+                                                           dk + off, dv + off, N, d, window, scale);
+        else
+            r = gformer_oracle_linear_head_bidir_bwd_f64(q + off, k + off, v + off, dout + off, dq + off,
+                                                         dk + off, dv + off, N, d, phi, eps);
+        if (r) {
+#pragma omp critical
+            rc = r;
+        }
+    }
+    return rc;
+}
+
 int gformer_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -407,19 +407,24 @@ gf_status attn_forward(const void* q, const void* k, const void* v, void* out, v
     std::lock_guard<std::mutex> lock(g_enqueue_mutex);
     SideStream* side = nullptr;
     if (win && lin && p->overlap) e = side_stream_for_current_device(&side);
+    bool forked = false;
     if (side && e == hipSuccess) {
       // fork: the windowed heads wait for what is already in `s`, then run beside the linear ones
       e = hipEventRecord(side->fork, s);
       if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
+      forked = e == hipSuccess;
       if (e == hipSuccess) e = launch_windowed(side->stream);
-      if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
     }
     // The read-out kernel wants every compute unit at once (one piece each), so only the state
     // pass, whose small workgroups pack two to a unit, shares the chip with the windowed heads.
     if ((mask & GF_LAUNCH_LINEAR_STATE) && e == hipSuccess) e = launch_linear_state_mfma(a, s);
-    if (side) {
-      if (e == hipSuccess) e = hipStreamWaitEvent(s, side->join, 0);  // join
-    } else if (win && e == hipSuccess) {
+    if (forked) {
+      // join, also after a failed launch: a side stream left waiting on the fork would break a
+      // capture in progress and leave `s` unordered against what did get enqueued
+      const hipError_t j1 = hipEventRecord(side->join, side->stream);
+      const hipError_t j2 = j1 == hipSuccess ? hipStreamWaitEvent(s, side->join, 0) : j1;
+      if (e == hipSuccess) e = j2;
+    } else if (win && !side && e == hipSuccess) {
       e = launch_windowed(s);
     }
     if ((mask & GF_LAUNCH_LINEAR_MAIN) && e == hipSuccess)
@@ -632,11 +637,17 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
     if (both && p->overlap) e = side_stream_for_current_device(&side);
     if (side && e == hipSuccess) {
       e = hipEventRecord(side->fork, stream);
-      if (e == hipSuccess) e = launch_linear_backward_mfma(a, stream);
-      if (e == hipSuccess) e = hipStreamWaitEvent(side->stream, side->fork, 0);
-      if (e == hipSuccess) e = launch_windowed_backward_mfma(a, side->stream);
-      if (e == hipSuccess) e = hipEventRecord(side->join, side->stream);
-      if (e == hipSuccess) e = hipStreamWaitEvent(stream, side->join, 0);
+      if (e == hipSuccess) {
+        e = launch_linear_backward_mfma(a, stream);
+        hipError_t f = hipStreamWaitEvent(side->stream, side->fork, 0);
+        if (f == hipSuccess) {
+          if (e == hipSuccess) e = launch_windowed_backward_mfma(a, side->stream);
+          // join whatever happened after the fork
+          f = hipEventRecord(side->join, side->stream);
+          if (f == hipSuccess) f = hipStreamWaitEvent(stream, side->join, 0);
+        }
+        if (e == hipSuccess) e = f;
+      }
     } else if (e == hipSuccess) {
       e = launch_windowed_backward_mfma(a, stream);
       if (e == hipSuccess) e = launch_linear_backward_mfma(a, stream);

@@ -903,3 +903,104 @@ def test_backward_is_linear_in_the_output_gradient_and_splits_by_head():
         ref = co.linear_head_bwd(q[bb, 2], k[bb, 2], v[bb, 2], d1[bb, 2], eps=0.1)
         for x, y in zip(a, ref):
             assert max_abs(x[bb, 2], y) == 0
+
+
+# ---------------------------------------------------------------------------------------
+# backward pass of the bidirectional variant
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N,d,w", [(9, 3, 4), (7, 4, 1), (8, 2, 5), (6, 2, 50)])
+def test_bidirectional_windowed_backward_is_the_derivative_of_the_forward(N, d, w):
+    """Central differences of the (separately pinned) bidirectional forward oracle."""
+    q, k, v, do = (_rand((N, d), 400 + s) for s in range(4))
+    f = lambda a, b, c: co.windowed_head(a, b, c, w, 0.7, bidirectional=True)
+    dq, dk, dv = co.windowed_head_bwd(q, k, v, do, w, 0.7, bidirectional=True)
+    assert max_abs(dq, _central_differences(lambda x: f(x, k, v), q, do)) <= 1e-7
+    assert max_abs(dk, _central_differences(lambda x: f(q, x, v), k, do)) <= 1e-7
+    assert max_abs(dv, _central_differences(lambda x: f(q, k, x), v, do)) <= 1e-7
+
+
+@pytest.mark.parametrize("phi", [co.PHI_ELU1, co.PHI_IDENTITY])
+@pytest.mark.parametrize("N,d", [(8, 3), (5, 4)])
+def test_bidirectional_linear_backward_is_the_derivative_of_the_forward(N, d, phi):
+    q, k, v, do = (_rand((N, d), 410 + s) for s in range(4))
+    if phi == co.PHI_IDENTITY:
+        q, k = np.abs(q) + 0.5, np.abs(k) + 0.5
+    eps = 0.25
+    f = lambda a, b, c: co.linear_head(a, b, c, phi=phi, eps=eps, bidirectional=True)
+    dq, dk, dv = co.linear_head_bwd(q, k, v, do, phi=phi, eps=eps, bidirectional=True)
+    assert max_abs(dq, _central_differences(lambda x: f(x, k, v), q, do)) <= 1e-7
+    assert max_abs(dk, _central_differences(lambda x: f(q, x, v), k, do)) <= 1e-7
+    assert max_abs(dv, _central_differences(lambda x: f(q, k, x), v, do)) <= 1e-7
+
+
+def test_bidirectional_backward_against_library_autograd():
+    """The two definitions written with library tensor routines (softmax under a centred band
+    mask; state first for the linear head) and differentiated by the library's reverse mode."""
+    N, d = 150, 8
+    q, k, v, do = (torch.tensor(_rand((N, d), 420 + s)) for s in range(4))
+    idx = torch.arange(N)
+    for w in (37, 38, 1, 400):       # odd, even (one more on the left), self only, everything
+        left, right = w // 2, w - 1 - w // 2
+        band = (idx[None, :] >= idx[:, None] - left) & (idx[None, :] <= idx[:, None] + right)
+        tq, tk, tv = (t.clone().requires_grad_(True) for t in (q, k, v))
+        o = torch.softmax(((tq @ tk.T) * 0.3).masked_fill(~band, float("-inf")), dim=-1) @ tv
+        (o * do).sum().backward()
+        dq, dk, dv = co.windowed_head_bwd(q.numpy(), k.numpy(), v.numpy(), do.numpy(), w, 0.3, bidirectional=True)
+        assert max_abs(dq, tq.grad.numpy()) <= 1e-12 and max_abs(dk, tk.grad.numpy()) <= 1e-12, w
+        assert max_abs(dv, tv.grad.numpy()) <= 1e-12, w
+    tq, tk, tv = (t.clone().requires_grad_(True) for t in (q, k, v))
+    fq, fk = torch.nn.functional.elu(tq) + 1, torch.nn.functional.elu(tk) + 1
+    o = (fq @ (fk.T @ tv)) / ((fq @ fk.sum(0))[:, None] + 0.125)      # section II-B, state first
+    (o * do).sum().backward()
+    dq, dk, dv = co.linear_head_bwd(q.numpy(), k.numpy(), v.numpy(), do.numpy(), eps=0.125, bidirectional=True)
+    assert max_abs(dq, tq.grad.numpy()) <= 1e-11 and max_abs(dk, tk.grad.numpy()) <= 1e-11
+    assert max_abs(dv, tv.grad.numpy()) <= 1e-11
+    # a window that covers everything is full softmax attention: the library's fused routine
+    tq, tk, tv = (t.clone().requires_grad_(True) for t in (q, k, v))
+    o = torch.nn.functional.scaled_dot_product_attention(tq[None], tk[None], tv[None], scale=0.3)[0]
+    (o * do).sum().backward()
+    dq, dk, dv = co.windowed_head_bwd(q.numpy(), k.numpy(), v.numpy(), do.numpy(), 2 * N, 0.3, bidirectional=True)
+    assert max_abs(dq, tq.grad.numpy()) <= 1e-12 and max_abs(dk, tk.grad.numpy()) <= 1e-12
+    assert max_abs(dv, tv.grad.numpy()) <= 1e-12
+
+
+def test_bidirectional_backward_closed_forms_and_relations():
+    N, d = 40, 6
+    q, k, v, do = (_rand((N, d), 430 + s) for s in range(4))
+    # windows of one and two tokens coincide with the causal window (nothing to the right)
+    for w in (1, 2):
+        for a, b in zip(co.windowed_head_bwd(q, k, v, do, w, 0.5, bidirectional=True),
+                        co.windowed_head_bwd(q, k, v, do, w, 0.5)):
+            assert max_abs(a, b) == 0
+    # the linear head does not know the order of the (key, value) pairs: permuting them permutes
+    # dk and dv and leaves dq alone
+    perm = np.random.default_rng(7).permutation(N)
+    a = co.linear_head_bwd(q, k, v, do, eps=0.1, bidirectional=True)
+    b = co.linear_head_bwd(q, k[perm], v[perm], do, eps=0.1, bidirectional=True)
+    assert max_abs(a[0], b[0]) <= 1e-12 and max_abs(a[1][perm], b[1]) <= 1e-12 and max_abs(a[2][perm], b[2]) <= 1e-12
+    # only the last token's output gets a gradient: the last causal row sees every key too
+    last = np.zeros_like(do)
+    last[-1] = do[-1]
+    for x, y in zip(co.linear_head_bwd(q, k, v, last, eps=0.1, bidirectional=True),
+                    co.linear_head_bwd(q, k, v, last, eps=0.1)):
+        assert max_abs(x, y) <= 1e-13
+    # scale invariance of the ratio (identity map, eps = 0): sum_j k_j.dk_j = 0, q_i.dq_i = 0
+    qp, kp = np.abs(q) + 0.5, np.abs(k) + 0.5
+    dq, dk, dv = co.linear_head_bwd(qp, kp, v, do, phi=co.PHI_IDENTITY, bidirectional=True)
+    assert abs((kp * dk).sum()) <= 1e-11 and max_abs((qp * dq).sum(axis=1), np.zeros(N)) <= 1e-11
+    # weights sum to one: with a constant added to every value nothing but dv could change, and
+    # sum_j dv_j = sum_i dO_i (eps = 0)
+    dq2, dk2, dv2 = co.linear_head_bwd(q, k, v + 3.0, do, bidirectional=True)
+    dq1, dk1, dv1 = co.linear_head_bwd(q, k, v, do, bidirectional=True)
+    assert max_abs(dq1, dq2) <= 1e-11 and max_abs(dk1, dk2) <= 1e-11 and max_abs(dv1, dv2) <= 1e-13
+    assert max_abs(dv1.sum(axis=0), do.sum(axis=0)) <= 1e-12
+    # the layer driver places heads like the forward one
+    B, H, w, H0 = 2, 3, 7, 1
+    q4, k4, v4, d4 = (_rand((B, H, 30, 4), 440 + s) for s in range(4))
+    full = co.attn_bwd(q4, k4, v4, d4, w, H0, softmax_scale=0.5, eps=0.1, bidirectional=True)
+    for bb in range(B):
+        for x, y in zip(full, co.windowed_head_bwd(q4[bb, 0], k4[bb, 0], v4[bb, 0], d4[bb, 0], w, 0.5, bidirectional=True)):
+            assert max_abs(x[bb, 0], y) == 0
+        for x, y in zip(full, co.linear_head_bwd(q4[bb, 2], k4[bb, 2], v4[bb, 2], d4[bb, 2], eps=0.1, bidirectional=True)):
+            assert max_abs(x[bb, 2], y) == 0
