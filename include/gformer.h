@@ -222,25 +222,31 @@ gf_status gformer_attn_prefill(const void* q, const void* k, const void* v, void
                                const gformer_params* p, void* workspace, size_t workspace_bytes,
                                void* hip_stream);
 
-/* Backward pass of the causal layer: the gradients of a scalar loss with respect to Q, K and V
- * from its gradient with respect to the layer's output.  The paper trains its models (sections
- * IV-B to IV-D) but prints no backward formulas: these are the derivatives of section III-B,
- * Eq. 1 (softmax over the causal window) and of section II-B's ratio with Algorithm 1's running
- * sums, the feature map's slope included.
+/* Backward pass of the layer, causal or bidirectional (params.bidirectional): the gradients of a
+ * scalar loss with respect to Q, K and V from its gradient with respect to the layer's output.
+ * The paper trains its models (sections IV-B to IV-D) but prints no backward formulas: these are
+ * the derivatives of section III-B, Eq. 1 (softmax over the window) and of section II-B's ratio
+ * with Algorithm 1's running sums (bidirectional: with the sums over all keys), the feature map's
+ * slope included.
  *   q, k, v : device, as for gformer_attn_fwd, read
  *   dout    : device, gradient with respect to the layer's output, layout of o_stride, read
  *             (the forward result itself is not an input: what the derivatives need of it is
  *             recomputed in fp32, since the stored result is rounded to the element type)
  *   dq, dk, dv : device, written; laid out like q, k, v (their strides); must not overlap any
  *             input or each other
- *   workspace : device, gformer_attn_bwd_workspace_bytes bytes (8 per token and head), 256-byte
- *             aligned; scratch for per-row softmax statistics / denominators
+ *   workspace : device, gformer_attn_bwd_workspace_bytes bytes, 256-byte aligned: 8 bytes per
+ *             token and head (per-row softmax statistics / denominators), rounded up to 256,
+ *             plus, for a bidirectional call, two (d*d + d) fp32 sums per linear head
  * Kernels: a bf16 call runs on the matrix cores (params.impl GF_IMPL_AUTO or GF_IMPL_MFMA: bf16
- * products, fp32 accumulation, softmax statistics, denominators and carried sums in fp32);
+ * products, fp32 accumulation, softmax statistics, denominators and carried sums in fp32; the
+ * two operands of the linear heads whose rounding would cost more than the bf16 mode's 2e-2 per
+ * row, T' and the in-chunk weights of the numerator, travel as bf16 pairs);
  * GF_IMPL_SCALAR and every fp32 call run on plain-FMA kernels (fp32 arithmetic on either
- * storage type).  GF_IMPL_MFMA with fp32 storage, GF_IMPL_MFMA_BLOCKED, GF_IMPL_MFMA_STREAM and
- * params.bidirectional = 1 are GF_ERR_UNSUPPORTED.  params.launch_mask must be 0; segment_len
- * is ignored.  params.overlap = 1 (matrix-core kernels, both head groups present): the windowed
+ * storage type), and so do the linear heads of a bidirectional call on either storage type
+ * (three sweeps over each head: the sums over all keys, dq with the sums over all queries, dk
+ * and dv).  GF_IMPL_MFMA with fp32 storage, GF_IMPL_MFMA_BLOCKED, GF_IMPL_MFMA_STREAM and
+ * GF_IMPL_MFMA_CHUNK are GF_ERR_UNSUPPORTED.  params.launch_mask must be 0; segment_len and chunk
+ * are ignored.  params.overlap = 1 (matrix-core kernels, both head groups present): the windowed
  * heads' passes run on the library's side stream beside the linear heads' scans, which leave
  * compute units idle when there are fewer heads than units; same fork/join as in
  * gformer_attn_fwd, same results.

@@ -412,9 +412,9 @@ def gformer_attn_bwd_raw(q_ptr, k_ptr, v_ptr, dout_ptr, dq_ptr, dk_ptr, dv_ptr, 
 
 def gformer_attn_bwd(q, k, v, dout, dq, dk, dv, window: int, n_sparse_heads: int, *,
                      phi=GF_PHI_ELU1, impl=GF_IMPL_AUTO, softmax_scale=1.0, eps=0.0, overlap=0,
-                     workspace=None, stream: Optional[int] = None):
-    """Backward of the causal layer on [B, H, N, d] device tensors: fills dq, dk, dv (laid out
-    like q, k, v) from `dout`, the gradient with respect to the layer's output."""
+                     bidirectional=0, workspace=None, stream: Optional[int] = None):
+    """Backward of the layer (causal or bidirectional) on [B, H, N, d] device tensors: fills dq,
+    dk, dv (laid out like q, k, v) from `dout`, the gradient with respect to the layer's output."""
     import torch
 
     if not all(x.is_cuda for x in (q, k, v, dout, dq, dk, dv)):
@@ -424,7 +424,8 @@ def gformer_attn_bwd(q, k, v, dout, dq, dk, dv, window: int, n_sparse_heads: int
     dtype = GF_BF16 if q.dtype == torch.bfloat16 else GF_F32
     B, H, N, d = (int(x) for x in q.shape)
     params = make_params(dtype=dtype, n_sparse_heads=n_sparse_heads, phi=phi, impl=impl,
-                         softmax_scale=softmax_scale, eps=eps, overlap=overlap, q_stride=_strides3(q),
+                         softmax_scale=softmax_scale, eps=eps, overlap=overlap,
+                         bidirectional=bidirectional, q_stride=_strides3(q),
                          k_stride=_strides3(k), v_stride=_strides3(v), o_stride=_strides3(dout))
     need = gformer_attn_bwd_workspace_bytes(B, H, N, d, window, params)
     ws_ptr, ws_bytes = 0, 0

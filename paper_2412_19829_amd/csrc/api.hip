@@ -564,11 +564,22 @@ gf_status gformer_random_features(const void* x, const void* w, void* out, int B
   return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
 }
 
+namespace {
+// per-token statistics [B, H, N, 2] fp32, rounded up to 256 bytes
+size_t bwd_stats_bytes(int B, int H, int N) {
+  return ((size_t)B * H * N * 2 * sizeof(float) + 255) / 256 * 256;
+}
+}  // namespace
+
 size_t gformer_attn_bwd_workspace_bytes(int B, int H, int N, int d, int window,
                                         const gformer_params* p) {
-  (void)d; (void)window; (void)p;
+  (void)window;
   if (B <= 0 || H <= 0 || N <= 0) return 0;
-  return (size_t)B * H * N * 2 * sizeof(float);
+  size_t need = bwd_stats_bytes(B, H, N);
+  // bidirectional linear heads: the two d x d sums (and their vectors) of every head
+  if (p && p->bidirectional == 1 && p->n_sparse_heads >= 0 && p->n_sparse_heads < H && d > 0)
+    need += (size_t)B * (H - p->n_sparse_heads) * 2 * ((size_t)d * d + d) * sizeof(float);
+  return need;
 }
 
 gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq,
@@ -578,7 +589,8 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
   if (!p) return GF_ERR_INVALID_ARG;
   if (p->struct_size != sizeof(gformer_params)) return GF_ERR_INVALID_ARG;
   // a bf16 call runs on the matrix-core kernels (AUTO, MFMA) unless SCALAR asks for the plain-FMA
-  // kernels, which are also the fp32 path.  Causal form only.
+  // kernels, which are also the fp32 path and, on either storage type, the linear heads of the
+  // bidirectional layer.
   if (p->impl == GF_IMPL_MFMA_BLOCKED || p->impl == GF_IMPL_MFMA_STREAM ||
       p->impl == GF_IMPL_MFMA_CHUNK)
     return GF_ERR_UNSUPPORTED;
@@ -589,7 +601,6 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
   Resolved r;
   const gf_status st = resolve(B, H, N, d, window, &pp, &r);
   if (st != GF_OK) return st;
-  if (p->bidirectional != 0) return GF_ERR_UNSUPPORTED;
   if (p->launch_mask != 0) return GF_ERR_INVALID_ARG;
   if (B == 0 || H == 0 || N == 0) return GF_OK;
   if (!q || !k || !v || !dout || !dq || !dk || !dv) return GF_ERR_INVALID_ARG;
@@ -616,11 +627,19 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
   a.dq = dq; a.dk = dk; a.dv = dv;
   a.B = B; a.H = H; a.N = N; a.d = d;
   a.window = window < N ? window : N;   // a wider window sees no more keys; keeps row + window in range
+  a.causal = p->bidirectional ? 0 : 1;
+  a.wleft = window_left(window, p->bidirectional, N);
+  a.wright = window_right(window, p->bidirectional, N);
   a.H0 = p->n_sparse_heads;
   a.phi = p->phi;
   a.scale = p->softmax_scale;
   a.eps = p->eps;
   a.ws = reinterpret_cast<float*>(workspace);
+  a.ws_state = a.causal ? nullptr
+                        : reinterpret_cast<float*>(static_cast<char*>(workspace) + bwd_stats_bytes(B, H, N));
+  auto launch_linear = [&](hipStream_t on) {
+    return a.causal ? launch_linear_backward_mfma(a, on) : launch_linear_backward_bidir(a, true, on);
+  };
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   const bool bf16 = p->dtype == GF_BF16;
   const bool mfma = bf16 && p->impl != GF_IMPL_SCALAR;
@@ -638,7 +657,7 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
     if (side && e == hipSuccess) {
       e = hipEventRecord(side->fork, stream);
       if (e == hipSuccess) {
-        e = launch_linear_backward_mfma(a, stream);
+        e = launch_linear(stream);
         hipError_t f = hipStreamWaitEvent(side->stream, side->fork, 0);
         if (f == hipSuccess) {
           if (e == hipSuccess) e = launch_windowed_backward_mfma(a, side->stream);
@@ -650,10 +669,13 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
       }
     } else if (e == hipSuccess) {
       e = launch_windowed_backward_mfma(a, stream);
-      if (e == hipSuccess) e = launch_linear_backward_mfma(a, stream);
+      if (e == hipSuccess) e = launch_linear(stream);
     }
-  } else {
+  } else if (a.causal) {
     e = launch_backward_scalar(a, bf16, true, true, stream);
+  } else {
+    e = launch_backward_scalar(a, bf16, true, false, stream);   // the windowed heads
+    if (e == hipSuccess) e = launch_linear_backward_bidir(a, bf16, stream);
   }
   return e == hipSuccess ? GF_OK : GF_ERR_DEVICE;
 }

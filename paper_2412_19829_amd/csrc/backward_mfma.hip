@@ -82,7 +82,7 @@ __global__ __launch_bounds__(NT, 2) void windowed_bwd_band_kernel(BwdArgs a) {
   const int h = (lb / nrb) % a.H0, b = lb / (nrb * a.H0);
   const int i0 = rb * BR;
   const int r0 = i0 + wave * WR;
-  const int N = a.N, wl = a.window - 1;
+  const int N = a.N, wl = a.wleft, wr = a.wright;
 
   auto head = [&](const TensorView& t) {
     return reinterpret_cast<const uint16_t*>(t.base) + b * t.sb + h * t.sh;
@@ -122,15 +122,17 @@ __global__ __launch_bounds__(NT, 2) void windowed_bwd_band_kernel(BwdArgs a) {
   __builtin_amdgcn_sched_barrier(0);   // keep these loads in front of the tile loads (in-order return)
 
   // streamed rows this lane's resident row interacts with: [lo, hi]
-  //   resident query i: keys i - wl .. i;  resident key j: queries j .. min(j + wl, N - 1)
-  const int lo = RES_Q ? ri - wl : ri;
-  const int hi = RES_Q ? min(ri, N - 1) : min(ri + wl, N - 1);
-  const int span = max(hi - lo + 1, 0);          // 0: none (a key row past N)
+  //   resident query i: keys i - wl .. min(i + wr, N - 1) (causal: wr = 0);
+  //   resident key j: the queries that see it, j - wr .. min(j + wl, N - 1)
+  const int back = RES_Q ? wl : wr, ahead = RES_Q ? wr : wl;
+  const int lo = ri - back;
+  const int hi = min(ri + ahead, N - 1);
+  const int span = max(hi - lo + 1, 0);          // rows past N: whatever they gather is never stored
   // over the wave: union [ulo, uhi], intersection [ilo, ihi] of the lanes' intervals
-  const int ulo = RES_Q ? r0 - wl : r0, uhi = RES_Q ? r0 + WR - 1 : r0 + WR - 1 + wl;
-  const int ilo = RES_Q ? r0 + WR - 1 - wl : r0 + WR - 1, ihi = RES_Q ? r0 : r0 + wl;
-  const int tfirst = RES_Q ? max(0, i0 - wl) / BC : i0 / BC;
-  const int tlast = RES_Q ? min(N - 1, i0 + BR - 1) / BC : min(N - 1, i0 + BR - 1 + wl) / BC;
+  const int ulo = r0 - back, uhi = r0 + WR - 1 + ahead;
+  const int ilo = r0 + WR - 1 - back, ihi = r0 + ahead;
+  const int tfirst = max(0, i0 - back) / BC;
+  const int tlast = min(N - 1, i0 + BR - 1 + ahead) / BC;
   const float sc = (a.scale == 0.f ? 1e-30f : a.scale) * kLog2e;
 
   // global -> register -> LDS staging of a tile, as in the forward kernel

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kBwdThreads) void windowed_bwd_q_kernel(BwdArgs a) 
       qreg[cc] = Storage<T>::load(a.q.base, qoff + i * a.q.sn + cc * 64 + lane);
       doreg[cc] = Storage<T>::load(a.dout.base, ooff + i * a.dout.sn + cc * 64 + lane);
     }
-    const int lo = max(0, i - a.window + 1), hi = i;
+    const int lo = max(0, i - a.wleft), hi = min(a.N - 1, i + a.wright);
     // lane j's score against this query; lanes past the last visible key read that key again
     auto score = [&](int j) {
       return dot_row_with_spread<T, D>(a.k.base, koff + (int64_t)min(j, hi) * a.k.sn, qreg) * a.scale;
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(kBwdThreads) void windowed_bwd_q_kernel(BwdArgs a) 
 }
 
 // ---------------------------------------------------------------------------------------
-// windowed heads, per key row: dk_j and dv_j over the queries j .. j + w - 1 that see key j
+// windowed heads, per key row: dk_j and dv_j over the queries that see key j (causal: j .. j + w - 1)
 // grid = (ceil(N / kBwdRows), H0, B), block = 256; reads (lse_i, D_i) left by the kernel above
 // ---------------------------------------------------------------------------------------
 template <typename T, int D>
@@ -173,8 +173,9 @@ __global__ __launch_bounds__(kBwdThreads) void windowed_bwd_kv_kernel(BwdArgs a)
       acck[cc] = 0.f;
       accv[cc] = 0.f;
     }
-    const int ihi = (int)min((int64_t)a.N - 1, (int64_t)j + a.window - 1);
-    for (int i0 = j; i0 <= ihi; i0 += 64) {
+    // the queries that see key j: j - wright .. j + wleft, cut at the ends
+    const int ilo = max(0, j - a.wright), ihi = min(a.N - 1, j + a.wleft);
+    for (int i0 = ilo; i0 <= ihi; i0 += 64) {
       const int i = i0 + lane;
       const bool valid = i <= ihi;
       const int ii = min(i, ihi);   // lanes past the last query read that query again

@@ -95,10 +95,13 @@ struct BwdArgs {
   TensorView q, k, v, dout;
   void *dq, *dk, *dv;
   int B, H, N, d;
-  int window;
+  int window;         // causal calls: tokens in the window, cut at N
+  int wleft, wright;  // windowed heads: token i sees keys i - wleft .. i + wright (cut at the ends)
+  int causal;         // 1: causal layer; 0: bidirectional (centred window, linear heads over all keys)
   int H0;
   int phi;
   float scale, eps;
+  float* ws_state;    // bidirectional linear heads: [B * (H - H0)][2][d*d + d] fp32, (S, z) then (B, Y)
   int lin_segments;   // workgroups per linear head in the matrix-core scans (set by their launcher)
   int lin_bounds[5];  // segment s covers chunks [lin_bounds[s], lin_bounds[s+1]) (reverse scan: mirrored)
   float* ws;   // [B, H, N, 2] fp32: windowed heads (log-sum-exp, dO.o), linear heads (den, dO.o / den),
@@ -110,6 +113,8 @@ hipError_t launch_backward_scalar(const BwdArgs& a, bool bf16, bool windowed_hea
 // bf16 matrix-core kernels for the windowed heads and for the linear heads
 hipError_t launch_windowed_backward_mfma(const BwdArgs& a, hipStream_t s);
 hipError_t launch_linear_backward_mfma(const BwdArgs& a, hipStream_t s);
+// bidirectional linear heads (plain-FMA kernels on either storage type)
+hipError_t launch_linear_backward_bidir(const BwdArgs& a, bool bf16, hipStream_t s);
 
 // One call of the random-feature pre-map: heads [head_begin, head_end) of x -> the same heads of out.
 struct FeatureArgs {

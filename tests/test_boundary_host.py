@@ -298,7 +298,12 @@ def test_backward_argument_checks_on_the_host():
     a = (1, 2, 16, 64, 4)
     ptrs = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000]
     ws = (0x10000, 1 << 20)
-    assert gb.gformer_attn_bwd_workspace_bytes(*a, p) == 1 * 2 * 16 * 2 * 4
+    assert gb.gformer_attn_bwd_workspace_bytes(*a, p) == 1 * 2 * 16 * 2 * 4    # 8 bytes per token and head
+    assert gb.gformer_attn_bwd_workspace_bytes(1, 2, 17, 64, 4, p) == 512      # ... rounded up to 256
+    # the bidirectional layer also parks two (d*d + d) sums per linear head there
+    pb = gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1, bidirectional=1)
+    assert gb.gformer_attn_bwd_workspace_bytes(*a, pb) == 256 + 1 * 1 * 2 * (64 * 64 + 64) * 4
+    assert gb.gformer_attn_bwd_raw(*ptrs, *a, pb, ws[0], 256) == gb.GF_ERR_WORKSPACE
     assert gb.gformer_attn_bwd_workspace_bytes(0, 2, 16, 64, 4, p) == 0
     for i in range(7):                      # any null pointer
         bad = list(ptrs)
@@ -320,7 +325,6 @@ def test_backward_argument_checks_on_the_host():
         assert gb.gformer_attn_bwd_raw(*ptrs, *a, q, *ws) == gb.GF_ERR_UNSUPPORTED
     q = gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1, impl=gb.GF_IMPL_MFMA)   # matrix cores: bf16 only
     assert gb.gformer_attn_bwd_raw(*ptrs, *a, q, *ws) == gb.GF_ERR_UNSUPPORTED
-    assert gb.gformer_attn_bwd_raw(*ptrs, *a, gb.make_params(n_sparse_heads=1, bidirectional=1), *ws) == gb.GF_ERR_UNSUPPORTED
     assert gb.gformer_attn_bwd_raw(*ptrs, *a, gb.make_params(n_sparse_heads=1, launch_mask=1), *ws) == gb.GF_ERR_INVALID_ARG
     assert gb.gformer_attn_bwd_raw(*ptrs, 1, 2, 16, 96, 4, p, *ws) == gb.GF_ERR_UNSUPPORTED     # head size
     assert gb.gformer_attn_bwd_raw(*ptrs, 1, 2, 16, 64, 0, p, *ws) == gb.GF_ERR_INVALID_ARG     # window

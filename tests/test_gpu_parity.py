@@ -911,6 +911,68 @@ def test_backward_overlap_gives_the_same_bits():
         check_grad(g, r, "bf16", name, dout, AUTO)
 
 
+BIDIR_BWD_SHAPES = [
+    # B, H, N, d, window, H0
+    (1, 2, 1, 64, 4, 1),
+    (2, 3, 77, 64, 1, 2),          # every token sees itself only
+    (1, 4, 333, 64, 32, 2),
+    (1, 2, 300, 128, 101, 1),      # odd window: symmetric
+    (1, 2, 300, 128, 100, 1),      # even window: one more on the left
+    (1, 2, 200, 64, 1000, 1),      # everything visible
+    (1, 3, 1025, 128, 256, 1),
+    (2, 2, 513, 128, 70, 0),
+    (1, 2, 640, 64, 129, 2),
+    (1, 2, 700, 64, 600, 1),       # more than 256 visible keys
+]
+
+
+@pytest.mark.parametrize("path", BWD_PATHS, ids=BWD_PATH_IDS)
+@pytest.mark.parametrize("shape", BIDIR_BWD_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_bidirectional_backward_shapes(shape, path):
+    """Gradients of the bidirectional layer (window centred on the token, linear heads over all
+    keys) against the oracle's derivatives."""
+    dtype, impl = path
+    B, H, N, d, w, H0 = shape
+    q, k, v = synth(B, H, N, d, dtype, 67)
+    dout = synth(B, H, N, d, dtype, 68)[2]
+    got = run_bwd(q, k, v, dout, dtype, w, H0, impl=impl, bidirectional=1)
+    ref = co.attn_bwd(q, k, v, dout, w, H0, bidirectional=True)
+    for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+        check_grad(g, r, dtype, f"{name} {shape}", dout, impl)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_bidirectional_backward_options_and_layout(dtype):
+    """Softmax scale, eps, identity feature map, the paper's [B, N, H, E] storage, window = INT_MAX,
+    a long sequence; and the side-stream schedule gives the same bits."""
+    B, H, N, d, w, H0 = 2, 4, 150, 64, 41, 2
+    q, k, v = synth(B, H, N, d, dtype, 69, q_prescaled=False)
+    dout = synth(B, H, N, d, dtype, 70)[2]
+    q[:, H0:] = np.abs(q[:, H0:]) + np.float32(0.125)
+    k[:, H0:] = np.abs(k[:, H0:]) + np.float32(0.125)
+    if dtype == "bf16":
+        q, k = gi.round_to_bf16(q), gi.round_to_bf16(k)
+    kw = dict(softmax_scale=0.125, eps=0.5, phi=gb.GF_PHI_IDENTITY, bidirectional=1)
+    got = run_bwd(q, k, v, dout, dtype, w, H0, layout="bnhd", **kw)
+    ref = co.attn_bwd(q, k, v, dout, w, H0, phi=co.PHI_IDENTITY, softmax_scale=0.125, eps=0.5, bidirectional=True)
+    for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+        check_grad(g, r, dtype, name, dout, AUTO)
+    got = run_bwd(q, k, v, dout, dtype, 2 ** 31 - 1, H0, **kw)
+    ref = co.attn_bwd(q, k, v, dout, 2 * N, H0, phi=co.PHI_IDENTITY, softmax_scale=0.125, eps=0.5, bidirectional=True)
+    for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+        check_grad(g, r, dtype, f"{name} window=INT_MAX", dout, AUTO)
+    if dtype == "bf16":
+        B, H, N, d, w, H0 = 1, 2, 4099, 128, 257, 1
+        q, k, v = synth(B, H, N, d, "bf16", 73)
+        dout = synth(B, H, N, d, "bf16", 74)[2]
+        one = run_bwd(q, k, v, dout, "bf16", w, H0, bidirectional=1)
+        two = run_bwd(q, k, v, dout, "bf16", w, H0, bidirectional=1, overlap=1)
+        ref = co.attn_bwd(q, k, v, dout, w, H0, bidirectional=True)
+        for g, g2, r, name in zip(one, two, ref, ("dq", "dk", "dv")):
+            check_grad(g, r, "bf16", f"{name} 4099 tokens", dout, AUTO)
+            assert np.array_equal(g, g2), f"{name}: the side-stream schedule changed the bits"
+
+
 def test_backward_refuses_what_it_does_not_cover():
     import torch
     t = [torch.zeros(1, 2, 64, 64, device="cuda", dtype=torch.bfloat16) for _ in range(7)]
@@ -921,10 +983,7 @@ def test_backward_refuses_what_it_does_not_cover():
     with pytest.raises(gb.GformerError) as e:
         gb.gformer_attn_bwd(*f, 8, 1, impl=MFMA)      # matrix-core kernels are bf16 only
     assert e.value.status == gb.GF_ERR_UNSUPPORTED
-    p = gb.make_params(n_sparse_heads=1, bidirectional=1)
     ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
-    st = gb.gformer_attn_bwd_raw(*(x.data_ptr() for x in t), 1, 2, 64, 64, 8, p, ws.data_ptr(), ws.numel(), 0)
-    assert st == gb.GF_ERR_UNSUPPORTED
     p = gb.make_params(n_sparse_heads=1)
     st = gb.gformer_attn_bwd_raw(*(x.data_ptr() for x in t), 1, 2, 64, 64, 8, p, 0, 0, 0)
     assert st == gb.GF_ERR_WORKSPACE
