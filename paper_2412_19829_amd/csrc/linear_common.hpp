@@ -129,7 +129,7 @@ template <int D> struct Staging {
 // (row t0 + i*RP of the head, kept in scalar registers) plus one per-thread byte offset that
 // never changes, so a load costs no vector address arithmetic beyond its clamp.  Rows past N-1
 // (a head's last chunk only) re-read row N-1, in bounds.  Streamed once: non-temporal loads
-// (measured ~7.1 TB/s vs ~6.1 TB/s for plain loads).
+// (measured ~7.1 TB/s vs ~6.1 TB/s for plain loads) unless NT = false asks for plain ones.
 template <int D> struct PieceOffsets {
   uint32_t off;   // byte offset of (row r0, columns col..col+7) from the piece's first row
   uint32_t colb;  // byte offset of the thread's columns inside a row
@@ -138,7 +138,7 @@ template <int D> struct PieceOffsets {
       : off(2u * (uint32_t)(st.r0 * (int)row_stride + st.col)), colb(2u * (uint32_t)st.col),
         sn((int)row_stride) {}
 };
-template <int D>
+template <int D, bool NT = true>
 __device__ __forceinline__ void load_chunk(u32x4 (&dst)[LinCfg<D>::PIECES], const uint16_t* head,
                                            int t0, int N, const PieceOffsets<D>& po) {
   using C = LinCfg<D>;
@@ -149,8 +149,8 @@ __device__ __forceinline__ void load_chunk(u32x4 (&dst)[LinCfg<D>::PIECES], cons
     const int first = min(i * C::RP, last);  // uniform: the piece's first row, clamped
     const char* base = chunk + 2u * (uint32_t)(first * po.sn);
     const uint32_t lim = 2u * (uint32_t)((last - first) * po.sn) + po.colb;
-    dst[i] = __builtin_nontemporal_load(
-        reinterpret_cast<const u32x4*>(base + (size_t)min(po.off, lim)));
+    const u32x4* src = reinterpret_cast<const u32x4*>(base + (size_t)min(po.off, lim));
+    dst[i] = NT ? __builtin_nontemporal_load(src) : *src;
   }
 }
 
