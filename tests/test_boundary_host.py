@@ -293,6 +293,21 @@ def test_prefill_argument_checks_on_the_host():
     assert gb.gformer_attn_prefill_raw(0, 0, 0, 0, 0, 0, 0, 1, 2, 0, 64, 4, p) == gb.GF_OK
 
 
+def test_prefill_with_the_general_chunk_kernel_is_refused_on_the_host():
+    """Only the kernel specialised for chunks of 64 writes the states a decode step continues
+    from: a prefill call that would run the general-chunk kernel says so before any launch."""
+    ptrs = (0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000)
+    a = (1, 2, 256, 64, 4)
+    ws = (0x10000, 1 << 24)
+    for kw in (dict(chunk=128), dict(chunk=256), dict(impl=gb.GF_IMPL_MFMA_CHUNK)):
+        p = gb.make_params(n_sparse_heads=1, **kw)
+        assert gb.gformer_attn_prefill_raw(*ptrs, *a, p, *ws) == gb.GF_ERR_UNSUPPORTED
+    # all heads windowed: no linear state to write, nothing to refuse on that account ... but the
+    # call would launch, so it is only planned here
+    p = gb.make_params(n_sparse_heads=2, chunk=128)
+    assert gb.gformer_attn_plan(*a, p)[0] == gb.GF_OK
+
+
 def test_backward_argument_checks_on_the_host():
     p = gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1)
     a = (1, 2, 16, 64, 4)

@@ -711,15 +711,27 @@ def _sweep_cases():
         impl = [MFMA, BLOCKED, STREAM, SCALAR][int(rng.integers(0, 4))]
         if impl == STREAM and H0 > 0 and w > 257:
             impl = MFMA
-        cases.append((B, H, N, d, w, H0, bi, layout, impl))
+        cases.append((B, H, N, d, w, H0, bi, layout, impl, 0))
+    # the general-chunk kernel: chunk sizes 64 (forced), 128, 256 on random shapes
+    rng = np.random.default_rng(2025)
+    for _ in range(14):
+        d = int(rng.choice([64, 128]))
+        chunk = int(rng.choice([64, 128, 256] if d == 64 else [64, 128]))
+        B = int(rng.integers(1, 4))
+        H = int(rng.integers(1, 6))
+        N = int(rng.choice([int(rng.integers(1, 300)), int(rng.integers(300, 1500)), int(rng.integers(1500, 5000))]))
+        w = int(rng.choice([1, int(rng.integers(2, 258)), int(rng.integers(258, 900))]))
+        H0 = int(rng.integers(0, H))
+        layout = "bnhd" if rng.integers(0, 3) == 0 else "bhnd"
+        cases.append((B, H, N, d, w, H0, 0, layout, CHUNK if chunk == 64 else MFMA, chunk))
     return cases
 
 
 @pytest.mark.parametrize("case", _sweep_cases(), ids=lambda c: "x".join(map(str, c)))
 def test_seeded_sweep(case):
-    B, H, N, d, w, H0, bi, layout, impl = case
+    B, H, N, d, w, H0, bi, layout, impl, chunk = case
     q, k, v = synth(B, H, N, d, "bf16", 500 + N + w)
-    got = run_gpu(q, k, v, "bf16", w, H0, layout=layout, impl=impl, bidirectional=bi)
+    got = run_gpu(q, k, v, "bf16", w, H0, layout=layout, impl=impl, bidirectional=bi, chunk=chunk)
     ref = co.attn_fwd(q, k, v, w, H0, linear_form=co.LINEAR_RECURRENT, bidirectional=bool(bi))
     check(got, ref, "bf16", str(case))
 
@@ -853,18 +865,20 @@ def _bwd_sweep_cases():
         H0 = int(rng.integers(0, H + 1))
         layout = "bnhd" if rng.integers(0, 3) == 0 else "bhnd"
         path = BWD_PATHS[int(rng.integers(0, 3))] if rng.integers(0, 3) == 0 else ("bf16", AUTO)
-        cases.append((B, H, N, d, w, H0, layout, path[0], path[1]))
+        cases.append((B, H, N, d, w, H0, layout, path[0], path[1], 0))
+    for c in list(cases[:12]):      # the same shapes once more as the bidirectional layer
+        cases.append(c[:-1] + (1,))
     return cases
 
 
 @pytest.mark.parametrize("case", _bwd_sweep_cases(), ids=lambda c: "x".join(map(str, c)))
 def test_backward_seeded_sweep(case):
     """Random shapes, windows, head splits and layouts; mostly the matrix-core kernels."""
-    B, H, N, d, w, H0, layout, dtype, impl = case
+    B, H, N, d, w, H0, layout, dtype, impl, bi = case
     q, k, v = synth(B, H, N, d, dtype, 900 + N + w)
     dout = synth(B, H, N, d, dtype, 901 + N + w)[2]
-    got = run_bwd(q, k, v, dout, dtype, w, H0, layout=layout, impl=impl)
-    ref = co.attn_bwd(q, k, v, dout, w, H0)
+    got = run_bwd(q, k, v, dout, dtype, w, H0, layout=layout, impl=impl, bidirectional=bi)
+    ref = co.attn_bwd(q, k, v, dout, w, H0, bidirectional=bool(bi))
     for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
         check_grad(g, r, dtype, f"{name} {case}", dout, impl)
 
