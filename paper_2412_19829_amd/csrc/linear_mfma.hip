@@ -35,6 +35,12 @@
 
 #include <type_traits>
 
+// Register sets of the read-out kernel's producers (chunks of loads in flight): 2 or 3.  Three
+// were measured and are no faster (178 against 176 us on the headline layer).
+#ifndef GF_MAIN_SETS
+#define GF_MAIN_SETS 2
+#endif
+
 namespace gformer {
 namespace {
 
@@ -308,9 +314,10 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
     const Staging<D> st(tid - C::NTC);
     const PieceOffsets<D> qo(st, a.q.sn), ko(st, a.k.sn), vo(st, a.v.sn);
     ChunkCursor<D> cl(a, g0), cs(a, g0), co(a, g0);  // next chunk to load / stage / write out
-    // two register sets: chunk m travels in set m % 2; a set is reloaded with the chunk two
-    // further on as soon as it has been staged
-    u32x4 q0[C::PIECES], k0[C::PIECES], v0[C::PIECES], q1[C::PIECES], k1[C::PIECES], v1[C::PIECES];
+    // NSETS register sets: chunk m travels in set m % NSETS; a set is reloaded with the chunk
+    // NSETS further on as soon as it has been staged
+    constexpr int NSETS = GF_MAIN_SETS;
+    u32x4 qs[NSETS][C::PIECES], ks[NSETS][C::PIECES], vs[NSETS][C::PIECES];
     int nl = 0, no = 0;  // chunks loaded / written so far
     auto load_q = [&](u32x4 (&qr)[C::PIECES]) { load_chunk<D>(qr, cl.hp.q, cl.t0(), N, qo); };
     auto load_kv = [&](u32x4 (&kr)[C::PIECES], u32x4 (&vr)[C::PIECES]) {
@@ -379,50 +386,54 @@ __global__ __launch_bounds__(LinCfg<D>::NT, D == 64 ? 2 : 1) void linear_main_ke
     constexpr int kGeneral = 0, kFirst = 1, kSteady = 2;
     auto lead_in = [&](auto mode) {
       constexpr bool S = decltype(mode)::value != kGeneral;
-      load_q(q0);
-      load_kv(k0, v0);
-      if (S || nchunks > 1) {
-        load_q(q1);
-        load_kv(k1, v1);
-      }
-      stage_q(q0, 0);
-      stage_kv(k0, v0, 0);
-      if (S || nchunks > 2) {
-        load_q(q0);
-        load_kv(k0, v0);
+#pragma unroll
+      for (int i = 0; i < NSETS; ++i)
+        if (S || nchunks > i) {
+          load_q(qs[i]);
+          load_kv(ks[i], vs[i]);
+        }
+      stage_q(qs[0], 0);
+      stage_kv(ks[0], vs[0], 0);
+      if (S || nchunks > NSETS) {
+        load_q(qs[0]);
+        load_kv(ks[0], vs[0]);
       }
       lds_barrier();  // chunk 0 staged
     };
-    auto round2 = [&](int n, auto mode) {
+    // while the consumers work on chunk n: stage chunk n + 1 out of its set, reload the set with
+    // chunk n + 1 + NSETS, write out chunk n - 1.  False when chunk n was the piece's last.
+    auto step = [&](auto set_tag, auto mode, int n) {
+      constexpr int SET = decltype(set_tag)::value;
       constexpr int M = decltype(mode)::value;
       constexpr bool S = M != kGeneral;
-      if (S || n + 1 < nchunks) stage_q(q1, n + 1);
-      if (S || n + 3 < nchunks) load_q(q1);
+      if (S || n + 1 < nchunks) stage_q(qs[SET], n + 1);
+      if (S || n + 1 + NSETS < nchunks) load_q(qs[SET]);
       lds_barrier();  // (a)
-      if (M == kSteady || (M == kGeneral && n > 0)) store_out();
-      if (S || n + 1 < nchunks) stage_kv(k1, v1, n + 1);
-      if (S || n + 3 < nchunks) load_kv(k1, v1);
+      if (M == kSteady || n > 0) store_out();
+      if (S || n + 1 < nchunks) stage_kv(ks[SET], vs[SET], n + 1);
+      if (S || n + 1 + NSETS < nchunks) load_kv(ks[SET], vs[SET]);
       lds_barrier();  // (b)
-      if (!S && n + 1 >= nchunks) return false;
-      if (S || n + 2 < nchunks) stage_q(q0, n + 2);
-      if (S || n + 4 < nchunks) load_q(q0);
-      lds_barrier();  // (a)
-      store_out();
-      if (S || n + 2 < nchunks) stage_kv(k0, v0, n + 2);
-      if (S || n + 4 < nchunks) load_kv(k0, v0);
-      lds_barrier();  // (b)
+      return S || n + 1 < nchunks;
+    };
+    // NSETS chunks per round, n a multiple of NSETS: chunk n + 1 + i sits in set (1 + i) % NSETS
+    auto round = [&](int n, auto mode) {
+      if (!step(std::integral_constant<int, 1 % NSETS>{}, mode, n)) return false;
+      if (!step(std::integral_constant<int, 2 % NSETS>{}, mode, n + 1)) return false;
+      if constexpr (NSETS == 3)
+        if (!step(std::integral_constant<int, 0>{}, mode, n + 2)) return false;
       return true;
     };
+    static_assert(NSETS == 2 || NSETS == 3, "rounds are written out for two or three sets");
     int n = 0;
-    if (nchunks > 4) {
+    if (nchunks > 2 * NSETS) {
       lead_in(std::integral_constant<int, kFirst>{});
-      round2(0, std::integral_constant<int, kFirst>{});
-      for (n = 2; n + 4 < nchunks; n += 2) round2(n, std::integral_constant<int, kSteady>{});
+      round(0, std::integral_constant<int, kFirst>{});
+      for (n = NSETS; n + 2 * NSETS < nchunks; n += NSETS) round(n, std::integral_constant<int, kSteady>{});
     } else {
       lead_in(std::integral_constant<int, kGeneral>{});
     }
-    for (; n < nchunks; n += 2)
-      if (!round2(n, std::integral_constant<int, kGeneral>{})) break;
+    for (; n < nchunks; n += NSETS)
+      if (!round(n, std::integral_constant<int, kGeneral>{})) break;
     lds_barrier();  // (c) last chunk's rows are in LDS
     store_out();
     return;
