@@ -438,8 +438,22 @@ def main() -> int:
         backward()
         torch.cuda.synchronize()
         t_bwd_overlap = event_time(backward, 20)
+        pbi = gb.make_params(dtype=gb.GF_BF16, n_sparse_heads=H0, bidirectional=1)
+        need_bi = gb.gformer_attn_bwd_workspace_bytes(wl.B, wl.H, wl.N, wl.d, wl.window, pbi)
+        ws_bi = torch.empty(need_bi, dtype=torch.uint8, device=tq.device)
+
+        def backward_bidir():
+            st_ = gb.gformer_attn_bwd_raw(tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), tdo.data_ptr(),
+                                          dq_.data_ptr(), dk_.data_ptr(), dv_.data_ptr(), wl.B, wl.H, wl.N,
+                                          wl.d, wl.window, pbi, ws_bi.data_ptr(), need_bi, stream)
+            if st_ != gb.GF_OK:
+                raise gb.GformerError(st_, gb.gformer_status_string(st_))
+        backward_bidir()
+        torch.cuda.synchronize()
+        t_bwd_bidir = event_time(backward_bidir, 20)
         modes["backward"] = {"ms": round(t_bwd * 1e3, 3), "tokens_per_s": round(wl.B * wl.N / t_bwd, 1),
                              "ms_overlap_1": round(t_bwd_overlap * 1e3, 3),
+                             "ms_bidirectional": round(t_bwd_bidir * 1e3, 3),
                              "note": "gformer_attn_bwd, bf16 matrix-core kernels: four band passes over the "
                                      "windowed heads, a forward and a reverse chunk scan over the linear heads"}
         # The contract's fifth configuration: a 12-layer decoder around the library, reporting the

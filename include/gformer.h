@@ -242,9 +242,10 @@ gf_status gformer_attn_prefill(const void* q, const void* k, const void* v, void
  * two operands of the linear heads whose rounding would cost more than the bf16 mode's 2e-2 per
  * row, T' and the in-chunk weights of the numerator, travel as bf16 pairs);
  * GF_IMPL_SCALAR and every fp32 call run on plain-FMA kernels (fp32 arithmetic on either
- * storage type), and so do the linear heads of a bidirectional call on either storage type
- * (three sweeps over each head: the sums over all keys, dq with the sums over all queries, dk
- * and dv).  GF_IMPL_MFMA with fp32 storage, GF_IMPL_MFMA_BLOCKED, GF_IMPL_MFMA_STREAM and
+ * storage type).  The linear heads of a bidirectional call take three sweeps over each head (the
+ * sums over all keys, dq with the sums over all queries, dk and dv), on the matrix cores for a
+ * bf16 call, with the d x d sums and dO / den as bf16 pairs where a difference of nearly equal
+ * terms depends on them.  GF_IMPL_MFMA with fp32 storage, GF_IMPL_MFMA_BLOCKED, GF_IMPL_MFMA_STREAM and
  * GF_IMPL_MFMA_CHUNK are GF_ERR_UNSUPPORTED.  params.launch_mask must be 0; segment_len and chunk
  * are ignored.  params.overlap = 1 (matrix-core kernels, both head groups present): the windowed
  * heads' passes run on the library's side stream beside the linear heads' scans, which leave

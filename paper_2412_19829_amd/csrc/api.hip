@@ -576,9 +576,10 @@ size_t gformer_attn_bwd_workspace_bytes(int B, int H, int N, int d, int window,
   (void)window;
   if (B <= 0 || H <= 0 || N <= 0) return 0;
   size_t need = bwd_stats_bytes(B, H, N);
-  // bidirectional linear heads: the two d x d sums (and their vectors) of every head
+  // bidirectional linear heads: the two d x d sums (and their vectors) of every head, each in up
+  // to kBidirStateSlots per-segment partials
   if (p && p->bidirectional == 1 && p->n_sparse_heads >= 0 && p->n_sparse_heads < H && d > 0)
-    need += (size_t)B * (H - p->n_sparse_heads) * 2 * ((size_t)d * d + d) * sizeof(float);
+    need += (size_t)B * (H - p->n_sparse_heads) * 2 * kBidirStateSlots * ((size_t)d * d + d) * sizeof(float);
   return need;
 }
 
@@ -638,7 +639,7 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
   a.ws_state = a.causal ? nullptr
                         : reinterpret_cast<float*>(static_cast<char*>(workspace) + bwd_stats_bytes(B, H, N));
   auto launch_linear = [&](hipStream_t on) {
-    return a.causal ? launch_linear_backward_mfma(a, on) : launch_linear_backward_bidir(a, true, on);
+    return a.causal ? launch_linear_backward_mfma(a, on) : launch_linear_backward_bidir_mfma(a, on);
   };
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   const bool bf16 = p->dtype == GF_BF16;

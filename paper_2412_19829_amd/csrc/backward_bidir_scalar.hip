@@ -33,7 +33,7 @@ template <int D> struct BidirCfg {
 
 struct HeadOffsets {
   int64_t q, k, v, o;
-  float* state;   // this head's two (d*d + d) blocks
+  float* state;   // this head's first sum; the second starts kBidirStateSlots blocks further on
 };
 template <int D> __device__ __forceinline__ HeadOffsets head_offsets(const BwdArgs& a) {
   const int h = a.H0 + blockIdx.x, b = blockIdx.y;
@@ -42,7 +42,7 @@ template <int D> __device__ __forceinline__ HeadOffsets head_offsets(const BwdAr
   o.k = b * a.k.sb + h * a.k.sh;
   o.v = b * a.v.sb + h * a.v.sh;
   o.o = b * a.dout.sb + h * a.dout.sh;
-  o.state = a.ws_state + ((int64_t)b * (a.H - a.H0) + blockIdx.x) * 2 * BidirCfg<D>::STATE;
+  o.state = a.ws_state + ((int64_t)b * (a.H - a.H0) + blockIdx.x) * 2 * kBidirStateSlots * BidirCfg<D>::STATE;
   return o;
 }
 
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void linear_bidir_dq_kernel(BwdArgs a) {
       if (g == 0) yc = fmaf(cvec[t], f, yc);
     }
   }
-  float* out = ho.state + C::STATE;
+  float* out = ho.state + kBidirStateSlots * C::STATE;
 #pragma unroll
   for (int x = 0; x < C::EPT; ++x) out[c * D + e0 + x] = bacc[x];
   if (g == 0) out[D * D + c] = yc;
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(kThreads) void linear_bidir_dkv_kernel(BwdArgs a) {
   float* vv = fk + kChunk * C::TR;      // [CH][TR]
   const int tid = threadIdx.x, c = tid % D, g = tid / D;
   const HeadOffsets ho = head_offsets<D>(a);
-  const float* in = ho.state + C::STATE;
+  const float* in = ho.state + kBidirStateSlots * C::STATE;
   for (int x = tid; x < D * D; x += kThreads) Bm[(x / D) * C::SR + x % D] = in[x];
   if (tid < D) y[tid] = in[D * D + tid];
 

@@ -101,7 +101,9 @@ struct BwdArgs {
   int H0;
   int phi;
   float scale, eps;
-  float* ws_state;    // bidirectional linear heads: [B * (H - H0)][2][d*d + d] fp32, (S, z) then (B, Y)
+  float* ws_state;    // bidirectional linear heads: [B * (H - H0)][2][4][d*d + d] fp32: the sums
+                      // (S, z) and (B, Y) of every head, each in up to four per-segment partials
+                      // (matrix row-major [feature][value], then the vector)
   int lin_segments;   // workgroups per linear head in the matrix-core scans (set by their launcher)
   int lin_bounds[5];  // segment s covers chunks [lin_bounds[s], lin_bounds[s+1]) (reverse scan: mirrored)
   float* ws;   // [B, H, N, 2] fp32: windowed heads (log-sum-exp, dO.o), linear heads (den, dO.o / den),
@@ -113,8 +115,10 @@ hipError_t launch_backward_scalar(const BwdArgs& a, bool bf16, bool windowed_hea
 // bf16 matrix-core kernels for the windowed heads and for the linear heads
 hipError_t launch_windowed_backward_mfma(const BwdArgs& a, hipStream_t s);
 hipError_t launch_linear_backward_mfma(const BwdArgs& a, hipStream_t s);
-// bidirectional linear heads (plain-FMA kernels on either storage type)
+// bidirectional linear heads: plain-FMA kernels on either storage type, matrix-core kernels (bf16)
 hipError_t launch_linear_backward_bidir(const BwdArgs& a, bool bf16, hipStream_t s);
+hipError_t launch_linear_backward_bidir_mfma(const BwdArgs& a, hipStream_t s);
+constexpr int kBidirStateSlots = 4;   // per-segment partials kept per sum
 
 // One call of the random-feature pre-map: heads [head_begin, head_end) of x -> the same heads of out.
 struct FeatureArgs {

@@ -315,9 +315,10 @@ def test_backward_argument_checks_on_the_host():
     ws = (0x10000, 1 << 20)
     assert gb.gformer_attn_bwd_workspace_bytes(*a, p) == 1 * 2 * 16 * 2 * 4    # 8 bytes per token and head
     assert gb.gformer_attn_bwd_workspace_bytes(1, 2, 17, 64, 4, p) == 512      # ... rounded up to 256
-    # the bidirectional layer also parks two (d*d + d) sums per linear head there
+    # the bidirectional layer also parks two (d*d + d) sums per linear head there, each in up to
+    # four per-segment partials
     pb = gb.make_params(dtype=gb.GF_F32, n_sparse_heads=1, bidirectional=1)
-    assert gb.gformer_attn_bwd_workspace_bytes(*a, pb) == 256 + 1 * 1 * 2 * (64 * 64 + 64) * 4
+    assert gb.gformer_attn_bwd_workspace_bytes(*a, pb) == 256 + 1 * 1 * 2 * 4 * (64 * 64 + 64) * 4
     assert gb.gformer_attn_bwd_raw(*ptrs, *a, pb, ws[0], 256) == gb.GF_ERR_WORKSPACE
     assert gb.gformer_attn_bwd_workspace_bytes(0, 2, 16, 64, 4, p) == 0
     for i in range(7):                      # any null pointer

@@ -987,6 +987,21 @@ def test_bidirectional_backward_options_and_layout(dtype):
             assert np.array_equal(g, g2), f"{name}: the side-stream schedule changed the bits"
 
 
+@pytest.mark.parametrize("N", [1, 2, 3, 5, 8, 13, 30])
+def test_bidirectional_backward_of_heads_with_a_handful_of_tokens(N):
+    """With few tokens the two sides of dphi(q) = S g - c z and dphi(k) = B v - Y are nearly equal
+    (one token: exactly equal, both gradients vanish); the matrix-core kernels carry S, B and g as
+    bf16 pairs for this.  Both head sizes, three inputs each."""
+    for d in (64, 128):
+        for seed in (1, 2, 3):
+            q, k, v = synth(1, 2, N, d, "bf16", 7000 + 31 * N + seed)
+            dout = synth(1, 2, N, d, "bf16", 8000 + 31 * N + seed)[2]
+            got = run_bwd(q, k, v, dout, "bf16", 3, 0, bidirectional=1)
+            ref = co.attn_bwd(q, k, v, dout, 3, 0, bidirectional=True)
+            for g, r, name in zip(got, ref, ("dq", "dk", "dv")):
+                check_grad(g, r, "bf16", f"{name} N={N} d={d} seed={seed}", dout, AUTO)
+
+
 def test_backward_refuses_what_it_does_not_cover():
     import torch
     t = [torch.zeros(1, 2, 64, 64, device="cuda", dtype=torch.bfloat16) for _ in range(7)]
