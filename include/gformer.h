@@ -36,7 +36,10 @@
  *     before going on
  *     (an event fork/join, also valid under stream capture); the stream and its two events are
  *     created on first use and kept until the process ends.  Calls are serialised by a mutex
- *     while they enqueue.
+ *     while they enqueue.  Per-device state (that side stream, the scratch of
+ *     gformer_attn_fwd_noalloc) is looked up by the CURRENT device: call with the device of
+ *     `hip_stream` current; a non-NULL stream of another device is refused with GF_ERR_DEVICE
+ *     before anything is launched.
  *   - No exception crosses this boundary.  Argument errors are detected on the host before
  *     anything is launched and reported through gf_status.
  *   - Supported: d in {64, 128}; any N >= 0 (N == 0 or B*H == 0 is a no-op); any window >= 1

@@ -55,11 +55,29 @@ struct SideStream {
 SideStream g_side[kMaxDevices];
 std::mutex g_enqueue_mutex;
 
-hipError_t side_stream_for_current_device(SideStream** out) {
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
+// The device a call works on: the current one, which must also be the device of the caller's
+// stream when that is not the null stream (kernels launched on a stream run on the stream's
+// device, while per-device state below is looked up by the current one).
+hipError_t call_device(hipStream_t s, int* dev) {
+  hipError_t e = hipGetDevice(dev);
   if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (s != nullptr) {
+    int sdev = -1;
+    // a stream under capture may refuse the query; the device check is then skipped
+    if (hipStreamGetDevice(s, &sdev) == hipSuccess) {
+      if (sdev != *dev) return hipErrorInvalidDevice;
+    } else {
+      (void)hipGetLastError();
+    }
+  }
+  if (*dev < 0 || *dev >= kMaxDevices) return hipErrorInvalidDevice;
+  return hipSuccess;
+}
+
+hipError_t side_stream_for_current_device(hipStream_t caller, SideStream** out) {
+  int dev = 0;
+  hipError_t e = call_device(caller, &dev);
+  if (e != hipSuccess) return e;
   SideStream& s = g_side[dev];
   if (!s.ready) {
     if ((e = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking)) != hipSuccess) return e;
@@ -80,11 +98,10 @@ constexpr size_t kScratchBytes = GFORMER_NOALLOC_SCRATCH_BYTES;
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 std::atomic<void*> g_scratch_ptr[kMaxDevices];
 
-hipError_t scratch_for_current_device(void** out) {
+hipError_t scratch_for_current_device(hipStream_t caller, void** out) {
   int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
+  hipError_t e = call_device(caller, &dev);
   if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
   void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
   if (!ptr) {
     e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
@@ -406,7 +423,7 @@ gf_status attn_forward(const void* q, const void* k, const void* v, void* out, v
     const bool lin = (mask & (GF_LAUNCH_LINEAR_STATE | GF_LAUNCH_LINEAR_MAIN)) && a.H0 < a.H;
     std::lock_guard<std::mutex> lock(g_enqueue_mutex);
     SideStream* side = nullptr;
-    if (win && lin && p->overlap) e = side_stream_for_current_device(&side);
+    if (win && lin && p->overlap) e = side_stream_for_current_device(s, &side);
     bool forked = false;
     if (side && e == hipSuccess) {
       // fork: the windowed heads wait for what is already in `s`, then run beside the linear ones
@@ -457,7 +474,7 @@ gf_status gformer_attn_fwd_noalloc(const void* q, const void* k, const void* v, 
   void* ws = nullptr;
   if (r.plan.workspace_bytes > 0) {
     std::lock_guard<std::mutex> lock(g_enqueue_mutex);
-    if (scratch_for_current_device(&ws) != hipSuccess) {
+    if (scratch_for_current_device(reinterpret_cast<hipStream_t>(hip_stream), &ws) != hipSuccess) {
       (void)hipGetLastError();
       return GF_ERR_DEVICE;
     }
@@ -654,7 +671,7 @@ gf_status gformer_attn_bwd(const void* q, const void* k, const void* v, const vo
     const bool both = a.H0 > 0 && a.H0 < a.H;
     std::lock_guard<std::mutex> lock(g_enqueue_mutex);
     SideStream* side = nullptr;
-    if (both && p->overlap) e = side_stream_for_current_device(&side);
+    if (both && p->overlap) e = side_stream_for_current_device(stream, &side);
     if (side && e == hipSuccess) {
       e = hipEventRecord(side->fork, stream);
       if (e == hipSuccess) {
