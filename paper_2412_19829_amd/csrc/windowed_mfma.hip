@@ -14,6 +14,15 @@
 // running max / sum / rescale are lane-local apart from one exchange between lane l and l^32),
 // online softmax in base 2, then O^T += V^T P^T with P^T taken straight from the score
 // registers.  Only tiles cut by the diagonal or the window edge are masked.
+//
+// The K tiles run one step ahead of the V tiles: a step first turns the scores of tile t (made
+// at the end of the step before) into weights, which is vector work only, and then issues the
+// value products of tile t and the score products of tile t+1 back to back, sixteen and sixteen
+// matrix instructions over six independent accumulators with their LDS operands fetched ahead.
+// So a wave alternates between a stretch that needs only the vector unit and a stretch that
+// needs only the matrix core and LDS, and the two waves a SIMD holds fill each other's gaps.
+#include <type_traits>
+
 #include "common.hpp"
 #include "mfma.hpp"
 
@@ -25,14 +34,11 @@ constexpr int BC = 64;               // keys per tile
 constexpr int WQ = 32;               // queries per wave
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <int D> struct WinTiles {
+template <int D> struct WinSmem {
   static constexpr int KROW = D + 8;    // row stride = 4 dwords mod 64: conflict-free b128 reads
   static constexpr int VROW = D + 32;   // row stride = 16 dwords mod 64: conflict-free tr reads
-  uint16_t k[BC * KROW];
-  uint16_t v[BC * VROW];
-};
-template <int D> struct WinSmem {
-  WinTiles<D> buf[2];  // tile t in buf[t % 2]: one is filled while the other is read
+  uint16_t k[2][BC * KROW];   // K tile t in k[(t - first tile) % 2], V tile t in v[...] likewise:
+  uint16_t v[2][BC * VROW];   // one of each is filled while the other is read
 };
 
 // NEG: the softmax scale is negative, so the largest logit belongs to the smallest raw score
@@ -43,7 +49,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   constexpr int MT = D / 32;           // 32-row tiles of O^T
   constexpr int KCH = BC * D / 8 / kMfmaWindowThreads;  // 16-byte K chunks per thread per tile
   using Smem = WinSmem<D>;
-  using Tiles = WinTiles<D>;
+  constexpr int KROW = Smem::KROW, VROW = Smem::VROW;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
 
@@ -121,135 +127,161 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   const uint32_t koff = 2u * (uint32_t)(prow * ksn) + colb, voff = 2u * (uint32_t)(prow * vsn) + colb;
   u32x4 kst[KCH];
   u32x4 vst[KCH];
-  auto load_tile = [&](int t) {
+  auto load_rows = [&](u32x4 (&dst)[KCH], const uint16_t* base, int sn, uint32_t off, int t) {
     const int t0 = t * BC;
     const int last = min(N - 1 - t0, BC - 1);
-    const char* kbase = reinterpret_cast<const char*>(kp + (int64_t)t0 * ksn);
-    const char* vbase = reinterpret_cast<const char*>(vp + (int64_t)t0 * vsn);
+    const char* rb = reinterpret_cast<const char*>(base + (int64_t)t0 * sn);
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
       const int first = min(i * RP, last);  // uniform
-      const uint32_t klim = 2u * (uint32_t)((last - first) * ksn) + colb;
-      const uint32_t vlim = 2u * (uint32_t)((last - first) * vsn) + colb;
-      kst[i] = *reinterpret_cast<const u32x4*>(kbase + 2u * (uint32_t)(first * ksn) + (size_t)min(koff, klim));
-      vst[i] = *reinterpret_cast<const u32x4*>(vbase + 2u * (uint32_t)(first * vsn) + (size_t)min(voff, vlim));
+      const uint32_t lim = 2u * (uint32_t)((last - first) * sn) + colb;
+      dst[i] = *reinterpret_cast<const u32x4*>(rb + 2u * (uint32_t)(first * sn) + (size_t)min(off, lim));
     }
   };
-  auto store_tile = [&](Tiles& b) {
+  auto store_rows = [&](uint16_t* tile, int stride, const u32x4 (&src)[KCH]) {
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      *reinterpret_cast<u32x4*>(&b.k[(prow + i * RP) * Tiles::KROW + pcol]) = kst[i];
-      *reinterpret_cast<u32x4*>(&b.v[(prow + i * RP) * Tiles::VROW + pcol]) = vst[i];
-    }
+    for (int i = 0; i < KCH; ++i)
+      *reinterpret_cast<u32x4*>(&tile[(prow + i * RP) * stride + pcol]) = src[i];
   };
 
-  // Tile t is computed from buf[t % 2] while tile t+1 is stored into the other buffer and tile
-  // t+2 is on its way from memory: one barrier per tile.
-  load_tile(kfirst);
-  store_tile(sm.buf[0]);
-  if (kfirst < klast) load_tile(kfirst + 1);
-  lds_barrier();
-  for (int t = kfirst; t <= klast; ++t) {
-    const Tiles& cur = sm.buf[(t - kfirst) & 1];
-    if (t < klast) store_tile(sm.buf[(t - kfirst + 1) & 1]);
-    if (t + 1 < klast) load_tile(t + 2);
+  // S^T = K Q^T for the two 32-key halves of a tile: two accumulator chains taken in turn, the
+  // K operands of a k-step fetched while the step before is on the matrix core
+  f32x16 s[2];
+  auto scores = [&](const uint16_t* ktile) {
+    const uint16_t* kr0 = ktile + ln * KROW + 8 * lh;
+    const uint16_t* kr1 = kr0 + 32 * KROW;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+    bf16x8 ka[2][2];
+    ka[0][0] = lds_read16(kr0);
+    ka[0][1] = lds_read16(kr1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) {
+        ka[(ks + 1) & 1][0] = lds_read16(kr0 + 16 * (ks + 1));
+        ka[(ks + 1) & 1][1] = lds_read16(kr1 + 16 * (ks + 1));
+      }
+      s[0] = mfma32(ka[ks & 1][0], qreg[ks], s[0]);
+      s[1] = mfma32(ka[ks & 1][1], qreg[ks], s[1]);
+    }
+  };
+  // this lane's corner of the V operand reads: row 4*lh of the tile plus the transpose pattern
+  const int vlane = 4 * lh * VROW + lds_operand_tr_lane_offset(VROW, lane);
+
+  // One step: tile t's scores (in s) become weights, then the value products of tile t and, unless
+  // this is the last tile, the score products of tile t+1.  Tile t+1's keys and tile t's values
+  // move from the staging registers to LDS at the top of the step and are waited for at its one
+  // barrier, by which time every wave is done reading what they overwrite (read two steps ago);
+  // the loads of tile t+2's keys and tile t+1's values are in flight meanwhile.
+  auto step = [&](int t, auto last_tag) {
+    constexpr bool LAST = decltype(last_tag)::value;
+    const int it = t - kfirst;
+    if (!LAST) store_rows(sm.k[(it + 1) & 1], KROW, kst);
+    store_rows(sm.v[it & 1], VROW, vst);
+    if (!LAST) {
+      if (t + 1 < klast) load_rows(kst, kp, ksn, koff, t + 2);
+      load_rows(vst, vp, vsn, voff, t + 1);
+    }
     const int t0 = t * BC;
-    // keys visible to query i: i - wl <= j <= min(i + wr, N - 1); a tile with none for this
-    // wave's queries is skipped, a tile every one of them sees in full needs no mask
-    if (!(t0 > q0 + WQ - 1 + wr || t0 + BC - 1 < q0 - wl)) {
-      const bool need_mask =
-          !(t0 + BC - 1 <= q0 + wr && t0 >= q0 + WQ - 1 - wl && t0 + BC <= N);
-
-      // S^T = K Q^T for the two 32-key halves of the tile
-      f32x16 s[2];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
-        const uint16_t* krow = &cur.k[(32 * kt + ln) * Tiles::KROW + 8 * lh];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4*>(krow + 16 * ks));
-          s[kt] = mfma32(ka, qreg[ks], s[kt]);
-        }
-      }
-      // Online softmax in base 2 on the raw scores: p = 2^(s*sc - m), m a per-query reference.
-      // The reference follows the running maximum lazily: accumulators are rescaled only when
-      // some query's maximum grows by more than 8 (weights stay <= 2^8, harmless in bf16/fp32),
-      // which after the first tile or two is rare.
-      constexpr float worst = NEG ? INFINITY : -INFINITY;
-      if (need_mask) {
-        // register (kt, r) of this lane is key t0 + c + 4*lh, c = 32*kt + 8*(r/4) + r%4;
-        // with hi = min(qi + wr, N - 1) the key is visible iff 0 <= hi - key <= hi - (qi - wl)
-        const int qi = q0 + ln;
-        const int hi = min(qi + wr, N - 1);
-        const int rel = hi - t0 - 4 * lh;
-        const int wv = hi - qi + wl + 1;   // visible keys of this query (<= 0: none, a row past N)
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int c = 32 * kt + 8 * (r / 4) + (r % 4);
-            s[kt][r] = ((unsigned)(rel - c) >= (unsigned)max(wv, 0)) ? worst : s[kt][r];
-          }
-      }
-      float ext = worst;
+    // keys visible to query i: i - wl <= j <= min(i + wr, N - 1); a tile every query of this wave
+    // sees in full needs no mask (one it sees nothing of is masked in full: weights 0)
+    const bool need_mask =
+        !(t0 + BC - 1 <= q0 + wr && t0 >= q0 + WQ - 1 - wl && t0 + BC <= N);
+    // Online softmax in base 2 on the raw scores: p = 2^(s*sc - m), m a per-query reference.
+    // The reference follows the running maximum lazily: accumulators are rescaled only when
+    // some query's maximum grows by more than 8 (weights stay <= 2^8, harmless in bf16/fp32),
+    // which after the first tile or two is rare.
+    constexpr float worst = NEG ? INFINITY : -INFINITY;
+    if (need_mask) {
+      // register (kt, r) of this lane is key t0 + c + 4*lh, c = 32*kt + 8*(r/4) + r%4;
+      // with hi = min(qi + wr, N - 1) the key is visible iff 0 <= hi - key <= hi - (qi - wl)
+      const int qi = q0 + ln;
+      const int hi = min(qi + wr, N - 1);
+      int rel = hi - t0 - 4 * lh;
+      // opaque to the optimiser: left to itself it keeps all 32 values of rel - c in registers
+      // across the loop and steps each of them on every tile
+      asm volatile("" : "+v"(rel));
+      const unsigned wv = (unsigned)max(hi - qi + wl + 1, 0);   // visible keys (0: a row past N)
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int r = 0; r < 16; r += 2)
-          ext = NEG ? fminf(ext, fminf(s[kt][r], s[kt][r + 1])) : fmaxf(ext, fmaxf(s[kt][r], s[kt][r + 1]));
-      float mloc = (ext == worst) ? -INFINITY : ext * sc;   // no visible key in this lane's half
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-      if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.f) != 0) {   // wave-uniform
-        const float m_new = fmaxf(m_run, mloc);
-        const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);  // 0 on the first visible tile
-        m_run = m_new;
-        l_run *= alpha;
+        for (int r = 0; r < 16; ++r) {
+          const int c = 32 * kt + 8 * (r / 4) + (r % 4);
+          s[kt][r] = ((unsigned)(rel - c) >= wv) ? worst : s[kt][r];
+        }
+    }
+    float ext = worst;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+    for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
-      }
-      const float m_use = (m_run == -INFINITY) ? 0.f : m_run;  // a query with no visible key yet
-      uint32_t pb[2][8];  // P^T as packed bf16: pb[kt][4*kb + i] covers registers 8*kb+2i, +1
-      float lsum = 0.f;
+      for (int r = 0; r < 16; r += 2)
+        ext = NEG ? min3(ext, s[kt][r], s[kt][r + 1]) : max3(ext, s[kt][r], s[kt][r + 1]);
+    float mloc = (ext == worst) ? -INFINITY : ext * sc;   // no visible key in this lane's half
+    mloc = max_over_halves(mloc);
+    if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.f) != 0) {   // wave-uniform
+      const float m_new = fmaxf(m_run, mloc);
+      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);  // 0 on the first visible tile
+      m_run = m_new;
+      l_run *= alpha;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; r += 2) {
+        for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
+    }
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;  // a query with no visible key yet
+    bf16x8 pbv[2][2];  // P^T as packed bf16 operands: pbv[kt][kb] covers registers 8*kb .. 8*kb+7
+    float lsum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        u32x4 pw;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = 8 * kb + 2 * i;
           const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][r], sc, -m_use));
           const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], sc, -m_use));
-          const uint32_t pk = pack_bf16(p0, p1);
-          pb[kt][r / 2] = pk;
+          pw[i] = pack_bf16(p0, p1);
           // the row sum uses the rounded weights the PV product sees
-          lsum = dot2_ones_bf16(pk, lsum);
+          lsum = dot2_ones_bf16(pw[i], lsum);
         }
+        pbv[kt][kb] = as_bf16x8(pw);
       }
-      l_run += lsum;
+    }
+    l_run += lsum;
 
-      // O^T += V^T P^T
+    lds_barrier();   // tile t's values and tile t+1's keys are in place
+
+    // O^T += V^T P^T
+    const uint16_t* vt = sm.v[it & 1] + vlane;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          u32x4 pw;
-          pw[0] = pb[kt][4 * kb + 0]; pw[1] = pb[kt][4 * kb + 1];
-          pw[2] = pb[kt][4 * kb + 2]; pw[3] = pb[kt][4 * kb + 3];
-          const bf16x8 pbv = as_bf16x8(pw);
+      for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            // keys in the order the score registers hold them: 16*kb + 4*lh + j, then + 8
-            const int r0 = 32 * kt + 16 * kb + 4 * lh;
-            const bf16x8 va_ = lds_operand_tr(cur.v, Tiles::VROW, r0, r0 + 8, 32 * mt, lane);
-            oacc[mt] = mfma32(va_, pbv, oacc[mt]);
-          }
+        for (int mt = 0; mt < MT; ++mt) {
+          // keys in the order the score registers hold them: 16*kb + 4*lh + j, then + 8
+          const int r0 = 32 * kt + 16 * kb;
+          const bf16x8 va_ = lds_operand_tr_at(vt, VROW, r0, r0 + 8, 32 * mt);
+          oacc[mt] = mfma32(va_, pbv[kt][kb], oacc[mt]);
         }
       }
     }
-    lds_barrier();  // tile t is consumed, tile t+1 is in place
-  }
+    if (!LAST) scores(sm.k[(it + 1) & 1]);
+  };
+
+  load_rows(kst, kp, ksn, koff, kfirst);
+  store_rows(sm.k[0], KROW, kst);
+  load_rows(vst, vp, vsn, voff, kfirst);
+  if (kfirst < klast) load_rows(kst, kp, ksn, koff, kfirst + 1);
+  lds_barrier();
+  scores(sm.k[0]);
+  for (int t = kfirst; t < klast; ++t) step(t, std::false_type{});
+  step(klast, std::true_type{});
+  lds_barrier();   // every wave is done with the tiles: their memory takes the output rows
 
   // normalise; rows go through LDS (the K/V tiles are dead by now) so that they leave as whole
   // rows, 16 bytes per lane.  Lane owns query q0+ln, value columns 32*mt + 8*g + 4*lh + 0..3.
@@ -257,7 +289,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   const float inv = 1.f / l_tot;
   constexpr int OROW = D + 8;
   static_assert(BR * OROW * 2 <= (int)sizeof(Smem), "output staging must fit in the tile memory");
-  uint16_t* ot = reinterpret_cast<uint16_t*>(&sm);  // the loop's last barrier has freed the tiles
+  uint16_t* ot = reinterpret_cast<uint16_t*>(&sm);
   {
     uint16_t* orow = ot + (WQ * wave + ln) * OROW + 4 * lh;
 #pragma unroll
