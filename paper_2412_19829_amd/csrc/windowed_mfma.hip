@@ -175,9 +175,15 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   // move from the staging registers to LDS at the top of the step and are waited for at its one
   // barrier, by which time every wave is done reading what they overwrite (read two steps ago);
   // the loads of tile t+2's keys and tile t+1's values are in flight meanwhile.
+  // does any query of this wave see any key of tile t?  (wave-uniform)
+  auto in_band = [&](int t) {
+    const int t0 = t * BC;
+    return !(t0 > q0 + WQ - 1 + wr || t0 + BC - 1 < q0 - wl);
+  };
   auto step = [&](int t, auto last_tag) {
     constexpr bool LAST = decltype(last_tag)::value;
     const int it = t - kfirst;
+    const bool mine = in_band(t);
     if (!LAST) store_rows(sm.k[(it + 1) & 1], KROW, kst);
     store_rows(sm.v[it & 1], VROW, vst);
     if (!LAST) {
@@ -185,8 +191,10 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
       load_rows(vst, vp, vsn, voff, t + 1);
     }
     const int t0 = t * BC;
+    bf16x8 pbv[2][2];  // P^T as packed bf16 operands: pbv[kt][kb] covers registers 8*kb .. 8*kb+7
+    if (mine) {
     // keys visible to query i: i - wl <= j <= min(i + wr, N - 1); a tile every query of this wave
-    // sees in full needs no mask (one it sees nothing of is masked in full: weights 0)
+    // sees in full needs no mask; one it sees nothing of is left out (mine)
     const bool need_mask =
         !(t0 + BC - 1 <= q0 + wr && t0 >= q0 + WQ - 1 - wl && t0 + BC <= N);
     // Online softmax in base 2 on the raw scores: p = 2^(s*sc - m), m a per-query reference.
@@ -232,7 +240,6 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
         for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;  // a query with no visible key yet
-    bf16x8 pbv[2][2];  // P^T as packed bf16 operands: pbv[kt][kb] covers registers 8*kb .. 8*kb+7
     float lsum = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -252,11 +259,13 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
       }
     }
     l_run += lsum;
+    }
 
     lds_barrier();   // tile t's values and tile t+1's keys are in place
 
     // O^T += V^T P^T
     const uint16_t* vt = sm.v[it & 1] + vlane;
+    if (mine) {
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
@@ -270,7 +279,8 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
         }
       }
     }
-    if (!LAST) scores(sm.k[(it + 1) & 1]);
+    }
+    if (!LAST && in_band(t + 1)) scores(sm.k[(it + 1) & 1]);
   };
 
   load_rows(kst, kp, ksn, koff, kfirst);
@@ -278,7 +288,7 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
   load_rows(vst, vp, vsn, voff, kfirst);
   if (kfirst < klast) load_rows(kst, kp, ksn, koff, kfirst + 1);
   lds_barrier();
-  scores(sm.k[0]);
+  if (in_band(kfirst)) scores(sm.k[0]);
   for (int t = kfirst; t < klast; ++t) step(t, std::false_type{});
   step(klast, std::true_type{});
   lds_barrier();   // every wave is done with the tiles: their memory takes the output rows
