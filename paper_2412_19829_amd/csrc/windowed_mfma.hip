@@ -193,72 +193,72 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
     const int t0 = t * BC;
     bf16x8 pbv[2][2];  // P^T as packed bf16 operands: pbv[kt][kb] covers registers 8*kb .. 8*kb+7
     if (mine) {
-    // keys visible to query i: i - wl <= j <= min(i + wr, N - 1); a tile every query of this wave
-    // sees in full needs no mask; one it sees nothing of is left out (mine)
-    const bool need_mask =
-        !(t0 + BC - 1 <= q0 + wr && t0 >= q0 + WQ - 1 - wl && t0 + BC <= N);
-    // Online softmax in base 2 on the raw scores: p = 2^(s*sc - m), m a per-query reference.
-    // The reference follows the running maximum lazily: accumulators are rescaled only when
-    // some query's maximum grows by more than 8 (weights stay <= 2^8, harmless in bf16/fp32),
-    // which after the first tile or two is rare.
-    constexpr float worst = NEG ? INFINITY : -INFINITY;
-    if (need_mask) {
-      // register (kt, r) of this lane is key t0 + c + 4*lh, c = 32*kt + 8*(r/4) + r%4;
-      // with hi = min(qi + wr, N - 1) the key is visible iff 0 <= hi - key <= hi - (qi - wl)
-      const int qi = q0 + ln;
-      const int hi = min(qi + wr, N - 1);
-      int rel = hi - t0 - 4 * lh;
-      // opaque to the optimiser: left to itself it keeps all 32 values of rel - c in registers
-      // across the loop and steps each of them on every tile
-      asm volatile("" : "+v"(rel));
-      const unsigned wv = (unsigned)max(hi - qi + wl + 1, 0);   // visible keys (0: a row past N)
+      // keys visible to query i: i - wl <= j <= min(i + wr, N - 1); a tile every query of this wave
+      // sees in full needs no mask; one it sees nothing of is left out (mine)
+      const bool need_mask =
+          !(t0 + BC - 1 <= q0 + wr && t0 >= q0 + WQ - 1 - wl && t0 + BC <= N);
+      // Online softmax in base 2 on the raw scores: p = 2^(s*sc - m), m a per-query reference.
+      // The reference follows the running maximum lazily: accumulators are rescaled only when
+      // some query's maximum grows by more than 8 (weights stay <= 2^8, harmless in bf16/fp32),
+      // which after the first tile or two is rare.
+      constexpr float worst = NEG ? INFINITY : -INFINITY;
+      if (need_mask) {
+        // register (kt, r) of this lane is key t0 + c + 4*lh, c = 32*kt + 8*(r/4) + r%4;
+        // with hi = min(qi + wr, N - 1) the key is visible iff 0 <= hi - key <= hi - (qi - wl)
+        const int qi = q0 + ln;
+        const int hi = min(qi + wr, N - 1);
+        int rel = hi - t0 - 4 * lh;
+        // opaque to the optimiser: left to itself it keeps all 32 values of rel - c in registers
+        // across the loop and steps each of them on every tile
+        asm volatile("" : "+v"(rel));
+        const unsigned wv = (unsigned)max(hi - qi + wl + 1, 0);   // visible keys (0: a row past N)
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int c = 32 * kt + 8 * (r / 4) + (r % 4);
+            s[kt][r] = ((unsigned)(rel - c) >= wv) ? worst : s[kt][r];
+          }
+      }
+      float ext = worst;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int c = 32 * kt + 8 * (r / 4) + (r % 4);
-          s[kt][r] = ((unsigned)(rel - c) >= wv) ? worst : s[kt][r];
-        }
-    }
-    float ext = worst;
+        for (int r = 0; r < 16; r += 2)
+          ext = NEG ? min3(ext, s[kt][r], s[kt][r + 1]) : max3(ext, s[kt][r], s[kt][r + 1]);
+      float mloc = (ext == worst) ? -INFINITY : ext * sc;   // no visible key in this lane's half
+      mloc = max_over_halves(mloc);
+      if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.f) != 0) {   // wave-uniform
+        const float m_new = fmaxf(m_run, mloc);
+        const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);  // 0 on the first visible tile
+        m_run = m_new;
+        l_run *= alpha;
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int r = 0; r < 16; r += 2)
-        ext = NEG ? min3(ext, s[kt][r], s[kt][r + 1]) : max3(ext, s[kt][r], s[kt][r + 1]);
-    float mloc = (ext == worst) ? -INFINITY : ext * sc;   // no visible key in this lane's half
-    mloc = max_over_halves(mloc);
-    if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.f) != 0) {   // wave-uniform
-      const float m_new = fmaxf(m_run, mloc);
-      const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);  // 0 on the first visible tile
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
-    }
-    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;  // a query with no visible key yet
-    float lsum = 0.f;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        u32x4 pw;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int r = 8 * kb + 2 * i;
-          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][r], sc, -m_use));
-          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], sc, -m_use));
-          pw[i] = pack_bf16(p0, p1);
-          // the row sum uses the rounded weights the PV product sees
-          lsum = dot2_ones_bf16(pw[i], lsum);
-        }
-        pbv[kt][kb] = as_bf16x8(pw);
+          for (int r = 0; r < 16; ++r) oacc[mt][r] *= alpha;
       }
-    }
-    l_run += lsum;
+      const float m_use = (m_run == -INFINITY) ? 0.f : m_run;  // a query with no visible key yet
+      float lsum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          u32x4 pw;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int r = 8 * kb + 2 * i;
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][r], sc, -m_use));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][r + 1], sc, -m_use));
+            pw[i] = pack_bf16(p0, p1);
+            // the row sum uses the rounded weights the PV product sees
+            lsum = dot2_ones_bf16(pw[i], lsum);
+          }
+          pbv[kt][kb] = as_bf16x8(pw);
+        }
+      }
+      l_run += lsum;
     }
 
     lds_barrier();   // tile t's values and tile t+1's keys are in place
@@ -267,18 +267,18 @@ __global__ __launch_bounds__(kMfmaWindowThreads, 2) void windowed_mfma_kernel(At
     const uint16_t* vt = sm.v[it & 1] + vlane;
     if (mine) {
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+      for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          // keys in the order the score registers hold them: 16*kb + 4*lh + j, then + 8
-          const int r0 = 32 * kt + 16 * kb;
-          const bf16x8 va_ = lds_operand_tr_at(vt, VROW, r0, r0 + 8, 32 * mt);
-          oacc[mt] = mfma32(va_, pbv[kt][kb], oacc[mt]);
+          for (int mt = 0; mt < MT; ++mt) {
+            // keys in the order the score registers hold them: 16*kb + 4*lh + j, then + 8
+            const int r0 = 32 * kt + 16 * kb;
+            const bf16x8 va_ = lds_operand_tr_at(vt, VROW, r0, r0 + 8, 32 * mt);
+            oacc[mt] = mfma32(va_, pbv[kt][kb], oacc[mt]);
+          }
         }
       }
-    }
     }
     if (!LAST && in_band(t + 1)) scores(sm.k[(it + 1) & 1]);
   };
