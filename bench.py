@@ -394,6 +394,35 @@ def main() -> int:
         modes["decode"] = {"us_per_step": round(t_dec * 1e6, 2), "tokens_per_s": round(wl.B / t_dec, 1),
                            "gbs": round(dec_bytes / t_dec / 1e9, 1),
                            "note": "full rings; bytes = rings read once + states read and written once"}
+        # the same step as a serving loop would issue it: 32 consecutive steps captured in one graph
+        # (the call enqueues one kernel and nothing else), replayed
+        try:
+            steps_per_graph = 32
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                cap = torch.cuda.current_stream().cuda_stream
+                for i in range(steps_per_graph):
+                    st_ = gb.gformer_attn_decode_raw(q1.data_ptr(), k1.data_ptr(), v1.data_ptr(), o1.data_ptr(),
+                                                     ptr(kc), ptr(vc), ptr(stt), wl.B, wl.H, wl.d, wl.window,
+                                                     2 * wl.window + i, pdec, cap)
+                    if st_ != gb.GF_OK:
+                        raise gb.GformerError(st_, gb.gformer_status_string(st_))
+            for _ in range(3):
+                graph.replay()
+            torch.cuda.synchronize()
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record()
+            for _ in range(20):
+                graph.replay()
+            g1.record()
+            torch.cuda.synchronize()
+            t_graph = g0.elapsed_time(g1) * 1e-3 / (20 * steps_per_graph)
+            modes["decode"]["us_per_step_in_graph"] = round(t_graph * 1e6, 2)
+            modes["decode"]["gbs_in_graph"] = round(dec_bytes / t_graph / 1e9, 1)
+        except Exception as exc:   # the eager figure above stands on its own
+            modes["decode"]["graph_error"] = str(exc)[:200]
         # The paper's own timing shapes (section IV-A and IV-D: batch 4, 16 heads of size 64, 3 of
         # them windowed, sequence 1k-6k, window 128), for context next to its Gaudi figures.
         # These working sets (8-50 MB) sit in the caches: times only, no HBM fraction.

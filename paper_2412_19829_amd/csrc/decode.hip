@@ -65,6 +65,95 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(DecodeArgs a) {
     const int cnt = (int)(a.t + 1 < (int64_t)w ? a.t + 1 : (int64_t)w);
     const int slot = (int)(a.t % w);
     const int64_t ring = ((int64_t)b * a.H0 + h) * w * D;
+    if constexpr (sizeof(T) == 2) {
+      if (w <= kDecodeThreads) {
+        // Rings of at most one row per thread in 16-bit storage: every load of the step -- this
+        // thread's key row and its pieces of the value rows -- is issued before anything waits, so
+        // the step costs one trip to memory instead of three in a row.  The row of slot t % w is
+        // taken from the new token itself (its copy into the ring is under way in the same step).
+        constexpr int C8 = D / 8, RG = kDecodeThreads / C8, VR = kDecodeThreads / RG;
+        const int c0 = 8 * (tid % C8), g = tid / C8;
+        const uint16_t* kin = reinterpret_cast<const uint16_t*>(a.k) + tok;
+        const uint16_t* vin = reinterpret_cast<const uint16_t*>(a.v) + tok;
+        const uint16_t* kring = reinterpret_cast<const uint16_t*>(a.kcache) + ring;
+        const uint16_t* vring = reinterpret_cast<const uint16_t*>(a.vcache) + ring;
+        uint4 kr[C8], vr[VR];
+        if (tid < cnt) {
+          const uint16_t* src = tid == slot ? kin : kring + (int64_t)tid * D;
+#pragma unroll
+          for (int c = 0; c < C8; ++c) kr[c] = *reinterpret_cast<const uint4*>(src + 8 * c);
+        }
+#pragma unroll
+        for (int i = 0; i < VR; ++i) {
+          const int r = g + RG * i;
+          if (r < cnt) {
+            const uint16_t* src = r == slot ? vin : vring + (int64_t)r * D;
+            vr[i] = *reinterpret_cast<const uint4*>(src + c0);
+          }
+        }
+        if (tid < D) {
+          Storage<T>::store(a.kcache, ring + (int64_t)slot * D + tid, Storage<T>::load(a.k, tok + tid));
+          Storage<T>::store(a.vcache, ring + (int64_t)slot * D + tid, Storage<T>::load(a.v, tok + tid));
+          qs[tid] = Storage<T>::load(a.q, tok + tid);
+        }
+        __syncthreads();
+        auto widen = [](const uint4& u, float (&x)[8]) {
+          const uint32_t wd[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            x[2 * j] = __uint_as_float(wd[j] << 16);
+            x[2 * j + 1] = __uint_as_float(wd[j] & 0xffff0000u);
+          }
+        };
+        float mloc = -INFINITY;
+        if (tid < cnt) {
+          float acc = 0.f;
+#pragma unroll
+          for (int c = 0; c < C8; ++c) {
+            float kx[8];
+            widen(kr[c], kx);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc = fmaf(qs[8 * c + j], kx[j], acc);
+          }
+          acc *= a.scale;
+          s[tid] = acc;
+          mloc = acc;
+        }
+        const float m = block_reduce(mloc, red, true);   // also makes s[] visible
+        float lloc = 0.f;
+        if (tid < cnt) {
+          const float p = expf(s[tid] - m);
+          s[tid] = p;
+          lloc = p;
+        }
+        const float l = block_reduce(lloc, red, false);
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+#pragma unroll
+        for (int i = 0; i < VR; ++i) {
+          const int r = g + RG * i;
+          if (r < cnt) {
+            float vx[8];
+            widen(vr[i], vx);
+            const float p = s[r];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = fmaf(p, vx[j], acc[j]);
+          }
+        }
+        float* part = qs + D;            // [RG][D]
+#pragma unroll
+        for (int j = 0; j < 8; ++j) part[g * D + c0 + j] = acc[j];
+        __syncthreads();
+        if (tid < D) {
+          float o = 0.f;
+#pragma unroll
+          for (int gg = 0; gg < RG; ++gg) o += part[gg * D + tid];
+          Storage<T>::store(a.out, tok + tid, o / l);
+        }
+        return;
+      }
+    }
     if (tid < D) {
       Storage<T>::store(a.kcache, ring + (int64_t)slot * D + tid, Storage<T>::load(a.k, tok + tid));
       Storage<T>::store(a.vcache, ring + (int64_t)slot * D + tid, Storage<T>::load(a.v, tok + tid));
