@@ -565,7 +565,10 @@ def test_bidirectional_llm7b_full_size_sampled_heads():
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(2, 3, 150, 64, 40, 1), (1, 2, 90, 128, 200, 1), (1, 2, 70, 64, 1, 2),
-                                   (2, 2, 60, 128, 16, 0)], ids=str)
+                                   (2, 2, 60, 128, 16, 0),
+                                   # a ring of exactly one row per thread that wraps, and one with more rows
+                                   # than threads (the two code paths of the 16-bit ring)
+                                   (1, 2, 300, 128, 256, 2), (1, 2, 330, 64, 300, 1)], ids=str)
 def test_decode_steps_match_full_forward(dtype, shape):
     import torch
     B, H, T, d, w, H0 = shape
